@@ -1,0 +1,194 @@
+"""Pins for the oracle's draft head and beam search (Eq. 1-3, Alg. 3 inference)."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from _definitions import chain_scores_by_definition, chain_scores_grid_L3, log_softmax
+
+
+def _small(seed, B=3, d=8, e=4, V=6, L=3, w_std=0.7):
+    cfg = synth.StepConfig("t", B=B, d=d, e=e, L=L, V=V, K=1, N=1, dtype="f32",
+                           catalog="uniform", w_std=w_std)
+    return cfg, synth.draft_inputs(cfg, seed)
+
+
+def test_level1_logp_is_a_library_matvec_and_log_softmax(oracle):
+    cfg, x = _small(1, B=5, d=33, e=7, V=19)
+    o = oracle.draft_level(1, cfg.L, cfg.radices, 4, x["H"][:, 0], x["W"][0], x["E"][0],
+                           want_logp=True)
+    z = torch.from_numpy(x["H"][:, 0]).double() @ torch.from_numpy(x["W"][0][:33]).double()
+    want = torch.log_softmax(z, dim=-1).numpy()
+    assert np.abs(o["logp"][:, 0, :] - want).max() < 1e-12
+    assert np.abs(np.exp(o["logp"]).sum(-1) - 1).max() < 1e-12
+
+
+def test_level2_logits_use_the_concatenated_input(oracle):
+    cfg, x = _small(2, B=4, d=16, e=5, V=11)
+    rng = np.random.default_rng(3)
+    state = rng.normal(size=(4, 3, 5)).astype(np.float32)
+    key = np.arange(12, dtype=np.uint64).reshape(4, 3)
+    score = -rng.random((4, 3)).astype(np.float32)
+    o = oracle.draft_level(2, 3, cfg.radices, 3, x["H"][:, 1], x["W"][1], x["E"][1],
+                           state, key, score, want_logp=True)
+    Hc = torch.cat([torch.from_numpy(x["H"][:, 1]).double()[:, None, :].expand(4, 3, 16),
+                    torch.from_numpy(state).double()], dim=-1)
+    want = torch.log_softmax(Hc @ torch.from_numpy(x["W"][1]).double(), dim=-1).numpy()
+    assert np.abs(o["logp"] - want).max() < 1e-12
+    # swapping the two blocks of W (a transposed-operand style mistake) must be visible
+    Wsw = np.concatenate([x["W"][1][16:], x["W"][1][:16]])
+    bad = torch.log_softmax(Hc @ torch.from_numpy(Wsw).double(), dim=-1).numpy()
+    assert np.abs(o["logp"] - bad).max() > 1e-3
+    # candidate bookkeeping: score = parent score + logp, key = parent key + code * T_1
+    for b in range(4):
+        for j in range(3):
+            p, c = o["parent"][b, j], o["code"][b, j]
+            assert o["key"][b, j] == key[b, p] + np.uint64(c * 11)
+            assert abs(o["score"][b, j] - (score[b, p] + want[b, p, c])) < 1e-6
+            assert np.allclose(o["state"][b, j], state[b, p] + x["E"][1][c], atol=1e-7)
+
+
+def test_zero_weights_give_uniform_probabilities_and_the_tie_rule(oracle):
+    cfg, x = _small(3, B=2, d=8, e=4, V=9)
+    W0 = [np.zeros_like(w) for w in x["W"]]
+    outs = oracle.decode(x["H"], W0, x["E"], cfg.radices, 4)
+    o1, o2, o3 = outs
+    assert (o1["code"] == np.arange(4)).all() and (o1["parent"] == 0).all()
+    assert np.allclose(o1["score"], -np.log(9))
+    # level 2: all 16 candidates tie; parent rank 0 wins, lower codes first
+    assert (o2["parent"] == 0).all() and (o2["code"] == np.arange(4)).all()
+    assert np.allclose(o2["score"], -2 * np.log(9))
+    assert (o3["parent"] == 0).all() and (o3["code"] == np.arange(4)).all()
+    assert (o3["key"][0] == np.array([0, 81, 162, 243], dtype=np.uint64)).all()
+    assert (o3["count"] == 4).all()
+
+
+def test_per_beam_topk_then_merge_equals_global_topk_below_last_level(oracle):
+    cfg, x = _small(4, B=6, d=12, e=6, V=13)
+    K = 5
+    o1 = oracle.draft_level(1, 3, cfg.radices, K, x["H"][:, 0], x["W"][0], x["E"][0],
+                            want_logp=True)
+    order = np.argsort(-o1["logp"][:, 0, :], axis=-1, kind="stable")[:, :K]
+    assert (o1["code"] == order).all()                      # level 1 = full sort of V values
+    o2 = oracle.draft_level(2, 3, cfg.radices, K, x["H"][:, 1], x["W"][1], x["E"][1],
+                            o1["state"], o1["key"], o1["score"], want_logp=True)
+    for b in range(6):
+        allc = [(-(np.float32(np.float64(o1["score"][b, p]) + o2["logp"][b, p, v])), p, v)
+                for p in range(K) for v in range(13)]
+        allc.sort()
+        want = allc[:K]
+        got = [(-o2["score"][b, j], o2["parent"][b, j], o2["code"][b, j]) for j in range(K)]
+        assert got == want
+
+
+@pytest.mark.parametrize("seed,V,L", [(5, 4, 3), (6, 7, 2), (7, 3, 3)])
+def test_exhaustive_beam_equals_brute_force_over_all_tuples(oracle, seed, V, L):
+    cfg, x = _small(seed, B=2, d=6, e=3, V=V, L=L)
+    total = V ** L
+    rng = np.random.default_rng(seed)
+    valid = rng.random(total) < 0.4
+    tuples = np.array([t for t in np.ndindex(*([V] * L))], dtype=np.int32)
+    cat = tuples[valid]
+    s = oracle.ItemSet(cat, cfg.radices)
+    K = total                                   # no pruning can bite: beam search is exhaustive
+    outs = oracle.decode(x["H"], x["W"], x["E"], cfg.radices, K, itemset=s)
+    last = outs[-1]
+    for b in range(2):
+        truth = chain_scores_by_definition(x["H"][b], x["W"], x["E"])
+        assert abs(sum(np.exp(v) for v in truth.values()) - 1) < 1e-12
+        vt = sorted(((-truth[tuple(t)], i) for i, t in enumerate(cat.tolist())))
+        assert last["count"][b] == len(cat)
+        got = oracle.unpack(last["key"][b, :len(cat)], cfg.radices)
+        got_scores = last["score"][b, :len(cat)]
+        want_scores = np.array([-v for v, _ in vt])
+        assert np.abs(got_scores - want_scores).max() < 2e-6
+        assert (np.diff(got_scores) <= 0).all()
+        assert sorted(map(tuple, got.tolist())) == sorted(map(tuple, cat.tolist()))
+        for t, sc in zip(got.tolist(), got_scores):
+            assert abs(truth[tuple(t)] - sc) < 2e-6
+        assert (last["key"][b, len(cat):] == np.uint64(2**64 - 1)).all()
+        assert np.isneginf(last["score"][b, len(cat):]).all()
+
+
+def test_beam_search_invariants_with_real_pruning(oracle):
+    cfg, x = _small(8, B=5, d=10, e=5, V=12)
+    K = 4
+    tuples = np.array([t for t in np.ndindex(12, 12, 12)], dtype=np.int32)
+    rng = np.random.default_rng(8)
+    cat = tuples[rng.random(len(tuples)) < 0.3]
+    s = oracle.ItemSet(cat, cfg.radices)
+    outs = oracle.decode(x["H"], x["W"], x["E"], cfg.radices, K, itemset=s)
+    free = oracle.decode(x["H"], x["W"], x["E"], cfg.radices, K, itemset=None)
+    assert (free[-1]["count"] == K).all()
+    o2, o3 = outs[1], outs[2]
+    chk = oracle.draft_level(3, 3, cfg.radices, K, x["H"][:, 2], x["W"][2], None,
+                             o2["state"], o2["key"], o2["score"], None, want_logp=True)
+    catset = set(map(tuple, cat.tolist()))
+    for b in range(5):
+        truth = chain_scores_by_definition(x["H"][b], x["W"], x["E"])
+        # the K x K candidates of the last level: per-beam top-K codes
+        cands = []
+        for p in range(K):
+            top = np.argsort(-chk["logp"][b, p], kind="stable")[:K]
+            prefix = tuple(oracle.unpack(o2["key"][b, p:p + 1], cfg.radices)[0][:2])
+            cands += [prefix + (int(v),) for v in top]
+        assert len(set(cands)) == K * K
+        valid = [t for t in cands if t in catset]
+        n = int(o3["count"][b])
+        assert n == min(K, len(valid))
+        got = [tuple(t) for t in oracle.unpack(o3["key"][b, :n], cfg.radices).tolist()]
+        assert len(set(got)) == n and set(got) <= set(valid)
+        sc = o3["score"][b, :n]
+        assert (np.diff(sc) <= 0).all()
+        for t, v in zip(got, sc):
+            assert abs(truth[t] - v) < 2e-6                 # carries its brute-force chain score
+        worst = sc[-1] if n else np.inf
+        for t in valid:
+            if t not in got:
+                assert truth[t] <= worst + 2e-6             # nothing better was left out
+
+
+def test_tiny_config_against_all_256_cubed_tuples(oracle):
+    cfg = synth.get_config("tiny")
+    x = synth.draft_inputs(cfg, 42)
+    cat, _ = synth.uniform_catalog(cfg.radices, cfg.N, 42)
+    # the tiny catalog has density 0.06 %, so plant the unverified beams' tuples too
+    free = oracle.decode(x["H"], x["W"], x["E"], cfg.radices, cfg.K)
+    plant = oracle.unpack(free[-1]["key"].ravel(), cfg.radices)
+    keep = synth.plant_mask(plant, cfg.radices, 42)
+    cat2 = synth.planted_catalog(cfg.radices, cat, plant[keep], plant[~keep], 42)
+    assert cat2.shape == cat.shape
+    s = oracle.ItemSet(cat2, cfg.radices)
+    outs = oracle.decode(x["H"], x["W"], x["E"], cfg.radices, cfg.K, itemset=s)
+    bitmap = np.zeros((256,) * 3, dtype=bool)
+    bitmap[cat2[:, 0], cat2[:, 1], cat2[:, 2]] = True
+    emitted = 0
+    for b in range(cfg.B):
+        grid, lp1 = chain_scores_grid_L3(x["H"][b], x["W"], x["E"])
+        assert abs(np.exp(grid).sum() - 1) < 1e-9
+        top1 = np.argsort(-lp1, kind="stable")[:cfg.K]
+        assert (outs[0]["code"][b] == top1).all()
+        assert np.abs(outs[0]["score"][b] - lp1[top1]).max() < 1e-6
+        n = int(outs[2]["count"][b])
+        emitted += n
+        t = oracle.unpack(outs[2]["key"][b, :n], cfg.radices)
+        assert bitmap[t[:, 0], t[:, 1], t[:, 2]].all()
+        assert np.abs(grid[t[:, 0], t[:, 1], t[:, 2]] - outs[2]["score"][b, :n]).max() < 2e-6
+        tf = oracle.unpack(free[2]["key"][b], cfg.radices)
+        assert np.abs(grid[tf[:, 0], tf[:, 1], tf[:, 2]] - free[2]["score"][b]).max() < 2e-6
+    assert emitted > 0
+    # un-planted: almost surely nothing survives; counts may be zero and must pad correctly
+    s0 = oracle.ItemSet(cat, cfg.radices)
+    o0 = oracle.decode(x["H"], x["W"], x["E"], cfg.radices, cfg.K, itemset=s0)[-1]
+    for b in range(cfg.B):
+        n = int(o0["count"][b])
+        assert (o0["parent"][b, n:] == -1).all() and (o0["code"][b, n:] == -1).all()
+
+
+def test_state_rounding_to_bf16(oracle):
+    cfg, x = _small(9, B=2, d=8, e=16, V=10, w_std=0.3)
+    o = oracle.draft_level(1, 3, cfg.radices, 3, x["H"][:, 0], x["W"][0], x["E"][0],
+                           round_state_bf16=True)
+    want = torch.from_numpy(x["E"][0][o["code"]]).to(torch.bfloat16).float().numpy()
+    assert (o["state"] == want).all()
+    assert (synth.round_to_bf16(x["E"][0]) == torch.from_numpy(x["E"][0]).to(torch.bfloat16).float().numpy()).all()
