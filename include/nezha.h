@@ -1,0 +1,157 @@
+/* nezha.h - C ABI of the MI355X (gfx950) implementation of NEZHA's decoding
+ * step: batched self-drafting of semantic-ID items by beam search over the
+ * codebook levels (Sec. 3.2, Eq. 1-3; Alg. 3, inference part) followed by the
+ * model-free hash-set verification of the drafted tuples (Sec. 3.3, Eq. 4-5).
+ *
+ * Notation follows the paper: L levels, T_l codes at level l ("radices"), beam
+ * size K, h_l the backbone's hidden state at placeholder l, s_l / c_l the
+ * draft head's state, V the set of valid item indices.
+ *
+ * General rules
+ *  - Every function returns NEZHA_OK (0) or a negative error code and never
+ *    throws.  nezha_last_error() gives a text for the last failure on the
+ *    calling thread.
+ *  - All argument checks run on the host before anything is enqueued, so a
+ *    failed call has no effect on the device.
+ *  - "device pointer" = memory of the current HIP device; "host pointer" =
+ *    ordinary process memory.  Inputs are borrowed and never written.
+ *    Outputs and workspaces are allocated by the caller.  The only memory the
+ *    library owns is inside a nezha_itemset.
+ *  - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
+ *    nezha_verify_tuples and nezha_draft_step only enqueue work on it and
+ *    return; they never synchronise and never allocate, so they can be
+ *    captured into a HIP graph.
+ *  - Inputs must be finite (no NaN / inf).
+ */
+#ifndef NEZHA_H_
+#define NEZHA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct nezha_itemset nezha_itemset; /* opaque, device resident, owned by the library */
+
+typedef enum { NEZHA_F32 = 0, NEZHA_BF16 = 1 } nezha_dtype;
+
+enum {
+  NEZHA_OK = 0,
+  NEZHA_EINVAL = -1, /* bad argument (null pointer, size or shape outside the supported range) */
+  NEZHA_ENOMEM = -2, /* device or host allocation failed */
+  NEZHA_EHIP = -3,   /* a HIP runtime call failed */
+  NEZHA_ERANGE = -4, /* prod T_l >= 2^64-1, or a catalog code outside [0, T_l) */
+  NEZHA_EFULL = -5   /* the hash table could not take every key (should not happen) */
+};
+
+/* Limits of this implementation. */
+#define NEZHA_MAX_LEVELS 8
+#define NEZHA_MAX_BEAM 128 /* K and K_in */
+
+const char* nezha_last_error(void); /* thread local, never NULL */
+
+/* ---- the set of valid items V (Sec. 3.3: "a hash set", pre-computed) ------------------
+ *
+ * Builds the set { P(v) : v in catalog } where P is the mixed-radix index of
+ * Eq. 4 (level 1 is the least significant digit).
+ *   codes       int32 [n, L] row major, tuple i = codes[i*L .. i*L+L-1], level 1 first;
+ *               host pointer if codes_on_device == 0, else device pointer.  n >= 0.
+ *   radices     host int32 [L] = T_1..T_L, each >= 1, 1 <= L <= NEZHA_MAX_LEVELS,
+ *               prod T_l <= 2^64 - 1 (the value 2^64-1 is reserved for "empty").
+ *   load_factor in (0, 0.9]; the table gets ceil(n / load_factor) key slots,
+ *               rounded up to whole 64-byte buckets.
+ * Duplicate tuples are stored once.  A code outside [0, T_l) gives NEZHA_ERANGE.
+ * The work runs on hip_stream and the call waits for it (building is an offline
+ * step in the paper).  On success *out holds the new set. */
+int nezha_build_itemset(const int32_t* codes, int64_t n, int32_t L, const int32_t* radices,
+                        int codes_on_device, double load_factor, void* hip_stream,
+                        nezha_itemset** out);
+
+/* Any of the output pointers may be NULL.  radices: host int32 [L]. */
+int nezha_itemset_info(const nezha_itemset* set, int64_t* n_distinct, int64_t* n_slots,
+                       int32_t* L, int32_t* radices);
+
+/* Frees the set (NULL is accepted).  The caller makes sure no enqueued work still uses it. */
+int nezha_free_itemset(nezha_itemset* set);
+
+/* ---- stand-alone verification (Eq. 4 + Eq. 5 on a batch of tuples) ---------------------
+ *
+ *   codes      device int32 [n, L] (L of the set), n >= 0
+ *   out_mask   device uint8 [n]: 1 if the tuple is a valid item, else 0.  A tuple
+ *              with a code outside [0, T_l) is rejected (0); it is not an error.
+ *   out_index  device int64 [n] or NULL: the indices i of the accepted tuples in
+ *              ascending order (Eq. 5 filters "in place": order is kept);
+ *              entries beyond the count are left untouched.
+ *   out_count  device int64 [1] or NULL: number of accepted tuples.
+ *   workspace  device memory of at least nezha_verify_workspace(n) bytes, 16-byte
+ *              aligned; contents are scratch. */
+int nezha_verify_tuples(const nezha_itemset* set, const int32_t* codes, int64_t n,
+                        uint8_t* out_mask, int64_t* out_index, int64_t* out_count,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+size_t nezha_verify_workspace(int64_t n);
+
+/* ---- one level of the draft head's beam search (Alg. 3, inference loop body) -----------
+ *
+ * For each of B requests and each of its K_in live beams (rank order) the call
+ *   1. forms the logits of Eq. 2, z = [h_l ; c] W_l (one linear layer on the
+ *      concatenation of the placeholder hidden state and the beam's state, no
+ *      bias), and their log-softmax over the T_level codes;
+ *   2. takes the beam's K most probable codes (equal values: lower code first);
+ *   3. gives each candidate the cumulative score parent_score + logp (float32;
+ *      the log of the paper's cumulative probability) and the index
+ *      parent_key + code * prod_{j<level} T_j (Eq. 4, one more digit);
+ *   4. at level == L and with a set given, drops every candidate whose index is
+ *      not in the set (Eq. 5);
+ *   5. keeps the K candidates of largest score (ties: lower parent rank, then
+ *      better within-beam rank), in non-increasing score order;
+ *   6. at level < L, forms each survivor's next state by Eq. 3 with the additive
+ *      Transition: c' = c_parent + E_l[code].
+ */
+typedef struct {
+  int32_t B;              /* requests in the batch, >= 0 */
+  int32_t L;              /* levels of the semantic ID */
+  int32_t level;          /* this call's level, 1..L */
+  int32_t K;              /* beams kept, 1 <= K <= min(T_level, NEZHA_MAX_BEAM) */
+  int32_t K_in;           /* live beams entering: 1 at level 1, else K of the previous call */
+  int32_t d;              /* width of h_l */
+  int32_t e;              /* width of the state c and of the code embeddings */
+  const int32_t* radices; /* host int32 [L] */
+  nezha_dtype dtype;      /* of H, W, E and the states; scores are always float32 */
+  int64_t h_row_stride;   /* elements between consecutive requests in H_l (>= d) */
+} nezha_step_desc;
+
+/* All data pointers are device pointers.
+ *   in:  H_l [B, d] (row b at H_l + b*h_row_stride); W_l [(d+e), T_level] row major,
+ *        rows 0..d-1 act on h_l, rows d..d+e-1 on the state; E_l [T_level, e]
+ *        (ignored when level == L, may be NULL there); state_in [B, K_in, e]
+ *        (NULL = all zero, the initial state); key_in uint64 [B, K_in] and
+ *        score_in float32 [B, K_in] (NULL = 0, the empty prefix);
+ *        set: consulted only when level == L; NULL = no verification.
+ *   out: key_out uint64 [B, K], score_out float32 [B, K], parent_out int32 [B, K]
+ *        (rank of the parent beam), code_out int32 [B, K], state_out [B, K, e]
+ *        (NULL allowed when level == L), count_out int32 [B] (NULL allowed):
+ *        number of beams kept, = K unless verification left fewer.  Slots at or
+ *        beyond the count hold key 2^64-1, score -inf, parent -1, code -1, state 0.
+ *   workspace: device memory of at least nezha_draft_step_workspace(desc) bytes,
+ *        256-byte aligned; scratch.
+ * Shape limits: K, K_in <= NEZHA_MAX_BEAM; T_level a multiple of 16; with
+ * NEZHA_BF16 d and e multiples of 32, with NEZHA_F32 d >= 1 and e a multiple
+ * of 4; e <= 256.  Anything else gives NEZHA_EINVAL. */
+int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W_l,
+                     const void* E_l, const void* state_in, const uint64_t* key_in,
+                     const float* score_in, const nezha_itemset* set, uint64_t* key_out,
+                     float* score_out, int32_t* parent_out, int32_t* code_out,
+                     void* state_out, int32_t* count_out, void* workspace,
+                     size_t workspace_bytes, void* hip_stream);
+size_t nezha_draft_step_workspace(const nezha_step_desc* desc); /* 0 if desc is invalid */
+
+/* Inverse of Eq. 4 on the host: keys[n] -> codes int32 [n, L] (level 1 first).  Host pointers. */
+int nezha_unpack_keys(const uint64_t* keys, int64_t n, int32_t L, const int32_t* radices,
+                      int32_t* codes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NEZHA_H_ */

@@ -1,0 +1,252 @@
+"""ctypes binding of libnezha.so (see include/nezha.h for the contract of each call).
+Argument marshalling only."""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+NEZHA_F32, NEZHA_BF16 = 0, 1
+MAX_LEVELS = 8
+
+EXPORTS = ["nezha_last_error", "nezha_build_itemset", "nezha_itemset_info", "nezha_free_itemset",
+           "nezha_verify_tuples", "nezha_verify_workspace", "nezha_draft_step",
+           "nezha_draft_step_workspace", "nezha_unpack_keys"]
+
+
+class NezhaError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("nezha error %d: %s" % (code, text))
+        self.code = code
+
+
+class _StepDesc(C.Structure):
+    _fields_ = [("B", C.c_int32), ("L", C.c_int32), ("level", C.c_int32), ("K", C.c_int32),
+                ("K_in", C.c_int32), ("d", C.c_int32), ("e", C.c_int32),
+                ("radices", C.POINTER(C.c_int32)), ("dtype", C.c_int),
+                ("h_row_stride", C.c_int64)]
+
+
+def library_path():
+    return os.path.join(_HERE, "libnezha.so")
+
+
+def load_library():
+    """Loads the built library; builds it first only if no built library exists."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        from . import build as _build
+        _build.build()
+    lib = C.CDLL(path)
+    lib.nezha_last_error.restype = C.c_char_p
+    lib.nezha_verify_workspace.restype = C.c_size_t
+    lib.nezha_verify_workspace.argtypes = [C.c_int64]
+    lib.nezha_draft_step_workspace.restype = C.c_size_t
+    lib.nezha_draft_step_workspace.argtypes = [C.POINTER(_StepDesc)]
+    lib.nezha_build_itemset.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int,
+                                        C.c_double, C.c_void_p, C.POINTER(C.c_void_p)]
+    lib.nezha_itemset_info.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64),
+                                       C.POINTER(C.c_int32), C.c_void_p]
+    lib.nezha_free_itemset.argtypes = [C.c_void_p]
+    lib.nezha_verify_tuples.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                        C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.nezha_draft_step.argtypes = [C.POINTER(_StepDesc)] + [C.c_void_p] * 14 + [C.c_size_t,
+                                                                                  C.c_void_p]
+    lib.nezha_unpack_keys.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
+    _LIB = lib
+    return lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise NezhaError(rc, load_library().nezha_last_error().decode())
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _radices(radices):
+    arr = (C.c_int32 * len(radices))(*[int(r) for r in radices])
+    return arr
+
+
+class ItemSet:
+    """Owner of a device-resident nezha_itemset."""
+
+    def __init__(self, handle, L, radices):
+        self._h = handle
+        self.L = L
+        self.radices = list(radices)
+
+    def info(self):
+        n, slots, L = C.c_int64(), C.c_int64(), C.c_int32()
+        rad = (C.c_int32 * MAX_LEVELS)()
+        _check(load_library().nezha_itemset_info(self._h, C.byref(n), C.byref(slots), C.byref(L), rad))
+        return {"n_distinct": n.value, "n_slots": slots.value, "L": L.value,
+                "radices": list(rad[:L.value])}
+
+    def close(self):
+        if self._h is not None:
+            h, self._h = self._h, None
+            _check(load_library().nezha_free_itemset(h))
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def build_itemset(codes, radices, load_factor=0.5, stream=None):
+    """nezha_build_itemset.  codes: int32 [n, L], a CPU tensor / numpy array (host
+    pointer) or a CUDA tensor (device pointer)."""
+    lib = load_library()
+    if isinstance(codes, np.ndarray):
+        codes = torch.from_numpy(np.ascontiguousarray(codes, dtype=np.int32))
+    codes = codes.contiguous()
+    if codes.dtype != torch.int32 or codes.dim() != 2 or codes.shape[1] != len(radices):
+        raise ValueError("codes must be int32 [n, L]")
+    out = C.c_void_p()
+    rad = _radices(radices)
+    on_dev = 1 if codes.is_cuda else 0
+    s = _stream(stream) if torch.cuda.is_available() else None
+    _check(lib.nezha_build_itemset(_ptr(codes) if codes.numel() else None, codes.shape[0],
+                                   len(radices), rad, on_dev, float(load_factor), s,
+                                   C.byref(out)))
+    return ItemSet(out, len(radices), radices)
+
+
+def verify_workspace(n):
+    return int(load_library().nezha_verify_workspace(int(n)))
+
+
+def verify_tuples(itemset, codes, out_mask=None, out_index=None, out_count=None, workspace=None,
+                  want_index=True, stream=None):
+    """nezha_verify_tuples on a CUDA int32 [n, L] tensor.  Returns (mask uint8 [n],
+    index int64 [n] (first count entries valid), count int64 [1]); tensors are
+    allocated here unless given."""
+    n = codes.shape[0]
+    dev = codes.device
+    if out_mask is None:
+        out_mask = torch.empty(n, dtype=torch.uint8, device=dev)
+    if want_index and out_index is None:
+        out_index = torch.empty(n, dtype=torch.int64, device=dev)
+    if want_index and out_count is None:
+        out_count = torch.empty(1, dtype=torch.int64, device=dev)
+    if workspace is None:
+        workspace = torch.empty(max(16, verify_workspace(n)), dtype=torch.uint8, device=dev)
+    _check(load_library().nezha_verify_tuples(itemset._h, _ptr(codes), n, _ptr(out_mask),
+                                              _ptr(out_index), _ptr(out_count), _ptr(workspace),
+                                              workspace.numel(), _stream(stream)))
+    return out_mask, out_index, out_count
+
+
+def _desc(B, L, level, K, K_in, d, e, radices, dtype, h_row_stride):
+    rad = _radices(radices)
+    dsc = _StepDesc(B, L, level, K, K_in, d, e, C.cast(rad, C.POINTER(C.c_int32)),
+                    NEZHA_BF16 if dtype == torch.bfloat16 else NEZHA_F32, h_row_stride)
+    dsc._keep = rad
+    return dsc
+
+
+def draft_step_workspace(B, L, level, K, K_in, d, e, radices, dtype):
+    dsc = _desc(B, L, level, K, K_in, d, e, radices, dtype, d)
+    return int(load_library().nezha_draft_step_workspace(C.byref(dsc)))
+
+
+def draft_step(level, L, radices, K, H_l, W_l, E_l=None, state_in=None, key_in=None,
+               score_in=None, itemset=None, out=None, workspace=None, stream=None,
+               h_row_stride=None):
+    """nezha_draft_step for one level.  H_l [B, d] (a view with a row stride is
+    fine), W_l [(d+e), V], E_l [V, e]; state_in [B, K_in, e], key_in int64-as-uint64
+    [B, K_in], score_in float32 [B, K_in].  `out` may hold preallocated tensors
+    key, score, parent, code, state, count.  Returns that dict."""
+    B, d = H_l.shape
+    V = int(radices[level - 1])
+    e = W_l.shape[0] - d
+    dev, dt = H_l.device, H_l.dtype
+    if h_row_stride is None:
+        h_row_stride = H_l.stride(0) if B > 1 else d
+    K_in = 1 if key_in is None and state_in is None else (
+        state_in.shape[1] if state_in is not None else key_in.shape[1])
+    if out is None:
+        out = {}
+    out.setdefault("key", torch.empty((B, K), dtype=torch.int64, device=dev))
+    out.setdefault("score", torch.empty((B, K), dtype=torch.float32, device=dev))
+    out.setdefault("parent", torch.empty((B, K), dtype=torch.int32, device=dev))
+    out.setdefault("code", torch.empty((B, K), dtype=torch.int32, device=dev))
+    out.setdefault("count", torch.empty((B,), dtype=torch.int32, device=dev))
+    if level < L and "state" not in out:
+        out["state"] = torch.empty((B, K, e), dtype=dt, device=dev)
+    dsc = _desc(B, L, level, K, K_in, d, e, radices, dt, h_row_stride)
+    if workspace is None:
+        need = int(load_library().nezha_draft_step_workspace(C.byref(dsc)))
+        workspace = torch.empty(max(256, need), dtype=torch.uint8, device=dev)
+    _check(load_library().nezha_draft_step(
+        C.byref(dsc), _ptr(H_l), _ptr(W_l), _ptr(E_l), _ptr(state_in), _ptr(key_in),
+        _ptr(score_in), itemset._h if itemset is not None else None, _ptr(out["key"]),
+        _ptr(out["score"]), _ptr(out["parent"]), _ptr(out["code"]), _ptr(out.get("state")),
+        _ptr(out["count"]), _ptr(workspace), workspace.numel(), _stream(stream)))
+    return out
+
+
+class DraftBuffers:
+    """Preallocated outputs and workspace for a full L-level decode, so that the
+    timed loop allocates nothing."""
+
+    def __init__(self, B, L, K, d, e, radices, dtype, device):
+        self.outs = []
+        need = 256
+        for level in range(1, L + 1):
+            K_in = 1 if level == 1 else K
+            need = max(need, draft_step_workspace(B, L, level, K, K_in, d, e, radices, dtype))
+            o = {"key": torch.empty((B, K), dtype=torch.int64, device=device),
+                 "score": torch.empty((B, K), dtype=torch.float32, device=device),
+                 "parent": torch.empty((B, K), dtype=torch.int32, device=device),
+                 "code": torch.empty((B, K), dtype=torch.int32, device=device),
+                 "count": torch.empty((B,), dtype=torch.int32, device=device)}
+            if level < L:
+                o["state"] = torch.empty((B, K, e), dtype=dtype, device=device)
+            self.outs.append(o)
+        self.workspace = torch.empty(need, dtype=torch.uint8, device=device)
+
+
+def decode(H, W, E, radices, K, itemset=None, buffers=None, stream=None):
+    """All L levels of the inference loop of Alg. 3: L calls of nezha_draft_step on one
+    stream, each level's outputs feeding the next.  H [B, L, d]; W, E lists per level."""
+    L = len(W)
+    B, _, d = H.shape
+    e = W[0].shape[0] - d
+    if buffers is None:
+        buffers = DraftBuffers(B, L, K, d, e, radices, H.dtype, H.device)
+    state = key = score = None
+    for level in range(1, L + 1):
+        o = draft_step(level, L, radices, K, H[:, level - 1, :], W[level - 1],
+                       E[level - 1] if level < L else None, state, key, score,
+                       itemset if level == L else None, out=buffers.outs[level - 1],
+                       workspace=buffers.workspace, stream=stream, h_row_stride=H.stride(0))
+        state, key, score = o.get("state"), o["key"], o["score"]
+    return buffers.outs
+
+
+def unpack_keys(keys, radices):
+    """Inverse of Eq. 4 on the host (nezha_unpack_keys): uint64/int64 [n] -> int32 [n, L]."""
+    k = np.ascontiguousarray(np.asarray(keys).astype(np.uint64, copy=False).ravel())
+    out = np.empty((k.size, len(radices)), dtype=np.int32)
+    rad = _radices(radices)
+    _check(load_library().nezha_unpack_keys(k.ctypes.data_as(C.c_void_p), k.size, len(radices),
+                                            rad, out.ctypes.data_as(C.c_void_p)))
+    return out

@@ -1,0 +1,40 @@
+"""Compile the HIP sources into paper_2511_18793_amd/libnezha.so for gfx950."""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+SOURCES = [os.path.join(HERE, "csrc", f) for f in ("itemset.hip", "draft.hip")]
+HEADERS = [os.path.join(HERE, "csrc", "nezha_internal.h"), os.path.join(ROOT, "include", "nezha.h")]
+OUT = os.path.join(HERE, "libnezha.so")
+
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+         "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(HERE, "csrc"),
+         # packed fp32 instructions off: hipcc must not form v_pk_*_f32 from float code
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Wall", "-Wno-unused-command-line-argument"]
+
+
+def is_stale():
+    if not os.path.exists(OUT):
+        return True
+    t = os.path.getmtime(OUT)
+    return any(os.path.getmtime(f) > t for f in SOURCES + HEADERS)
+
+
+def build(verbose=False):
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc] + FLAGS + SOURCES + ["-o", OUT]
+    if verbose:
+        print(" ".join(cmd))
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + err)
+    if verbose and err.strip():
+        print(err)
+    return OUT
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

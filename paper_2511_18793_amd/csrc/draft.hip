@@ -1,0 +1,853 @@
+// One level of the draft head's beam search (Alg. 3, inference loop body; Eq. 2-3) with the
+// last level's hash-set verification (Eq. 4-5) for a batch of requests.
+//
+// Kernels, in launch order:
+//   pack_weights_kernel  W_l (bf16, row major) -> MFMA operand order (bf16 workloads only)
+//   user_gemm_*          A_l = H_l * W_l[0:d]              (the beam-independent part of Eq. 2)
+//   expand_kernel        per beam: z = A_l + c * W_l[d:d+e] by MFMA, online log-sum-exp and
+//                        streaming top-K of the codes; logits never leave the registers
+//   merge_kernel         per request: cumulative scores, Eq. 4 indices, Eq. 5 probes, the K
+//                        best surviving candidates, and the additive Transition of Eq. 3
+#include "nezha_internal.h"
+
+namespace nezha {
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ float bf16_to_float(uint16_t h) {
+  return __uint_as_float((uint32_t)h << 16);
+}
+__device__ __forceinline__ uint16_t float_to_bf16(float f) {  // round to nearest even
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+// Order-preserving map float -> uint32 (larger float <=> larger integer) and back.
+__device__ __forceinline__ uint32_t ordered_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  return u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
+}
+__device__ __forceinline__ float unordered_bits(uint32_t o) {
+  uint32_t u = (o & 0x80000000u) ? (o ^ 0x80000000u) : ~o;
+  return __uint_as_float(u);
+}
+
+// ---- cross-lane helpers (wave64) ---------------------------------------------------------
+// Orders this wave's LDS traffic: the hardware runs one wave's LDS instructions in issue
+// order, so only the compiler has to be kept from moving accesses across this point.
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+}
+__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int lane_mask) {
+  const int addr = ((int)(threadIdx.x & 63) ^ lane_mask) << 2;
+  uint32_t lo = (uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int)(uint32_t)v);
+  uint32_t hi = (uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int)(uint32_t)(v >> 32));
+  return ((uint64_t)hi << 32) | lo;
+}
+
+// Bitonic sort of 64*NPL keys held NPL per lane, descending in position p = lane*NPL + j.
+template <int NPL>
+__device__ __forceinline__ void sort_desc(uint64_t (&key)[NPL]) {
+  const int lane = threadIdx.x & 63;
+  constexpr int N = 64 * NPL;
+#pragma unroll
+  for (int k = 2; k <= N; k <<= 1) {
+#pragma unroll
+    for (int dist = k >> 1; dist >= 1; dist >>= 1) {
+      if (dist < NPL) {
+#pragma unroll
+        for (int j = 0; j < NPL; ++j) {
+          if ((j & dist) == 0) {
+            const int j2 = j | dist;
+            // block direction: descending where bit k of the position is clear
+            const bool desc = (k < NPL) ? ((j & k) == 0)
+                                        : (k == N ? true : ((lane & (k / NPL)) == 0));
+            const uint64_t a = key[j], b = key[j2];
+            const bool a_gt = a > b;
+            const bool swap = desc ? !a_gt : a_gt;
+            key[j] = swap ? b : a;
+            key[j2] = swap ? a : b;
+          }
+        }
+      } else {
+        const int lm = dist / NPL;
+        const bool is_lo = (lane & lm) == 0;
+        const bool desc = (k == N) ? true : ((lane & (k / NPL)) == 0);
+        const bool keep_max = (is_lo == desc);
+#pragma unroll
+        for (int j = 0; j < NPL; ++j) {
+          const uint64_t other = shfl_xor_u64(key[j], lm);
+          const bool gt = key[j] > other;
+          key[j] = (gt == keep_max) ? key[j] : other;
+        }
+      }
+    }
+  }
+}
+
+// A streaming top-K of 64-bit keys for one wave.  The buffer lives in LDS (CAP keys); keys
+// that beat the threshold are appended with a ballot prefix; when fewer than 64 free places
+// remain the buffer is sorted and cut back to the K largest, which raises the threshold.
+template <int CAP>
+struct WaveTopK {
+  uint64_t* buf;   // LDS, CAP entries, private to the wave
+  int cnt;         // wave uniform
+  uint64_t tau;    // keys must be > tau to enter; wave uniform
+  int K;
+
+  __device__ __forceinline__ void init(uint64_t* b, int k) {
+    buf = b;
+    cnt = 0;
+    tau = 0;
+    K = k;
+  }
+  // Sort, keep the K largest at buf[0..), update tau.
+  __device__ __forceinline__ void compact() {
+    constexpr int NPL = CAP / 64;
+    const int lane = threadIdx.x & 63;
+    uint64_t key[NPL];
+    wave_sync();
+#pragma unroll
+    for (int j = 0; j < NPL; ++j) {
+      const int e = j * 64 + lane;
+      key[j] = e < cnt ? buf[e] : 0ull;
+    }
+    sort_desc<NPL>(key);
+    wave_sync();
+    const int keep = cnt < K ? cnt : K;
+#pragma unroll
+    for (int j = 0; j < NPL; ++j) {
+      const int p = lane * NPL + j;
+      if (p < keep) buf[p] = key[j];
+    }
+    wave_sync();
+    cnt = keep;
+    tau = (keep == K) ? buf[K - 1] : 0ull;
+  }
+  // One key per lane (0 = nothing).  All lanes of the wave must call this together.
+  __device__ __forceinline__ void push(uint64_t key) {
+    const bool pass = key > tau;
+    const uint64_t bal = __ballot(pass);
+    if (bal) {
+      const int pos = cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32),
+                                                      __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0));
+      if (pass) buf[pos] = key;
+      cnt += __popcll(bal);
+      if (cnt > CAP - 64) compact();
+    }
+  }
+};
+
+// ---- weight packing -------------------------------------------------------------------------
+// Wp[((ct*KS + ks)*64 + lane)*8 + j] = W[ks*32 + 8*(lane/16) + j][ct*16 + lane%16]
+// i.e. for every 16-column tile ct and 32-row step ks, the 64 lanes' B operands of
+// v_mfma_f32_16x16x32_bf16 lie in one contiguous 1 KiB block.
+__global__ __launch_bounds__(256) void pack_weights_kernel(const uint16_t* __restrict__ W,
+                                                           uint16_t* __restrict__ Wp, int rows,
+                                                           int V) {
+  const int KS = rows / 32;
+  const int64_t total = (int64_t)(V / 16) * KS * 64;
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int lane = (int)(idx & 63);
+  const int64_t blk = idx >> 6;
+  const int ks = (int)(blk % KS);
+  const int ct = (int)(blk / KS);
+  const int col = ct * 16 + (lane & 15);
+  const int k0 = ks * 32 + 8 * (lane >> 4);
+  uint16_t v[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) v[j] = W[(int64_t)(k0 + j) * V + col];
+  uint4 out;
+  out.x = v[0] | ((uint32_t)v[1] << 16);
+  out.y = v[2] | ((uint32_t)v[3] << 16);
+  out.z = v[4] | ((uint32_t)v[5] << 16);
+  out.w = v[6] | ((uint32_t)v[7] << 16);
+  reinterpret_cast<uint4*>(Wp)[idx] = out;
+}
+
+// ---- user-part projection, bf16: A[B,V] = H[B,d] * W[0:d, V] -----------------------------
+// Workgroup = 4 waves in a 2x2 grid, each wave TM x TN tiles of 16x16 (v_mfma_f32_16x16x32_bf16).
+// H is staged through LDS in operand order; W comes packed and is copied to LDS as is.
+template <int TM, int TN>
+__global__ __launch_bounds__(256) void user_gemm_bf16_kernel(
+    const uint16_t* __restrict__ H, int64_t h_stride, const uint16_t* __restrict__ Wp,
+    float* __restrict__ A, int B, int d, int V, int KS_total) {
+  constexpr int BM = 2 * TM * 16, BN = 2 * TN * 16;
+  constexpr int RT = BM / 16, CT = BN / 16;       // 16-row / 16-col tiles per workgroup
+  __shared__ uint4 sA[2][RT * 64];                // [row tile][lane] 16 B = one operand each
+  __shared__ uint4 sB[2][CT * 64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int row0 = blockIdx.y * BM, ct0 = blockIdx.x * CT;
+  const int KS = d / 32;
+  const int n_ct = V / 16;
+
+  floatx4 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  constexpr int A_PER_THREAD = (RT * 64 + 255) / 256;
+  constexpr int B_PER_THREAD = (CT * 64 + 255) / 256;
+  uint4 ra[A_PER_THREAD], rb[B_PER_THREAD];
+
+  auto load_global = [&](int ks) {
+#pragma unroll
+    for (int u = 0; u < A_PER_THREAD; ++u) {
+      const int o = tid + u * 256;                 // operand slot: row tile * 64 + lane
+      ra[u] = uint4{0, 0, 0, 0};
+      if (o < RT * 64) {
+        const int rt = o >> 6, l = o & 63;
+        const int row = row0 + rt * 16 + (l & 15);
+        if (row < B)
+          ra[u] = *reinterpret_cast<const uint4*>(H + (int64_t)row * h_stride + ks * 32 +
+                                                  8 * (l >> 4));
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < B_PER_THREAD; ++u) {
+      const int o = tid + u * 256;
+      rb[u] = uint4{0, 0, 0, 0};
+      if (o < CT * 64) {
+        const int ct = ct0 + (o >> 6);
+        if (ct < n_ct)
+          rb[u] = reinterpret_cast<const uint4*>(Wp)[((int64_t)ct * KS_total + ks) * 64 + (o & 63)];
+      }
+    }
+  };
+  auto store_lds = [&](int buf) {
+#pragma unroll
+    for (int u = 0; u < A_PER_THREAD; ++u)
+      if (tid + u * 256 < RT * 64) sA[buf][tid + u * 256] = ra[u];
+#pragma unroll
+    for (int u = 0; u < B_PER_THREAD; ++u)
+      if (tid + u * 256 < CT * 64) sB[buf][tid + u * 256] = rb[u];
+  };
+
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+  for (int ks = 0; ks < KS; ++ks) {
+    const int cur = ks & 1;
+    if (ks + 1 < KS) load_global(ks + 1);
+    bf16x8 fa[TM], fb[TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+      fa[i] = *reinterpret_cast<const bf16x8*>(&sA[cur][(wm * TM + i) * 64 + lane]);
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+      fb[j] = *reinterpret_cast<const bf16x8*>(&sB[cur][(wn * TN + j) * 64 + lane]);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    if (ks + 1 < KS) {
+      store_lds(cur ^ 1);
+      __syncthreads();
+    }
+  }
+  // result layout of the 16x16 MFMA: register i of lane l is row 4*(l/16)+i, column l%16
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int ct = ct0 + wn * TN + j;
+      if (ct >= n_ct) continue;
+      const int col = ct * 16 + (lane & 15);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int row = row0 + (wm * TM + i) * 16 + 4 * (lane >> 4) + r;
+        if (row < B) A[(int64_t)row * V + col] = acc[i][j][r];
+      }
+    }
+}
+
+// ---- user-part projection, fp32 (small correctness-first shapes) -----------------------------
+__global__ __launch_bounds__(256) void user_gemm_f32_kernel(const float* __restrict__ H,
+                                                            int64_t h_stride,
+                                                            const float* __restrict__ W,
+                                                            float* __restrict__ A, int B, int d,
+                                                            int V) {
+  const int v = blockIdx.x * blockDim.x + threadIdx.x;
+  const int b = blockIdx.y;
+  if (v >= V || b >= B) return;
+  const float* h = H + (int64_t)b * h_stride;
+  float s = 0.f;
+  for (int i = 0; i < d; ++i) s = fmaf(h[i], W[(int64_t)i * V + v], s);
+  A[(int64_t)b * V + v] = s;
+}
+
+// ---- beam-part projection + log-softmax + per-beam top-K --------------------------------------
+struct ExpandArgs {
+  const void* state;     // [rows, e] or NULL (level 1: the state is zero)
+  const void* Wbeam;     // bf16: packed W (whole matrix); f32: row-major W (whole matrix)
+  const float* A;        // [B, V] user part
+  int32_t* cand_code;    // [rows, K]
+  float* cand_logp;      // [rows, K]
+  int rows;              // B * K_in
+  int K_in, K, V, d, e;
+  int KS_total;          // bf16: (d+e)/32
+};
+
+// One wave per workgroup, 16 beams (rows) per wave.  For each block of 64 codes the wave forms
+// the 16x64 logits in four 16x16 MFMA accumulators (initialised with the user part), updates
+// every row's running (max, sum of exponentials) and appends the logits above the row's
+// current threshold to the row's LDS buffer.  Buffers are cut back to the K best by a
+// sort when they run short of room, which raises the threshold.  Register i of lane l
+// belongs to row 4*(l/16)+i and code column l%16 of the tile.
+template <bool BF16, int CAP>
+__global__ __launch_bounds__(64) void expand_kernel(ExpandArgs a) {
+  extern __shared__ __align__(16) uint64_t lds[];
+  uint64_t* buf = lds;                                   // [16][CAP]
+  float* row_lse = reinterpret_cast<float*>(lds + 16 * CAP);   // [16]
+  int* row_cnt = reinterpret_cast<int*>(row_lse + 16);          // [16]
+
+  const int lane = threadIdx.x, g = lane >> 4, c = lane & 15;
+  const int R0 = blockIdx.x * 16;
+  const int V = a.V, K = a.K, e = a.e;
+  const bool has_beam = a.state != nullptr;
+  constexpr int KSMAX = BF16 ? 8 : 64;
+  const int KS = BF16 ? e / 32 : e / 4;
+
+  // A operands of the MFMA: this lane's row is R0 + c
+  bf16x8 fa16[BF16 ? KSMAX : 1];
+  float fa32[BF16 ? 1 : KSMAX];
+  if (has_beam) {
+    const int row = R0 + c;
+    if constexpr (BF16) {
+      const uint16_t* st = static_cast<const uint16_t*>(a.state);
+#pragma unroll
+      for (int ks = 0; ks < KSMAX; ++ks) {
+        uint4 v = uint4{0, 0, 0, 0};
+        if (ks < KS && row < a.rows)
+          v = *reinterpret_cast<const uint4*>(st + (int64_t)row * e + ks * 32 + 8 * g);
+        fa16[ks] = *reinterpret_cast<bf16x8*>(&v);
+      }
+    } else {
+      const float* st = static_cast<const float*>(a.state);
+#pragma unroll
+      for (int ks = 0; ks < KSMAX; ++ks)
+        fa32[ks] = (ks < KS && row < a.rows) ? st[(int64_t)row * e + ks * 4 + g] : 0.f;
+    }
+  }
+
+  // per-row state, replicated over the 16 lanes of a group: rows 4g+i
+  float tau[4], m[4], s[4];
+  int cnt[4];
+  int64_t a_off[4];
+  bool row_ok[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = R0 + 4 * g + i;
+    row_ok[i] = row < a.rows;
+    tau[i] = row_ok[i] ? -INFINITY : INFINITY;
+    m[i] = -INFINITY;
+    s[i] = 0.f;
+    cnt[i] = 0;
+    a_off[i] = (int64_t)((row_ok[i] ? row : 0) / a.K_in) * V;
+  }
+  const int lim = CAP - 64;
+  const int n_ct = V / 16;
+
+  for (int ct0 = 0; ct0 < n_ct; ct0 += 4) {
+    floatx4 acc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int ct = ct0 + t;
+      if (ct < n_ct) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[t][i] = a.A[a_off[i] + ct * 16 + c];
+      } else {
+        acc[t] = floatx4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+      }
+    }
+    if (has_beam) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int ct = ct0 + t;
+        if (ct < n_ct) {
+          if constexpr (BF16) {
+            const uint4* wp = static_cast<const uint4*>(a.Wbeam) +
+                              ((int64_t)ct * a.KS_total + a.d / 32) * 64 + lane;
+#pragma unroll
+            for (int ks = 0; ks < KSMAX; ++ks) {
+              if (ks < KS) {
+                uint4 v = wp[ks * 64];
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                    fa16[ks], *reinterpret_cast<bf16x8*>(&v), acc[t], 0, 0, 0);
+              }
+            }
+          } else {
+            const float* w = static_cast<const float*>(a.Wbeam) + (int64_t)a.d * V + ct * 16 + c;
+#pragma unroll
+            for (int ks = 0; ks < KSMAX; ++ks) {
+              if (ks < KS) {
+                const float bv = w[(int64_t)(ks * 4 + g) * V];
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa32[ks], bv, acc[t], 0, 0, 0);
+              }
+            }
+          }
+        }
+      }
+    }
+    // running log-sum-exp, one (max, sum) pair per lane and row
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float mx = fmaxf(fmaxf(acc[0][i], acc[1][i]), fmaxf(acc[2][i], acc[3][i]));
+      const float mn = fmaxf(m[i], mx);
+      float sum = s[i] * __builtin_amdgcn_exp2f((m[i] - mn) * kLog2e);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) sum += __builtin_amdgcn_exp2f((acc[t][i] - mn) * kLog2e);
+      s[i] = sum;
+      m[i] = mn;
+    }
+    // threshold filter and append
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float z = acc[t][i];
+        const bool pass = z > tau[i];
+        const uint64_t bal = __ballot(pass);
+        if (bal) {
+          const uint32_t grp = (uint32_t)(bal >> (16 * g)) & 0xFFFFu;
+          const int pos = cnt[i] + __popc(grp & ((1u << c) - 1u));
+          if (pass) {
+            const uint32_t code = (uint32_t)((ct0 + t) * 16 + c);
+            buf[(4 * g + i) * CAP + pos] = ((uint64_t)ordered_bits(z) << 32) | (uint32_t)~code;
+          }
+          cnt[i] += __popc(grp);
+        }
+      }
+    }
+    // rows that could overflow on the next block of 64 codes are cut back to their K best
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint64_t fb = __ballot(cnt[i] > lim);
+      while (fb) {
+        const int l0 = __builtin_ctzll(fb);
+        const int gg = l0 >> 4;
+        fb &= ~(0xFFFFull << (16 * gg));
+        WaveTopK<CAP> q;
+        q.buf = buf + (4 * gg + i) * CAP;
+        q.cnt = __builtin_amdgcn_readlane(cnt[i], l0);
+        q.K = K;
+        q.tau = 0;
+        q.compact();
+        if (g == gg) {
+          cnt[i] = q.cnt;
+          tau[i] = (q.cnt == K) ? unordered_bits((uint32_t)(q.tau >> 32)) : -INFINITY;
+        }
+      }
+    }
+  }
+
+  // log-sum-exp of each row: merge the 16 lanes' (max, sum) pairs of every group
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    float mm = m[i], ss = s[i];
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) {
+      const float om = __shfl_xor(mm, off);
+      const float os = __shfl_xor(ss, off);
+      const float mn = fmaxf(mm, om);
+      ss = ss * __builtin_amdgcn_exp2f((mm - mn) * kLog2e) +
+           os * __builtin_amdgcn_exp2f((om - mn) * kLog2e);
+      mm = mn;
+    }
+    if (c == 0) {
+      row_lse[4 * g + i] = mm + __builtin_amdgcn_logf(ss) * kLn2;
+      row_cnt[4 * g + i] = cnt[i];
+    }
+  }
+  __syncthreads();
+  constexpr int NPL = CAP / 64;
+  for (int r = 0; r < 16; ++r) {
+    const int row = R0 + r;
+    if (row >= a.rows) break;
+    WaveTopK<CAP> q;
+    q.buf = buf + r * CAP;
+    q.cnt = row_cnt[r];
+    q.K = K;
+    q.tau = 0;
+    q.compact();
+    const float lse = row_lse[r];
+#pragma unroll
+    for (int j = 0; j < NPL; ++j) {
+      const int p = lane * NPL + j;   // compact() left the sorted keys at buf[0..K)
+      if (p < q.cnt) {
+        const uint64_t key = q.buf[p];
+        a.cand_code[(int64_t)row * K + p] = (int32_t)(~(uint32_t)key);
+        a.cand_logp[(int64_t)row * K + p] = unordered_bits((uint32_t)(key >> 32)) - lse;
+      }
+    }
+  }
+}
+
+// ---- per-request merge, verification, pruning and state update ---------------------------------
+struct MergeArgs {
+  const int32_t* cand_code;
+  const float* cand_logp;
+  const uint64_t* key_in;   // [B, K_in] or NULL
+  const float* score_in;    // [B, K_in] or NULL
+  const void* state_in;     // [B, K_in, e] or NULL
+  const void* E;            // [V, e] (used when state_out != NULL)
+  SetView set;              // slots == NULL: no verification
+  uint64_t mult;            // prod_{j<level} T_j
+  uint64_t* key_out;
+  float* score_out;
+  int32_t* parent_out;
+  int32_t* code_out;
+  void* state_out;          // or NULL
+  int32_t* count_out;       // or NULL
+  int K_in, K, e;
+};
+
+// One workgroup (4 waves) per request.  Every candidate (parent p, within-beam rank r) gets the
+// sort key (ordered score, ~(p*K+r)), or 0 if the verifier rejects it; each wave keeps the K
+// largest keys of its share of the candidates, then wave 0 merges the four lists.
+template <bool BF16, int CAP>
+__global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
+  __shared__ uint64_t wbuf[5][CAP];
+  __shared__ int wcnt[4];
+  __shared__ int32_t fin_parent[NEZHA_MAX_BEAM], fin_code[NEZHA_MAX_BEAM];
+  __shared__ int fin_count;
+  const int b = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int K = a.K, K_in = a.K_in;
+  const int n_c = K_in * K;
+  const bool verify = a.set.slots != nullptr;
+
+  WaveTopK<CAP> q;
+  q.init(wbuf[wave], K);
+  for (int base = wave * 64; base < n_c; base += 256) {   // wave uniform trip count
+    const int i = base + lane;
+    uint64_t sk = 0;
+    if (i < n_c) {
+      const int p = i / K;
+      const int64_t o = (int64_t)(b * K_in + p) * K + (i - p * K);
+      const float score = (a.score_in ? a.score_in[b * K_in + p] : 0.f) + a.cand_logp[o];
+      bool ok = true;
+      if (verify) {
+        const uint64_t key = (a.key_in ? a.key_in[b * K_in + p] : 0ull) +
+                             (uint64_t)(uint32_t)a.cand_code[o] * a.mult;
+        ok = set_contains(a.set, key);
+      }
+      if (ok) sk = ((uint64_t)ordered_bits(score) << 32) | (uint32_t)~(uint32_t)i;
+    }
+    q.push(sk);
+  }
+  q.compact();
+  if (lane == 0) wcnt[wave] = q.cnt;
+  __syncthreads();
+  if (wave == 0) {
+    WaveTopK<CAP> f;
+    f.init(wbuf[4], K);
+    for (int w = 0; w < 4; ++w) {
+      const int n = wcnt[w];
+      for (int base = 0; base < n; base += 64)
+        f.push(base + lane < n ? wbuf[w][base + lane] : 0ull);
+    }
+    f.compact();
+    constexpr int NPL = (NEZHA_MAX_BEAM + 63) / 64;
+#pragma unroll
+    for (int j = 0; j < NPL; ++j) {
+      const int p = lane + 64 * j;
+      if (p < K) {
+        const int64_t o = (int64_t)b * K + p;
+        if (p < f.cnt) {
+          const uint64_t sk = f.buf[p];
+          const int i = (int)(~(uint32_t)sk);
+          const int par = i / K;
+          const int32_t code = a.cand_code[(int64_t)(b * K_in + par) * K + (i - par * K)];
+          a.key_out[o] = (a.key_in ? a.key_in[b * K_in + par] : 0ull) +
+                         (uint64_t)(uint32_t)code * a.mult;
+          a.score_out[o] = unordered_bits((uint32_t)(sk >> 32));
+          a.parent_out[o] = par;
+          a.code_out[o] = code;
+          fin_parent[p] = par;
+          fin_code[p] = code;
+        } else {
+          a.key_out[o] = kEmpty;
+          a.score_out[o] = -INFINITY;
+          a.parent_out[o] = -1;
+          a.code_out[o] = -1;
+          fin_parent[p] = -1;
+          fin_code[p] = -1;
+        }
+      }
+    }
+    if (lane == 0) {
+      fin_count = f.cnt;
+      if (a.count_out) a.count_out[b] = f.cnt;
+    }
+  }
+  __syncthreads();
+  if (a.state_out) {
+    // Eq. 3, additive Transition: c' = c_parent + E[code]; 8 elements per thread and step
+    const int e = a.e, per = e / (BF16 ? 8 : 4);
+    for (int idx = tid; idx < K * per; idx += 256) {
+      const int j = idx / per, t = idx - j * per;
+      const int par = fin_parent[j], code = fin_code[j];
+      if constexpr (BF16) {
+        uint16_t* out = static_cast<uint16_t*>(a.state_out) + ((int64_t)b * K + j) * e + t * 8;
+        uint4 r = uint4{0, 0, 0, 0};
+        if (par >= 0) {
+          const uint4 ev = *reinterpret_cast<const uint4*>(
+              static_cast<const uint16_t*>(a.E) + (int64_t)code * e + t * 8);
+          uint4 sv = uint4{0, 0, 0, 0};
+          if (a.state_in)
+            sv = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(a.state_in) +
+                                                 ((int64_t)b * K_in + par) * e + t * 8);
+          const uint32_t ew[4] = {ev.x, ev.y, ev.z, ev.w}, sw[4] = {sv.x, sv.y, sv.z, sv.w};
+          uint32_t ow[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const float lo = bf16_to_float((uint16_t)ew[u]) + bf16_to_float((uint16_t)sw[u]);
+            const float hi = bf16_to_float((uint16_t)(ew[u] >> 16)) +
+                             bf16_to_float((uint16_t)(sw[u] >> 16));
+            ow[u] = (uint32_t)float_to_bf16(lo) | ((uint32_t)float_to_bf16(hi) << 16);
+          }
+          r = uint4{ow[0], ow[1], ow[2], ow[3]};
+        }
+        *reinterpret_cast<uint4*>(out) = r;
+      } else {
+        float* out = static_cast<float*>(a.state_out) + ((int64_t)b * K + j) * e + t * 4;
+        float4 r = float4{0.f, 0.f, 0.f, 0.f};
+        if (par >= 0) {
+          const float4 ev = *reinterpret_cast<const float4*>(static_cast<const float*>(a.E) +
+                                                             (int64_t)code * e + t * 4);
+          float4 sv = float4{0.f, 0.f, 0.f, 0.f};
+          if (a.state_in)
+            sv = *reinterpret_cast<const float4*>(static_cast<const float*>(a.state_in) +
+                                                  ((int64_t)b * K_in + par) * e + t * 4);
+          r = float4{ev.x + sv.x, ev.y + sv.y, ev.z + sv.z, ev.w + sv.w};
+        }
+        *reinterpret_cast<float4*>(out) = r;
+      }
+    }
+  }
+}
+
+// ---- host side ---------------------------------------------------------------------------------
+struct Plan {
+  size_t wp_off, a_off, code_off, logp_off, total;
+  int cap;
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int check_desc(const nezha_step_desc* dsc, Plan* plan) {
+  if (!dsc) return fail(NEZHA_EINVAL, "desc is NULL");
+  if (dsc->B < 0) return fail(NEZHA_EINVAL, "B = %d is negative", dsc->B);
+  if (dsc->L < 1 || dsc->L > NEZHA_MAX_LEVELS)
+    return fail(NEZHA_EINVAL, "L = %d outside 1..%d", dsc->L, NEZHA_MAX_LEVELS);
+  if (dsc->level < 1 || dsc->level > dsc->L)
+    return fail(NEZHA_EINVAL, "level = %d outside 1..L = %d", dsc->level, dsc->L);
+  if (!dsc->radices) return fail(NEZHA_EINVAL, "radices is NULL");
+  uint64_t mult[NEZHA_MAX_LEVELS];
+  if (!radix_multipliers(dsc->L, dsc->radices, mult))
+    return fail(NEZHA_ERANGE, "radices must be >= 1 with a product of at most 2^64-1");
+  const int V = dsc->radices[dsc->level - 1];
+  if (dsc->K < 1 || dsc->K > NEZHA_MAX_BEAM || dsc->K > V)
+    return fail(NEZHA_EINVAL, "K = %d outside 1..min(T_level = %d, %d)", dsc->K, V, NEZHA_MAX_BEAM);
+  if (dsc->K_in < 1 || dsc->K_in > NEZHA_MAX_BEAM)
+    return fail(NEZHA_EINVAL, "K_in = %d outside 1..%d", dsc->K_in, NEZHA_MAX_BEAM);
+  if (dsc->dtype != NEZHA_F32 && dsc->dtype != NEZHA_BF16)
+    return fail(NEZHA_EINVAL, "unknown dtype %d", (int)dsc->dtype);
+  if (V % 16 != 0) return fail(NEZHA_EINVAL, "T_level = %d is not a multiple of 16", V);
+  const bool bf16 = dsc->dtype == NEZHA_BF16;
+  if (dsc->d < 1 || (bf16 && dsc->d % 32 != 0))
+    return fail(NEZHA_EINVAL, "d = %d must be >= 1 (a multiple of 32 for bf16)", dsc->d);
+  if (dsc->e < 1 || dsc->e > 256 || dsc->e % (bf16 ? 32 : 4) != 0)
+    return fail(NEZHA_EINVAL, "e = %d must be a multiple of %d in 1..256", dsc->e, bf16 ? 32 : 4);
+  if (dsc->h_row_stride < dsc->d || (bf16 && dsc->h_row_stride % 8 != 0))
+    return fail(NEZHA_EINVAL, "h_row_stride = %lld must be >= d (a multiple of 8 for bf16)",
+                (long long)dsc->h_row_stride);
+  if ((int64_t)dsc->B * dsc->K_in > 0x7FFFFFFF / NEZHA_MAX_BEAM)
+    return fail(NEZHA_EINVAL, "B * K_in too large");
+  if (plan) {
+    const size_t rows = (size_t)dsc->B * dsc->K_in;
+    size_t off = 0;
+    plan->wp_off = off;
+    if (bf16) off += align_up((size_t)(dsc->d + dsc->e) * V * 2, 256);
+    plan->a_off = off;
+    off += align_up((size_t)dsc->B * V * 4, 256);
+    plan->code_off = off;
+    off += align_up(rows * dsc->K * 4, 256);
+    plan->logp_off = off;
+    off += align_up(rows * dsc->K * 4, 256);
+    plan->total = off < 256 ? 256 : off;
+    plan->cap = dsc->K <= 32 ? 128 : 256;
+  }
+  return NEZHA_OK;
+}
+
+template <typename Kern>
+int allow_lds(Kern kern, size_t bytes) {
+  if (bytes > 64 * 1024) {
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (err != hipSuccess)
+      return fail(NEZHA_EHIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(err));
+  }
+  return NEZHA_OK;
+}
+
+}  // namespace
+}  // namespace nezha
+
+using namespace nezha;
+
+extern "C" {
+
+size_t nezha_draft_step_workspace(const nezha_step_desc* desc) {
+  Plan p;
+  if (check_desc(desc, &p) != NEZHA_OK) return 0;
+  return p.total;
+}
+
+int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W_l,
+                     const void* E_l, const void* state_in, const uint64_t* key_in,
+                     const float* score_in, const nezha_itemset* set, uint64_t* key_out,
+                     float* score_out, int32_t* parent_out, int32_t* code_out,
+                     void* state_out, int32_t* count_out, void* workspace,
+                     size_t workspace_bytes, void* hip_stream) {
+  Plan plan;
+  int rc = check_desc(desc, &plan);
+  if (rc != NEZHA_OK) return rc;
+  const int B = desc->B, K = desc->K, K_in = desc->K_in, d = desc->d, e = desc->e;
+  const int level = desc->level, L = desc->L;
+  const int V = desc->radices[level - 1];
+  const bool bf16 = desc->dtype == NEZHA_BF16;
+  if (!H_l || !W_l) return fail(NEZHA_EINVAL, "H_l or W_l is NULL");
+  if (!key_out || !score_out || !parent_out || !code_out)
+    return fail(NEZHA_EINVAL, "an output pointer is NULL");
+  if (level < L && !state_out) return fail(NEZHA_EINVAL, "state_out is NULL below the last level");
+  if (state_out && !E_l) return fail(NEZHA_EINVAL, "E_l is NULL but state_out is wanted");
+  if (!workspace) return fail(NEZHA_EINVAL, "workspace is NULL");
+  if (workspace_bytes < plan.total)
+    return fail(NEZHA_EINVAL, "workspace has %zu bytes, %zu needed", workspace_bytes, plan.total);
+  if (reinterpret_cast<uintptr_t>(workspace) & 255)
+    return fail(NEZHA_EINVAL, "workspace is not 256-byte aligned");
+  const uintptr_t align_mask = 15;
+  if ((reinterpret_cast<uintptr_t>(H_l) | reinterpret_cast<uintptr_t>(W_l) |
+       reinterpret_cast<uintptr_t>(E_l) | reinterpret_cast<uintptr_t>(state_in) |
+       reinterpret_cast<uintptr_t>(state_out)) & align_mask)
+    return fail(NEZHA_EINVAL, "H_l, W_l, E_l and the states must be 16-byte aligned");
+  if (set) {
+    if (set->magic != kSetMagic) return fail(NEZHA_EINVAL, "not an item set");
+    if (set->L != L) return fail(NEZHA_EINVAL, "item set has L = %d, desc has %d", set->L, L);
+    for (int l = 0; l < L; ++l)
+      if (set->radices[l] != desc->radices[l])
+        return fail(NEZHA_EINVAL, "item set and desc disagree on radix %d", l + 1);
+  }
+  if (B == 0) return NEZHA_OK;
+  uint64_t mult[NEZHA_MAX_LEVELS];
+  radix_multipliers(L, desc->radices, mult);
+
+  hipStream_t stream = (hipStream_t)hip_stream;
+  char* ws = static_cast<char*>(workspace);
+  uint16_t* Wp = reinterpret_cast<uint16_t*>(ws + plan.wp_off);
+  float* A = reinterpret_cast<float*>(ws + plan.a_off);
+  int32_t* cand_code = reinterpret_cast<int32_t*>(ws + plan.code_off);
+  float* cand_logp = reinterpret_cast<float*>(ws + plan.logp_off);
+  const int rows = B * K_in;
+  const int KS_total = (d + e) / 32;
+
+  if (bf16) {
+    const int64_t total = (int64_t)(V / 16) * KS_total * 64;
+    hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
+                       stream, static_cast<const uint16_t*>(W_l), Wp, d + e, V);
+    NEZHA_HIP_CHECK(hipGetLastError());
+    const bool big = (int64_t)B * V >= (int64_t)128 * 128 * 256;
+    if (big) {
+      dim3 grid((V + 127) / 128, (B + 127) / 128);
+      hipLaunchKernelGGL((user_gemm_bf16_kernel<4, 4>), grid, dim3(256), 0, stream,
+                         static_cast<const uint16_t*>(H_l), desc->h_row_stride,
+                         (const uint16_t*)Wp, A, B, d, V, KS_total);
+    } else {
+      dim3 grid((V + 31) / 32, (B + 31) / 32);
+      hipLaunchKernelGGL((user_gemm_bf16_kernel<1, 1>), grid, dim3(256), 0, stream,
+                         static_cast<const uint16_t*>(H_l), desc->h_row_stride,
+                         (const uint16_t*)Wp, A, B, d, V, KS_total);
+    }
+    NEZHA_HIP_CHECK(hipGetLastError());
+  } else {
+    dim3 grid((V + 255) / 256, B);
+    hipLaunchKernelGGL(user_gemm_f32_kernel, grid, dim3(256), 0, stream,
+                       static_cast<const float*>(H_l), desc->h_row_stride,
+                       static_cast<const float*>(W_l), A, B, d, V);
+    NEZHA_HIP_CHECK(hipGetLastError());
+  }
+
+  ExpandArgs ea;
+  ea.state = state_in;
+  ea.Wbeam = bf16 ? static_cast<const void*>(Wp) : W_l;
+  ea.A = A;
+  ea.cand_code = cand_code;
+  ea.cand_logp = cand_logp;
+  ea.rows = rows;
+  ea.K_in = K_in;
+  ea.K = K;
+  ea.V = V;
+  ea.d = d;
+  ea.e = e;
+  ea.KS_total = KS_total;
+  {
+    const size_t lds = (size_t)16 * plan.cap * 8 + 16 * 4 + 16 * 4;
+    dim3 grid((rows + 15) / 16), block(64);
+#define LAUNCH_EXPAND(BF, CAPV)                                                       \
+  do {                                                                                \
+    rc = allow_lds(expand_kernel<BF, CAPV>, lds);                                     \
+    if (rc != NEZHA_OK) return rc;                                                    \
+    hipLaunchKernelGGL((expand_kernel<BF, CAPV>), grid, block, lds, stream, ea);      \
+  } while (0)
+    if (bf16 && plan.cap == 128) LAUNCH_EXPAND(true, 128);
+    else if (bf16) LAUNCH_EXPAND(true, 256);
+    else if (plan.cap == 128) LAUNCH_EXPAND(false, 128);
+    else LAUNCH_EXPAND(false, 256);
+#undef LAUNCH_EXPAND
+    NEZHA_HIP_CHECK(hipGetLastError());
+  }
+
+  MergeArgs ma;
+  ma.cand_code = cand_code;
+  ma.cand_logp = cand_logp;
+  ma.key_in = key_in;
+  ma.score_in = score_in;
+  ma.state_in = state_in;
+  ma.E = E_l;
+  ma.set = SetView{(set && level == L) ? set->slots : nullptr, set ? set->n_buckets : 0};
+  ma.mult = mult[level - 1];
+  ma.key_out = key_out;
+  ma.score_out = score_out;
+  ma.parent_out = parent_out;
+  ma.code_out = code_out;
+  ma.state_out = state_out;
+  ma.count_out = count_out;
+  ma.K_in = K_in;
+  ma.K = K;
+  ma.e = e;
+  {
+    dim3 grid(B), block(256);
+    if (bf16 && plan.cap == 128) hipLaunchKernelGGL((merge_kernel<true, 128>), grid, block, 0, stream, ma);
+    else if (bf16) hipLaunchKernelGGL((merge_kernel<true, 256>), grid, block, 0, stream, ma);
+    else if (plan.cap == 128) hipLaunchKernelGGL((merge_kernel<false, 128>), grid, block, 0, stream, ma);
+    else hipLaunchKernelGGL((merge_kernel<false, 256>), grid, block, 0, stream, ma);
+    NEZHA_HIP_CHECK(hipGetLastError());
+  }
+  return NEZHA_OK;
+}
+
+}  // extern "C"

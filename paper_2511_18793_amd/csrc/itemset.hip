@@ -1,0 +1,449 @@
+// The model-free verifier (Sec. 3.3): an open-addressing hash set of the packed 64-bit item
+// indices of Eq. 4 in device memory, its parallel build, and the stand-alone batch
+// verification of Eq. 5 with order-preserving compaction of the accepted tuples.
+#include <new>
+
+#include "nezha_internal.h"
+
+namespace nezha {
+
+char* error_buffer() {
+  static thread_local char buf[512] = "";
+  return buf;
+}
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(error_buffer(), 512, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+bool radix_multipliers(int32_t L, const int32_t* radices, uint64_t* mult) {
+  unsigned __int128 p = 1;
+  for (int32_t l = 0; l < L; ++l) {
+    if (radices[l] < 1) return false;
+    mult[l] = (uint64_t)p;
+    p *= (unsigned __int128)(uint32_t)radices[l];
+    if (p > (unsigned __int128)0xFFFFFFFFFFFFFFFFull) return false;
+  }
+  return true;
+}
+
+namespace {
+
+struct Radix {
+  int32_t L;
+  int32_t T[NEZHA_MAX_LEVELS];
+  uint64_t mult[NEZHA_MAX_LEVELS];
+};
+
+// Eq. 4 on one tuple; false if a code is outside its radix.
+__device__ __forceinline__ bool pack_tuple(const int32_t* t, const Radix& r, uint64_t& key) {
+  key = 0;
+  bool ok = true;
+  for (int l = 0; l < r.L; ++l) {
+    int32_t c = t[l];
+    ok &= (uint32_t)c < (uint32_t)r.T[l];
+    key += (uint64_t)(uint32_t)c * r.mult[l];
+  }
+  return ok;
+}
+
+__global__ void fill_empty_kernel(uint64_t* slots, uint64_t n) {
+  uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) slots[i] = kEmpty;
+}
+
+// One thread per catalog tuple: pack, then claim the first free slot on the probe path with a
+// 64-bit compare-and-swap.  Only the value the CAS returns decides, so a stale plain read
+// can do no harm.  status[0]: tuples with a bad code; status[1]: keys that found no slot;
+// status[2]: distinct keys stored.
+__global__ void insert_kernel(const int32_t* __restrict__ codes, int64_t n, Radix r,
+                              uint64_t* slots, uint64_t n_buckets,
+                              unsigned long long* status) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    uint64_t key;
+    if (!pack_tuple(codes + i * r.L, r, key)) {
+      atomicAdd(&status[0], 1ull);
+      continue;
+    }
+    uint64_t b = home_bucket(key, n_buckets);
+    bool done = false;
+    for (uint64_t step = 0; step < n_buckets && !done; ++step) {
+      unsigned long long* bucket = reinterpret_cast<unsigned long long*>(slots + b * kBucketSlots);
+      for (int s = 0; s < kBucketSlots && !done; ++s) {
+        unsigned long long cur = __atomic_load_n(&bucket[s], __ATOMIC_RELAXED);
+        if (cur == kEmpty) cur = atomicCAS(&bucket[s], (unsigned long long)kEmpty, key);
+        if (cur == kEmpty) {
+          atomicAdd(&status[2], 1ull);
+          done = true;
+        } else if (cur == key) {
+          done = true;  // duplicate tuple: stored once
+        }
+      }
+      b = (b + 1 == n_buckets) ? 0 : b + 1;
+    }
+    if (!done) atomicAdd(&status[1], 1ull);
+  }
+}
+
+// ---- stand-alone verification ----------------------------------------------------------
+constexpr int kVerifyThreads = 256;
+constexpr int kPerThread = 4;                                 // consecutive tuples per lane
+constexpr int kVerifyBlock = kVerifyThreads * kPerThread;     // tuples per workgroup
+
+// Pass 1: pack + probe, write the mask bytes and the number of accepted tuples per block.
+template <int L>
+__global__ __launch_bounds__(kVerifyThreads) void verify_probe_kernel(
+    const int32_t* __restrict__ codes, int64_t n, Radix r, SetView set,
+    uint8_t* __restrict__ mask, int32_t* __restrict__ block_count) {
+  __shared__ int32_t wave_count[kVerifyThreads / 64];
+  const int64_t base = ((int64_t)blockIdx.x * kVerifyThreads + threadIdx.x) * kPerThread;
+  uint64_t key[kPerThread];
+  bool ok[kPerThread];
+#pragma unroll
+  for (int j = 0; j < kPerThread; ++j) {
+    ok[j] = false;
+    key[j] = 0;
+    if (base + j < n) {
+      int32_t t[NEZHA_MAX_LEVELS];
+      const int LL = (L > 0) ? L : r.L;
+#pragma unroll
+      for (int l = 0; l < (L > 0 ? L : NEZHA_MAX_LEVELS); ++l)
+        if (l < LL) t[l] = codes[(base + j) * LL + l];
+      ok[j] = pack_tuple(t, r, key[j]);
+    }
+  }
+  int cnt = 0;
+  uint32_t bits = 0;
+#pragma unroll
+  for (int j = 0; j < kPerThread; ++j) {
+    bool in = ok[j] && set_contains(set, key[j]);
+    bits |= (in ? 1u : 0u) << (8 * j);
+    cnt += in ? 1 : 0;
+  }
+  if (base + kPerThread <= n && (reinterpret_cast<uintptr_t>(mask) & 3) == 0) {
+    *reinterpret_cast<uint32_t*>(mask + base) = bits;
+  } else {
+#pragma unroll
+    for (int j = 0; j < kPerThread; ++j)
+      if (base + j < n) mask[base + j] = (bits >> (8 * j)) & 1u;
+  }
+  // block total: wave reduction by cross-lane adds, then a 4-entry LDS sum
+  for (int off = 32; off > 0; off >>= 1) cnt += __shfl_down(cnt, off);
+  if ((threadIdx.x & 63) == 0) wave_count[threadIdx.x >> 6] = cnt;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int s = 0;
+    for (int w = 0; w < kVerifyThreads / 64; ++w) s += wave_count[w];
+    block_count[blockIdx.x] = s;
+  }
+}
+
+// Pass 2 (one workgroup): exclusive scan of the per-block counts, total to out_count.
+__global__ __launch_bounds__(1024) void verify_scan_kernel(const int32_t* __restrict__ block_count,
+                                                           int64_t n_blocks,
+                                                           int64_t* __restrict__ block_offset,
+                                                           int64_t* __restrict__ out_count) {
+  __shared__ int64_t wave_sum[16];
+  __shared__ int64_t carry_s;
+  if (threadIdx.x == 0) carry_s = 0;
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int64_t start = 0; start < n_blocks; start += 1024) {
+    int64_t i = start + threadIdx.x;
+    int64_t v = (i < n_blocks) ? block_count[i] : 0;
+    int64_t incl = v;
+    for (int off = 1; off < 64; off <<= 1) {
+      int64_t t = __shfl_up(incl, off);
+      if (lane >= off) incl += t;
+    }
+    if (lane == 63) wave_sum[wave] = incl;
+    __syncthreads();
+    int64_t before = carry_s;
+    for (int w = 0; w < wave; ++w) before += wave_sum[w];
+    if (i < n_blocks) block_offset[i] = before + incl - v;
+    __syncthreads();
+    if (threadIdx.x == 1023) carry_s = before + incl;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0 && out_count) *out_count = carry_s;
+}
+
+// Pass 3: every block turns its mask bytes into ascending indices at its offset
+// (ballot-free per-lane popcounts, wave prefix by cross-lane adds, LDS across waves).
+__global__ __launch_bounds__(kVerifyThreads) void verify_scatter_kernel(
+    const uint8_t* __restrict__ mask, int64_t n, const int64_t* __restrict__ block_offset,
+    int64_t* __restrict__ out_index) {
+  __shared__ int32_t wave_total[kVerifyThreads / 64];
+  const int64_t base = ((int64_t)blockIdx.x * kVerifyThreads + threadIdx.x) * kPerThread;
+  uint32_t bits = 0;
+  if (base + kPerThread <= n && (reinterpret_cast<uintptr_t>(mask) & 3) == 0) {
+    bits = *reinterpret_cast<const uint32_t*>(mask + base);
+  } else {
+    for (int j = 0; j < kPerThread; ++j)
+      if (base + j < n) bits |= (uint32_t)(mask[base + j] & 1u) << (8 * j);
+  }
+  const int mine = __popc(bits);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int incl = mine;
+  for (int off = 1; off < 64; off <<= 1) {
+    int t = __shfl_up(incl, off);
+    if (lane >= off) incl += t;
+  }
+  if (lane == 63) wave_total[wave] = incl;
+  __syncthreads();
+  int64_t pos = block_offset[blockIdx.x] + incl - mine;
+  for (int w = 0; w < wave; ++w) pos += wave_total[w];
+#pragma unroll
+  for (int j = 0; j < kPerThread; ++j)
+    if ((bits >> (8 * j)) & 1u) out_index[pos++] = base + j;
+}
+
+}  // namespace
+}  // namespace nezha
+
+using namespace nezha;
+
+extern "C" {
+
+const char* nezha_last_error(void) { return error_buffer(); }
+
+int nezha_build_itemset(const int32_t* codes, int64_t n, int32_t L, const int32_t* radices,
+                        int codes_on_device, double load_factor, void* hip_stream,
+                        nezha_itemset** out) {
+  if (!out) return fail(NEZHA_EINVAL, "out is NULL");
+  *out = nullptr;
+  if (n < 0) return fail(NEZHA_EINVAL, "n = %lld is negative", (long long)n);
+  if (n > 0 && !codes) return fail(NEZHA_EINVAL, "codes is NULL");
+  if (!radices) return fail(NEZHA_EINVAL, "radices is NULL");
+  if (L < 1 || L > NEZHA_MAX_LEVELS)
+    return fail(NEZHA_EINVAL, "L = %d outside 1..%d", L, NEZHA_MAX_LEVELS);
+  if (!(load_factor > 0.0 && load_factor <= 0.9))
+    return fail(NEZHA_EINVAL, "load_factor %g outside (0, 0.9]", load_factor);
+  Radix r;
+  r.L = L;
+  for (int l = 0; l < NEZHA_MAX_LEVELS; ++l) {
+    r.T[l] = l < L ? radices[l] : 1;
+    r.mult[l] = 0;
+  }
+  if (!radix_multipliers(L, radices, r.mult))
+    return fail(NEZHA_ERANGE, "radices must be >= 1 with a product of at most 2^64-1");
+
+  double want = (double)n / load_factor;
+  if (want > 9.0e15) return fail(NEZHA_EINVAL, "table too large");
+  uint64_t n_slots = (uint64_t)want;
+  if ((double)n_slots < want) ++n_slots;
+  uint64_t n_buckets = (n_slots + kBucketSlots - 1) / kBucketSlots;
+  if (n_buckets == 0) n_buckets = 1;
+  n_slots = n_buckets * kBucketSlots;
+
+  hipStream_t stream = (hipStream_t)hip_stream;
+  nezha_itemset* s = new (std::nothrow) nezha_itemset;
+  if (!s) return fail(NEZHA_ENOMEM, "host allocation failed");
+  s->slots = nullptr;
+  s->n_buckets = n_buckets;
+  s->n_distinct = 0;
+  s->L = L;
+  for (int l = 0; l < NEZHA_MAX_LEVELS; ++l) {
+    s->radices[l] = r.T[l];
+    s->mult[l] = r.mult[l];
+  }
+  s->magic = kSetMagic;
+
+  unsigned long long* status = nullptr;
+  int32_t* staged = nullptr;
+  int rc = NEZHA_OK;
+  auto cleanup = [&](int code) {
+    if (status) (void)hipFree(status);
+    if (staged) (void)hipFree(staged);
+    if (code != NEZHA_OK) {
+      if (s->slots) (void)hipFree(s->slots);
+      s->magic = 0;
+      delete s;
+    }
+    return code;
+  };
+#define BUILD_CHECK(expr)                                                                  \
+  do {                                                                                     \
+    hipError_t _e = (expr);                                                                \
+    if (_e != hipSuccess) {                                                                \
+      rc = fail(_e == hipErrorOutOfMemory ? NEZHA_ENOMEM : NEZHA_EHIP, "%s failed: %s",    \
+                #expr, hipGetErrorString(_e));                                             \
+      return cleanup(rc);                                                                  \
+    }                                                                                      \
+  } while (0)
+
+  BUILD_CHECK(hipGetDevice(&s->device));
+  BUILD_CHECK(hipMalloc((void**)&s->slots, n_slots * sizeof(uint64_t)));
+  BUILD_CHECK(hipMalloc((void**)&status, 4 * sizeof(unsigned long long)));
+  BUILD_CHECK(hipMemsetAsync(status, 0, 4 * sizeof(unsigned long long), stream));
+  {
+    uint64_t blocks = (n_slots + 1023) / 1024;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(fill_empty_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, s->slots,
+                       n_slots);
+    BUILD_CHECK(hipGetLastError());
+  }
+  const int64_t chunk_max = (int64_t)1 << 25;  // tuples staged per copy when codes are on the host
+  if (!codes_on_device && n > 0) {
+    int64_t cap = n < chunk_max ? n : chunk_max;
+    BUILD_CHECK(hipMalloc((void**)&staged, (size_t)cap * L * sizeof(int32_t)));
+  }
+  for (int64_t start = 0; start < n; start += chunk_max) {
+    int64_t m = n - start < chunk_max ? n - start : chunk_max;
+    const int32_t* src = codes + start * L;
+    if (!codes_on_device) {
+      BUILD_CHECK(hipMemcpyAsync(staged, src, (size_t)m * L * sizeof(int32_t),
+                                 hipMemcpyHostToDevice, stream));
+      src = staged;
+    }
+    int64_t blocks = (m + 255) / 256;
+    if (blocks > 262144) blocks = 262144;
+    hipLaunchKernelGGL(insert_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, m, r,
+                       s->slots, n_buckets, status);
+    BUILD_CHECK(hipGetLastError());
+    if (!codes_on_device) BUILD_CHECK(hipStreamSynchronize(stream));
+  }
+  unsigned long long host_status[4] = {0, 0, 0, 0};
+  BUILD_CHECK(hipMemcpyAsync(host_status, status, sizeof(host_status), hipMemcpyDeviceToHost,
+                             stream));
+  BUILD_CHECK(hipStreamSynchronize(stream));
+#undef BUILD_CHECK
+  if (host_status[0] != 0) {
+    rc = fail(NEZHA_ERANGE, "%llu catalog tuples have a code outside [0, T_l)", host_status[0]);
+    return cleanup(rc);
+  }
+  if (host_status[1] != 0) {
+    rc = fail(NEZHA_EFULL, "%llu keys found no free slot", host_status[1]);
+    return cleanup(rc);
+  }
+  s->n_distinct = (int64_t)host_status[2];
+  *out = s;
+  return cleanup(NEZHA_OK);
+}
+
+int nezha_itemset_info(const nezha_itemset* set, int64_t* n_distinct, int64_t* n_slots,
+                       int32_t* L, int32_t* radices) {
+  if (!set || set->magic != kSetMagic) return fail(NEZHA_EINVAL, "not an item set");
+  if (n_distinct) *n_distinct = set->n_distinct;
+  if (n_slots) *n_slots = (int64_t)(set->n_buckets * kBucketSlots);
+  if (L) *L = set->L;
+  if (radices)
+    for (int l = 0; l < set->L; ++l) radices[l] = set->radices[l];
+  return NEZHA_OK;
+}
+
+int nezha_free_itemset(nezha_itemset* set) {
+  if (!set) return NEZHA_OK;
+  if (set->magic != kSetMagic) return fail(NEZHA_EINVAL, "not an item set (freed twice?)");
+  set->magic = 0;
+  hipError_t e = set->slots ? hipFree(set->slots) : hipSuccess;
+  delete set;
+  if (e != hipSuccess) return fail(NEZHA_EHIP, "hipFree failed: %s", hipGetErrorString(e));
+  return NEZHA_OK;
+}
+
+size_t nezha_verify_workspace(int64_t n) {
+  if (n < 0) return 0;
+  size_t blocks = (size_t)((n + kVerifyBlock - 1) / kVerifyBlock);
+  if (blocks == 0) blocks = 1;
+  size_t counts = (blocks * sizeof(int32_t) + 15) & ~(size_t)15;
+  return counts + blocks * sizeof(int64_t);
+}
+
+int nezha_verify_tuples(const nezha_itemset* set, const int32_t* codes, int64_t n,
+                        uint8_t* out_mask, int64_t* out_index, int64_t* out_count,
+                        void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!set || set->magic != kSetMagic) return fail(NEZHA_EINVAL, "not an item set");
+  if (n < 0) return fail(NEZHA_EINVAL, "n = %lld is negative", (long long)n);
+  if (n > 0 && (!codes || !out_mask)) return fail(NEZHA_EINVAL, "codes or out_mask is NULL");
+  const bool compact = out_index || out_count;
+  if (n > 0 && compact) {
+    if (!workspace) return fail(NEZHA_EINVAL, "workspace is NULL");
+    if (workspace_bytes < nezha_verify_workspace(n))
+      return fail(NEZHA_EINVAL, "workspace has %zu bytes, %zu needed", workspace_bytes,
+                  nezha_verify_workspace(n));
+    if (reinterpret_cast<uintptr_t>(workspace) & 15)
+      return fail(NEZHA_EINVAL, "workspace is not 16-byte aligned");
+  }
+  if (n > (int64_t)kVerifyBlock * 0x7FFFFFFF) return fail(NEZHA_EINVAL, "n too large");
+  hipStream_t stream = (hipStream_t)hip_stream;
+  const int64_t blocks = n == 0 ? 1 : (n + kVerifyBlock - 1) / kVerifyBlock;
+  const size_t counts_bytes = ((size_t)blocks * sizeof(int32_t) + 15) & ~(size_t)15;
+  int32_t* block_count = compact && n > 0 ? static_cast<int32_t*>(workspace) : nullptr;
+  int64_t* block_offset =
+      compact && n > 0 ? reinterpret_cast<int64_t*>(static_cast<char*>(workspace) + counts_bytes)
+                       : nullptr;
+  Radix r;
+  r.L = set->L;
+  for (int l = 0; l < NEZHA_MAX_LEVELS; ++l) {
+    r.T[l] = set->radices[l];
+    r.mult[l] = set->mult[l];
+  }
+  SetView view{set->slots, set->n_buckets};
+  if (n == 0) {
+    if (out_count) {
+      hipLaunchKernelGGL(verify_scan_kernel, dim3(1), dim3(1024), 0, stream,
+                         (const int32_t*)nullptr, (int64_t)0, (int64_t*)nullptr, out_count);
+      NEZHA_HIP_CHECK(hipGetLastError());
+    }
+    return NEZHA_OK;
+  }
+  // The probe pass needs somewhere to put block counts even when they are not wanted.
+  if (!block_count) {
+    if (!workspace || workspace_bytes < nezha_verify_workspace(n))
+      return fail(NEZHA_EINVAL, "workspace has %zu bytes, %zu needed", workspace_bytes,
+                  nezha_verify_workspace(n));
+    block_count = static_cast<int32_t*>(workspace);
+  }
+  dim3 grid((unsigned)blocks), block(kVerifyThreads);
+  switch (set->L) {
+    case 3:
+      hipLaunchKernelGGL(verify_probe_kernel<3>, grid, block, 0, stream, codes, n, r, view,
+                         out_mask, block_count);
+      break;
+    case 4:
+      hipLaunchKernelGGL(verify_probe_kernel<4>, grid, block, 0, stream, codes, n, r, view,
+                         out_mask, block_count);
+      break;
+    default:
+      hipLaunchKernelGGL(verify_probe_kernel<0>, grid, block, 0, stream, codes, n, r, view,
+                         out_mask, block_count);
+  }
+  NEZHA_HIP_CHECK(hipGetLastError());
+  if (compact) {
+    hipLaunchKernelGGL(verify_scan_kernel, dim3(1), dim3(1024), 0, stream,
+                       (const int32_t*)block_count, blocks, block_offset, out_count);
+    NEZHA_HIP_CHECK(hipGetLastError());
+    if (out_index) {
+      hipLaunchKernelGGL(verify_scatter_kernel, grid, block, 0, stream,
+                         (const uint8_t*)out_mask, n, (const int64_t*)block_offset, out_index);
+      NEZHA_HIP_CHECK(hipGetLastError());
+    }
+  }
+  return NEZHA_OK;
+}
+
+int nezha_unpack_keys(const uint64_t* keys, int64_t n, int32_t L, const int32_t* radices,
+                      int32_t* codes) {
+  if (n < 0 || L < 1 || L > NEZHA_MAX_LEVELS || !radices || (n > 0 && (!keys || !codes)))
+    return fail(NEZHA_EINVAL, "bad argument");
+  for (int l = 0; l < L; ++l)
+    if (radices[l] < 1) return fail(NEZHA_EINVAL, "radix < 1");
+  for (int64_t i = 0; i < n; ++i) {
+    uint64_t k = keys[i];
+    for (int l = 0; l < L; ++l) {
+      uint64_t T = (uint64_t)radices[l];
+      codes[i * L + l] = (int32_t)(k % T);
+      k /= T;
+    }
+  }
+  return NEZHA_OK;
+}
+
+}  // extern "C"
