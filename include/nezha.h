@@ -136,6 +136,8 @@ typedef struct {
  *        beyond the count hold key 2^64-1, score -inf, parent -1, code -1, state 0.
  *   workspace: device memory of at least nezha_draft_step_workspace(desc) bytes,
  *        256-byte aligned; scratch.
+ * Alignment: E_l and the states 16 bytes; H_l (every row) and W_l 16 bytes with NEZHA_BF16,
+ * 4 bytes with NEZHA_F32.
  * Shape limits: K, K_in <= NEZHA_MAX_BEAM; T_level a multiple of 16; with
  * NEZHA_BF16 d and e multiples of 32, with NEZHA_F32 d >= 1 and e a multiple
  * of 4; e <= 256.  Anything else gives NEZHA_EINVAL. */

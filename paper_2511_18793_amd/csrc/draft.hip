@@ -730,6 +730,7 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
   const int level = desc->level, L = desc->L;
   const int V = desc->radices[level - 1];
   const bool bf16 = desc->dtype == NEZHA_BF16;
+  if (desc->B == 0) return NEZHA_OK;  // an empty batch has nothing to read or write
   if (!H_l || !W_l) return fail(NEZHA_EINVAL, "H_l or W_l is NULL");
   if (!key_out || !score_out || !parent_out || !code_out)
     return fail(NEZHA_EINVAL, "an output pointer is NULL");
@@ -740,11 +741,13 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
     return fail(NEZHA_EINVAL, "workspace has %zu bytes, %zu needed", workspace_bytes, plan.total);
   if (reinterpret_cast<uintptr_t>(workspace) & 255)
     return fail(NEZHA_EINVAL, "workspace is not 256-byte aligned");
-  const uintptr_t align_mask = 15;
-  if ((reinterpret_cast<uintptr_t>(H_l) | reinterpret_cast<uintptr_t>(W_l) |
-       reinterpret_cast<uintptr_t>(E_l) | reinterpret_cast<uintptr_t>(state_in) |
-       reinterpret_cast<uintptr_t>(state_out)) & align_mask)
-    return fail(NEZHA_EINVAL, "H_l, W_l, E_l and the states must be 16-byte aligned");
+  // bf16 operands are fetched 16 bytes at a time; the float32 path reads H and W element-wise
+  const uintptr_t hw_mask = bf16 ? 15 : 3;
+  if ((reinterpret_cast<uintptr_t>(H_l) | reinterpret_cast<uintptr_t>(W_l)) & hw_mask)
+    return fail(NEZHA_EINVAL, "H_l and W_l must be %d-byte aligned", (int)hw_mask + 1);
+  if ((reinterpret_cast<uintptr_t>(E_l) | reinterpret_cast<uintptr_t>(state_in) |
+       reinterpret_cast<uintptr_t>(state_out)) & 15)
+    return fail(NEZHA_EINVAL, "E_l and the states must be 16-byte aligned");
   if (set) {
     if (set->magic != kSetMagic) return fail(NEZHA_EINVAL, "not an item set");
     if (set->L != L) return fail(NEZHA_EINVAL, "item set has L = %d, desc has %d", set->L, L);
@@ -752,7 +755,6 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
       if (set->radices[l] != desc->radices[l])
         return fail(NEZHA_EINVAL, "item set and desc disagree on radix %d", l + 1);
   }
-  if (B == 0) return NEZHA_OK;
   uint64_t mult[NEZHA_MAX_LEVELS];
   radix_multipliers(L, desc->radices, mult);
 

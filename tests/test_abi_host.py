@@ -1,0 +1,107 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2511_18793_amd as nz
+from paper_2511_18793_amd import api
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "nezha.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(nezha_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = nz.load_library()
+    names = declared_functions()
+    assert len(names) >= 9
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(api.EXPORTS) == names
+
+
+def test_last_error_is_never_null():
+    assert isinstance(nz.load_library().nezha_last_error(), bytes)
+
+
+def test_unpack_keys_inverts_the_printed_example():
+    assert nz.unpack_keys(np.array([852723], dtype=np.uint64), [512] * 3).tolist() == [[243, 129, 3]]
+    assert nz.unpack_keys(np.array([104], dtype=np.uint64), [3, 5, 7]).tolist() == [[2, 4, 6]]
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(load_factor=0.0), -1), (dict(load_factor=0.95), -1), (dict(radices=[0, 4, 4]), -4),
+    (dict(radices=[1 << 30, 1 << 30, 1 << 30]), -4), (dict(radices=[4] * 9), -1),
+])
+def test_build_itemset_argument_errors(kw, code):
+    radices = kw.pop("radices", [4, 4, 4])
+    codes = np.zeros((2, len(radices)), dtype=np.int32)
+    with pytest.raises(nz.NezhaError) as ei:
+        nz.build_itemset(codes, radices, **kw)
+    assert ei.value.code == code
+
+
+def test_free_null_itemset_is_ok():
+    assert nz.load_library().nezha_free_itemset(None) == 0
+
+
+def test_workspace_queries():
+    assert nz.verify_workspace(0) > 0
+    assert nz.verify_workspace(4_000_000) >= 3907 * 12
+    assert nz.verify_workspace(-1) == 0
+    ok = nz.draft_step_workspace(256, 3, 2, 20, 20, 512, 128, [256] * 3, torch.bfloat16)
+    assert ok >= 640 * 256 * 2 + 256 * 256 * 4 + 2 * 5120 * 20 * 4
+    # invalid descriptions give 0
+    assert nz.draft_step_workspace(256, 3, 4, 20, 20, 512, 128, [256] * 3, torch.bfloat16) == 0
+    assert nz.draft_step_workspace(256, 3, 2, 300, 20, 512, 128, [256] * 3, torch.bfloat16) == 0
+    assert nz.draft_step_workspace(256, 3, 2, 20, 20, 500, 128, [256] * 3, torch.bfloat16) == 0
+    assert nz.draft_step_workspace(256, 3, 2, 20, 20, 512, 100, [256] * 3, torch.bfloat16) == 0
+    assert nz.draft_step_workspace(4, 3, 2, 20, 20, 64, 64, [250] * 3, torch.float32) == 0
+    assert nz.draft_step_workspace(4, 3, 1, 4, 1, 64, 64, [256] * 3, torch.float32) > 0
+
+
+def _call_step(**over):
+    """nezha_draft_step with fake (never dereferenced) pointers: only the host checks run."""
+    lib = nz.load_library()
+    a = dict(B=4, L=3, level=2, K=4, K_in=4, d=64, e=64, radices=[256] * 3,
+             dtype=torch.float32, stride=64, ws_bytes=1 << 24, fake=0x1000, ws=0x10000,
+             null=())
+    a.update(over)
+    dsc = api._desc(a["B"], a["L"], a["level"], a["K"], a["K_in"], a["d"], a["e"], a["radices"],
+                    a["dtype"], a["stride"])
+    names = ["H", "W", "E", "state_in", "key_in", "score_in", "set", "key_out", "score_out",
+             "parent_out", "code_out", "state_out", "count_out"]
+    ptrs = [None if (n in a["null"] or n == "set") else C.c_void_p(a["fake"]) for n in names]
+    rc = lib.nezha_draft_step(C.byref(dsc), *ptrs, C.c_void_p(a["ws"]), a["ws_bytes"], None)
+    return rc, lib.nezha_last_error().decode()
+
+
+@pytest.mark.parametrize("over,code", [
+    (dict(level=0), -1), (dict(level=4), -1), (dict(K=0), -1), (dict(K=129), -1),
+    (dict(K=4, radices=[256, 2, 256]), -1),            # K > T_level
+    (dict(K_in=0), -1), (dict(e=6), -1), (dict(e=512), -1), (dict(stride=32), -1),
+    (dict(radices=[1 << 30] * 3), -4), (dict(null=("H",)), -1), (dict(null=("key_out",)), -1),
+    (dict(null=("state_out",)), -1), (dict(ws_bytes=16), -1), (dict(ws=0x10010), -1),
+    (dict(fake=0x1004), -1), (dict(dtype=torch.bfloat16), -1),   # bf16 needs d, e multiples of 32... d=64,e=64 ok -> alignment fake ok; see below
+])
+def test_draft_step_argument_errors(over, code):
+    if over.get("dtype") is torch.bfloat16:
+        over = dict(over, d=48)
+    rc, text = _call_step(**over)
+    assert rc == code, text
+    assert text
+
+
+def test_verify_tuples_rejects_a_non_set():
+    lib = nz.load_library()
+    rc = lib.nezha_verify_tuples(None, None, 0, None, None, None, None, 0, None)
+    assert rc == -1
