@@ -1,0 +1,324 @@
+#!/usr/bin/env python3
+"""Benchmark of the NEZHA draft + verify step on one MI355X.
+
+One "step" is one full decode of a batch: L calls of nezha_draft_step (beam expansion at every
+level, hash-set verification and pruning at the last) on synthetic inputs that are already
+resident in device memory.  The metric is verified candidate items per second: the B*K*K
+level-L candidates submitted to the verifier per decode, divided by the decode time.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload serving|large|wide|tiny|
+                    paper_yelp|paper_beauty|paper_games|stress] [--eager] [--no-cpu-baseline]
+
+Prints ONE JSON line.  `roofline` describes the kernel that took the most time, timed with HIP
+events by the library itself; `cpu_baseline` is the CPU oracle timed on the host cores."""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import synth  # noqa: E402
+import paper_2511_18793_amd as nz  # noqa: E402
+
+# MI355X peaks used for the roofline fractions.
+PEAK_HBM_GBS = 8000.0
+PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+# plain (unpacked, non-FMA) fp32 vector issue rate: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz
+PEAK_ALU_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+# issue slots the fused expansion needs per logit: add of the user part (folded into the MFMA
+# accumulator, not counted), scale (1), exponential (quarter rate: 4), sum (1), running max (1),
+# threshold compare (1)
+EXPAND_SLOTS_PER_LOGIT = 8
+BUCKET_BYTES = 64
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="serving")
+    ap.add_argument("--seed", type=int, default=42)
+    ap.add_argument("--eager", action="store_true",
+                    help="launch every step through the C ABI instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--batch", type=int, default=0, help="override B (debugging)")
+    ap.add_argument("--catalog", type=int, default=0, help="override N (debugging)")
+    return ap.parse_args()
+
+
+def percentile(xs, q):
+    return float(np.percentile(np.asarray(xs, dtype=np.float64), q))
+
+
+def kernel_models(cfg):
+    """Algorithmic work of one launch of each kernel at each level: (bound, unit, amount)."""
+    B, K, V, d, e, L = cfg.B, cfg.K, cfg.V, cfg.d, cfg.e, cfg.L
+    esz = 2 if cfg.dtype == "bf16" else 4
+    per_level = []
+    for level in range(1, L + 1):
+        K_in = 1 if level == 1 else K
+        rows = B * K_in
+        probes = rows * K if level == L else 0
+        per_level.append({
+            "pack_weights_kernel": ("hbm", 2.0 * (d + e) * V * esz),
+            "user_gemm_kernel": ("mfma", 2.0 * B * d * V),
+            "expand_kernel": ("alu", float(EXPAND_SLOTS_PER_LOGIT) * rows * V),
+            "merge_kernel": ("hbm", rows * K * 8.0 + probes * BUCKET_BYTES
+                             + B * K * (24.0 + (2 * e * esz if level < L else 0))),
+        })
+    return per_level
+
+
+def bench_draft(args, cfg):
+    dev = torch.device("cuda:0")
+    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    t0 = time.time()
+    x = synth.draft_inputs(cfg, args.seed)
+    H = torch.from_numpy(x["H"]).to(dev).to(dt)
+    W = [torch.from_numpy(w).to(dev).to(dt) for w in x["W"]]
+    E = [torch.from_numpy(w).to(dev).to(dt) for w in x["E"]]
+    bufs = nz.DraftBuffers(cfg.B, cfg.L, cfg.K, cfg.d, cfg.e, cfg.radices, dt, dev)
+
+    # Catalog: Zipf / uniform background, with about 70 % of the unverified top-K beams planted
+    # so that about 30 % of them are hallucinations (this pass runs without a verifier).
+    free = nz.decode(H, W, E, cfg.radices, cfg.K, None, buffers=bufs)
+    torch.cuda.synchronize()
+    beams = nz.unpack_keys(free[-1]["key"].cpu().numpy().ravel(), cfg.radices)
+    if cfg.catalog == "uniform":
+        background = synth.uniform_catalog(cfg.radices, cfg.N, args.seed)[0]
+    else:
+        background = synth.zipf_catalog(cfg.radices, cfg.N, args.seed, cfg.zipf_s,
+                                        depth=2 if cfg.catalog == "zipf12" else 1)
+    keep = synth.plant_mask(beams, cfg.radices, args.seed)
+    catalog = synth.planted_catalog(cfg.radices, background, beams[keep], beams[~keep], args.seed)
+    del background
+    itemset = nz.build_itemset(catalog, cfg.radices, cfg.load_factor)
+    setup_s = time.time() - t0
+
+    def step():
+        nz.decode(H, W, E, cfg.radices, cfg.K, itemset, buffers=bufs)
+
+    graph = None
+    if not args.eager:
+        step()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        run = graph.replay
+    else:
+        run = step
+
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    t_wall = time.perf_counter()
+    ev[0].record()
+    for i in range(args.steps):
+        run()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_wall) * 1e3
+    total_ms = ev[0].elapsed_time(ev[-1])
+    per_step = [ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]
+    accepted = int(bufs.outs[-1]["count"].sum().item())
+    hallucinated = 1.0 - float(keep.mean())
+
+    # Per-kernel durations: the same steps again, eager, with the library's event timing on.
+    nz.profile_reset()
+    nz.profile_enable(True)
+    prof_steps = min(args.steps, 50)
+    for _ in range(prof_steps):
+        step()
+    torch.cuda.synchronize()
+    prof = nz.profile_read()
+    nz.profile_enable(False)
+    nz.profile_reset()
+
+    models = kernel_models(cfg)
+    kernels = {}
+    for name, (launches, ms) in prof.items():
+        bound = models[0][name][0]
+        work = sum(m[name][1] for m in models) * prof_steps        # all levels, all steps
+        kernels[name] = {"bound": bound, "launches": launches, "avg_us": 1e3 * ms / launches,
+                         "total_ms": ms, "work": work}
+    dom = max(kernels, key=lambda k: kernels[k]["total_ms"])
+    kd = kernels[dom]
+    if kd["bound"] == "mfma":
+        unit, peak = "TFLOP/s", PEAK_MFMA_TFLOPS[cfg.dtype]
+        achieved = kd["work"] / (kd["total_ms"] * 1e-3) / 1e12
+    elif kd["bound"] == "alu":
+        unit, peak = "Tops/s", PEAK_ALU_TOPS
+        achieved = kd["work"] / (kd["total_ms"] * 1e-3) / 1e12
+    else:
+        unit, peak = "GB/s", PEAK_HBM_GBS
+        achieved = kd["work"] / (kd["total_ms"] * 1e-3) / 1e9
+    roofline = {"kernel": dom, "bound": kd["bound"], "achieved": achieved, "peak": peak,
+                "unit": unit, "frac": achieved / peak, "traffic": None,
+                "avg_launch_us": kd["avg_us"],
+                "timing": "HIP events by the library around each launch, eager pass of %d steps"
+                          % prof_steps}
+    if dom == "expand_kernel":
+        flops = sum(2.0 * cfg.B * (1 if l == 0 else cfg.K) * cfg.e * cfg.V * (0 if l == 0 else 1)
+                    for l in range(cfg.L)) * prof_steps
+        roofline["mfma_tflops"] = flops / (kd["total_ms"] * 1e-3) / 1e12
+    breakdown = {k: {"avg_us": round(v["avg_us"], 3), "launches": v["launches"]}
+                 for k, v in kernels.items()}
+
+    cands = cfg.B * cfg.K * cfg.K if cfg.L > 1 else cfg.B * cfg.K
+    ms_per_step = total_ms / args.steps
+    result = {
+        "metric": "verified candidate items/sec (level-L candidates submitted to the hash-set "
+                  "verifier per full L-level decode / decode time), 1 MI355X",
+        "value": cands / (ms_per_step * 1e-3),
+        "unit": "items/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "p50_step_ms": percentile(per_step, 50), "p90_step_ms": percentile(per_step, 90),
+        "p99_step_ms": percentile(per_step, 99),
+        "wall_ms_per_step": wall_ms / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "B": cfg.B, "d": cfg.d, "e": cfg.e, "L": cfg.L,
+                   "V": cfg.V, "K": cfg.K, "catalog_items": int(catalog.shape[0]),
+                   "load_factor": cfg.load_factor, "candidates_per_step": cands,
+                   "accepted_per_step": accepted, "hallucinated_topk_frac": round(hallucinated, 3),
+                   "launch": "eager" if args.eager else "hip_graph_replay",
+                   "setup_s": round(setup_s, 1)},
+        "accepted_items_per_s": accepted / (ms_per_step * 1e-3),
+        "roofline": roofline,
+        "kernels": breakdown,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline_draft(cfg, x, catalog, cands)
+    return result
+
+
+def cpu_baseline_draft(cfg, x, catalog, cands):
+    """The CPU oracle, as it stands, on the host cores: a bounded sample of requests of the same
+    workload, scaled to the batch."""
+    from oracle import oracle as orc
+    threads = os.cpu_count() or 1
+    oset = orc.ItemSet(catalog, cfg.radices)
+    # about 2.2 * B*K*(d+e)*V multiply-adds per decode; keep the sample near 10 s of CPU work
+    macs_per_req = (1 + (cfg.L - 1) * cfg.K) * (cfg.d + cfg.e) * cfg.V
+    budget = 4e9 * threads
+    n = int(max(1, min(cfg.B, budget // max(1, macs_per_req))))
+    Hs = x["H"][:n]
+    t = time.perf_counter()
+    orc.decode(Hs, x["W"], x["E"], cfg.radices, cfg.K, oset,
+               round_state_bf16=cfg.dtype == "bf16", threads=threads)
+    dt = time.perf_counter() - t
+    return {"value": cands * (n / cfg.B) / dt, "unit": "items/s", "cores": min(threads, n),
+            "kind": "oracle", "seconds": round(dt, 3),
+            "sample": "%d of %d requests, full decode incl. set lookups, scaled by request count"
+                      % (n, cfg.B)}
+
+
+def bench_stress(args, cfg):
+    """Stand-alone verifier: probes per second and bytes per second over the hash table."""
+    dev = torch.device("cuda:0")
+    N = args.catalog or cfg.N
+    t0 = time.time()
+    cat, pi = synth.uniform_catalog(cfg.radices, N, args.seed)
+    itemset = nz.build_itemset(cat, cfg.radices, cfg.load_factor)
+    q, present = synth.stress_queries(cfg.radices, N, pi, args.seed, cfg.queries)
+    setup_s = time.time() - t0
+    qd = torch.from_numpy(q).to(dev)
+    n = qd.shape[0]
+    mask = torch.empty(n, dtype=torch.uint8, device=dev)
+    idx = torch.empty(n, dtype=torch.int64, device=dev)
+    cnt = torch.empty(1, dtype=torch.int64, device=dev)
+    ws = torch.empty(nz.verify_workspace(n), dtype=torch.uint8, device=dev)
+
+    def step():
+        nz.verify_tuples(itemset, qd, mask, idx, cnt, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    ev[0].record()
+    for i in range(args.steps):
+        step()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    total_ms = ev[0].elapsed_time(ev[-1])
+    per_step = [ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]
+    accepted = int(cnt.item())
+    assert accepted == int(present.sum())
+
+    nz.profile_reset()
+    nz.profile_enable(True)
+    prof_steps = min(args.steps, 50)
+    for _ in range(prof_steps):
+        step()
+    torch.cuda.synchronize()
+    prof = nz.profile_read()
+    nz.profile_enable(False)
+    nz.profile_reset()
+    launches, ms = prof["verify_probe_kernel"]
+    bytes_per_probe = 4 * cfg.L + BUCKET_BYTES + 1
+    achieved = n * bytes_per_probe * launches / (ms * 1e-3) / 1e9
+    ms_per_step = total_ms / args.steps
+    result = {
+        "metric": "verified candidate items/sec (stand-alone hash-set verifier: tuples probed "
+                  "per second, mask + ordered index list written), 1 MI355X",
+        "value": n / (ms_per_step * 1e-3), "unit": "items/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "p50_step_ms": percentile(per_step, 50), "p99_step_ms": percentile(per_step, 99),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u64",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "catalog_items": N, "L": cfg.L, "V": cfg.V,
+                   "load_factor": cfg.load_factor, "queries": n, "accepted": accepted,
+                   "table_bytes": itemset.info()["n_slots"] * 8, "setup_s": round(setup_s, 1)},
+        "roofline": {"kernel": "verify_probe_kernel", "bound": "hbm", "achieved": achieved,
+                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS,
+                     "traffic": None, "avg_launch_us": 1e3 * ms / launches,
+                     "bytes_per_probe": bytes_per_probe},
+        "kernels": {k: {"avg_us": round(1e3 * v[1] / v[0], 3), "launches": v[0]}
+                    for k, v in prof.items()},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        m = min(N, 5_000_000)                      # a 10^8-element std::unordered_set is too slow
+        oset = orc.ItemSet(cat[:m], cfg.radices)
+        qs = q[:1_000_000]
+        t = time.perf_counter()
+        oset.verify_tuples(qs)
+        dt = time.perf_counter() - t
+        result["cpu_baseline"] = {"value": len(qs) / dt, "unit": "items/s", "cores": 1,
+                                  "kind": "oracle", "seconds": round(dt, 3),
+                                  "sample": "10^6 of the queries against a set of the first "
+                                            "%d catalog items (single thread)" % m}
+    return result
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: every request is independent and this build runs on "
+              "a single MI355X; --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    cfg = synth.get_config(args.workload)
+    if args.batch:
+        cfg = cfg.scaled(B=args.batch)
+    if args.catalog and cfg.B:
+        cfg = cfg.scaled(N=args.catalog)
+    result = bench_stress(args, cfg) if cfg.B == 0 else bench_draft(args, cfg)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

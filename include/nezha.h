@@ -149,6 +149,17 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
                      size_t workspace_bytes, void* hip_stream);
 size_t nezha_draft_step_workspace(const nezha_step_desc* desc); /* 0 if desc is invalid */
 
+/* ---- per-kernel timing (measurement aid, not part of the paper's method) -----------------
+ * While enabled, every kernel launch of the library is bracketed by two HIP events on the
+ * launch stream (this creates events, so calls made while it is on cannot be captured into a
+ * graph).  nezha_profile_read waits for the events of one kernel kind (0 <=
+ * kind < nezha_profile_kinds()) and returns its name, number of launches and summed
+ * duration in milliseconds; nezha_profile_reset drops all records. */
+int nezha_profile_enable(int on);
+int nezha_profile_reset(void);
+int nezha_profile_kinds(void);
+int nezha_profile_read(int kind, const char** name, int64_t* launches, double* total_ms);
+
 /* Inverse of Eq. 4 on the host: keys[n] -> codes int32 [n, L] (level 1 first).  Host pointers. */
 int nezha_unpack_keys(const uint64_t* keys, int64_t n, int32_t L, const int32_t* radices,
                       int32_t* codes);

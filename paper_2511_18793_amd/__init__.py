@@ -6,8 +6,10 @@ streams).  There is no CPU fallback: calls fail loudly when the library or a
 GPU is missing."""
 from .api import (NezhaError, ItemSet, build_itemset, verify_tuples, draft_step,
                   draft_step_workspace, verify_workspace, unpack_keys, decode,
-                  library_path, load_library, DraftBuffers)
+                  library_path, load_library, DraftBuffers, profile_enable,
+                  profile_reset, profile_read)
 
 __all__ = ["NezhaError", "ItemSet", "build_itemset", "verify_tuples", "draft_step",
            "draft_step_workspace", "verify_workspace", "unpack_keys", "decode",
-           "library_path", "load_library", "DraftBuffers"]
+           "library_path", "load_library", "DraftBuffers", "profile_enable", "profile_reset",
+           "profile_read"]

@@ -14,7 +14,8 @@ MAX_LEVELS = 8
 
 EXPORTS = ["nezha_last_error", "nezha_build_itemset", "nezha_itemset_info", "nezha_free_itemset",
            "nezha_verify_tuples", "nezha_verify_workspace", "nezha_draft_step",
-           "nezha_draft_step_workspace", "nezha_unpack_keys"]
+           "nezha_draft_step_workspace", "nezha_unpack_keys", "nezha_profile_enable",
+           "nezha_profile_reset", "nezha_profile_kinds", "nezha_profile_read"]
 
 
 class NezhaError(RuntimeError):
@@ -240,6 +241,26 @@ def decode(H, W, E, radices, K, itemset=None, buffers=None, stream=None):
                        workspace=buffers.workspace, stream=stream, h_row_stride=H.stride(0))
         state, key, score = o.get("state"), o["key"], o["score"]
     return buffers.outs
+
+
+def profile_enable(on):
+    _check(load_library().nezha_profile_enable(1 if on else 0))
+
+
+def profile_reset():
+    _check(load_library().nezha_profile_reset())
+
+
+def profile_read():
+    """{kernel name: (launches, total milliseconds)} for every kernel kind that ran."""
+    lib = load_library()
+    out = {}
+    for kind in range(lib.nezha_profile_kinds()):
+        name, n, ms = C.c_char_p(), C.c_int64(), C.c_double()
+        _check(lib.nezha_profile_read(kind, C.byref(name), C.byref(n), C.byref(ms)))
+        if n.value:
+            out[name.value.decode()] = (n.value, ms.value)
+    return out
 
 
 def unpack_keys(keys, radices):

@@ -769,9 +769,13 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
 
   if (bf16) {
     const int64_t total = (int64_t)(V / 16) * KS_total * 64;
+    {
+    ProfileScope prof(kPackWeights, stream);
     hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
                        stream, static_cast<const uint16_t*>(W_l), Wp, d + e, V);
+    }
     NEZHA_HIP_CHECK(hipGetLastError());
+    ProfileScope prof(kUserGemm, stream);
     const bool big = (int64_t)B * V >= (int64_t)128 * 128 * 256;
     if (big) {
       dim3 grid((V + 127) / 128, (B + 127) / 128);
@@ -787,6 +791,7 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
     NEZHA_HIP_CHECK(hipGetLastError());
   } else {
     dim3 grid((V + 255) / 256, B);
+    ProfileScope prof(kUserGemm, stream);
     hipLaunchKernelGGL(user_gemm_f32_kernel, grid, dim3(256), 0, stream,
                        static_cast<const float*>(H_l), desc->h_row_stride,
                        static_cast<const float*>(W_l), A, B, d, V);
@@ -809,6 +814,7 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
   {
     const size_t lds = (size_t)16 * plan.cap * 8 + 16 * 4 + 16 * 4;
     dim3 grid((rows + 15) / 16), block(64);
+    ProfileScope prof(kExpand, stream);
 #define LAUNCH_EXPAND(BF, CAPV)                                                       \
   do {                                                                                \
     rc = allow_lds(expand_kernel<BF, CAPV>, lds);                                     \
@@ -843,6 +849,7 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
   ma.e = e;
   {
     dim3 grid(B), block(256);
+    ProfileScope prof(kMerge, stream);
     if (bf16 && plan.cap == 128) hipLaunchKernelGGL((merge_kernel<true, 128>), grid, block, 0, stream, ma);
     else if (bf16) hipLaunchKernelGGL((merge_kernel<true, 256>), grid, block, 0, stream, ma);
     else if (plan.cap == 128) hipLaunchKernelGGL((merge_kernel<false, 128>), grid, block, 0, stream, ma);

@@ -1,7 +1,9 @@
 // The model-free verifier (Sec. 3.3): an open-addressing hash set of the packed 64-bit item
 // indices of Eq. 4 in device memory, its parallel build, and the stand-alone batch
 // verification of Eq. 5 with order-preserving compaction of the accepted tuples.
+#include <mutex>
 #include <new>
+#include <vector>
 
 #include "nezha_internal.h"
 
@@ -17,6 +19,40 @@ int fail(int code, const char* fmt, ...) {
   vsnprintf(error_buffer(), 512, fmt, ap);
   va_end(ap);
   return code;
+}
+
+// ---- per-kernel timing -------------------------------------------------------------------
+namespace {
+struct ProfileRecord {
+  KernelKind kind;
+  hipEvent_t start, stop;
+};
+std::mutex g_prof_mutex;
+std::vector<ProfileRecord> g_prof_records;
+bool g_prof_on = false;
+const char* const kKernelNames[kKernelKinds] = {
+    "pack_weights_kernel", "user_gemm_kernel", "expand_kernel", "merge_kernel",
+    "verify_probe_kernel", "verify_scan_kernel", "verify_scatter_kernel", "insert_kernel"};
+}  // namespace
+
+ProfileScope::ProfileScope(KernelKind kind, hipStream_t s) : slot(-1), stream(s) {
+  if (!g_prof_on) return;
+  ProfileRecord r;
+  r.kind = kind;
+  if (hipEventCreate(&r.start) != hipSuccess) return;
+  if (hipEventCreate(&r.stop) != hipSuccess) {
+    (void)hipEventDestroy(r.start);
+    return;
+  }
+  (void)hipEventRecord(r.start, stream);
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
+  g_prof_records.push_back(r);
+  slot = (int)g_prof_records.size() - 1;
+}
+ProfileScope::~ProfileScope() {
+  if (slot < 0) return;
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
+  if (slot < (int)g_prof_records.size()) (void)hipEventRecord(g_prof_records[slot].stop, stream);
 }
 
 bool radix_multipliers(int32_t L, const int32_t* radices, uint64_t* mult) {
@@ -304,8 +340,11 @@ int nezha_build_itemset(const int32_t* codes, int64_t n, int32_t L, const int32_
     }
     int64_t blocks = (m + 255) / 256;
     if (blocks > 262144) blocks = 262144;
-    hipLaunchKernelGGL(insert_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, m, r,
-                       s->slots, n_buckets, status);
+    {
+      ProfileScope prof(kInsert, stream);
+      hipLaunchKernelGGL(insert_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, m, r,
+                         s->slots, n_buckets, status);
+    }
     BUILD_CHECK(hipGetLastError());
     if (!codes_on_device) BUILD_CHECK(hipStreamSynchronize(stream));
   }
@@ -402,6 +441,8 @@ int nezha_verify_tuples(const nezha_itemset* set, const int32_t* codes, int64_t 
     block_count = static_cast<int32_t*>(workspace);
   }
   dim3 grid((unsigned)blocks), block(kVerifyThreads);
+  {
+  ProfileScope prof(kVerifyProbe, stream);
   switch (set->L) {
     case 3:
       hipLaunchKernelGGL(verify_probe_kernel<3>, grid, block, 0, stream, codes, n, r, view,
@@ -415,17 +456,61 @@ int nezha_verify_tuples(const nezha_itemset* set, const int32_t* codes, int64_t 
       hipLaunchKernelGGL(verify_probe_kernel<0>, grid, block, 0, stream, codes, n, r, view,
                          out_mask, block_count);
   }
+  }
   NEZHA_HIP_CHECK(hipGetLastError());
   if (compact) {
-    hipLaunchKernelGGL(verify_scan_kernel, dim3(1), dim3(1024), 0, stream,
-                       (const int32_t*)block_count, blocks, block_offset, out_count);
+    {
+      ProfileScope prof(kVerifyScan, stream);
+      hipLaunchKernelGGL(verify_scan_kernel, dim3(1), dim3(1024), 0, stream,
+                         (const int32_t*)block_count, blocks, block_offset, out_count);
+    }
     NEZHA_HIP_CHECK(hipGetLastError());
     if (out_index) {
+      ProfileScope prof(kVerifyScatter, stream);
       hipLaunchKernelGGL(verify_scatter_kernel, grid, block, 0, stream,
                          (const uint8_t*)out_mask, n, (const int64_t*)block_offset, out_index);
-      NEZHA_HIP_CHECK(hipGetLastError());
     }
+    NEZHA_HIP_CHECK(hipGetLastError());
   }
+  return NEZHA_OK;
+}
+
+int nezha_profile_enable(int on) {
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
+  g_prof_on = on != 0;
+  return NEZHA_OK;
+}
+
+int nezha_profile_reset(void) {
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
+  for (ProfileRecord& r : g_prof_records) {
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
+  g_prof_records.clear();
+  return NEZHA_OK;
+}
+
+int nezha_profile_kinds(void) { return (int)kKernelKinds; }
+
+int nezha_profile_read(int kind, const char** name, int64_t* launches, double* total_ms) {
+  if (kind < 0 || kind >= (int)kKernelKinds) return fail(NEZHA_EINVAL, "kind out of range");
+  if (name) *name = kKernelNames[kind];
+  int64_t n = 0;
+  double ms = 0.0;
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
+  for (const ProfileRecord& r : g_prof_records) {
+    if ((int)r.kind != kind) continue;
+    hipError_t e = hipEventSynchronize(r.stop);
+    float t = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, r.start, r.stop);
+    if (e != hipSuccess)
+      return fail(NEZHA_EHIP, "reading a timing event failed: %s", hipGetErrorString(e));
+    ms += t;
+    ++n;
+  }
+  if (launches) *launches = n;
+  if (total_ms) *total_ms = ms;
   return NEZHA_OK;
 }
 

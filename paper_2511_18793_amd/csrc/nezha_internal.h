@@ -25,6 +25,19 @@ int fail(int code, const char* fmt, ...);
 // Positional multipliers of Eq. 4; false if prod T_l > 2^64-1 or a radix < 1.
 bool radix_multipliers(int32_t L, const int32_t* radices, uint64_t* mult);
 
+// ---- optional per-kernel timing with HIP events (off by default) ------------------------
+enum KernelKind {
+  kPackWeights = 0, kUserGemm, kExpand, kMerge, kVerifyProbe, kVerifyScan, kVerifyScatter,
+  kInsert, kKernelKinds
+};
+// Brackets the launches made while it is alive with two events on `stream` when timing is on.
+struct ProfileScope {
+  ProfileScope(KernelKind kind, hipStream_t stream);
+  ~ProfileScope();
+  int slot;
+  hipStream_t stream;
+};
+
 struct SetView {  // what kernels need from an item set
   const uint64_t* slots;
   uint64_t n_buckets;
