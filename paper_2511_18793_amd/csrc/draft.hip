@@ -45,16 +45,52 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
 }
-__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int lane_mask) {
-  const int addr = ((int)(threadIdx.x & 63) ^ lane_mask) << 2;
-  uint32_t lo = (uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int)(uint32_t)v);
-  uint32_t hi = (uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int)(uint32_t)(v >> 32));
-  return ((uint64_t)hi << 32) | lo;
+
+// Value of lane (lane ^ M) for a compile-time M.  Distances 1, 2 and 8 are one DPP move
+// (quad permutes, rotation by 8 inside a row of 16 lanes); 4 takes the two rotations by 4 and
+// 12; 16 and 32 use the gfx950 row / half-wave swaps.
+template <int M>
+__device__ __forceinline__ uint32_t lane_xor(uint32_t v, int lane) {
+  if constexpr (M == 1) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true);
+  } else if constexpr (M == 2) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);
+  } else if constexpr (M == 4) {
+    const uint32_t down = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x124, 0xF, 0xF, true);
+    const uint32_t up = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x12C, 0xF, 0xF, true);
+    return (lane & 4) ? down : up;   // row_ror:4 reads lane-4, row_ror:12 reads lane+4
+  } else if constexpr (M == 8) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x128, 0xF, 0xF, true);
+  } else if constexpr (M == 16) {
+    const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    return (lane & 16) ? r[0] : r[1];
+  } else {
+    static_assert(M == 32, "lane distance");
+    const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return (lane & 32) ? r[0] : r[1];
+  }
 }
 
-// Bitonic sort of 64*NPL keys held NPL per lane, descending in position p = lane*NPL + j.
-template <int NPL>
-__device__ __forceinline__ void sort_desc(uint64_t (&key)[NPL]) {
+// One compare-exchange step of the bitonic network across lanes at distance LM, for R
+// independent sequences at once (independent work hides the cross-lane latency).
+template <int NPL, int R, int LM>
+__device__ __forceinline__ void cross_step(uint64_t (&key)[R][NPL], int lane, bool keep_max) {
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int j = 0; j < NPL; ++j) {
+      const uint32_t lo = lane_xor<LM>((uint32_t)key[r][j], lane);
+      const uint32_t hi = lane_xor<LM>((uint32_t)(key[r][j] >> 32), lane);
+      const uint64_t other = ((uint64_t)hi << 32) | lo;
+      const bool gt = key[r][j] > other;
+      key[r][j] = (gt == keep_max) ? key[r][j] : other;
+    }
+}
+
+// Bitonic sort of R sequences of 64*NPL keys, NPL per lane, descending in position
+// p = lane*NPL + j.
+template <int NPL, int R>
+__device__ __forceinline__ void sort_desc(uint64_t (&key)[R][NPL]) {
   const int lane = threadIdx.x & 63;
   constexpr int N = 64 * NPL;
 #pragma unroll
@@ -63,32 +99,83 @@ __device__ __forceinline__ void sort_desc(uint64_t (&key)[NPL]) {
     for (int dist = k >> 1; dist >= 1; dist >>= 1) {
       if (dist < NPL) {
 #pragma unroll
-        for (int j = 0; j < NPL; ++j) {
-          if ((j & dist) == 0) {
-            const int j2 = j | dist;
-            // block direction: descending where bit k of the position is clear
-            const bool desc = (k < NPL) ? ((j & k) == 0)
-                                        : (k == N ? true : ((lane & (k / NPL)) == 0));
-            const uint64_t a = key[j], b = key[j2];
-            const bool a_gt = a > b;
-            const bool swap = desc ? !a_gt : a_gt;
-            key[j] = swap ? b : a;
-            key[j2] = swap ? a : b;
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+          for (int j = 0; j < NPL; ++j) {
+            if ((j & dist) == 0) {
+              const int j2 = j | dist;
+              // block direction: descending where bit k of the position is clear
+              const bool desc = (k < NPL) ? ((j & k) == 0)
+                                          : (k == N ? true : ((lane & (k / NPL)) == 0));
+              const uint64_t a = key[r][j], b = key[r][j2];
+              const bool a_gt = a > b;
+              const bool swap = desc ? !a_gt : a_gt;
+              key[r][j] = swap ? b : a;
+              key[r][j2] = swap ? a : b;
+            }
           }
-        }
       } else {
         const int lm = dist / NPL;
         const bool is_lo = (lane & lm) == 0;
         const bool desc = (k == N) ? true : ((lane & (k / NPL)) == 0);
         const bool keep_max = (is_lo == desc);
-#pragma unroll
-        for (int j = 0; j < NPL; ++j) {
-          const uint64_t other = shfl_xor_u64(key[j], lm);
-          const bool gt = key[j] > other;
-          key[j] = (gt == keep_max) ? key[j] : other;
-        }
+        if (lm == 1) cross_step<NPL, R, 1>(key, lane, keep_max);
+        else if (lm == 2) cross_step<NPL, R, 2>(key, lane, keep_max);
+        else if (lm == 4) cross_step<NPL, R, 4>(key, lane, keep_max);
+        else if (lm == 8) cross_step<NPL, R, 8>(key, lane, keep_max);
+        else if (lm == 16) cross_step<NPL, R, 16>(key, lane, keep_max);
+        else cross_step<NPL, R, 32>(key, lane, keep_max);
       }
     }
+  }
+}
+
+// Cuts R LDS buffers (R rows) back to their K largest keys, sorted descending at buf[0..):
+// rows[r] points at CAP keys of which cnt[r] are in use.  On return cnt[r] = min(cnt[r], K)
+// and tau[r] is the K-th largest key (0 while fewer than K are held).  Wave uniform.
+template <int CAP, int NPL, int R>
+__device__ __forceinline__ void compact_rows_n(uint64_t* const (&rows)[R], int (&cnt)[R],
+                                               uint64_t (&tau)[R], int K) {
+  const int lane = threadIdx.x & 63;
+  uint64_t key[R][NPL];
+  wave_sync();
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int j = 0; j < NPL; ++j) {
+      const int e = j * 64 + lane;
+      key[r][j] = e < cnt[r] ? rows[r][e] : 0ull;
+    }
+  sort_desc<NPL, R>(key);
+  wave_sync();
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int keep = cnt[r] < K ? cnt[r] : K;
+#pragma unroll
+    for (int j = 0; j < NPL; ++j) {
+      const int p = lane * NPL + j;
+      if (p < keep) rows[r][p] = key[r][j];
+    }
+    cnt[r] = keep;
+  }
+  wave_sync();
+#pragma unroll
+  for (int r = 0; r < R; ++r) tau[r] = (cnt[r] == K) ? rows[r][K - 1] : 0ull;
+}
+
+// Picks the smallest network that holds every row (all counts are wave uniform).
+template <int CAP, int R>
+__device__ __forceinline__ void compact_rows(uint64_t* const (&rows)[R], int (&cnt)[R],
+                                             uint64_t (&tau)[R], int K) {
+  int most = 0;
+#pragma unroll
+  for (int r = 0; r < R; ++r) most = cnt[r] > most ? cnt[r] : most;
+  if (most <= 64) {
+    compact_rows_n<CAP, 1, R>(rows, cnt, tau, K);
+  } else if (CAP == 128 || most <= 128) {
+    compact_rows_n<CAP, 2, R>(rows, cnt, tau, K);
+  } else {
+    compact_rows_n<CAP, CAP / 64, R>(rows, cnt, tau, K);
   }
 }
 
@@ -110,26 +197,12 @@ struct WaveTopK {
   }
   // Sort, keep the K largest at buf[0..), update tau.
   __device__ __forceinline__ void compact() {
-    constexpr int NPL = CAP / 64;
-    const int lane = threadIdx.x & 63;
-    uint64_t key[NPL];
-    wave_sync();
-#pragma unroll
-    for (int j = 0; j < NPL; ++j) {
-      const int e = j * 64 + lane;
-      key[j] = e < cnt ? buf[e] : 0ull;
-    }
-    sort_desc<NPL>(key);
-    wave_sync();
-    const int keep = cnt < K ? cnt : K;
-#pragma unroll
-    for (int j = 0; j < NPL; ++j) {
-      const int p = lane * NPL + j;
-      if (p < keep) buf[p] = key[j];
-    }
-    wave_sync();
-    cnt = keep;
-    tau = (keep == K) ? buf[K - 1] : 0ull;
+    uint64_t* const rows[1] = {buf};
+    int c[1] = {cnt};
+    uint64_t t[1] = {0};
+    compact_rows<CAP, 1>(rows, c, t, K);
+    cnt = c[0];
+    tau = t[0];
   }
   // One key per lane (0 = nothing).  All lanes of the wave must call this together.
   __device__ __forceinline__ void push(uint64_t key) {
@@ -299,35 +372,39 @@ struct ExpandArgs {
   int KS_total;          // bf16: (d+e)/32
 };
 
-// One wave per workgroup, 16 beams (rows) per wave.  For each block of 64 codes the wave forms
-// the 16x64 logits in four 16x16 MFMA accumulators (initialised with the user part), updates
-// every row's running (max, sum of exponentials) and appends the logits above the row's
-// current threshold to the row's LDS buffer.  Buffers are cut back to the K best by a
-// sort when they run short of room, which raises the threshold.  Register i of lane l
-// belongs to row 4*(l/16)+i and code column l%16 of the tile.
-template <bool BF16, int CAP>
-__global__ __launch_bounds__(64) void expand_kernel(ExpandArgs a) {
+// A workgroup of NW waves owns 16 beams (rows); wave w takes the blocks of 64 codes
+// w, w+NW, ...  For each block the wave forms the 16x64 logits in four 16x16 MFMA
+// accumulators (initialised with the user part), updates every row's running (max, sum of
+// exponentials) and appends the logits above the row's current threshold to the row's LDS
+// buffer.  Buffers are cut back to the K best by a sort when they run short of room, which
+// raises the threshold.  Register i of lane l belongs to row 4*(l/16)+i and code column l%16
+// of the tile.  With NW > 1 the waves' per-row lists are merged at the end (NW*K <= CAP).
+// KST: compile-time bound on the number of MFMA steps over e (bf16: e/32, f32: e/4).
+template <bool BF16, int CAP, int KST, int NW>
+__global__ __launch_bounds__(64 * NW) void expand_kernel(ExpandArgs a) {
   extern __shared__ __align__(16) uint64_t lds[];
-  uint64_t* buf = lds;                                   // [16][CAP]
-  float* row_lse = reinterpret_cast<float*>(lds + 16 * CAP);   // [16]
-  int* row_cnt = reinterpret_cast<int*>(row_lse + 16);          // [16]
+  uint64_t* buf_all = lds;                                            // [NW][16][CAP]
+  float* part_m = reinterpret_cast<float*>(lds + NW * 16 * CAP);      // [NW][16]
+  float* part_s = part_m + NW * 16;                                   // [NW][16]
+  int* part_cnt = reinterpret_cast<int*>(part_s + NW * 16);           // [NW][16]
 
-  const int lane = threadIdx.x, g = lane >> 4, c = lane & 15;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int g = lane >> 4, c = lane & 15;
   const int R0 = blockIdx.x * 16;
   const int V = a.V, K = a.K, e = a.e;
   const bool has_beam = a.state != nullptr;
-  constexpr int KSMAX = BF16 ? 8 : 64;
   const int KS = BF16 ? e / 32 : e / 4;
+  uint64_t* buf = buf_all + wave * 16 * CAP;
 
   // A operands of the MFMA: this lane's row is R0 + c
-  bf16x8 fa16[BF16 ? KSMAX : 1];
-  float fa32[BF16 ? 1 : KSMAX];
+  bf16x8 fa16[BF16 ? KST : 1];
+  float fa32[BF16 ? 1 : KST];
   if (has_beam) {
     const int row = R0 + c;
     if constexpr (BF16) {
       const uint16_t* st = static_cast<const uint16_t*>(a.state);
 #pragma unroll
-      for (int ks = 0; ks < KSMAX; ++ks) {
+      for (int ks = 0; ks < KST; ++ks) {
         uint4 v = uint4{0, 0, 0, 0};
         if (ks < KS && row < a.rows)
           v = *reinterpret_cast<const uint4*>(st + (int64_t)row * e + ks * 32 + 8 * g);
@@ -336,7 +413,7 @@ __global__ __launch_bounds__(64) void expand_kernel(ExpandArgs a) {
     } else {
       const float* st = static_cast<const float*>(a.state);
 #pragma unroll
-      for (int ks = 0; ks < KSMAX; ++ks)
+      for (int ks = 0; ks < KST; ++ks)
         fa32[ks] = (ks < KS && row < a.rows) ? st[(int64_t)row * e + ks * 4 + g] : 0.f;
     }
   }
@@ -345,60 +422,81 @@ __global__ __launch_bounds__(64) void expand_kernel(ExpandArgs a) {
   float tau[4], m[4], s[4];
   int cnt[4];
   int64_t a_off[4];
-  bool row_ok[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int row = R0 + 4 * g + i;
-    row_ok[i] = row < a.rows;
-    tau[i] = row_ok[i] ? -INFINITY : INFINITY;
+    const bool ok = row < a.rows;
+    tau[i] = ok ? -INFINITY : INFINITY;
     m[i] = -INFINITY;
     s[i] = 0.f;
     cnt[i] = 0;
-    a_off[i] = (int64_t)((row_ok[i] ? row : 0) / a.K_in) * V;
+    a_off[i] = (int64_t)((ok ? row : 0) / a.K_in) * V;
   }
-  const int lim = CAP - 64;
+  constexpr int lim = CAP - 64;
   const int n_ct = V / 16;
+  const int n_blk = (n_ct + 3) / 4;
 
-  for (int ct0 = 0; ct0 < n_ct; ct0 += 4) {
-    floatx4 acc[4];
+  // operands of one block of 64 codes: the user part (accumulator start values) and, for
+  // bf16, the packed B operands, fetched one block ahead of their use
+  float aq[4][4];
+  uint4 bq[4][BF16 ? KST : 1];
+  auto fetch = [&](int blk) {
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      const int ct = ct0 + t;
+      const int ct = blk * 4 + t;
       if (ct < n_ct) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) acc[t][i] = a.A[a_off[i] + ct * 16 + c];
-      } else {
-        acc[t] = floatx4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-      }
-    }
-    if (has_beam) {
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const int ct = ct0 + t;
-        if (ct < n_ct) {
-          if constexpr (BF16) {
+        for (int i = 0; i < 4; ++i) aq[t][i] = a.A[a_off[i] + ct * 16 + c];
+        if constexpr (BF16) {
+          if (has_beam) {
             const uint4* wp = static_cast<const uint4*>(a.Wbeam) +
                               ((int64_t)ct * a.KS_total + a.d / 32) * 64 + lane;
 #pragma unroll
-            for (int ks = 0; ks < KSMAX; ++ks) {
-              if (ks < KS) {
-                uint4 v = wp[ks * 64];
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                    fa16[ks], *reinterpret_cast<bf16x8*>(&v), acc[t], 0, 0, 0);
-              }
-            }
-          } else {
-            const float* w = static_cast<const float*>(a.Wbeam) + (int64_t)a.d * V + ct * 16 + c;
-#pragma unroll
-            for (int ks = 0; ks < KSMAX; ++ks) {
-              if (ks < KS) {
-                const float bv = w[(int64_t)(ks * 4 + g) * V];
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa32[ks], bv, acc[t], 0, 0, 0);
-              }
-            }
+            for (int ks = 0; ks < KST; ++ks)
+              if (ks < KS) bq[t][ks] = wp[ks * 64];
           }
         }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) aq[t][i] = -INFINITY;
       }
+    }
+  };
+  auto project = [&](int blk, floatx4 (&acc)[4]) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      acc[t] = floatx4{aq[t][0], aq[t][1], aq[t][2], aq[t][3]};
+      const int ct = blk * 4 + t;
+      if (has_beam && ct < n_ct) {
+        if constexpr (BF16) {
+#pragma unroll
+          for (int ks = 0; ks < KST; ++ks)
+            if (ks < KS)
+              acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                  fa16[ks], *reinterpret_cast<bf16x8*>(&bq[t][ks]), acc[t], 0, 0, 0);
+        } else {
+          const float* w = static_cast<const float*>(a.Wbeam) + (int64_t)a.d * V + ct * 16 + c;
+#pragma unroll
+          for (int ks = 0; ks < KST; ++ks)
+            if (ks < KS)
+              acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(
+                  fa32[ks], w[(int64_t)(ks * 4 + g) * V], acc[t], 0, 0, 0);
+        }
+      }
+    }
+  };
+
+  floatx4 acc[4], acc_next[4];
+  int blk = wave;
+  if (blk < n_blk) {
+    fetch(blk);
+    project(blk, acc);
+    if (blk + NW < n_blk) fetch(blk + NW);
+  }
+  for (; blk < n_blk; blk += NW) {
+    if (blk + NW < n_blk) {
+      project(blk + NW, acc_next);                 // MFMAs run while the block below is scanned
+      if (blk + 2 * NW < n_blk) fetch(blk + 2 * NW);
     }
     // running log-sum-exp, one (max, sum) pair per lane and row
 #pragma unroll
@@ -423,36 +521,36 @@ __global__ __launch_bounds__(64) void expand_kernel(ExpandArgs a) {
           const uint32_t grp = (uint32_t)(bal >> (16 * g)) & 0xFFFFu;
           const int pos = cnt[i] + __popc(grp & ((1u << c) - 1u));
           if (pass) {
-            const uint32_t code = (uint32_t)((ct0 + t) * 16 + c);
+            const uint32_t code = (uint32_t)((blk * 4 + t) * 16 + c);
             buf[(4 * g + i) * CAP + pos] = ((uint64_t)ordered_bits(z) << 32) | (uint32_t)~code;
           }
           cnt[i] += __popc(grp);
         }
       }
     }
-    // rows that could overflow on the next block of 64 codes are cut back to their K best
+    // rows that could overflow on the next block are cut back to their K best, four rows
+    // (one accumulator register index) at a time
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      uint64_t fb = __ballot(cnt[i] > lim);
-      while (fb) {
-        const int l0 = __builtin_ctzll(fb);
-        const int gg = l0 >> 4;
-        fb &= ~(0xFFFFull << (16 * gg));
-        WaveTopK<CAP> q;
-        q.buf = buf + (4 * gg + i) * CAP;
-        q.cnt = __builtin_amdgcn_readlane(cnt[i], l0);
-        q.K = K;
-        q.tau = 0;
-        q.compact();
-        if (g == gg) {
-          cnt[i] = q.cnt;
-          tau[i] = (q.cnt == K) ? unordered_bits((uint32_t)(q.tau >> 32)) : -INFINITY;
-        }
+      if (__ballot(cnt[i] > lim)) {
+        uint64_t* const rows[4] = {buf + (0 + i) * CAP, buf + (4 + i) * CAP, buf + (8 + i) * CAP,
+                                   buf + (12 + i) * CAP};
+        int rc[4] = {__builtin_amdgcn_readlane(cnt[i], 0), __builtin_amdgcn_readlane(cnt[i], 16),
+                     __builtin_amdgcn_readlane(cnt[i], 32), __builtin_amdgcn_readlane(cnt[i], 48)};
+        uint64_t rt[4];
+        compact_rows<CAP, 4>(rows, rc, rt, K);
+        const int my_cnt = g == 0 ? rc[0] : g == 1 ? rc[1] : g == 2 ? rc[2] : rc[3];
+        const uint64_t my_tau = g == 0 ? rt[0] : g == 1 ? rt[1] : g == 2 ? rt[2] : rt[3];
+        cnt[i] = my_cnt;
+        if (tau[i] != INFINITY)
+          tau[i] = (my_cnt == K) ? unordered_bits((uint32_t)(my_tau >> 32)) : -INFINITY;
       }
     }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) acc[t] = acc_next[t];
   }
 
-  // log-sum-exp of each row: merge the 16 lanes' (max, sum) pairs of every group
+  // this wave's (max, sum) of each row: merge the 16 lanes of every group
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     float mm = m[i], ss = s[i];
@@ -461,34 +559,92 @@ __global__ __launch_bounds__(64) void expand_kernel(ExpandArgs a) {
       const float om = __shfl_xor(mm, off);
       const float os = __shfl_xor(ss, off);
       const float mn = fmaxf(mm, om);
-      ss = ss * __builtin_amdgcn_exp2f((mm - mn) * kLog2e) +
-           os * __builtin_amdgcn_exp2f((om - mn) * kLog2e);
+      const float wa = (mm == mn) ? 1.f : __builtin_amdgcn_exp2f((mm - mn) * kLog2e);
+      const float wb = (om == mn) ? 1.f : __builtin_amdgcn_exp2f((om - mn) * kLog2e);
+      ss = ss * wa + os * wb;
       mm = mn;
     }
     if (c == 0) {
-      row_lse[4 * g + i] = mm + __builtin_amdgcn_logf(ss) * kLn2;
-      row_cnt[4 * g + i] = cnt[i];
+      part_m[wave * 16 + 4 * g + i] = mm;
+      part_s[wave * 16 + 4 * g + i] = ss;
+      part_cnt[wave * 16 + 4 * g + i] = cnt[i];
     }
   }
-  __syncthreads();
-  constexpr int NPL = CAP / 64;
-  for (int r = 0; r < 16; ++r) {
-    const int row = R0 + r;
-    if (row >= a.rows) break;
-    WaveTopK<CAP> q;
-    q.buf = buf + r * CAP;
-    q.cnt = row_cnt[r];
-    q.K = K;
-    q.tau = 0;
-    q.compact();
-    const float lse = row_lse[r];
+  wave_sync();
+  // final cut of this wave's 16 rows: sorted K best at the front of each buffer
+  for (int r0 = 0; r0 < 16; r0 += 4) {
+    uint64_t* const rows[4] = {buf + r0 * CAP, buf + (r0 + 1) * CAP, buf + (r0 + 2) * CAP,
+                               buf + (r0 + 3) * CAP};
+    int rc[4];
+    uint64_t rt[4];
 #pragma unroll
-    for (int j = 0; j < NPL; ++j) {
-      const int p = lane * NPL + j;   // compact() left the sorted keys at buf[0..K)
-      if (p < q.cnt) {
-        const uint64_t key = q.buf[p];
+    for (int r = 0; r < 4; ++r)
+      rc[r] = __builtin_amdgcn_readfirstlane(part_cnt[wave * 16 + r0 + r]);
+    compact_rows<CAP, 4>(rows, rc, rt, K);
+    if (lane == 0) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) part_cnt[wave * 16 + r0 + r] = rc[r];
+    }
+  }
+  if constexpr (NW == 1) {
+    wave_sync();
+    for (int r = 0; r < 16; ++r) {
+      const int row = R0 + r;
+      if (row >= a.rows) break;
+      const float lse = part_m[r] + __builtin_amdgcn_logf(part_s[r]) * kLn2;
+      const int n = part_cnt[r];
+      for (int p = lane; p < n; p += 64) {
+        const uint64_t key = buf[r * CAP + p];
         a.cand_code[(int64_t)row * K + p] = (int32_t)(~(uint32_t)key);
         a.cand_logp[(int64_t)row * K + p] = unordered_bits((uint32_t)(key >> 32)) - lse;
+      }
+    }
+  } else {
+    __syncthreads();
+    // wave w merges rows w*RPW .. : every row's NW sorted lists (at most NW*K <= CAP keys)
+    constexpr int RPW = 16 / NW;
+    constexpr int NPL = CAP / 64;
+    static_assert(RPW >= 1 && RPW <= 4, "rows per wave in the merge");
+    uint64_t key[RPW][NPL];
+#pragma unroll
+    for (int r = 0; r < RPW; ++r) {
+      const int lr = wave * RPW + r;
+#pragma unroll
+      for (int j = 0; j < NPL; ++j) {
+        const int el = j * 64 + lane;
+        const int w = el / K, idx = el - w * K;
+        key[r][j] = (w < NW && idx < part_cnt[w * 16 + lr]) ? buf_all[(w * 16 + lr) * CAP + idx]
+                                                            : 0ull;
+      }
+    }
+    sort_desc<NPL, RPW>(key);
+#pragma unroll
+    for (int r = 0; r < RPW; ++r) {
+      const int lr = wave * RPW + r, row = R0 + lr;
+      if (row < a.rows) {
+        float mm = part_m[lr], ss = part_s[lr];
+        int total = part_cnt[lr];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) {
+          const float om = part_m[w * 16 + lr], os = part_s[w * 16 + lr];
+          const float mn = fmaxf(mm, om);
+          const float wa = (mm == mn) ? 1.f : __builtin_amdgcn_exp2f((mm - mn) * kLog2e);
+          const float wb = (om == mn) ? 1.f : __builtin_amdgcn_exp2f((om - mn) * kLog2e);
+          ss = ss * wa + os * wb;
+          mm = mn;
+          total += part_cnt[w * 16 + lr];
+        }
+        const float lse = mm + __builtin_amdgcn_logf(ss) * kLn2;
+        const int n = total < K ? total : K;
+#pragma unroll
+        for (int j = 0; j < NPL; ++j) {
+          const int p = lane * NPL + j;
+          if (p < n) {
+            a.cand_code[(int64_t)row * K + p] = (int32_t)(~(uint32_t)key[r][j]);
+            a.cand_logp[(int64_t)row * K + p] =
+                unordered_bits((uint32_t)(key[r][j] >> 32)) - lse;
+          }
+        }
       }
     }
   }
@@ -812,19 +968,37 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
   ea.e = e;
   ea.KS_total = KS_total;
   {
-    const size_t lds = (size_t)16 * plan.cap * 8 + 16 * 4 + 16 * 4;
-    dim3 grid((rows + 15) / 16), block(64);
+    // Few rows (a small batch): split each row group's codes over 4 waves so that more of the
+    // chip works and every wave's serial top-K chain is shorter.  Needs 4*K <= CAP for the
+    // final merge and at least 4 blocks of 64 codes.
+    const int groups = (rows + 15) / 16;
+    const bool split = bf16 && groups <= 1024 && V >= 256 && 4 * K <= plan.cap;
+    const int nw = split ? 4 : 1;
+    const size_t lds = (size_t)nw * 16 * plan.cap * 8 + (size_t)nw * 16 * 12;
+    dim3 grid(groups), block(64 * nw);
     ProfileScope prof(kExpand, stream);
-#define LAUNCH_EXPAND(BF, CAPV)                                                       \
-  do {                                                                                \
-    rc = allow_lds(expand_kernel<BF, CAPV>, lds);                                     \
-    if (rc != NEZHA_OK) return rc;                                                    \
-    hipLaunchKernelGGL((expand_kernel<BF, CAPV>), grid, block, lds, stream, ea);      \
+#define LAUNCH_EXPAND(BF, CAPV, KSTV, NWV)                                                    \
+  do {                                                                                        \
+    rc = allow_lds(expand_kernel<BF, CAPV, KSTV, NWV>, lds);                                  \
+    if (rc != NEZHA_OK) return rc;                                                            \
+    hipLaunchKernelGGL((expand_kernel<BF, CAPV, KSTV, NWV>), grid, block, lds, stream, ea);   \
   } while (0)
-    if (bf16 && plan.cap == 128) LAUNCH_EXPAND(true, 128);
-    else if (bf16) LAUNCH_EXPAND(true, 256);
-    else if (plan.cap == 128) LAUNCH_EXPAND(false, 128);
-    else LAUNCH_EXPAND(false, 256);
+#define LAUNCH_EXPAND_BF16(CAPV, NWV)                                  \
+  do {                                                                 \
+    if (e <= 64) LAUNCH_EXPAND(true, CAPV, 2, NWV);                    \
+    else if (e <= 128) LAUNCH_EXPAND(true, CAPV, 4, NWV);              \
+    else LAUNCH_EXPAND(true, CAPV, 8, NWV);                            \
+  } while (0)
+    if (bf16) {
+      if (plan.cap == 128 && nw == 4) LAUNCH_EXPAND_BF16(128, 4);
+      else if (plan.cap == 128) LAUNCH_EXPAND_BF16(128, 1);
+      else if (nw == 4) LAUNCH_EXPAND_BF16(256, 4);
+      else LAUNCH_EXPAND_BF16(256, 1);
+    } else {
+      if (plan.cap == 128) LAUNCH_EXPAND(false, 128, 64, 1);
+      else LAUNCH_EXPAND(false, 256, 64, 1);
+    }
+#undef LAUNCH_EXPAND_BF16
 #undef LAUNCH_EXPAND
     NEZHA_HIP_CHECK(hipGetLastError());
   }
