@@ -48,6 +48,9 @@ def parse_args():
     ap.add_argument("--eager", action="store_true",
                     help="launch every step through the C ABI instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run a plain elementwise copy of 256 MiB (torch.mul by 1) three "
+                         "times, so that hardware counters of a profiler run can be scaled")
     ap.add_argument("--batch", type=int, default=0, help="override B (debugging)")
     ap.add_argument("--catalog", type=int, default=0, help="override N (debugging)")
     return ap.parse_args()
@@ -266,6 +269,30 @@ def bench_stress(args, cfg):
     nz.profile_enable(False)
     nz.profile_reset()
     launches, ms = prof["verify_probe_kernel"]
+    # the same kernel on queries whose present keys are drawn uniformly (no help from caches)
+    qu, _ = synth.stress_queries(cfg.radices, N, pi, args.seed + 1, cfg.queries, zipf=False)
+    qud = torch.from_numpy(qu).to(dev)
+    # what the memory system delivers for independent random line reads over a buffer of the
+    # table's size: the denominator for "fraction of achievable random-access bandwidth"
+    table_bytes = itemset.info()["n_slots"] * 8
+    scratch = torch.zeros(table_bytes // 8, dtype=torch.int64, device=dev)
+    nz.profile_enable(True)
+    for _ in range(prof_steps):
+        nz.verify_tuples(itemset, qud, mask, idx, cnt, ws)
+    torch.cuda.synchronize()
+    uni_launches, uni_ms = nz.profile_read()["verify_probe_kernel"]
+    nz.profile_reset()
+    gather = {}
+    for line in (64, 128):
+        for _ in range(prof_steps + 3):
+            nz.bench_random_gather(scratch, n, line)
+        torch.cuda.synchronize()
+        gl, gms = nz.profile_read()["random_gather_kernel"]
+        nz.profile_reset()
+        gather[line] = {"lines_per_s": n * gl / (gms * 1e-3), "GBps": n * line * gl / (gms * 1e-3) / 1e9,
+                        "avg_us": 1e3 * gms / gl}
+    nz.profile_enable(False)
+    del scratch
     bytes_per_probe = 4 * cfg.L + BUCKET_BYTES + 1
     achieved = n * bytes_per_probe * launches / (ms * 1e-3) / 1e9
     ms_per_step = total_ms / args.steps
@@ -283,7 +310,12 @@ def bench_stress(args, cfg):
         "roofline": {"kernel": "verify_probe_kernel", "bound": "hbm", "achieved": achieved,
                      "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS,
                      "traffic": None, "avg_launch_us": 1e3 * ms / launches,
-                     "bytes_per_probe": bytes_per_probe},
+                     "bytes_per_probe": bytes_per_probe,
+                     "probes_per_s": n * launches / (ms * 1e-3),
+                     "uniform_present_probes_per_s": n * uni_launches / (uni_ms * 1e-3),
+                     "random_gather_64B": gather[64], "random_gather_128B": gather[128],
+                     "frac_of_achievable_random_access":
+                         (n * uni_launches / (uni_ms * 1e-3)) / gather[64]["lines_per_s"]},
         "kernels": {k: {"avg_us": round(1e3 * v[1] / v[0], 3), "launches": v[0]}
                     for k, v in prof.items()},
     }
@@ -311,6 +343,13 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
+    if args.calibrate:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     cfg = synth.get_config(args.workload)
     if args.batch:
         cfg = cfg.scaled(B=args.batch)

@@ -160,6 +160,14 @@ int nezha_profile_reset(void);
 int nezha_profile_kinds(void);
 int nezha_profile_read(int kind, const char** name, int64_t* launches, double* total_ms);
 
+/* Measurement aid for the verifier's roofline: n independent reads of whole, aligned lines of
+ * line_bytes (64 or 128) at pseudo-random places of the device buffer buf (bytes long, 128-byte
+ * aligned), four reads in flight per lane as in the verifier.  Timing n * line_bytes against the
+ * kernel's duration gives the random-access bandwidth the memory system can actually deliver
+ * for that buffer size.  sink: device uint64 [1], scratch.  Asynchronous on hip_stream. */
+int nezha_bench_random_gather(const void* buf, size_t bytes, int64_t n, int line_bytes,
+                              uint64_t seed, void* sink, void* hip_stream);
+
 /* Inverse of Eq. 4 on the host: keys[n] -> codes int32 [n, L] (level 1 first).  Host pointers. */
 int nezha_unpack_keys(const uint64_t* keys, int64_t n, int32_t L, const int32_t* radices,
                       int32_t* codes);

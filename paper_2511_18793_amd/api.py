@@ -15,7 +15,8 @@ MAX_LEVELS = 8
 EXPORTS = ["nezha_last_error", "nezha_build_itemset", "nezha_itemset_info", "nezha_free_itemset",
            "nezha_verify_tuples", "nezha_verify_workspace", "nezha_draft_step",
            "nezha_draft_step_workspace", "nezha_unpack_keys", "nezha_profile_enable",
-           "nezha_profile_reset", "nezha_profile_kinds", "nezha_profile_read"]
+           "nezha_profile_reset", "nezha_profile_kinds", "nezha_profile_read",
+           "nezha_bench_random_gather"]
 
 
 class NezhaError(RuntimeError):
@@ -241,6 +242,17 @@ def decode(H, W, E, radices, K, itemset=None, buffers=None, stream=None):
                        workspace=buffers.workspace, stream=stream, h_row_stride=H.stride(0))
         state, key, score = o.get("state"), o["key"], o["score"]
     return buffers.outs
+
+
+def bench_random_gather(buf, n, line_bytes=64, seed=1, stream=None):
+    """nezha_bench_random_gather over the CUDA tensor `buf` (any dtype, 128-byte aligned)."""
+    sink = torch.zeros(1, dtype=torch.int64, device=buf.device)
+    lib = load_library()
+    lib.nezha_bench_random_gather.argtypes = [C.c_void_p, C.c_size_t, C.c_int64, C.c_int,
+                                              C.c_uint64, C.c_void_p, C.c_void_p]
+    _check(lib.nezha_bench_random_gather(_ptr(buf), buf.numel() * buf.element_size(), int(n),
+                                         int(line_bytes), int(seed), _ptr(sink), _stream(stream)))
+    return sink
 
 
 def profile_enable(on):

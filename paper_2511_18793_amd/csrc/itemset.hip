@@ -32,7 +32,8 @@ std::vector<ProfileRecord> g_prof_records;
 bool g_prof_on = false;
 const char* const kKernelNames[kKernelKinds] = {
     "pack_weights_kernel", "user_gemm_kernel", "expand_kernel", "merge_kernel",
-    "verify_probe_kernel", "verify_scan_kernel", "verify_scatter_kernel", "insert_kernel"};
+    "verify_probe_kernel", "verify_scan_kernel", "verify_scatter_kernel", "insert_kernel",
+    "random_gather_kernel"};
 }  // namespace
 
 ProfileScope::ProfileScope(KernelKind kind, hipStream_t s) : slot(-1), stream(s) {
@@ -131,6 +132,7 @@ __global__ void insert_kernel(const int32_t* __restrict__ codes, int64_t n, Radi
 constexpr int kVerifyThreads = 256;
 constexpr int kPerThread = 4;                                 // consecutive tuples per lane
 constexpr int kVerifyBlock = kVerifyThreads * kPerThread;     // tuples per workgroup
+constexpr int64_t kFusedPrefixBlocks = 16384;                 // above this a scan kernel runs
 
 // Pass 1: pack + probe, write the mask bytes and the number of accepted tuples per block.
 template <int L>
@@ -212,10 +214,30 @@ __global__ __launch_bounds__(1024) void verify_scan_kernel(const int32_t* __rest
 
 // Pass 3: every block turns its mask bytes into ascending indices at its offset
 // (ballot-free per-lane popcounts, wave prefix by cross-lane adds, LDS across waves).
+//
+// block_offset != NULL: the offsets come from verify_scan_kernel.  block_offset == NULL: every
+// block sums the counts of the blocks before it itself (cheap up to a few thousand blocks) and
+// the last block writes the grand total to out_count.
 __global__ __launch_bounds__(kVerifyThreads) void verify_scatter_kernel(
     const uint8_t* __restrict__ mask, int64_t n, const int64_t* __restrict__ block_offset,
-    int64_t* __restrict__ out_index) {
+    const int32_t* __restrict__ block_count, int64_t* __restrict__ out_index,
+    int64_t* __restrict__ out_count) {
   __shared__ int32_t wave_total[kVerifyThreads / 64];
+  __shared__ int64_t wave_before[kVerifyThreads / 64];
+  int64_t offset = 0;
+  if (block_offset) {
+    offset = block_offset[blockIdx.x];
+  } else {
+    int64_t part = 0;
+    for (int i = threadIdx.x; i < (int)blockIdx.x; i += kVerifyThreads) part += block_count[i];
+    for (int off = 32; off > 0; off >>= 1) part += __shfl_down(part, off);
+    if ((threadIdx.x & 63) == 0) wave_before[threadIdx.x >> 6] = part;
+    __syncthreads();
+    for (int w = 0; w < kVerifyThreads / 64; ++w) offset += wave_before[w];
+    if (out_count && blockIdx.x == gridDim.x - 1 && threadIdx.x == 0)
+      *out_count = offset + block_count[blockIdx.x];
+    if (!out_index) return;
+  }
   const int64_t base = ((int64_t)blockIdx.x * kVerifyThreads + threadIdx.x) * kPerThread;
   uint32_t bits = 0;
   if (base + kPerThread <= n && (reinterpret_cast<uintptr_t>(mask) & 3) == 0) {
@@ -233,11 +255,35 @@ __global__ __launch_bounds__(kVerifyThreads) void verify_scatter_kernel(
   }
   if (lane == 63) wave_total[wave] = incl;
   __syncthreads();
-  int64_t pos = block_offset[blockIdx.x] + incl - mine;
+  int64_t pos = offset + incl - mine;
   for (int w = 0; w < wave; ++w) pos += wave_total[w];
 #pragma unroll
   for (int j = 0; j < kPerThread; ++j)
     if ((bits >> (8 * j)) & 1u) out_index[pos++] = base + j;
+}
+
+// Measurement aid: n independent reads of whole lines (LINE bytes, LINE-aligned) at pseudo-random
+// places of a buffer, four in flight per lane like the verifier's probes.  The loaded words are
+// folded into one value so the reads cannot be dropped.
+template <int LINE>
+__global__ __launch_bounds__(256) void random_gather_kernel(const uint64_t* __restrict__ buf,
+                                                            uint64_t n_lines, int64_t n,
+                                                            uint64_t seed, uint64_t* sink) {
+  const int64_t base = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  uint64_t acc = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (base + j < n) {
+      const uint64_t line = __umul64hi(hash64(seed + (uint64_t)(base + j)), n_lines);
+      const ulonglong2* p = reinterpret_cast<const ulonglong2*>(buf + line * (LINE / 8));
+#pragma unroll
+      for (int q = 0; q < LINE / 16; ++q) {
+        ulonglong2 v = p[q];
+        acc ^= v.x + v.y;
+      }
+    }
+  }
+  if (acc == 0x0123456789ABCDEFull) sink[0] = acc;   // practically never; keeps the loads alive
 }
 
 }  // namespace
@@ -458,7 +504,13 @@ int nezha_verify_tuples(const nezha_itemset* set, const int32_t* codes, int64_t 
   }
   }
   NEZHA_HIP_CHECK(hipGetLastError());
-  if (compact) {
+  if (compact && blocks <= kFusedPrefixBlocks) {
+    // few blocks: the scatter pass forms its own offsets, no separate scan launch
+    ProfileScope prof(kVerifyScatter, stream);
+    hipLaunchKernelGGL(verify_scatter_kernel, grid, block, 0, stream, (const uint8_t*)out_mask, n,
+                       (const int64_t*)nullptr, (const int32_t*)block_count, out_index, out_count);
+    NEZHA_HIP_CHECK(hipGetLastError());
+  } else if (compact) {
     {
       ProfileScope prof(kVerifyScan, stream);
       hipLaunchKernelGGL(verify_scan_kernel, dim3(1), dim3(1024), 0, stream,
@@ -468,10 +520,33 @@ int nezha_verify_tuples(const nezha_itemset* set, const int32_t* codes, int64_t 
     if (out_index) {
       ProfileScope prof(kVerifyScatter, stream);
       hipLaunchKernelGGL(verify_scatter_kernel, grid, block, 0, stream,
-                         (const uint8_t*)out_mask, n, (const int64_t*)block_offset, out_index);
+                         (const uint8_t*)out_mask, n, (const int64_t*)block_offset,
+                         (const int32_t*)block_count, out_index, (int64_t*)nullptr);
     }
     NEZHA_HIP_CHECK(hipGetLastError());
   }
+  return NEZHA_OK;
+}
+
+int nezha_bench_random_gather(const void* buf, size_t bytes, int64_t n, int line_bytes,
+                              uint64_t seed, void* sink, void* hip_stream) {
+  if (!buf || !sink || n < 0 || (line_bytes != 64 && line_bytes != 128) ||
+      bytes < (size_t)line_bytes || (reinterpret_cast<uintptr_t>(buf) & 127))
+    return fail(NEZHA_EINVAL, "bad argument");
+  if (n == 0) return NEZHA_OK;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  const uint64_t n_lines = bytes / (size_t)line_bytes;
+  dim3 grid((unsigned)((n + 1023) / 1024)), block(256);
+  ProfileScope prof(kGather, stream);
+  if (line_bytes == 64)
+    hipLaunchKernelGGL(random_gather_kernel<64>, grid, block, 0, stream,
+                       static_cast<const uint64_t*>(buf), n_lines, n, seed,
+                       static_cast<uint64_t*>(sink));
+  else
+    hipLaunchKernelGGL(random_gather_kernel<128>, grid, block, 0, stream,
+                       static_cast<const uint64_t*>(buf), n_lines, n, seed,
+                       static_cast<uint64_t*>(sink));
+  NEZHA_HIP_CHECK(hipGetLastError());
   return NEZHA_OK;
 }
 
