@@ -149,6 +149,14 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
                      size_t workspace_bytes, void* hip_stream);
 size_t nezha_draft_step_workspace(const nezha_step_desc* desc); /* 0 if desc is invalid */
 
+/* The beam-independent part of Eq. 2 alone: A_out[b, :] = h_{b,l} W_l[0:d, :] as float32
+ * [B, T_level] (these are the level-1 logits, where the state is zero).  Same desc, H_l, W_l,
+ * alignment and workspace rules as nezha_draft_step; K, K_in and the outputs are not used.
+ * Asynchronous on hip_stream. */
+int nezha_user_projection(const nezha_step_desc* desc, const void* H_l, const void* W_l,
+                          float* A_out, void* workspace, size_t workspace_bytes,
+                          void* hip_stream);
+
 /* ---- per-kernel timing (measurement aid, not part of the paper's method) -----------------
  * While enabled, every kernel launch of the library is bracketed by two HIP events on the
  * launch stream (this creates events, so calls made while it is on cannot be captured into a

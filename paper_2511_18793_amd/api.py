@@ -16,7 +16,7 @@ EXPORTS = ["nezha_last_error", "nezha_build_itemset", "nezha_itemset_info", "nez
            "nezha_verify_tuples", "nezha_verify_workspace", "nezha_draft_step",
            "nezha_draft_step_workspace", "nezha_unpack_keys", "nezha_profile_enable",
            "nezha_profile_reset", "nezha_profile_kinds", "nezha_profile_read",
-           "nezha_bench_random_gather"]
+           "nezha_bench_random_gather", "nezha_user_projection"]
 
 
 class NezhaError(RuntimeError):
@@ -202,6 +202,28 @@ def draft_step(level, L, radices, K, H_l, W_l, E_l=None, state_in=None, key_in=N
         _ptr(score_in), itemset._h if itemset is not None else None, _ptr(out["key"]),
         _ptr(out["score"]), _ptr(out["parent"]), _ptr(out["code"]), _ptr(out.get("state")),
         _ptr(out["count"]), _ptr(workspace), workspace.numel(), _stream(stream)))
+    return out
+
+
+def user_projection(level, L, radices, H_l, W_l, out=None, workspace=None, stream=None,
+                    h_row_stride=None):
+    """nezha_user_projection: float32 [B, T_level] = H_l @ W_l[:d]."""
+    B, d = H_l.shape
+    V = int(radices[level - 1])
+    e = W_l.shape[0] - d
+    if h_row_stride is None:
+        h_row_stride = H_l.stride(0) if B > 1 else d
+    if out is None:
+        out = torch.empty((B, V), dtype=torch.float32, device=H_l.device)
+    dsc = _desc(B, L, level, 1, 1, d, e, radices, H_l.dtype, h_row_stride)
+    lib = load_library()
+    if workspace is None:
+        need = int(lib.nezha_draft_step_workspace(C.byref(dsc)))
+        workspace = torch.empty(max(256, need), dtype=torch.uint8, device=H_l.device)
+    lib.nezha_user_projection.argtypes = [C.POINTER(_StepDesc), C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_void_p, C.c_size_t, C.c_void_p]
+    _check(lib.nezha_user_projection(C.byref(dsc), _ptr(H_l), _ptr(W_l), _ptr(out),
+                                     _ptr(workspace), workspace.numel(), _stream(stream)))
     return out
 
 

@@ -219,22 +219,41 @@ struct WaveTopK {
 };
 
 // ---- weight packing -------------------------------------------------------------------------
-// Wp[((ct*KS + ks)*64 + lane)*8 + j] = W[ks*32 + 8*(lane/16) + j][ct*16 + lane%16]
-// i.e. for every 16-column tile ct and 32-row step ks, the 64 lanes' B operands of
-// v_mfma_f32_16x16x32_bf16 lie in one contiguous 1 KiB block.
+// W_l (bf16, [(d+e), V] row major) is rearranged into MFMA operand order, two regions:
+//  user part (rows 0..d-1), for v_mfma_f32_32x32x16_bf16:
+//    Wu[((ct*KSu + ks)*64 + lane)*8 + j] = W[16*ks + 8*(lane/32) + j][32*ct + lane%32]
+//    (KSu = d/16; columns at or beyond V are clamped to V-1 and never used)
+//  beam part (rows d..d+e-1), for v_mfma_f32_16x16x32_bf16:
+//    Wb[((ct*KSb + ks)*64 + lane)*8 + j] = W[d + 32*ks + 8*(lane/16) + j][16*ct + lane%16]
+//    (KSb = e/32)
+// so that the 64 lanes' B operands of one MFMA are one contiguous 1 KiB block.
+__host__ __device__ inline int64_t packed_user_elems(int d, int V) {
+  return (int64_t)((V + 31) / 32) * 32 * d;
+}
 __global__ __launch_bounds__(256) void pack_weights_kernel(const uint16_t* __restrict__ W,
-                                                           uint16_t* __restrict__ Wp, int rows,
+                                                           uint16_t* __restrict__ Wp, int d, int e,
                                                            int V) {
-  const int KS = rows / 32;
-  const int64_t total = (int64_t)(V / 16) * KS * 64;
+  const int KSu = d / 16, KSb = e / 32;
+  const int64_t n_user = (int64_t)((V + 31) / 32) * KSu * 64;
+  const int64_t n_beam = (int64_t)(V / 16) * KSb * 64;
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= total) return;
-  const int lane = (int)(idx & 63);
-  const int64_t blk = idx >> 6;
-  const int ks = (int)(blk % KS);
-  const int ct = (int)(blk / KS);
-  const int col = ct * 16 + (lane & 15);
-  const int k0 = ks * 32 + 8 * (lane >> 4);
+  if (idx >= n_user + n_beam) return;
+  int col, k0;
+  if (idx < n_user) {
+    const int lane = (int)(idx & 63);
+    const int64_t blk = idx >> 6;
+    const int ks = (int)(blk % KSu), ct = (int)(blk / KSu);
+    col = ct * 32 + (lane & 31);
+    col = col < V ? col : V - 1;
+    k0 = ks * 16 + 8 * (lane >> 5);
+  } else {
+    const int64_t r = idx - n_user;
+    const int lane = (int)(r & 63);
+    const int64_t blk = r >> 6;
+    const int ks = (int)(blk % KSb), ct = (int)(blk / KSb);
+    col = ct * 16 + (lane & 15);
+    k0 = d + ks * 32 + 8 * (lane >> 4);
+  }
   uint16_t v[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) v[j] = W[(int64_t)(k0 + j) * V + col];
@@ -247,99 +266,173 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const uint16_t* __res
 }
 
 // ---- user-part projection, bf16: A[B,V] = H[B,d] * W[0:d, V] -----------------------------
-// Workgroup = 4 waves in a 2x2 grid, each wave TM x TN tiles of 16x16 (v_mfma_f32_16x16x32_bf16).
-// H is staged through LDS in operand order; W comes packed and is copied to LDS as is.
-template <int TM, int TN>
-__global__ __launch_bounds__(256) void user_gemm_bf16_kernel(
-    const uint16_t* __restrict__ H, int64_t h_stride, const uint16_t* __restrict__ Wp,
-    float* __restrict__ A, int B, int d, int V, int KS_total) {
-  constexpr int BM = 2 * TM * 16, BN = 2 * TN * 16;
-  constexpr int RT = BM / 16, CT = BN / 16;       // 16-row / 16-col tiles per workgroup
-  __shared__ uint4 sA[2][RT * 64];                // [row tile][lane] 16 B = one operand each
-  __shared__ uint4 sB[2][CT * 64];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int row0 = blockIdx.y * BM, ct0 = blockIdx.x * CT;
-  const int KS = d / 32;
-  const int n_ct = V / 16;
+// Operand blocks: 1 KiB = the 64 lanes' 16-byte operands of one v_mfma_f32_32x32x16_bf16 (lane l:
+// row or column l%32, k = 8*(l/32)..+7).  Result layout of the 32x32 MFMA: register r of lane l is
+// row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+__device__ __forceinline__ void load_block_to_lds(const void* gptr, void* lds_block) {
+  // 16 bytes per lane from global memory straight into LDS at lds_block + 16*lane
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
+                                   (__attribute__((address_space(3))) void*)lds_block, 16, 0, 0);
+}
 
-  floatx4 acc[TM][TN];
+// Workgroup of NWM x NWN waves, each wave TM x TN tiles of 32x32.  K advances 32 per stage (two
+// MFMA steps of 16).  LDS bandwidth is what bounds this kernel, so only H goes through LDS:
+// its tile is brought by global_load_lds (no staging registers) into one of four buffers, three
+// stages ahead of use.  The packed W operands are loaded straight from global memory / L2 into
+// registers, also three stages ahead (the waves of one column strip read the same lines).  One
+// barrier per stage.  Workgroup ids are remapped so that the tiles that run on one XCD (ids
+// equal modulo 8) are neighbours and share its L2.
+constexpr int kGemmBuffers = 4;
+template <int NWM, int NWN, int TM, int TN>
+__global__ __launch_bounds__(64 * NWM * NWN, 1) void user_gemm_bf16_kernel(
+    const uint16_t* __restrict__ H, int64_t h_stride, const uint16_t* __restrict__ Wu,
+    float* __restrict__ A, int B, int d, int V, int tiles_n, int tiles_total) {
+  typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+  constexpr int NW = NWM * NWN;
+  constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
+  constexpr int CT = BN / 32;                        // 32-column tiles per workgroup
+  constexpr int ASLOTS = BM * 4;                     // 16-byte slots of the H tile (64 B per row)
+  extern __shared__ __align__(16) uint4 smem[];      // [kGemmBuffers][H tile]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / NWN, wn = wave % NWN;
+  // Workgroup ids equal modulo 8 run on the same XCD.  When the grid allows it every XCD gets
+  // 4 x 8 blocks of tiles (4 H panels and 8 W panels live in its L2 at a time); otherwise a
+  // contiguous run of tiles.
+  int tile_m, tile_n;
+  {
+    const int t = blockIdx.x, xcd = t & 7, local = t >> 3;
+    if (tiles_total % 256 == 0 && tiles_n % 8 == 0 && (tiles_total / tiles_n) % 4 == 0) {
+      const int group = xcd + 8 * (local >> 5), groups_n = tiles_n >> 3;
+      tile_m = (group / groups_n) * 4 + ((local & 31) >> 3);
+      tile_n = (group % groups_n) * 8 + (local & 7);
+    } else {
+      const int per_xcd = tiles_total / 8;
+      const int lin = (per_xcd * 8 == tiles_total) ? xcd * per_xcd + local : t;
+      tile_m = lin / tiles_n;
+      tile_n = lin - tile_m * tiles_n;
+    }
+  }
+  const int row0 = tile_m * BM, ct0 = tile_n * CT;
+  const int n_ct = (V + 31) / 32;
+  const int KSu = d / 16;
+  const int stages = d / 32;
+
+  floatx16 acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-  constexpr int A_PER_THREAD = (RT * 64 + 255) / 256;
-  constexpr int B_PER_THREAD = (CT * 64 + 255) / 256;
-  uint4 ra[A_PER_THREAD], rb[B_PER_THREAD];
-
-  auto load_global = [&](int ks) {
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-    for (int u = 0; u < A_PER_THREAD; ++u) {
-      const int o = tid + u * 256;                 // operand slot: row tile * 64 + lane
-      ra[u] = uint4{0, 0, 0, 0};
-      if (o < RT * 64) {
-        const int rt = o >> 6, l = o & 63;
-        const int row = row0 + rt * 16 + (l & 15);
-        if (row < B)
-          ra[u] = *reinterpret_cast<const uint4*>(H + (int64_t)row * h_stride + ks * 32 +
-                                                  8 * (l >> 4));
-      }
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // H tile in LDS: row major, 64 bytes (this stage's 32 k) per row, with the 16-byte chunk index
+  // XOR-ed with (row/4)%4 so that operand reads are free of bank conflicts.  One fetch
+  // instruction brings 16 rows x 64 bytes; since lane l always lands at block + 16*l, the swizzle
+  // is applied to the global address the lane reads.  Rows beyond B are clamped (their results
+  // are never stored).  Wave w issues fetch instructions w, w+NW, ...
+  constexpr int AINS = BM / 16;
+  constexpr int APW = (AINS + NW - 1) / NW;
+  const uint16_t* a_ptr[APW];
+#pragma unroll
+  for (int u = 0; u < APW; ++u) {
+    int ins = wave + NW * u;
+    ins = ins < AINS ? ins : AINS - 1;               // surplus waves repeat the last instruction
+    int row = row0 + ins * 16 + (lane >> 2);
+    row = row < B ? row : B - 1;
+    a_ptr[u] = H + (int64_t)row * h_stride + 8 * ((lane & 3) ^ ((lane >> 4) & 3));
+  }
+  // packed W: operand block of column tile ct, step ks is 64 uint4 at (ct*KSu + ks)*64
+  const uint4* b_ptr[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    int ct = ct0 + wn * TN + j;
+    ct = ct < n_ct ? ct : n_ct - 1;                  // tiles beyond V: clamped, never stored
+    b_ptr[j] = reinterpret_cast<const uint4*>(Wu) + (int64_t)ct * KSu * 64 + lane;
+  }
+  uint4 fb[kGemmBuffers][2][TN];                     // W operands of the stages in flight
+  auto fetch = [&](int stage, uint4 (&b)[2][TN]) {
+    uint4* sa = smem + (stage % kGemmBuffers) * ASLOTS;
+#pragma unroll
+    for (int u = 0; u < APW; ++u) {
+      int ins = wave + NW * u;
+      ins = ins < AINS ? ins : AINS - 1;
+      load_block_to_lds(a_ptr[u] + stage * 32, sa + ins * 64);
     }
 #pragma unroll
-    for (int u = 0; u < B_PER_THREAD; ++u) {
-      const int o = tid + u * 256;
-      rb[u] = uint4{0, 0, 0, 0};
-      if (o < CT * 64) {
-        const int ct = ct0 + (o >> 6);
-        if (ct < n_ct)
-          rb[u] = reinterpret_cast<const uint4*>(Wp)[((int64_t)ct * KS_total + ks) * 64 + (o & 63)];
-      }
-    }
-  };
-  auto store_lds = [&](int buf) {
+    for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-    for (int u = 0; u < A_PER_THREAD; ++u)
-      if (tid + u * 256 < RT * 64) sA[buf][tid + u * 256] = ra[u];
-#pragma unroll
-    for (int u = 0; u < B_PER_THREAD; ++u)
-      if (tid + u * 256 < CT * 64) sB[buf][tid + u * 256] = rb[u];
+      for (int j = 0; j < TN; ++j) b[ks][j] = b_ptr[j][(stage * 2 + ks) * 64];
   };
-
-  load_global(0);
-  store_lds(0);
-  __syncthreads();
-  for (int ks = 0; ks < KS; ++ks) {
-    const int cur = ks & 1;
-    if (ks + 1 < KS) load_global(ks + 1);
-    bf16x8 fa[TM], fb[TN];
+  // LDS slot of this lane's A operand for row tile i, step ks: row = (wm*TM+i)*32 + lane%32,
+  // chunk = 2*ks + lane/32, slot = row*4 + (chunk ^ (row/4)%4)
+  int a_slot[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) a_slot[i] = ((wm * TM + i) * 32 + (lane & 31)) * 4;
+  const int a_sw = (lane >> 2) & 3, a_hi = lane >> 5;
+  constexpr int LOADS = APW + 2 * TN;                // loads per wave and stage
+  // at most `newer` stages' worth of this wave's loads still in flight (they complete in order)
+  auto wait_fetches = [&](int newer) {
+    constexpr int L1 = LOADS < 15 ? LOADS : 15, L2 = 2 * LOADS < 63 ? 2 * LOADS : 63;
+    if (newer >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | (L2 & 15) | ((L2 >> 4) << 14));
+    else if (newer == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | (L1 & 15) | ((L1 >> 4) << 14));
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
+  };
+  auto read_a = [&](int stage, int ks, bf16x8 (&fa)[TM]) {
+    const uint4* sa = smem + (stage % kGemmBuffers) * ASLOTS;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
-      fa[i] = *reinterpret_cast<const bf16x8*>(&sA[cur][(wm * TM + i) * 64 + lane]);
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-      fb[j] = *reinterpret_cast<const bf16x8*>(&sB[cur][(wn * TN + j) * 64 + lane]);
+      fa[i] = *reinterpret_cast<const bf16x8*>(&sa[a_slot[i] + ((2 * ks + a_hi) ^ a_sw)]);
+  };
+  auto multiply = [&](bf16x8 (&fa)[TM], uint4 (&b)[TN]) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    if (ks + 1 < KS) {
-      store_lds(cur ^ 1);
-      __syncthreads();
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+            fa[i], *reinterpret_cast<bf16x8*>(&b[j]), acc[i][j], 0, 0, 0);
+  };
+
+  // Software pipeline, unrolled over the four buffers so that every register set is addressed
+  // statically.  The H operands of the next MFMA step are read from LDS while the current
+  // step's MFMAs run.
+#pragma unroll
+  for (int p = 0; p < kGemmBuffers - 1; ++p)
+    if (p < stages) fetch(p, fb[p]);
+  bf16x8 fa0[TM], fa1[TM];
+  {
+    const int ahead = stages - 1;
+    wait_fetches(ahead < kGemmBuffers - 2 ? ahead : kGemmBuffers - 2);
+    __syncthreads();
+    read_a(0, 0, fa0);
+  }
+  for (int base = 0; base < stages; base += kGemmBuffers) {
+#pragma unroll
+    for (int q = 0; q < kGemmBuffers; ++q) {
+      const int stage = base + q;
+      if (stage < stages) {
+        read_a(stage, 1, fa1);
+        multiply(fa0, fb[q][0]);
+        if (stage + 1 < stages) {
+          const int ahead = stages - 2 - stage;      // fetched stages after stage+1
+          wait_fetches(ahead < kGemmBuffers - 3 ? ahead : kGemmBuffers - 3);
+          __syncthreads();  // stage+1 has landed everywhere; the buffer of stage-1 is free everywhere
+          if (stage + kGemmBuffers - 1 < stages)
+            fetch(stage + kGemmBuffers - 1, fb[(q + kGemmBuffers - 1) % kGemmBuffers]);
+          read_a(stage + 1, 0, fa0);
+        }
+        multiply(fa1, fb[q][1]);
+      }
     }
   }
-  // result layout of the 16x16 MFMA: register i of lane l is row 4*(l/16)+i, column l%16
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-      const int ct = ct0 + wn * TN + j;
-      if (ct >= n_ct) continue;
-      const int col = ct * 16 + (lane & 15);
+      const int col = (ct0 + wn * TN + j) * 32 + (lane & 31);
+      if (col >= V) continue;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int row = row0 + (wm * TM + i) * 16 + 4 * (lane >> 4) + r;
+      for (int r = 0; r < 16; ++r) {
+        const int row = row0 + (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
         if (row < B) A[(int64_t)row * V + col] = acc[i][j][r];
       }
     }
@@ -363,13 +456,12 @@ __global__ __launch_bounds__(256) void user_gemm_f32_kernel(const float* __restr
 // ---- beam-part projection + log-softmax + per-beam top-K --------------------------------------
 struct ExpandArgs {
   const void* state;     // [rows, e] or NULL (level 1: the state is zero)
-  const void* Wbeam;     // bf16: packed W (whole matrix); f32: row-major W (whole matrix)
+  const void* Wbeam;     // bf16: packed beam part of W; f32: row-major W (whole matrix)
   const float* A;        // [B, V] user part
   int32_t* cand_code;    // [rows, K]
   float* cand_logp;      // [rows, K]
   int rows;              // B * K_in
   int K_in, K, V, d, e;
-  int KS_total;          // bf16: (d+e)/32
 };
 
 // A workgroup of NW waves owns 16 beams (rows); wave w takes the blocks of 64 codes
@@ -449,8 +541,7 @@ __global__ __launch_bounds__(64 * NW) void expand_kernel(ExpandArgs a) {
         for (int i = 0; i < 4; ++i) aq[t][i] = a.A[a_off[i] + ct * 16 + c];
         if constexpr (BF16) {
           if (has_beam) {
-            const uint4* wp = static_cast<const uint4*>(a.Wbeam) +
-                              ((int64_t)ct * a.KS_total + a.d / 32) * 64 + lane;
+            const uint4* wp = static_cast<const uint4*>(a.Wbeam) + (int64_t)ct * KS * 64 + lane;
 #pragma unroll
             for (int ks = 0; ks < KST; ++ks)
               if (ks < KS) bq[t][ks] = wp[ks * 64];
@@ -836,7 +927,7 @@ int check_desc(const nezha_step_desc* dsc, Plan* plan) {
     const size_t rows = (size_t)dsc->B * dsc->K_in;
     size_t off = 0;
     plan->wp_off = off;
-    if (bf16) off += align_up((size_t)(dsc->d + dsc->e) * V * 2, 256);
+    if (bf16) off += align_up((size_t)(packed_user_elems(dsc->d, V) + (int64_t)dsc->e * V) * 2, 256);
     plan->a_off = off;
     off += align_up((size_t)dsc->B * V * 4, 256);
     plan->code_off = off;
@@ -860,12 +951,79 @@ int allow_lds(Kern kern, size_t bytes) {
   return NEZHA_OK;
 }
 
+// a1: packs W_l (bf16) and forms A = H_l * W_l[0:d] on `stream`.
+int launch_user_part(const nezha_step_desc* desc, const void* H_l, const void* W_l, uint16_t* Wp,
+                     float* A, hipStream_t stream) {
+  const int B = desc->B, d = desc->d, e = desc->e;
+  const int V = desc->radices[desc->level - 1];
+  const bool bf16 = desc->dtype == NEZHA_BF16;
+  int rc = NEZHA_OK;
+  if (bf16) {
+    const int64_t total = (int64_t)((V + 31) / 32) * (d / 16) * 64 + (int64_t)(V / 16) * (e / 32) * 64;
+    {
+      ProfileScope prof(kPackWeights, stream);
+      hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
+                         stream, static_cast<const uint16_t*>(W_l), Wp, d, e, V);
+    }
+    NEZHA_HIP_CHECK(hipGetLastError());
+    ProfileScope prof(kUserGemm, stream);
+    const uint16_t* Hp = static_cast<const uint16_t*>(H_l);
+#define LAUNCH_GEMM(NWM, NWN, TM, TN)                                                          \
+  do {                                                                                         \
+    constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;                                      \
+    const int tiles_m = (B + BM - 1) / BM, tiles_n = (V + BN - 1) / BN;                        \
+    const size_t lds = (size_t)kGemmBuffers * (BM * 4) * sizeof(uint4);                        \
+    rc = allow_lds(user_gemm_bf16_kernel<NWM, NWN, TM, TN>, lds);                              \
+    if (rc != NEZHA_OK) return rc;                                                             \
+    hipLaunchKernelGGL((user_gemm_bf16_kernel<NWM, NWN, TM, TN>), dim3(tiles_m * tiles_n),     \
+                       dim3(64 * NWM * NWN), lds, stream, Hp, desc->h_row_stride,              \
+                       (const uint16_t*)Wp, A, B, d, V, tiles_n, tiles_m * tiles_n);           \
+  } while (0)
+    const int64_t out_elems = (int64_t)B * V;
+    if (out_elems >= (int64_t)256 * 256 * 128) LAUNCH_GEMM(2, 4, 4, 2);       // 256 x 256 tiles
+    else if (out_elems >= (int64_t)128 * 128 * 64) LAUNCH_GEMM(2, 2, 2, 2);   // 128 x 128 tiles
+    else LAUNCH_GEMM(2, 2, 1, 1);                                              // 64 x 64 tiles
+#undef LAUNCH_GEMM
+    NEZHA_HIP_CHECK(hipGetLastError());
+  } else {
+    dim3 grid((V + 255) / 256, B);
+    ProfileScope prof(kUserGemm, stream);
+    hipLaunchKernelGGL(user_gemm_f32_kernel, grid, dim3(256), 0, stream,
+                       static_cast<const float*>(H_l), desc->h_row_stride,
+                       static_cast<const float*>(W_l), A, B, d, V);
+    NEZHA_HIP_CHECK(hipGetLastError());
+  }
+
+  return NEZHA_OK;
+}
+
 }  // namespace
 }  // namespace nezha
 
 using namespace nezha;
 
 extern "C" {
+
+int nezha_user_projection(const nezha_step_desc* desc, const void* H_l, const void* W_l,
+                          float* A_out, void* workspace, size_t workspace_bytes,
+                          void* hip_stream) {
+  Plan plan;
+  int rc = check_desc(desc, &plan);
+  if (rc != NEZHA_OK) return rc;
+  if (desc->B == 0) return NEZHA_OK;
+  const bool bf16 = desc->dtype == NEZHA_BF16;
+  if (!H_l || !W_l || !A_out) return fail(NEZHA_EINVAL, "H_l, W_l or A_out is NULL");
+  if (bf16 && (!workspace || workspace_bytes < plan.a_off))
+    return fail(NEZHA_EINVAL, "workspace has %zu bytes, %zu needed", workspace_bytes, plan.a_off);
+  if (bf16 && (reinterpret_cast<uintptr_t>(workspace) & 255))
+    return fail(NEZHA_EINVAL, "workspace is not 256-byte aligned");
+  const uintptr_t hw_mask = bf16 ? 15 : 3;
+  if ((reinterpret_cast<uintptr_t>(H_l) | reinterpret_cast<uintptr_t>(W_l)) & hw_mask)
+    return fail(NEZHA_EINVAL, "H_l and W_l must be %d-byte aligned", (int)hw_mask + 1);
+  if (reinterpret_cast<uintptr_t>(A_out) & 15) return fail(NEZHA_EINVAL, "A_out is not 16-byte aligned");
+  return launch_user_part(desc, H_l, W_l, static_cast<uint16_t*>(workspace), A_out,
+                          (hipStream_t)hip_stream);
+}
 
 size_t nezha_draft_step_workspace(const nezha_step_desc* desc) {
   Plan p;
@@ -921,42 +1079,13 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
   int32_t* cand_code = reinterpret_cast<int32_t*>(ws + plan.code_off);
   float* cand_logp = reinterpret_cast<float*>(ws + plan.logp_off);
   const int rows = B * K_in;
-  const int KS_total = (d + e) / 32;
 
-  if (bf16) {
-    const int64_t total = (int64_t)(V / 16) * KS_total * 64;
-    {
-    ProfileScope prof(kPackWeights, stream);
-    hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
-                       stream, static_cast<const uint16_t*>(W_l), Wp, d + e, V);
-    }
-    NEZHA_HIP_CHECK(hipGetLastError());
-    ProfileScope prof(kUserGemm, stream);
-    const bool big = (int64_t)B * V >= (int64_t)128 * 128 * 256;
-    if (big) {
-      dim3 grid((V + 127) / 128, (B + 127) / 128);
-      hipLaunchKernelGGL((user_gemm_bf16_kernel<4, 4>), grid, dim3(256), 0, stream,
-                         static_cast<const uint16_t*>(H_l), desc->h_row_stride,
-                         (const uint16_t*)Wp, A, B, d, V, KS_total);
-    } else {
-      dim3 grid((V + 31) / 32, (B + 31) / 32);
-      hipLaunchKernelGGL((user_gemm_bf16_kernel<1, 1>), grid, dim3(256), 0, stream,
-                         static_cast<const uint16_t*>(H_l), desc->h_row_stride,
-                         (const uint16_t*)Wp, A, B, d, V, KS_total);
-    }
-    NEZHA_HIP_CHECK(hipGetLastError());
-  } else {
-    dim3 grid((V + 255) / 256, B);
-    ProfileScope prof(kUserGemm, stream);
-    hipLaunchKernelGGL(user_gemm_f32_kernel, grid, dim3(256), 0, stream,
-                       static_cast<const float*>(H_l), desc->h_row_stride,
-                       static_cast<const float*>(W_l), A, B, d, V);
-    NEZHA_HIP_CHECK(hipGetLastError());
-  }
+  rc = launch_user_part(desc, H_l, W_l, Wp, A, stream);
+  if (rc != NEZHA_OK) return rc;
 
   ExpandArgs ea;
   ea.state = state_in;
-  ea.Wbeam = bf16 ? static_cast<const void*>(Wp) : W_l;
+  ea.Wbeam = bf16 ? static_cast<const void*>(Wp + packed_user_elems(d, V)) : W_l;
   ea.A = A;
   ea.cand_code = cand_code;
   ea.cand_logp = cand_logp;
@@ -966,7 +1095,6 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
   ea.V = V;
   ea.d = d;
   ea.e = e;
-  ea.KS_total = KS_total;
   {
     // Few rows (a small batch): split each row group's codes over 4 waves so that more of the
     // chip works and every wave's serial top-K chain is shorter.  Needs 4*K <= CAP for the

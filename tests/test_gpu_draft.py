@@ -70,10 +70,10 @@ def test_large_config_request_subsample(oracle):
 
 
 @pytest.mark.parametrize("B,d,e,V,K,L,dtype", [
-    (5, 32, 32, 48, 7, 3, "bf16"),        # partial last block of codes, ragged rows
+    (5, 64, 32, 48, 7, 3, "bf16"),        # partial last block of codes, ragged rows
     (3, 3, 4, 16, 16, 2, "f32"),          # K = V: every code is taken
     (2, 64, 32, 128, 1, 3, "bf16"),       # K = 1: greedy
-    (2, 32, 64, 256, 128, 2, "bf16"),     # the largest beam
+    (2, 64, 64, 256, 128, 2, "bf16"),     # the largest beam
     (17, 96, 96, 80, 33, 3, "f32"),       # 256-entry buffers in float32
     (33, 64, 256, 64, 5, 4, "bf16"),      # widest state
 ])
@@ -84,7 +84,7 @@ def test_odd_shapes(oracle, B, d, e, V, K, L, dtype):
 
 
 def test_zero_weights_follow_the_tie_rule(oracle):
-    cfg = synth.StepConfig("ties", B=3, d=32, e=32, L=3, V=64, K=6, N=1000, dtype="bf16",
+    cfg = synth.StepConfig("ties", B=3, d=64, e=32, L=3, V=64, K=6, N=1000, dtype="bf16",
                            catalog="uniform")
     x = synth.draft_inputs(cfg, 1)
     x["W"] = [np.zeros_like(w) for w in x["W"]]
