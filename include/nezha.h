@@ -120,6 +120,7 @@ typedef struct {
   const int32_t* radices; /* host int32 [L] */
   nezha_dtype dtype;      /* of H, W, E and the states; scores are always float32 */
   int64_t h_row_stride;   /* elements between consecutive requests in H_l (>= d) */
+  int32_t w_packed;       /* 0: W_l is row major; 1: W_l was written by nezha_pack_weights */
 } nezha_step_desc;
 
 /* All data pointers are device pointers.
@@ -148,6 +149,16 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
                      void* state_out, int32_t* count_out, void* workspace,
                      size_t workspace_bytes, void* hip_stream);
 size_t nezha_draft_step_workspace(const nezha_step_desc* desc); /* 0 if desc is invalid */
+
+/* The head's weights are trained parameters and do not change between calls, so their
+ * rearrangement into the order the matrix instructions read (done inside nezha_draft_step on
+ * every call when w_packed == 0) can be done once: nezha_pack_weights writes that form of W_l
+ * (NEZHA_BF16 only; desc gives d, e, radices, level) into W_packed, device memory of
+ * nezha_packed_weights_bytes(desc) bytes, 16-byte aligned, which is then passed as W_l with
+ * desc->w_packed = 1.  Asynchronous on hip_stream; allocates nothing. */
+size_t nezha_packed_weights_bytes(const nezha_step_desc* desc); /* 0 if not applicable */
+int nezha_pack_weights(const nezha_step_desc* desc, const void* W_l, void* W_packed,
+                       void* hip_stream);
 
 /* The beam-independent part of Eq. 2 alone: A_out[b, :] = h_{b,l} W_l[0:d, :] as float32
  * [B, T_level] (these are the level-1 logits, where the state is zero).  Same desc, H_l, W_l,

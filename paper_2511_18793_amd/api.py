@@ -16,7 +16,8 @@ EXPORTS = ["nezha_last_error", "nezha_build_itemset", "nezha_itemset_info", "nez
            "nezha_verify_tuples", "nezha_verify_workspace", "nezha_draft_step",
            "nezha_draft_step_workspace", "nezha_unpack_keys", "nezha_profile_enable",
            "nezha_profile_reset", "nezha_profile_kinds", "nezha_profile_read",
-           "nezha_bench_random_gather", "nezha_user_projection"]
+           "nezha_bench_random_gather", "nezha_user_projection", "nezha_pack_weights",
+           "nezha_packed_weights_bytes"]
 
 
 class NezhaError(RuntimeError):
@@ -29,7 +30,7 @@ class _StepDesc(C.Structure):
     _fields_ = [("B", C.c_int32), ("L", C.c_int32), ("level", C.c_int32), ("K", C.c_int32),
                 ("K_in", C.c_int32), ("d", C.c_int32), ("e", C.c_int32),
                 ("radices", C.POINTER(C.c_int32)), ("dtype", C.c_int),
-                ("h_row_stride", C.c_int64)]
+                ("h_row_stride", C.c_int64), ("w_packed", C.c_int32)]
 
 
 def library_path():
@@ -156,16 +157,48 @@ def verify_tuples(itemset, codes, out_mask=None, out_index=None, out_count=None,
     return out_mask, out_index, out_count
 
 
-def _desc(B, L, level, K, K_in, d, e, radices, dtype, h_row_stride):
+def _desc(B, L, level, K, K_in, d, e, radices, dtype, h_row_stride, w_packed=False):
     rad = _radices(radices)
     dsc = _StepDesc(B, L, level, K, K_in, d, e, C.cast(rad, C.POINTER(C.c_int32)),
-                    NEZHA_BF16 if dtype == torch.bfloat16 else NEZHA_F32, h_row_stride)
+                    NEZHA_BF16 if dtype == torch.bfloat16 else NEZHA_F32, h_row_stride,
+                    1 if w_packed else 0)
     dsc._keep = rad
     return dsc
 
 
-def draft_step_workspace(B, L, level, K, K_in, d, e, radices, dtype):
-    dsc = _desc(B, L, level, K, K_in, d, e, radices, dtype, d)
+class PackedWeights:
+    """W_l in the kernels' operand order (nezha_pack_weights); pass it where W_l is expected."""
+
+    def __init__(self, data, d, e, V):
+        self.data, self.d, self.e, self.V = data, d, e, V
+
+    @property
+    def shape(self):
+        return (self.d + self.e, self.V)
+
+    def data_ptr(self):
+        return self.data.data_ptr()
+
+
+def pack_weights(level, L, radices, W_l, d, stream=None):
+    """nezha_pack_weights for a bf16 W_l [(d+e), T_level]; returns a PackedWeights."""
+    lib = load_library()
+    V = int(radices[level - 1])
+    e = W_l.shape[0] - d
+    dsc = _desc(1, L, level, 1, 1, d, e, radices, W_l.dtype, d)
+    lib.nezha_packed_weights_bytes.restype = C.c_size_t
+    lib.nezha_packed_weights_bytes.argtypes = [C.POINTER(_StepDesc)]
+    n = int(lib.nezha_packed_weights_bytes(C.byref(dsc)))
+    if n == 0:
+        raise NezhaError(-1, "these weights cannot be packed (bf16 only; check the shapes)")
+    out = torch.empty(n, dtype=torch.uint8, device=W_l.device)
+    lib.nezha_pack_weights.argtypes = [C.POINTER(_StepDesc), C.c_void_p, C.c_void_p, C.c_void_p]
+    _check(lib.nezha_pack_weights(C.byref(dsc), _ptr(W_l), _ptr(out), _stream(stream)))
+    return PackedWeights(out, d, e, V)
+
+
+def draft_step_workspace(B, L, level, K, K_in, d, e, radices, dtype, w_packed=False):
+    dsc = _desc(B, L, level, K, K_in, d, e, radices, dtype, d, w_packed)
     return int(load_library().nezha_draft_step_workspace(C.byref(dsc)))
 
 
@@ -193,7 +226,8 @@ def draft_step(level, L, radices, K, H_l, W_l, E_l=None, state_in=None, key_in=N
     out.setdefault("count", torch.empty((B,), dtype=torch.int32, device=dev))
     if level < L and "state" not in out:
         out["state"] = torch.empty((B, K, e), dtype=dt, device=dev)
-    dsc = _desc(B, L, level, K, K_in, d, e, radices, dt, h_row_stride)
+    dsc = _desc(B, L, level, K, K_in, d, e, radices, dt, h_row_stride,
+                isinstance(W_l, PackedWeights))
     if workspace is None:
         need = int(load_library().nezha_draft_step_workspace(C.byref(dsc)))
         workspace = torch.empty(max(256, need), dtype=torch.uint8, device=dev)
@@ -215,7 +249,8 @@ def user_projection(level, L, radices, H_l, W_l, out=None, workspace=None, strea
         h_row_stride = H_l.stride(0) if B > 1 else d
     if out is None:
         out = torch.empty((B, V), dtype=torch.float32, device=H_l.device)
-    dsc = _desc(B, L, level, 1, 1, d, e, radices, H_l.dtype, h_row_stride)
+    dsc = _desc(B, L, level, 1, 1, d, e, radices, H_l.dtype, h_row_stride,
+                isinstance(W_l, PackedWeights))
     lib = load_library()
     if workspace is None:
         need = int(lib.nezha_draft_step_workspace(C.byref(dsc)))

@@ -912,6 +912,8 @@ int check_desc(const nezha_step_desc* dsc, Plan* plan) {
     return fail(NEZHA_EINVAL, "K_in = %d outside 1..%d", dsc->K_in, NEZHA_MAX_BEAM);
   if (dsc->dtype != NEZHA_F32 && dsc->dtype != NEZHA_BF16)
     return fail(NEZHA_EINVAL, "unknown dtype %d", (int)dsc->dtype);
+  if (dsc->w_packed != 0 && (dsc->w_packed != 1 || dsc->dtype != NEZHA_BF16))
+    return fail(NEZHA_EINVAL, "w_packed must be 0, or 1 with NEZHA_BF16");
   if (V % 16 != 0) return fail(NEZHA_EINVAL, "T_level = %d is not a multiple of 16", V);
   const bool bf16 = dsc->dtype == NEZHA_BF16;
   if (dsc->d < 1 || (bf16 && dsc->d % 32 != 0))
@@ -927,7 +929,8 @@ int check_desc(const nezha_step_desc* dsc, Plan* plan) {
     const size_t rows = (size_t)dsc->B * dsc->K_in;
     size_t off = 0;
     plan->wp_off = off;
-    if (bf16) off += align_up((size_t)(packed_user_elems(dsc->d, V) + (int64_t)dsc->e * V) * 2, 256);
+    if (bf16 && !dsc->w_packed)
+      off += align_up((size_t)(packed_user_elems(dsc->d, V) + (int64_t)dsc->e * V) * 2, 256);
     plan->a_off = off;
     off += align_up((size_t)dsc->B * V * 4, 256);
     plan->code_off = off;
@@ -951,7 +954,17 @@ int allow_lds(Kern kern, size_t bytes) {
   return NEZHA_OK;
 }
 
-// a1: packs W_l (bf16) and forms A = H_l * W_l[0:d] on `stream`.
+int launch_pack(const nezha_step_desc* desc, const void* W_l, uint16_t* Wp, hipStream_t stream) {
+  const int d = desc->d, e = desc->e, V = desc->radices[desc->level - 1];
+  const int64_t total = (int64_t)((V + 31) / 32) * (d / 16) * 64 + (int64_t)(V / 16) * (e / 32) * 64;
+  ProfileScope prof(kPackWeights, stream);
+  hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                     static_cast<const uint16_t*>(W_l), Wp, d, e, V);
+  NEZHA_HIP_CHECK(hipGetLastError());
+  return NEZHA_OK;
+}
+
+// a1: packs W_l (bf16, unless it comes packed) and forms A = H_l * W_l[0:d] on `stream`.
 int launch_user_part(const nezha_step_desc* desc, const void* H_l, const void* W_l, uint16_t* Wp,
                      float* A, hipStream_t stream) {
   const int B = desc->B, d = desc->d, e = desc->e;
@@ -959,13 +972,10 @@ int launch_user_part(const nezha_step_desc* desc, const void* H_l, const void* W
   const bool bf16 = desc->dtype == NEZHA_BF16;
   int rc = NEZHA_OK;
   if (bf16) {
-    const int64_t total = (int64_t)((V + 31) / 32) * (d / 16) * 64 + (int64_t)(V / 16) * (e / 32) * 64;
-    {
-      ProfileScope prof(kPackWeights, stream);
-      hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
-                         stream, static_cast<const uint16_t*>(W_l), Wp, d, e, V);
+    if (!desc->w_packed) {
+      rc = launch_pack(desc, W_l, Wp, stream);
+      if (rc != NEZHA_OK) return rc;
     }
-    NEZHA_HIP_CHECK(hipGetLastError());
     ProfileScope prof(kUserGemm, stream);
     const uint16_t* Hp = static_cast<const uint16_t*>(H_l);
 #define LAUNCH_GEMM(NWM, NWN, TM, TN)                                                          \
@@ -1013,16 +1023,34 @@ int nezha_user_projection(const nezha_step_desc* desc, const void* H_l, const vo
   if (desc->B == 0) return NEZHA_OK;
   const bool bf16 = desc->dtype == NEZHA_BF16;
   if (!H_l || !W_l || !A_out) return fail(NEZHA_EINVAL, "H_l, W_l or A_out is NULL");
-  if (bf16 && (!workspace || workspace_bytes < plan.a_off))
+  if (bf16 && !desc->w_packed && (!workspace || workspace_bytes < plan.a_off))
     return fail(NEZHA_EINVAL, "workspace has %zu bytes, %zu needed", workspace_bytes, plan.a_off);
-  if (bf16 && (reinterpret_cast<uintptr_t>(workspace) & 255))
+  if (bf16 && !desc->w_packed && (reinterpret_cast<uintptr_t>(workspace) & 255))
     return fail(NEZHA_EINVAL, "workspace is not 256-byte aligned");
   const uintptr_t hw_mask = bf16 ? 15 : 3;
   if ((reinterpret_cast<uintptr_t>(H_l) | reinterpret_cast<uintptr_t>(W_l)) & hw_mask)
     return fail(NEZHA_EINVAL, "H_l and W_l must be %d-byte aligned", (int)hw_mask + 1);
   if (reinterpret_cast<uintptr_t>(A_out) & 15) return fail(NEZHA_EINVAL, "A_out is not 16-byte aligned");
-  return launch_user_part(desc, H_l, W_l, static_cast<uint16_t*>(workspace), A_out,
-                          (hipStream_t)hip_stream);
+  uint16_t* Wp = desc->w_packed ? static_cast<uint16_t*>(const_cast<void*>(W_l))
+                                : static_cast<uint16_t*>(workspace);
+  return launch_user_part(desc, H_l, W_l, Wp, A_out, (hipStream_t)hip_stream);
+}
+
+size_t nezha_packed_weights_bytes(const nezha_step_desc* desc) {
+  if (check_desc(desc, nullptr) != NEZHA_OK || desc->dtype != NEZHA_BF16) return 0;
+  const int V = desc->radices[desc->level - 1];
+  return align_up((size_t)(packed_user_elems(desc->d, V) + (int64_t)desc->e * V) * 2, 256);
+}
+
+int nezha_pack_weights(const nezha_step_desc* desc, const void* W_l, void* W_packed,
+                       void* hip_stream) {
+  int rc = check_desc(desc, nullptr);
+  if (rc != NEZHA_OK) return rc;
+  if (desc->dtype != NEZHA_BF16) return fail(NEZHA_EINVAL, "only NEZHA_BF16 weights are packed");
+  if (!W_l || !W_packed) return fail(NEZHA_EINVAL, "W_l or W_packed is NULL");
+  if ((reinterpret_cast<uintptr_t>(W_l) | reinterpret_cast<uintptr_t>(W_packed)) & 15)
+    return fail(NEZHA_EINVAL, "W_l and W_packed must be 16-byte aligned");
+  return launch_pack(desc, W_l, static_cast<uint16_t*>(W_packed), (hipStream_t)hip_stream);
 }
 
 size_t nezha_draft_step_workspace(const nezha_step_desc* desc) {
@@ -1074,7 +1102,8 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
 
   hipStream_t stream = (hipStream_t)hip_stream;
   char* ws = static_cast<char*>(workspace);
-  uint16_t* Wp = reinterpret_cast<uint16_t*>(ws + plan.wp_off);
+  uint16_t* Wp = desc->w_packed ? static_cast<uint16_t*>(const_cast<void*>(W_l))
+                                : reinterpret_cast<uint16_t*>(ws + plan.wp_off);
   float* A = reinterpret_cast<float*>(ws + plan.a_off);
   int32_t* cand_code = reinterpret_cast<int32_t*>(ws + plan.code_off);
   float* cand_logp = reinterpret_cast<float*>(ws + plan.logp_off);

@@ -139,6 +139,33 @@ def test_decode_replays_correctly_from_a_hip_graph(oracle):
         del junk
 
 
+def test_weights_packed_once_give_identical_results(oracle):
+    cfg = synth.get_config("serving").scaled(B=48)
+    x, cat = planted_workload(oracle, cfg, 44, N=100_000)
+    gset = nz.build_itemset(cat, cfg.radices)
+    H, W, E = to_device(x, cfg)
+    ref = [{k: v.clone() for k, v in o.items()} for o in nz.decode(H, W, E, cfg.radices, cfg.K, gset)]
+    Wp = [nz.pack_weights(l + 1, cfg.L, cfg.radices, W[l], cfg.d) for l in range(cfg.L)]
+    got = nz.decode(H, Wp, E, cfg.radices, cfg.K, gset)
+    torch.cuda.synchronize()
+    for a, b in zip(ref, got):
+        for k in a:
+            assert torch.equal(a[k], b[k]), k
+
+
+def test_user_projection_is_the_level_one_logits(oracle):
+    """A_l = H_l W_l[0:d]: the logits of Eq. 2 at zero state, against a float64 product."""
+    for name, tol in (("tiny", 1e-5), ("serving", 2e-2)):
+        cfg = synth.get_config(name).scaled(B=37)
+        x = synth.draft_inputs(cfg, 42)
+        H, W, E = to_device(x, cfg)
+        A = nz.user_projection(1, cfg.L, cfg.radices, H[:, 0, :], W[0], h_row_stride=H.stride(0))
+        torch.cuda.synchronize()
+        want = x["H"][:, 0].astype(np.float64) @ x["W"][0][:cfg.d].astype(np.float64)
+        err = np.abs(to_np(A) - want).max()
+        assert err < min(tol, 1e-4), (name, err)
+
+
 def test_zero_requests_is_a_no_op():
     dev = device()
     H = torch.zeros((0, 64), dtype=torch.bfloat16, device=dev)
