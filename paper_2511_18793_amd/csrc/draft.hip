@@ -741,6 +741,117 @@ __global__ __launch_bounds__(64 * NW) void expand_kernel(ExpandArgs a) {
   }
 }
 
+// ---- the same step for small codebooks (T_l <= 1024, K <= 64) ------------------------------------
+// A workgroup of 8 waves owns 16 beams.  Phase A: the waves share out the 16-column MFMA tiles
+// and write the 16 x T_l logits (float32) to LDS.  Phase B: every wave takes two rows; a row's
+// logits sit T_l/64 per lane.  The K-th largest of the 64 per-lane maxima is a lower bound of the
+// row's K-th largest logit, so only the few logits at or above it are appended to the wave's
+// LDS list, which one small sort then cuts to the K best.  More waves work on fewer rows each
+// than in expand_kernel, which is what a small batch needs.
+template <int KST, int NVT>
+__global__ __launch_bounds__(512) void expand_small_kernel(ExpandArgs a) {
+  extern __shared__ __align__(16) uint64_t lds[];
+  constexpr int CAP = 256;
+  uint64_t* scratch = lds;                                   // [8 waves][CAP]
+  float* ztile = reinterpret_cast<float*>(lds + 8 * CAP);    // [16][V]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int g = lane >> 4, c = lane & 15;
+  const int R0 = blockIdx.x * 16;
+  const int V = a.V, K = a.K, e = a.e;
+  const bool has_beam = a.state != nullptr;
+  const int KS = e / 32;
+  const int n_ct = V / 16;
+
+  {  // phase A
+    bf16x8 fa16[KST];
+    if (has_beam) {
+      const int row = R0 + c;
+      const uint16_t* st = static_cast<const uint16_t*>(a.state);
+#pragma unroll
+      for (int ks = 0; ks < KST; ++ks) {
+        uint4 v = uint4{0, 0, 0, 0};
+        if (ks < KS && row < a.rows)
+          v = *reinterpret_cast<const uint4*>(st + (int64_t)row * e + ks * 32 + 8 * g);
+        fa16[ks] = *reinterpret_cast<bf16x8*>(&v);
+      }
+    }
+    int64_t a_off[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = R0 + 4 * g + i;
+      a_off[i] = (int64_t)((row < a.rows ? row : 0) / a.K_in) * V;
+    }
+    for (int ct = wave; ct < n_ct; ct += 8) {
+      floatx4 acc;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] = a.A[a_off[i] + ct * 16 + c];
+      if (has_beam) {
+        const uint4* wp = static_cast<const uint4*>(a.Wbeam) + (int64_t)ct * KS * 64 + lane;
+#pragma unroll
+        for (int ks = 0; ks < KST; ++ks)
+          if (ks < KS) {
+            uint4 v = wp[ks * 64];
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa16[ks], *reinterpret_cast<bf16x8*>(&v),
+                                                          acc, 0, 0, 0);
+          }
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) ztile[(4 * g + i) * V + ct * 16 + c] = acc[i];
+    }
+  }
+  __syncthreads();
+
+  // phase B
+  const int NV = (V + 63) / 64;
+  for (int rr = 0; rr < 2; ++rr) {
+    const int r = wave * 2 + rr, row = R0 + r;
+    if (row >= a.rows) continue;
+    float zv[NVT];
+    float m = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < NVT; ++j) {
+      const int col = j * 64 + lane;
+      zv[j] = (j < NV && col < V) ? ztile[r * V + col] : -INFINITY;
+      m = fmaxf(m, zv[j]);
+    }
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) m = fmaxf(m, __shfl_xor(m, off));
+    float ssum = 0.f;
+    uint64_t key[NVT];
+    uint64_t best = 0;
+#pragma unroll
+    for (int j = 0; j < NVT; ++j) {
+      const int col = j * 64 + lane;
+      const bool ok = j < NV && col < V;
+      ssum += ok ? __builtin_amdgcn_exp2f((zv[j] - m) * kLog2e) : 0.f;
+      key[j] = ok ? (((uint64_t)ordered_bits(zv[j]) << 32) | (uint32_t)~(uint32_t)col) : 0ull;
+      best = key[j] > best ? key[j] : best;
+    }
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) ssum += __shfl_xor(ssum, off);
+    const float lse = m + __builtin_amdgcn_logf(ssum) * kLn2;
+    // K-th largest of the per-lane maxima: every one of the row's K best keys is >= it
+    uint64_t mk[1][1] = {{best}};
+    sort_desc<1, 1>(mk);
+    const uint32_t bound_lo = __builtin_amdgcn_readlane((uint32_t)mk[0][0], K - 1);
+    const uint32_t bound_hi = __builtin_amdgcn_readlane((uint32_t)(mk[0][0] >> 32), K - 1);
+    WaveTopK<CAP> q;
+    q.init(scratch + wave * CAP, K);
+    q.tau = (((uint64_t)bound_hi << 32) | bound_lo) - 1ull;   // keys >= the bound enter
+#pragma unroll
+    for (int j = 0; j < NVT; ++j)
+      if (j < NV) q.push(key[j]);
+    q.compact();
+    wave_sync();
+    for (int p = lane; p < q.cnt; p += 64) {
+      const uint64_t kk = q.buf[p];
+      a.cand_code[(int64_t)row * K + p] = (int32_t)(~(uint32_t)kk);
+      a.cand_logp[(int64_t)row * K + p] = unordered_bits((uint32_t)(kk >> 32)) - lse;
+    }
+    wave_sync();
+  }
+}
+
 // ---- per-request merge, verification, pruning and state update ---------------------------------
 struct MergeArgs {
   const int32_t* cand_code;
@@ -1125,38 +1236,53 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
   ea.d = d;
   ea.e = e;
   {
-    // Few rows (a small batch): split each row group's codes over 4 waves so that more of the
-    // chip works and every wave's serial top-K chain is shorter.  Needs 4*K <= CAP for the
-    // final merge and at least 4 blocks of 64 codes.
     const int groups = (rows + 15) / 16;
-    const bool split = bf16 && groups <= 1024 && V >= 256 && 4 * K <= plan.cap;
-    const int nw = split ? 4 : 1;
-    const size_t lds = (size_t)nw * 16 * plan.cap * 8 + (size_t)nw * 16 * 12;
-    dim3 grid(groups), block(64 * nw);
     ProfileScope prof(kExpand, stream);
-#define LAUNCH_EXPAND(BF, CAPV, KSTV, NWV)                                                    \
-  do {                                                                                        \
-    rc = allow_lds(expand_kernel<BF, CAPV, KSTV, NWV>, lds);                                  \
-    if (rc != NEZHA_OK) return rc;                                                            \
-    hipLaunchKernelGGL((expand_kernel<BF, CAPV, KSTV, NWV>), grid, block, lds, stream, ea);   \
+    if (bf16 && V <= 1024 && K <= 64) {
+      // small codebook: 16 x T_l logits fit in LDS; 8 waves share 16 beams
+      const size_t lds = (size_t)8 * 256 * 8 + (size_t)16 * V * 4;
+      dim3 grid(groups), block(512);
+#define LAUNCH_SMALL(KSTV, NVTV)                                                            \
+  do {                                                                                      \
+    rc = allow_lds(expand_small_kernel<KSTV, NVTV>, lds);                                   \
+    if (rc != NEZHA_OK) return rc;                                                          \
+    hipLaunchKernelGGL((expand_small_kernel<KSTV, NVTV>), grid, block, lds, stream, ea);    \
   } while (0)
-#define LAUNCH_EXPAND_BF16(CAPV, NWV)                                  \
-  do {                                                                 \
-    if (e <= 64) LAUNCH_EXPAND(true, CAPV, 2, NWV);                    \
-    else if (e <= 128) LAUNCH_EXPAND(true, CAPV, 4, NWV);              \
-    else LAUNCH_EXPAND(true, CAPV, 8, NWV);                            \
-  } while (0)
-    if (bf16) {
-      if (plan.cap == 128 && nw == 4) LAUNCH_EXPAND_BF16(128, 4);
-      else if (plan.cap == 128) LAUNCH_EXPAND_BF16(128, 1);
-      else if (nw == 4) LAUNCH_EXPAND_BF16(256, 4);
-      else LAUNCH_EXPAND_BF16(256, 1);
+      if (V <= 256) {
+        if (e <= 64) LAUNCH_SMALL(2, 4);
+        else if (e <= 128) LAUNCH_SMALL(4, 4);
+        else LAUNCH_SMALL(8, 4);
+      } else {
+        if (e <= 64) LAUNCH_SMALL(2, 16);
+        else if (e <= 128) LAUNCH_SMALL(4, 16);
+        else LAUNCH_SMALL(8, 16);
+      }
+#undef LAUNCH_SMALL
     } else {
-      if (plan.cap == 128) LAUNCH_EXPAND(false, 128, 64, 1);
-      else LAUNCH_EXPAND(false, 256, 64, 1);
-    }
+      const size_t lds = (size_t)16 * plan.cap * 8 + (size_t)16 * 12;
+      dim3 grid(groups), block(64);
+#define LAUNCH_EXPAND(BF, CAPV, KSTV)                                                         \
+  do {                                                                                        \
+    rc = allow_lds(expand_kernel<BF, CAPV, KSTV, 1>, lds);                                    \
+    if (rc != NEZHA_OK) return rc;                                                            \
+    hipLaunchKernelGGL((expand_kernel<BF, CAPV, KSTV, 1>), grid, block, lds, stream, ea);     \
+  } while (0)
+#define LAUNCH_EXPAND_BF16(CAPV)                                 \
+  do {                                                           \
+    if (e <= 64) LAUNCH_EXPAND(true, CAPV, 2);                   \
+    else if (e <= 128) LAUNCH_EXPAND(true, CAPV, 4);             \
+    else LAUNCH_EXPAND(true, CAPV, 8);                           \
+  } while (0)
+      if (bf16) {
+        if (plan.cap == 128) LAUNCH_EXPAND_BF16(128);
+        else LAUNCH_EXPAND_BF16(256);
+      } else {
+        if (plan.cap == 128) LAUNCH_EXPAND(false, 128, 64);
+        else LAUNCH_EXPAND(false, 256, 64);
+      }
 #undef LAUNCH_EXPAND_BF16
 #undef LAUNCH_EXPAND
+    }
     NEZHA_HIP_CHECK(hipGetLastError());
   }
 
