@@ -121,6 +121,9 @@ typedef struct {
   nezha_dtype dtype;      /* of H, W, E and the states; scores are always float32 */
   int64_t h_row_stride;   /* elements between consecutive requests in H_l (>= d) */
   int32_t w_packed;       /* 0: W_l is row major; 1: W_l was written by nezha_pack_weights */
+  const float* user_part; /* optional device float32 [B, T_level], 16-byte aligned: h_l W_l[0:d]
+                             formed beforehand (nezha_user_projection[_levels]); then H_l is not
+                             read.  NULL: the call forms it itself */
 } nezha_step_desc;
 
 /* All data pointers are device pointers.
@@ -149,6 +152,17 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
                      void* state_out, int32_t* count_out, void* workspace,
                      size_t workspace_bytes, void* hip_stream);
 size_t nezha_draft_step_workspace(const nezha_step_desc* desc); /* 0 if desc is invalid */
+
+/* The user parts of levels 1..n_levels in one launch.  They do not depend on the beams, and all
+ * hidden states h_1..h_L come out of the same prefill, so they can be formed before the level
+ * loop and handed to nezha_draft_step through desc->user_part.  H, W_packed, A_out: host arrays
+ * of n_levels device pointers: H[i] = hidden states of level i+1 ([B, d], rows h_row_stride
+ * apart), W_packed[i] = that level's weights from nezha_pack_weights, A_out[i] = float32
+ * [B, T_{i+1}].  NEZHA_BF16 with desc->w_packed = 1 only; level, K, K_in of desc are not used.
+ * Asynchronous on hip_stream; allocates nothing. */
+int nezha_user_projection_levels(const nezha_step_desc* desc, int32_t n_levels,
+                                 const void* const* H, const void* const* W_packed,
+                                 float* const* A_out, void* hip_stream);
 
 /* The head's weights are trained parameters and do not change between calls, so their
  * rearrangement into the order the matrix instructions read (done inside nezha_draft_step on

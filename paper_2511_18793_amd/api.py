@@ -17,7 +17,7 @@ EXPORTS = ["nezha_last_error", "nezha_build_itemset", "nezha_itemset_info", "nez
            "nezha_draft_step_workspace", "nezha_unpack_keys", "nezha_profile_enable",
            "nezha_profile_reset", "nezha_profile_kinds", "nezha_profile_read",
            "nezha_bench_random_gather", "nezha_user_projection", "nezha_pack_weights",
-           "nezha_packed_weights_bytes"]
+           "nezha_packed_weights_bytes", "nezha_user_projection_levels"]
 
 
 class NezhaError(RuntimeError):
@@ -30,7 +30,8 @@ class _StepDesc(C.Structure):
     _fields_ = [("B", C.c_int32), ("L", C.c_int32), ("level", C.c_int32), ("K", C.c_int32),
                 ("K_in", C.c_int32), ("d", C.c_int32), ("e", C.c_int32),
                 ("radices", C.POINTER(C.c_int32)), ("dtype", C.c_int),
-                ("h_row_stride", C.c_int64), ("w_packed", C.c_int32)]
+                ("h_row_stride", C.c_int64), ("w_packed", C.c_int32),
+                ("user_part", C.c_void_p)]
 
 
 def library_path():
@@ -157,11 +158,12 @@ def verify_tuples(itemset, codes, out_mask=None, out_index=None, out_count=None,
     return out_mask, out_index, out_count
 
 
-def _desc(B, L, level, K, K_in, d, e, radices, dtype, h_row_stride, w_packed=False):
+def _desc(B, L, level, K, K_in, d, e, radices, dtype, h_row_stride, w_packed=False,
+          user_part=None):
     rad = _radices(radices)
     dsc = _StepDesc(B, L, level, K, K_in, d, e, C.cast(rad, C.POINTER(C.c_int32)),
                     NEZHA_BF16 if dtype == torch.bfloat16 else NEZHA_F32, h_row_stride,
-                    1 if w_packed else 0)
+                    1 if w_packed else 0, None if user_part is None else user_part.data_ptr())
     dsc._keep = rad
     return dsc
 
@@ -204,7 +206,7 @@ def draft_step_workspace(B, L, level, K, K_in, d, e, radices, dtype, w_packed=Fa
 
 def draft_step(level, L, radices, K, H_l, W_l, E_l=None, state_in=None, key_in=None,
                score_in=None, itemset=None, out=None, workspace=None, stream=None,
-               h_row_stride=None):
+               h_row_stride=None, user_part=None):
     """nezha_draft_step for one level.  H_l [B, d] (a view with a row stride is
     fine), W_l [(d+e), V], E_l [V, e]; state_in [B, K_in, e], key_in int64-as-uint64
     [B, K_in], score_in float32 [B, K_in].  `out` may hold preallocated tensors
@@ -227,7 +229,7 @@ def draft_step(level, L, radices, K, H_l, W_l, E_l=None, state_in=None, key_in=N
     if level < L and "state" not in out:
         out["state"] = torch.empty((B, K, e), dtype=dt, device=dev)
     dsc = _desc(B, L, level, K, K_in, d, e, radices, dt, h_row_stride,
-                isinstance(W_l, PackedWeights))
+                isinstance(W_l, PackedWeights), user_part)
     if workspace is None:
         need = int(load_library().nezha_draft_step_workspace(C.byref(dsc)))
         workspace = torch.empty(max(256, need), dtype=torch.uint8, device=dev)
@@ -262,6 +264,23 @@ def user_projection(level, L, radices, H_l, W_l, out=None, workspace=None, strea
     return out
 
 
+def user_projection_levels(H, Wp, radices, out, stream=None):
+    """nezha_user_projection_levels: H [B, L, d] (bf16), Wp list of PackedWeights, out list of
+    float32 [B, T_l] tensors; one launch for all levels."""
+    L = len(Wp)
+    B, _, d = H.shape
+    dsc = _desc(B, L, 1, 1, 1, d, Wp[0].e, radices, H.dtype, H.stride(0), True)
+    esz = H.element_size()
+    hp = (C.c_void_p * L)(*[H.data_ptr() + l * H.stride(1) * esz for l in range(L)])
+    wp = (C.c_void_p * L)(*[w.data_ptr() for w in Wp])
+    ap = (C.c_void_p * L)(*[o.data_ptr() for o in out])
+    lib = load_library()
+    lib.nezha_user_projection_levels.argtypes = [C.POINTER(_StepDesc), C.c_int32, C.c_void_p,
+                                                 C.c_void_p, C.c_void_p, C.c_void_p]
+    _check(lib.nezha_user_projection_levels(C.byref(dsc), L, hp, wp, ap, _stream(stream)))
+    return out
+
+
 class DraftBuffers:
     """Preallocated outputs and workspace for a full L-level decode, so that the
     timed loop allocates nothing."""
@@ -281,6 +300,8 @@ class DraftBuffers:
                 o["state"] = torch.empty((B, K, e), dtype=dtype, device=device)
             self.outs.append(o)
         self.workspace = torch.empty(need, dtype=torch.uint8, device=device)
+        self.user_parts = [torch.empty((B, int(radices[l])), dtype=torch.float32, device=device)
+                           for l in range(L)]
 
 
 def decode(H, W, E, radices, K, itemset=None, buffers=None, stream=None):
@@ -292,11 +313,16 @@ def decode(H, W, E, radices, K, itemset=None, buffers=None, stream=None):
     if buffers is None:
         buffers = DraftBuffers(B, L, K, d, e, radices, H.dtype, H.device)
     state = key = score = None
+    parts = None
+    if all(isinstance(w, PackedWeights) for w in W):
+        # the projections of h_1..h_L do not depend on the beams: one launch before the loop
+        parts = user_projection_levels(H, W, radices, buffers.user_parts, stream=stream)
     for level in range(1, L + 1):
         o = draft_step(level, L, radices, K, H[:, level - 1, :], W[level - 1],
                        E[level - 1] if level < L else None, state, key, score,
                        itemset if level == L else None, out=buffers.outs[level - 1],
-                       workspace=buffers.workspace, stream=stream, h_row_stride=H.stride(0))
+                       workspace=buffers.workspace, stream=stream, h_row_stride=H.stride(0),
+                       user_part=None if parts is None else parts[level - 1])
         state, key, score = o.get("state"), o["key"], o["score"]
     return buffers.outs
 

@@ -284,9 +284,9 @@ __device__ __forceinline__ void load_block_to_lds(const void* gptr, void* lds_bl
 // equal modulo 8) are neighbours and share its L2.
 constexpr int kGemmBuffers = 4;
 template <int NWM, int NWN, int TM, int TN>
-__global__ __launch_bounds__(64 * NWM * NWN, 1) void user_gemm_bf16_kernel(
+__device__ __forceinline__ void user_gemm_tile(
     const uint16_t* __restrict__ H, int64_t h_stride, const uint16_t* __restrict__ Wu,
-    float* __restrict__ A, int B, int d, int V, int tiles_n, int tiles_total) {
+    float* __restrict__ A, int B, int d, int V, int tiles_n, int tiles_total, int tile_id) {
   typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
   constexpr int NW = NWM * NWN;
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
@@ -300,7 +300,7 @@ __global__ __launch_bounds__(64 * NWM * NWN, 1) void user_gemm_bf16_kernel(
   // contiguous run of tiles.
   int tile_m, tile_n;
   {
-    const int t = blockIdx.x, xcd = t & 7, local = t >> 3;
+    const int t = tile_id, xcd = t & 7, local = t >> 3;
     if (tiles_total % 256 == 0 && tiles_n % 8 == 0 && (tiles_total / tiles_n) % 4 == 0) {
       const int group = xcd + 8 * (local >> 5), groups_n = tiles_n >> 3;
       tile_m = (group / groups_n) * 4 + ((local & 31) >> 3);
@@ -436,6 +436,34 @@ __global__ __launch_bounds__(64 * NWM * NWN, 1) void user_gemm_bf16_kernel(
         if (row < B) A[(int64_t)row * V + col] = acc[i][j][r];
       }
     }
+}
+
+template <int NWM, int NWN, int TM, int TN>
+__global__ __launch_bounds__(64 * NWM * NWN, 1) void user_gemm_bf16_kernel(
+    const uint16_t* __restrict__ H, int64_t h_stride, const uint16_t* __restrict__ Wu,
+    float* __restrict__ A, int B, int d, int V, int tiles_n, int tiles_total) {
+  user_gemm_tile<NWM, NWN, TM, TN>(H, h_stride, Wu, A, B, d, V, tiles_n, tiles_total, blockIdx.x);
+}
+
+// Several levels' projections in one launch: they do not depend on each other (all the hidden
+// states come out of the same prefill), so the level loop need not pay for them one by one.
+struct GemmGroup {
+  const uint16_t* H[NEZHA_MAX_LEVELS];
+  const uint16_t* Wu[NEZHA_MAX_LEVELS];
+  float* A[NEZHA_MAX_LEVELS];
+  int V[NEZHA_MAX_LEVELS];
+  int tiles_n[NEZHA_MAX_LEVELS];
+  int tile_begin[NEZHA_MAX_LEVELS + 1];
+  int n;
+};
+template <int NWM, int NWN, int TM, int TN>
+__global__ __launch_bounds__(64 * NWM * NWN, 1) void user_gemm_bf16_grouped_kernel(
+    GemmGroup grp, int64_t h_stride, int B, int d) {
+  int p = 0;
+  while (p + 1 < grp.n && (int)blockIdx.x >= grp.tile_begin[p + 1]) ++p;
+  // an odd tile count defeats the XCD remapping inside, which is what small problems want
+  user_gemm_tile<NWM, NWN, TM, TN>(grp.H[p], h_stride, grp.Wu[p], grp.A[p], B, d, grp.V[p],
+                                   grp.tiles_n[p], 1, (int)blockIdx.x - grp.tile_begin[p]);
 }
 
 // ---- user-part projection, fp32 (small correctness-first shapes) -----------------------------
@@ -749,7 +777,7 @@ __global__ __launch_bounds__(64 * NW) void expand_kernel(ExpandArgs a) {
 // LDS list, which one small sort then cuts to the K best.  More waves work on fewer rows each
 // than in expand_kernel, which is what a small batch needs.
 template <int KST, int NVT>
-__global__ __launch_bounds__(512) void expand_small_kernel(ExpandArgs a) {
+__global__ __launch_bounds__(512, 1) void expand_small_kernel(ExpandArgs a) {
   extern __shared__ __align__(16) uint64_t lds[];
   constexpr int CAP = 256;
   uint64_t* scratch = lds;                                   // [8 waves][CAP]
@@ -781,74 +809,171 @@ __global__ __launch_bounds__(512) void expand_small_kernel(ExpandArgs a) {
       const int row = R0 + 4 * g + i;
       a_off[i] = (int64_t)((row < a.rows ? row : 0) / a.K_in) * V;
     }
-    for (int ct = wave; ct < n_ct; ct += 8) {
-      floatx4 acc;
+    // two tiles (ct, ct + 8) per trip, all their loads issued before the first MFMA
+    for (int ct = wave; ct < n_ct; ct += 16) {
+      const bool two = ct + 8 < n_ct;
+      const int ct2 = two ? ct + 8 : ct;
+      floatx4 acc0, acc1;
+      uint4 w0[KST], w1[KST];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) acc[i] = a.A[a_off[i] + ct * 16 + c];
+      for (int i = 0; i < 4; ++i) {
+        acc0[i] = a.A[a_off[i] + ct * 16 + c];
+        acc1[i] = a.A[a_off[i] + ct2 * 16 + c];
+      }
       if (has_beam) {
-        const uint4* wp = static_cast<const uint4*>(a.Wbeam) + (int64_t)ct * KS * 64 + lane;
+        const uint4* wp0 = static_cast<const uint4*>(a.Wbeam) + (int64_t)ct * KS * 64 + lane;
+        const uint4* wp1 = static_cast<const uint4*>(a.Wbeam) + (int64_t)ct2 * KS * 64 + lane;
 #pragma unroll
         for (int ks = 0; ks < KST; ++ks)
           if (ks < KS) {
-            uint4 v = wp[ks * 64];
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa16[ks], *reinterpret_cast<bf16x8*>(&v),
-                                                          acc, 0, 0, 0);
+            w0[ks] = wp0[ks * 64];
+            w1[ks] = wp1[ks * 64];
+          }
+#pragma unroll
+        for (int ks = 0; ks < KST; ++ks)
+          if (ks < KS) {
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                fa16[ks], *reinterpret_cast<bf16x8*>(&w0[ks]), acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                fa16[ks], *reinterpret_cast<bf16x8*>(&w1[ks]), acc1, 0, 0, 0);
           }
       }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) ztile[(4 * g + i) * V + ct * 16 + c] = acc[i];
+      for (int i = 0; i < 4; ++i) {
+        ztile[(4 * g + i) * V + ct * 16 + c] = acc0[i];
+        if (two) ztile[(4 * g + i) * V + ct2 * 16 + c] = acc1[i];
+      }
     }
   }
   __syncthreads();
 
-  // phase B
+  // phase B: this wave's two rows side by side (independent work hides the cross-lane latency)
   const int NV = (V + 63) / 64;
+  const int r0 = wave * 2;
+  if (R0 + r0 >= a.rows) return;
+  bool live[2];
+  float zv[2][NVT], m[2], ssum[2];
+  uint64_t key[2][NVT], best[2][1];
+#pragma unroll
   for (int rr = 0; rr < 2; ++rr) {
-    const int r = wave * 2 + rr, row = R0 + r;
-    if (row >= a.rows) continue;
-    float zv[NVT];
-    float m = -INFINITY;
+    live[rr] = R0 + r0 + rr < a.rows;
+    m[rr] = -INFINITY;
 #pragma unroll
     for (int j = 0; j < NVT; ++j) {
       const int col = j * 64 + lane;
-      zv[j] = (j < NV && col < V) ? ztile[r * V + col] : -INFINITY;
-      m = fmaxf(m, zv[j]);
+      zv[rr][j] = (j < NV && col < V && live[rr]) ? ztile[(r0 + rr) * V + col] : -INFINITY;
+      m[rr] = fmaxf(m[rr], zv[rr][j]);
     }
+  }
+  auto reduce_max = [&](float (&x)[2]) {
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) m = fmaxf(m, __shfl_xor(m, off));
-    float ssum = 0.f;
-    uint64_t key[NVT];
-    uint64_t best = 0;
+    for (int rr = 0; rr < 2; ++rr) {
+      float v = x[rr];
+      v = fmaxf(v, __uint_as_float(lane_xor<1>(__float_as_uint(v), lane)));
+      v = fmaxf(v, __uint_as_float(lane_xor<2>(__float_as_uint(v), lane)));
+      v = fmaxf(v, __uint_as_float(lane_xor<4>(__float_as_uint(v), lane)));
+      v = fmaxf(v, __uint_as_float(lane_xor<8>(__float_as_uint(v), lane)));
+      v = fmaxf(v, __uint_as_float(lane_xor<16>(__float_as_uint(v), lane)));
+      v = fmaxf(v, __uint_as_float(lane_xor<32>(__float_as_uint(v), lane)));
+      x[rr] = v;
+    }
+  };
+  auto reduce_sum = [&](float (&x)[2]) {
+#pragma unroll
+    for (int rr = 0; rr < 2; ++rr) {
+      float v = x[rr];
+      v += __uint_as_float(lane_xor<1>(__float_as_uint(v), lane));
+      v += __uint_as_float(lane_xor<2>(__float_as_uint(v), lane));
+      v += __uint_as_float(lane_xor<4>(__float_as_uint(v), lane));
+      v += __uint_as_float(lane_xor<8>(__float_as_uint(v), lane));
+      v += __uint_as_float(lane_xor<16>(__float_as_uint(v), lane));
+      v += __uint_as_float(lane_xor<32>(__float_as_uint(v), lane));
+      x[rr] = v;
+    }
+  };
+  reduce_max(m);
+#pragma unroll
+  for (int rr = 0; rr < 2; ++rr) {
+    ssum[rr] = 0.f;
+    best[rr][0] = 0;
 #pragma unroll
     for (int j = 0; j < NVT; ++j) {
       const int col = j * 64 + lane;
-      const bool ok = j < NV && col < V;
-      ssum += ok ? __builtin_amdgcn_exp2f((zv[j] - m) * kLog2e) : 0.f;
-      key[j] = ok ? (((uint64_t)ordered_bits(zv[j]) << 32) | (uint32_t)~(uint32_t)col) : 0ull;
-      best = key[j] > best ? key[j] : best;
+      const bool ok = j < NV && col < V && live[rr];
+      ssum[rr] += ok ? __builtin_amdgcn_exp2f((zv[rr][j] - m[rr]) * kLog2e) : 0.f;
+      key[rr][j] = ok ? (((uint64_t)ordered_bits(zv[rr][j]) << 32) | (uint32_t)~(uint32_t)col) : 0ull;
+      best[rr][0] = key[rr][j] > best[rr][0] ? key[rr][j] : best[rr][0];
     }
+  }
+  reduce_sum(ssum);
+  // K-th largest of the per-lane maxima: every one of the row's K best keys is >= it
+  sort_desc<1, 2>(best);
+  uint64_t* rows[2] = {scratch + wave * CAP, scratch + wave * CAP + CAP / 2};
+  int rc[2];
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) ssum += __shfl_xor(ssum, off);
-    const float lse = m + __builtin_amdgcn_logf(ssum) * kLn2;
-    // K-th largest of the per-lane maxima: every one of the row's K best keys is >= it
-    uint64_t mk[1][1] = {{best}};
-    sort_desc<1, 1>(mk);
-    const uint32_t bound_lo = __builtin_amdgcn_readlane((uint32_t)mk[0][0], K - 1);
-    const uint32_t bound_hi = __builtin_amdgcn_readlane((uint32_t)(mk[0][0] >> 32), K - 1);
-    WaveTopK<CAP> q;
-    q.init(scratch + wave * CAP, K);
-    q.tau = (((uint64_t)bound_hi << 32) | bound_lo) - 1ull;   // keys >= the bound enter
+  for (int rr = 0; rr < 2; ++rr) {
+    const uint32_t bound_lo = __builtin_amdgcn_readlane((uint32_t)best[rr][0], K - 1);
+    const uint32_t bound_hi = __builtin_amdgcn_readlane((uint32_t)(best[rr][0] >> 32), K - 1);
+    const uint64_t bound = ((uint64_t)bound_hi << 32) | bound_lo;
+    // append the keys >= bound; a row gets CAP/2 places, which K * T_l/64 keys could exceed only
+    // in contrived cases: then the row falls back to the streaming top-K below
+    int cnt = 0;
+    bool overflow = false;
 #pragma unroll
-    for (int j = 0; j < NVT; ++j)
-      if (j < NV) q.push(key[j]);
-    q.compact();
-    wave_sync();
-    for (int p = lane; p < q.cnt; p += 64) {
-      const uint64_t kk = q.buf[p];
-      a.cand_code[(int64_t)row * K + p] = (int32_t)(~(uint32_t)kk);
-      a.cand_logp[(int64_t)row * K + p] = unordered_bits((uint32_t)(kk >> 32)) - lse;
+    for (int j = 0; j < NVT; ++j) {
+      if (j < NV) {
+        const bool pass = key[rr][j] >= bound && key[rr][j] != 0;
+        const uint64_t bal = __ballot(pass);
+        const int pos = cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32),
+                                                        __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0));
+        const int n = __popcll(bal);
+        if (cnt + n > CAP / 2) overflow = true;
+        if (pass && pos < CAP / 2) rows[rr][pos] = key[rr][j];
+        cnt += n;
+      }
     }
-    wave_sync();
+    rc[rr] = overflow ? -1 : cnt;
+  }
+  if (rc[0] < 0 || rc[1] < 0) {
+    // rare: too many keys tie with the bound; redo both rows with the general streaming top-K
+    for (int rr = 0; rr < 2; ++rr) {
+      wave_sync();
+      WaveTopK<CAP> q;
+      q.init(scratch + wave * CAP, K);
+      for (int j = 0; j < NV; ++j) {                       // keys rebuilt from the LDS tile
+        const int col = j * 64 + lane;
+        const bool ok = col < V && live[rr];
+        const float z = ok ? ztile[(r0 + rr) * V + col] : 0.f;
+        q.push(ok ? (((uint64_t)ordered_bits(z) << 32) | (uint32_t)~(uint32_t)col) : 0ull);
+      }
+      q.compact();
+      wave_sync();
+      if (live[rr]) {
+        const int row = R0 + r0 + rr;
+        const float lse = m[rr] + __builtin_amdgcn_logf(ssum[rr]) * kLn2;
+        for (int p = lane; p < q.cnt; p += 64) {
+          const uint64_t kk = q.buf[p];
+          a.cand_code[(int64_t)row * K + p] = (int32_t)(~(uint32_t)kk);
+          a.cand_logp[(int64_t)row * K + p] = unordered_bits((uint32_t)(kk >> 32)) - lse;
+        }
+      }
+    }
+    return;
+  }
+  uint64_t* const crows[2] = {rows[0], rows[1]};
+  uint64_t rt[2];
+  compact_rows<CAP / 2, 2>(crows, rc, rt, K);     // sorts both lists, keeps the K best
+#pragma unroll
+  for (int rr = 0; rr < 2; ++rr) {
+    if (live[rr]) {
+      const int row = R0 + r0 + rr;
+      const float lse = m[rr] + __builtin_amdgcn_logf(ssum[rr]) * kLn2;
+      for (int p = lane; p < rc[rr]; p += 64) {
+        const uint64_t kk = rows[rr][p];
+        a.cand_code[(int64_t)row * K + p] = (int32_t)(~(uint32_t)kk);
+        a.cand_logp[(int64_t)row * K + p] = unordered_bits((uint32_t)(kk >> 32)) - lse;
+      }
+    }
   }
 }
 
@@ -1147,6 +1272,71 @@ int nezha_user_projection(const nezha_step_desc* desc, const void* H_l, const vo
   return launch_user_part(desc, H_l, W_l, Wp, A_out, (hipStream_t)hip_stream);
 }
 
+int nezha_user_projection_levels(const nezha_step_desc* desc, int32_t n_levels,
+                                 const void* const* H, const void* const* W_packed,
+                                 float* const* A_out, void* hip_stream) {
+  if (!desc) return fail(NEZHA_EINVAL, "desc is NULL");
+  nezha_step_desc probe = *desc;
+  probe.level = 1;
+  probe.K = 1;
+  probe.K_in = 1;
+  if (n_levels < 1 || n_levels > desc->L) return fail(NEZHA_EINVAL, "n_levels outside 1..L");
+  if (desc->dtype != NEZHA_BF16 || !desc->w_packed)
+    return fail(NEZHA_EINVAL, "needs NEZHA_BF16 weights packed by nezha_pack_weights");
+  if (!H || !W_packed || !A_out) return fail(NEZHA_EINVAL, "a pointer array is NULL");
+  GemmGroup grp;
+  grp.n = n_levels;
+  int tiles = 0;
+  const int B = desc->B, d = desc->d;
+  for (int i = 0; i < n_levels; ++i) {
+    probe.level = i + 1;
+    int rc = check_desc(&probe, nullptr);
+    if (rc != NEZHA_OK) return rc;
+    if (!H[i] || !W_packed[i] || !A_out[i]) return fail(NEZHA_EINVAL, "a level's pointer is NULL");
+    if ((reinterpret_cast<uintptr_t>(H[i]) | reinterpret_cast<uintptr_t>(W_packed[i]) |
+         reinterpret_cast<uintptr_t>(A_out[i])) & 15)
+      return fail(NEZHA_EINVAL, "H, W_packed and A_out must be 16-byte aligned");
+    const int V = desc->radices[i];
+    grp.H[i] = static_cast<const uint16_t*>(H[i]);
+    grp.Wu[i] = static_cast<const uint16_t*>(W_packed[i]);
+    grp.A[i] = A_out[i];
+    grp.V[i] = V;
+    grp.tiles_n[i] = (V + 63) / 64;
+    grp.tile_begin[i] = tiles;
+    tiles += ((B + 63) / 64) * grp.tiles_n[i];
+  }
+  grp.tile_begin[n_levels] = tiles;
+  for (int i = n_levels; i < NEZHA_MAX_LEVELS; ++i) {
+    grp.H[i] = nullptr;
+    grp.Wu[i] = nullptr;
+    grp.A[i] = nullptr;
+    grp.V[i] = 0;
+    grp.tiles_n[i] = 0;
+    grp.tile_begin[i + 1] = tiles;
+  }
+  if (B == 0) return NEZHA_OK;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  int max_v = 0;
+  for (int i = 0; i < n_levels; ++i) max_v = desc->radices[i] > max_v ? desc->radices[i] : max_v;
+  if ((int64_t)B * max_v >= (int64_t)128 * 128 * 64) {
+    // large projections fill the chip on their own: one launch each, with the large tiles
+    for (int i = 0; i < n_levels; ++i) {
+      probe.level = i + 1;
+      int rc = launch_user_part(&probe, H[i], W_packed[i],
+                                static_cast<uint16_t*>(const_cast<void*>(W_packed[i])), A_out[i],
+                                stream);
+      if (rc != NEZHA_OK) return rc;
+    }
+    return NEZHA_OK;
+  }
+  const size_t lds = (size_t)kGemmBuffers * (64 * 4) * sizeof(uint4);
+  ProfileScope prof(kUserGemm, stream);
+  hipLaunchKernelGGL((user_gemm_bf16_grouped_kernel<2, 2, 1, 1>), dim3(tiles), dim3(256), lds, stream,
+                     grp, desc->h_row_stride, B, d);
+  NEZHA_HIP_CHECK(hipGetLastError());
+  return NEZHA_OK;
+}
+
 size_t nezha_packed_weights_bytes(const nezha_step_desc* desc) {
   if (check_desc(desc, nullptr) != NEZHA_OK || desc->dtype != NEZHA_BF16) return 0;
   const int V = desc->radices[desc->level - 1];
@@ -1184,7 +1374,9 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
   const int V = desc->radices[level - 1];
   const bool bf16 = desc->dtype == NEZHA_BF16;
   if (desc->B == 0) return NEZHA_OK;  // an empty batch has nothing to read or write
-  if (!H_l || !W_l) return fail(NEZHA_EINVAL, "H_l or W_l is NULL");
+  if ((!H_l && !desc->user_part) || !W_l) return fail(NEZHA_EINVAL, "H_l or W_l is NULL");
+  if (reinterpret_cast<uintptr_t>(desc->user_part) & 15)
+    return fail(NEZHA_EINVAL, "user_part is not 16-byte aligned");
   if (!key_out || !score_out || !parent_out || !code_out)
     return fail(NEZHA_EINVAL, "an output pointer is NULL");
   if (level < L && !state_out) return fail(NEZHA_EINVAL, "state_out is NULL below the last level");
@@ -1220,8 +1412,17 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
   float* cand_logp = reinterpret_cast<float*>(ws + plan.logp_off);
   const int rows = B * K_in;
 
-  rc = launch_user_part(desc, H_l, W_l, Wp, A, stream);
-  if (rc != NEZHA_OK) return rc;
+  if (desc->user_part) {
+    // the caller formed A_l already (nezha_user_projection / nezha_user_projection_levels)
+    A = const_cast<float*>(desc->user_part);
+    if (bf16 && !desc->w_packed) {
+      rc = launch_pack(desc, W_l, Wp, stream);
+      if (rc != NEZHA_OK) return rc;
+    }
+  } else {
+    rc = launch_user_part(desc, H_l, W_l, Wp, A, stream);
+    if (rc != NEZHA_OK) return rc;
+  }
 
   ExpandArgs ea;
   ea.state = state_in;
