@@ -997,22 +997,25 @@ struct MergeArgs {
 };
 
 // One workgroup (4 waves) per request.  Every candidate (parent p, within-beam rank r) gets the
-// sort key (ordered score, ~(p*K+r)), or 0 if the verifier rejects it; each wave keeps the K
-// largest keys of its share of the candidates, then wave 0 merges the four lists.
-template <bool BF16, int CAP>
+// sort key (ordered score, ~(p*K+r)), or 0 if the verifier rejects it; all keys go to LDS.  Each
+// lane remembers its two largest keys; the K-th largest of a wave's lane maxima bounds the
+// request's K-th largest key from below, so wave 0 then only has to sort the few keys at or above
+// the best of the four bounds.
+template <bool BF16>
 __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
-  __shared__ uint64_t wbuf[5][CAP];
-  __shared__ int wcnt[4];
+  constexpr int CAP = 256;
+  extern __shared__ __align__(16) uint64_t dyn[];   // [n_c keys][CAP top buffer]
+  __shared__ uint64_t bounds[4];
   __shared__ int32_t fin_parent[NEZHA_MAX_BEAM], fin_code[NEZHA_MAX_BEAM];
-  __shared__ int fin_count;
   const int b = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int K = a.K, K_in = a.K_in;
   const int n_c = K_in * K;
   const bool verify = a.set.slots != nullptr;
+  uint64_t* keys = dyn;
+  uint64_t* topbuf = dyn + ((n_c + 1) & ~1);
 
-  WaveTopK<CAP> q;
-  q.init(wbuf[wave], K);
+  uint64_t top0 = 0, top1 = 0;                       // this lane's two largest keys
   for (int base = wave * 64; base < n_c; base += 256) {   // wave uniform trip count
     const int i = base + lane;
     uint64_t sk = 0;
@@ -1027,21 +1030,39 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
         ok = set_contains(a.set, key);
       }
       if (ok) sk = ((uint64_t)ordered_bits(score) << 32) | (uint32_t)~(uint32_t)i;
+      keys[i] = sk;
     }
-    q.push(sk);
+    const uint64_t lo = sk > top0 ? top0 : sk;       // the smaller of (sk, top0)
+    top0 = sk > top0 ? sk : top0;
+    top1 = lo > top1 ? lo : top1;
   }
-  q.compact();
-  if (lane == 0) wcnt[wave] = q.cnt;
+  {
+    uint64_t bound;
+    if (K <= 64) {
+      uint64_t mk[1][1] = {{top0}};
+      sort_desc<1, 1>(mk);
+      bound = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)(mk[0][0] >> 32), K - 1) << 32) |
+              (uint32_t)__builtin_amdgcn_readlane((uint32_t)mk[0][0], K - 1);
+    } else {
+      uint64_t mk[1][2] = {{top0, top1}};
+      sort_desc<2, 1>(mk);                           // position 2*lane + j
+      const uint64_t pick = ((K - 1) & 1) ? mk[0][1] : mk[0][0];
+      bound = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)(pick >> 32), (K - 1) >> 1) << 32) |
+              (uint32_t)__builtin_amdgcn_readlane((uint32_t)pick, (K - 1) >> 1);
+    }
+    if (lane == 0) bounds[wave] = bound;
+  }
   __syncthreads();
   if (wave == 0) {
+    uint64_t tau = bounds[0];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) tau = bounds[w] > tau ? bounds[w] : tau;
     WaveTopK<CAP> f;
-    f.init(wbuf[4], K);
-    for (int w = 0; w < 4; ++w) {
-      const int n = wcnt[w];
-      for (int base = 0; base < n; base += 64)
-        f.push(base + lane < n ? wbuf[w][base + lane] : 0ull);
-    }
+    f.init(topbuf, K);
+    f.tau = tau ? tau - 1ull : 0ull;                 // keys >= tau enter
+    for (int base = 0; base < n_c; base += 64) f.push(base + lane < n_c ? keys[base + lane] : 0ull);
     f.compact();
+    wave_sync();
     constexpr int NPL = (NEZHA_MAX_BEAM + 63) / 64;
 #pragma unroll
     for (int j = 0; j < NPL; ++j) {
@@ -1070,10 +1091,7 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
         }
       }
     }
-    if (lane == 0) {
-      fin_count = f.cnt;
-      if (a.count_out) a.count_out[b] = f.cnt;
-    }
+    if (lane == 0 && a.count_out) a.count_out[b] = f.cnt;
   }
   __syncthreads();
   if (a.state_out) {
@@ -1507,11 +1525,17 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
   ma.e = e;
   {
     dim3 grid(B), block(256);
+    const size_t lds = ((size_t)((K_in * K + 1) & ~1) + 256) * sizeof(uint64_t);
     ProfileScope prof(kMerge, stream);
-    if (bf16 && plan.cap == 128) hipLaunchKernelGGL((merge_kernel<true, 128>), grid, block, 0, stream, ma);
-    else if (bf16) hipLaunchKernelGGL((merge_kernel<true, 256>), grid, block, 0, stream, ma);
-    else if (plan.cap == 128) hipLaunchKernelGGL((merge_kernel<false, 128>), grid, block, 0, stream, ma);
-    else hipLaunchKernelGGL((merge_kernel<false, 256>), grid, block, 0, stream, ma);
+    if (bf16) {
+      rc = allow_lds(merge_kernel<true>, lds);
+      if (rc != NEZHA_OK) return rc;
+      hipLaunchKernelGGL((merge_kernel<true>), grid, block, lds, stream, ma);
+    } else {
+      rc = allow_lds(merge_kernel<false>, lds);
+      if (rc != NEZHA_OK) return rc;
+      hipLaunchKernelGGL((merge_kernel<false>), grid, block, lds, stream, ma);
+    }
     NEZHA_HIP_CHECK(hipGetLastError());
   }
   return NEZHA_OK;
