@@ -77,6 +77,8 @@ def kernel_models(cfg):
             "expand_kernel": ("alu", float(EXPAND_SLOTS_PER_LOGIT) * rows * V),
             "merge_kernel": ("hbm", rows * K * 8.0 + probes * BUCKET_BYTES
                              + B * K * (24.0 + (2 * e * esz if level < L else 0))),
+            # expansion, merge, verification and Transition of one level in one launch
+            "level_small_kernel": ("alu", float(EXPAND_SLOTS_PER_LOGIT) * rows * V),
         })
     return per_level
 
@@ -179,7 +181,7 @@ def bench_draft(args, cfg):
                 "avg_launch_us": kd["avg_us"],
                 "timing": "HIP events by the library around each launch, eager pass of %d steps"
                           % prof_steps}
-    if dom == "expand_kernel":
+    if dom in ("expand_kernel", "level_small_kernel"):
         flops = sum(2.0 * cfg.B * (1 if l == 0 else cfg.K) * cfg.e * cfg.V * (0 if l == 0 else 1)
                     for l in range(cfg.L)) * prof_steps
         roofline["mfma_tflops"] = flops / (kd["total_ms"] * 1e-3) / 1e12

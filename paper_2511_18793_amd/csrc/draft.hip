@@ -769,6 +769,134 @@ __global__ __launch_bounds__(64 * NW) void expand_kernel(ExpandArgs a) {
   }
 }
 
+// Two rows of float32 logits in LDS (T_l = V values each, V/64 per lane): log-sum-exp and the K
+// best (logit, code) keys of each, sorted, handed to emit(row 0|1, rank, key, lse).  The K-th
+// largest of the 64 per-lane maxima is a lower bound of the row's K-th largest key, so only the
+// few keys at or above it are appended to the wave's LDS list (scratch, CAP keys, half per row),
+// which one small sort then cuts to the K best.  The two rows run side by side: independent
+// work hides the cross-lane latency.  K <= 64.  Whole wave.
+template <int NVT, int CAP, class Emit>
+__device__ __forceinline__ void two_rows_topk(const float* z0, const float* z1, bool live0,
+                                              bool live1, int V, int K, uint64_t* scratch,
+                                              Emit emit) {
+  const int lane = threadIdx.x & 63;
+  const int NV = (V + 63) / 64;
+  const float* zrow[2] = {z0, z1};
+  bool live[2] = {live0, live1};
+  float zv[2][NVT], m[2], ssum[2];
+  uint64_t key[2][NVT], best[2][1];
+#pragma unroll
+  for (int rr = 0; rr < 2; ++rr) {
+    m[rr] = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < NVT; ++j) {
+      const int col = j * 64 + lane;
+      zv[rr][j] = (j < NV && col < V && live[rr]) ? zrow[rr][col] : -INFINITY;
+      m[rr] = fmaxf(m[rr], zv[rr][j]);
+    }
+  }
+  auto reduce_max = [&](float (&x)[2]) {
+#pragma unroll
+    for (int rr = 0; rr < 2; ++rr) {
+      float v = x[rr];
+      v = fmaxf(v, __uint_as_float(lane_xor<1>(__float_as_uint(v), lane)));
+      v = fmaxf(v, __uint_as_float(lane_xor<2>(__float_as_uint(v), lane)));
+      v = fmaxf(v, __uint_as_float(lane_xor<4>(__float_as_uint(v), lane)));
+      v = fmaxf(v, __uint_as_float(lane_xor<8>(__float_as_uint(v), lane)));
+      v = fmaxf(v, __uint_as_float(lane_xor<16>(__float_as_uint(v), lane)));
+      v = fmaxf(v, __uint_as_float(lane_xor<32>(__float_as_uint(v), lane)));
+      x[rr] = v;
+    }
+  };
+  auto reduce_sum = [&](float (&x)[2]) {
+#pragma unroll
+    for (int rr = 0; rr < 2; ++rr) {
+      float v = x[rr];
+      v += __uint_as_float(lane_xor<1>(__float_as_uint(v), lane));
+      v += __uint_as_float(lane_xor<2>(__float_as_uint(v), lane));
+      v += __uint_as_float(lane_xor<4>(__float_as_uint(v), lane));
+      v += __uint_as_float(lane_xor<8>(__float_as_uint(v), lane));
+      v += __uint_as_float(lane_xor<16>(__float_as_uint(v), lane));
+      v += __uint_as_float(lane_xor<32>(__float_as_uint(v), lane));
+      x[rr] = v;
+    }
+  };
+  reduce_max(m);
+#pragma unroll
+  for (int rr = 0; rr < 2; ++rr) {
+    ssum[rr] = 0.f;
+    best[rr][0] = 0;
+#pragma unroll
+    for (int j = 0; j < NVT; ++j) {
+      const int col = j * 64 + lane;
+      const bool ok = j < NV && col < V && live[rr];
+      ssum[rr] += ok ? __builtin_amdgcn_exp2f((zv[rr][j] - m[rr]) * kLog2e) : 0.f;
+      key[rr][j] = ok ? (((uint64_t)ordered_bits(zv[rr][j]) << 32) | (uint32_t)~(uint32_t)col) : 0ull;
+      best[rr][0] = key[rr][j] > best[rr][0] ? key[rr][j] : best[rr][0];
+    }
+  }
+  reduce_sum(ssum);
+  // K-th largest of the per-lane maxima: every one of the row's K best keys is >= it
+  sort_desc<1, 2>(best);
+  uint64_t* rows[2] = {scratch, scratch + CAP / 2};
+  int rc[2];
+#pragma unroll
+  for (int rr = 0; rr < 2; ++rr) {
+    const uint32_t bound_lo = __builtin_amdgcn_readlane((uint32_t)best[rr][0], K - 1);
+    const uint32_t bound_hi = __builtin_amdgcn_readlane((uint32_t)(best[rr][0] >> 32), K - 1);
+    const uint64_t bound = ((uint64_t)bound_hi << 32) | bound_lo;
+    // append the keys >= bound; a row gets CAP/2 places, which K * T_l/64 keys could exceed only
+    // in contrived cases: then the row falls back to the streaming top-K below
+    int cnt = 0;
+    bool overflow = false;
+#pragma unroll
+    for (int j = 0; j < NVT; ++j) {
+      if (j < NV) {
+        const bool pass = key[rr][j] >= bound && key[rr][j] != 0;
+        const uint64_t bal = __ballot(pass);
+        const int pos = cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32),
+                                                        __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0));
+        const int n = __popcll(bal);
+        if (cnt + n > CAP / 2) overflow = true;
+        if (pass && pos < CAP / 2) rows[rr][pos] = key[rr][j];
+        cnt += n;
+      }
+    }
+    rc[rr] = overflow ? -1 : cnt;
+  }
+  if (rc[0] < 0 || rc[1] < 0) {
+    // rare: too many keys tie with the bound; redo both rows with the general streaming top-K
+    for (int rr = 0; rr < 2; ++rr) {
+      wave_sync();
+      WaveTopK<CAP> q;
+      q.init(scratch, K);
+      for (int j = 0; j < NV; ++j) {                       // keys rebuilt from the LDS tile
+        const int col = j * 64 + lane;
+        const bool ok = col < V && live[rr];
+        const float z = ok ? zrow[rr][col] : 0.f;
+        q.push(ok ? (((uint64_t)ordered_bits(z) << 32) | (uint32_t)~(uint32_t)col) : 0ull);
+      }
+      q.compact();
+      wave_sync();
+      if (live[rr]) {
+        const float lse = m[rr] + __builtin_amdgcn_logf(ssum[rr]) * kLn2;
+        for (int p = lane; p < q.cnt; p += 64) emit(rr, p, q.buf[p], lse);
+      }
+    }
+    return;
+  }
+  uint64_t* const crows[2] = {rows[0], rows[1]};
+  uint64_t rt[2];
+  compact_rows<CAP / 2, 2>(crows, rc, rt, K);     // sorts both lists, keeps the K best
+#pragma unroll
+  for (int rr = 0; rr < 2; ++rr) {
+    if (live[rr]) {
+      const float lse = m[rr] + __builtin_amdgcn_logf(ssum[rr]) * kLn2;
+      for (int p = lane; p < rc[rr]; p += 64) emit(rr, p, rows[rr][p], lse);
+    }
+  }
+}
+
 // ---- the same step for small codebooks (T_l <= 1024, K <= 64) ------------------------------------
 // A workgroup of 8 waves owns 16 beams.  Phase A: the waves share out the 16-column MFMA tiles
 // and write the 16 x T_l logits (float32) to LDS.  Phase B: every wave takes two rows; a row's
@@ -847,134 +975,17 @@ __global__ __launch_bounds__(512, 1) void expand_small_kernel(ExpandArgs a) {
   }
   __syncthreads();
 
-  // phase B: this wave's two rows side by side (independent work hides the cross-lane latency)
-  const int NV = (V + 63) / 64;
+  // phase B: this wave's two rows side by side
   const int r0 = wave * 2;
   if (R0 + r0 >= a.rows) return;
-  bool live[2];
-  float zv[2][NVT], m[2], ssum[2];
-  uint64_t key[2][NVT], best[2][1];
-#pragma unroll
-  for (int rr = 0; rr < 2; ++rr) {
-    live[rr] = R0 + r0 + rr < a.rows;
-    m[rr] = -INFINITY;
-#pragma unroll
-    for (int j = 0; j < NVT; ++j) {
-      const int col = j * 64 + lane;
-      zv[rr][j] = (j < NV && col < V && live[rr]) ? ztile[(r0 + rr) * V + col] : -INFINITY;
-      m[rr] = fmaxf(m[rr], zv[rr][j]);
-    }
-  }
-  auto reduce_max = [&](float (&x)[2]) {
-#pragma unroll
-    for (int rr = 0; rr < 2; ++rr) {
-      float v = x[rr];
-      v = fmaxf(v, __uint_as_float(lane_xor<1>(__float_as_uint(v), lane)));
-      v = fmaxf(v, __uint_as_float(lane_xor<2>(__float_as_uint(v), lane)));
-      v = fmaxf(v, __uint_as_float(lane_xor<4>(__float_as_uint(v), lane)));
-      v = fmaxf(v, __uint_as_float(lane_xor<8>(__float_as_uint(v), lane)));
-      v = fmaxf(v, __uint_as_float(lane_xor<16>(__float_as_uint(v), lane)));
-      v = fmaxf(v, __uint_as_float(lane_xor<32>(__float_as_uint(v), lane)));
-      x[rr] = v;
-    }
-  };
-  auto reduce_sum = [&](float (&x)[2]) {
-#pragma unroll
-    for (int rr = 0; rr < 2; ++rr) {
-      float v = x[rr];
-      v += __uint_as_float(lane_xor<1>(__float_as_uint(v), lane));
-      v += __uint_as_float(lane_xor<2>(__float_as_uint(v), lane));
-      v += __uint_as_float(lane_xor<4>(__float_as_uint(v), lane));
-      v += __uint_as_float(lane_xor<8>(__float_as_uint(v), lane));
-      v += __uint_as_float(lane_xor<16>(__float_as_uint(v), lane));
-      v += __uint_as_float(lane_xor<32>(__float_as_uint(v), lane));
-      x[rr] = v;
-    }
-  };
-  reduce_max(m);
-#pragma unroll
-  for (int rr = 0; rr < 2; ++rr) {
-    ssum[rr] = 0.f;
-    best[rr][0] = 0;
-#pragma unroll
-    for (int j = 0; j < NVT; ++j) {
-      const int col = j * 64 + lane;
-      const bool ok = j < NV && col < V && live[rr];
-      ssum[rr] += ok ? __builtin_amdgcn_exp2f((zv[rr][j] - m[rr]) * kLog2e) : 0.f;
-      key[rr][j] = ok ? (((uint64_t)ordered_bits(zv[rr][j]) << 32) | (uint32_t)~(uint32_t)col) : 0ull;
-      best[rr][0] = key[rr][j] > best[rr][0] ? key[rr][j] : best[rr][0];
-    }
-  }
-  reduce_sum(ssum);
-  // K-th largest of the per-lane maxima: every one of the row's K best keys is >= it
-  sort_desc<1, 2>(best);
-  uint64_t* rows[2] = {scratch + wave * CAP, scratch + wave * CAP + CAP / 2};
-  int rc[2];
-#pragma unroll
-  for (int rr = 0; rr < 2; ++rr) {
-    const uint32_t bound_lo = __builtin_amdgcn_readlane((uint32_t)best[rr][0], K - 1);
-    const uint32_t bound_hi = __builtin_amdgcn_readlane((uint32_t)(best[rr][0] >> 32), K - 1);
-    const uint64_t bound = ((uint64_t)bound_hi << 32) | bound_lo;
-    // append the keys >= bound; a row gets CAP/2 places, which K * T_l/64 keys could exceed only
-    // in contrived cases: then the row falls back to the streaming top-K below
-    int cnt = 0;
-    bool overflow = false;
-#pragma unroll
-    for (int j = 0; j < NVT; ++j) {
-      if (j < NV) {
-        const bool pass = key[rr][j] >= bound && key[rr][j] != 0;
-        const uint64_t bal = __ballot(pass);
-        const int pos = cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32),
-                                                        __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0));
-        const int n = __popcll(bal);
-        if (cnt + n > CAP / 2) overflow = true;
-        if (pass && pos < CAP / 2) rows[rr][pos] = key[rr][j];
-        cnt += n;
-      }
-    }
-    rc[rr] = overflow ? -1 : cnt;
-  }
-  if (rc[0] < 0 || rc[1] < 0) {
-    // rare: too many keys tie with the bound; redo both rows with the general streaming top-K
-    for (int rr = 0; rr < 2; ++rr) {
-      wave_sync();
-      WaveTopK<CAP> q;
-      q.init(scratch + wave * CAP, K);
-      for (int j = 0; j < NV; ++j) {                       // keys rebuilt from the LDS tile
-        const int col = j * 64 + lane;
-        const bool ok = col < V && live[rr];
-        const float z = ok ? ztile[(r0 + rr) * V + col] : 0.f;
-        q.push(ok ? (((uint64_t)ordered_bits(z) << 32) | (uint32_t)~(uint32_t)col) : 0ull);
-      }
-      q.compact();
-      wave_sync();
-      if (live[rr]) {
-        const int row = R0 + r0 + rr;
-        const float lse = m[rr] + __builtin_amdgcn_logf(ssum[rr]) * kLn2;
-        for (int p = lane; p < q.cnt; p += 64) {
-          const uint64_t kk = q.buf[p];
-          a.cand_code[(int64_t)row * K + p] = (int32_t)(~(uint32_t)kk);
-          a.cand_logp[(int64_t)row * K + p] = unordered_bits((uint32_t)(kk >> 32)) - lse;
-        }
-      }
-    }
-    return;
-  }
-  uint64_t* const crows[2] = {rows[0], rows[1]};
-  uint64_t rt[2];
-  compact_rows<CAP / 2, 2>(crows, rc, rt, K);     // sorts both lists, keeps the K best
-#pragma unroll
-  for (int rr = 0; rr < 2; ++rr) {
-    if (live[rr]) {
-      const int row = R0 + r0 + rr;
-      const float lse = m[rr] + __builtin_amdgcn_logf(ssum[rr]) * kLn2;
-      for (int p = lane; p < rc[rr]; p += 64) {
-        const uint64_t kk = rows[rr][p];
-        a.cand_code[(int64_t)row * K + p] = (int32_t)(~(uint32_t)kk);
-        a.cand_logp[(int64_t)row * K + p] = unordered_bits((uint32_t)(kk >> 32)) - lse;
-      }
-    }
-  }
+  const bool live0 = true, live1 = R0 + r0 + 1 < a.rows;
+  two_rows_topk<NVT, CAP>(ztile + r0 * V, ztile + (r0 + 1) * V, live0, live1, V, K,
+                          scratch + wave * CAP, [&](int rr, int p, uint64_t kk, float lse) {
+                            const int row = R0 + r0 + rr;
+                            a.cand_code[(int64_t)row * K + p] = (int32_t)(~(uint32_t)kk);
+                            a.cand_logp[(int64_t)row * K + p] =
+                                unordered_bits((uint32_t)(kk >> 32)) - lse;
+                          });
 }
 
 // ---- per-request merge, verification, pruning and state update ---------------------------------
@@ -995,6 +1006,58 @@ struct MergeArgs {
   int32_t* count_out;       // or NULL
   int K_in, K, e;
 };
+
+// Eq. 3 with the additive Transition for the K survivors of request b: c' = c_parent + E[code]
+// (zero for unused slots); 8 (bf16) or 4 (f32) elements per thread and step.
+template <bool BF16>
+__device__ __forceinline__ void update_states(const void* state_in, const void* E, void* state_out,
+                                              int b, int K, int K_in, int e,
+                                              const int32_t* fin_parent, const int32_t* fin_code,
+                                              int tid, int nthreads) {
+  {
+    const int per = e / (BF16 ? 8 : 4);
+    for (int idx = tid; idx < K * per; idx += nthreads) {
+      const int j = idx / per, t = idx - j * per;
+      const int par = fin_parent[j], code = fin_code[j];
+      if constexpr (BF16) {
+        uint16_t* out = static_cast<uint16_t*>(state_out) + ((int64_t)b * K + j) * e + t * 8;
+        uint4 r = uint4{0, 0, 0, 0};
+        if (par >= 0) {
+          const uint4 ev = *reinterpret_cast<const uint4*>(
+              static_cast<const uint16_t*>(E) + (int64_t)code * e + t * 8);
+          uint4 sv = uint4{0, 0, 0, 0};
+          if (state_in)
+            sv = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(state_in) +
+                                                 ((int64_t)b * K_in + par) * e + t * 8);
+          const uint32_t ew[4] = {ev.x, ev.y, ev.z, ev.w}, sw[4] = {sv.x, sv.y, sv.z, sv.w};
+          uint32_t ow[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const float lo = bf16_to_float((uint16_t)ew[u]) + bf16_to_float((uint16_t)sw[u]);
+            const float hi = bf16_to_float((uint16_t)(ew[u] >> 16)) +
+                             bf16_to_float((uint16_t)(sw[u] >> 16));
+            ow[u] = (uint32_t)float_to_bf16(lo) | ((uint32_t)float_to_bf16(hi) << 16);
+          }
+          r = uint4{ow[0], ow[1], ow[2], ow[3]};
+        }
+        *reinterpret_cast<uint4*>(out) = r;
+      } else {
+        float* out = static_cast<float*>(state_out) + ((int64_t)b * K + j) * e + t * 4;
+        float4 r = float4{0.f, 0.f, 0.f, 0.f};
+        if (par >= 0) {
+          const float4 ev = *reinterpret_cast<const float4*>(static_cast<const float*>(E) +
+                                                             (int64_t)code * e + t * 4);
+          float4 sv = float4{0.f, 0.f, 0.f, 0.f};
+          if (state_in)
+            sv = *reinterpret_cast<const float4*>(static_cast<const float*>(state_in) +
+                                                  ((int64_t)b * K_in + par) * e + t * 4);
+          r = float4{ev.x + sv.x, ev.y + sv.y, ev.z + sv.z, ev.w + sv.w};
+        }
+        *reinterpret_cast<float4*>(out) = r;
+      }
+    }
+  }
+}
 
 // One workgroup (4 waves) per request.  Every candidate (parent p, within-beam rank r) gets the
 // sort key (ordered score, ~(p*K+r)), or 0 if the verifier rejects it; all keys go to LDS.  Each
@@ -1094,50 +1157,176 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
     if (lane == 0 && a.count_out) a.count_out[b] = f.cnt;
   }
   __syncthreads();
-  if (a.state_out) {
-    // Eq. 3, additive Transition: c' = c_parent + E[code]; 8 elements per thread and step
-    const int e = a.e, per = e / (BF16 ? 8 : 4);
-    for (int idx = tid; idx < K * per; idx += 256) {
-      const int j = idx / per, t = idx - j * per;
-      const int par = fin_parent[j], code = fin_code[j];
-      if constexpr (BF16) {
-        uint16_t* out = static_cast<uint16_t*>(a.state_out) + ((int64_t)b * K + j) * e + t * 8;
-        uint4 r = uint4{0, 0, 0, 0};
-        if (par >= 0) {
-          const uint4 ev = *reinterpret_cast<const uint4*>(
-              static_cast<const uint16_t*>(a.E) + (int64_t)code * e + t * 8);
-          uint4 sv = uint4{0, 0, 0, 0};
-          if (a.state_in)
-            sv = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(a.state_in) +
-                                                 ((int64_t)b * K_in + par) * e + t * 8);
-          const uint32_t ew[4] = {ev.x, ev.y, ev.z, ev.w}, sw[4] = {sv.x, sv.y, sv.z, sv.w};
-          uint32_t ow[4];
+  if (a.state_out)
+    update_states<BF16>(a.state_in, a.E, a.state_out, b, K, K_in, a.e, fin_parent, fin_code, tid, 256);
+}
+
+// ---- whole level in one kernel for small shapes (bf16, T_l <= 512, K and K_in <= 32) -----------
+// One workgroup of 16 waves per request.  Phase A: the request's K_in x T_l logits by MFMA into
+// LDS (the user-part row is the accumulators' start value).  Phase B: two rows per wave,
+// two_rows_topk, the per-beam lists stay in LDS.  Phase C: every candidate gets its cumulative
+// score, its Eq. 4 index and (last level) its hash-set probe; the K best survivors are found as in
+// merge_kernel.  Then the additive Transition.  Nothing but the level's outputs leaves the chip.
+struct LevelArgs {
+  const void* state_in;     // [B, K_in, e] or NULL
+  const void* Wbeam;        // packed beam part of W
+  const float* A;           // [B, V] user part
+  const uint64_t* key_in;   // [B, K_in] or NULL
+  const float* score_in;    // [B, K_in] or NULL
+  const void* E;            // [V, e] (used when state_out != NULL)
+  SetView set;              // slots == NULL: no verification
+  uint64_t mult;            // prod_{j<level} T_j
+  uint64_t* key_out;
+  float* score_out;
+  int32_t* parent_out;
+  int32_t* code_out;
+  void* state_out;          // or NULL
+  int32_t* count_out;       // or NULL
+  int K_in, K, V, e;
+};
+constexpr int kLevelWaves = 16, kLevelRows = 32, kLevelBeam = 32;
+template <int KST, int NVT>
+__global__ __launch_bounds__(64 * kLevelWaves, 1) void level_small_kernel(LevelArgs a) {
+  constexpr int CAP = 256;
+  extern __shared__ __align__(16) uint64_t lds[];
+  uint64_t* scratch = lds;                                            // [16 waves][CAP]
+  uint64_t* lists = scratch + kLevelWaves * CAP;                      // [32 rows][32]
+  uint64_t* keys2 = lists + kLevelRows * kLevelBeam;                  // [32*32]
+  uint64_t* topbuf = keys2 + kLevelRows * kLevelBeam;                 // [CAP]
+  float* ztile = reinterpret_cast<float*>(topbuf + CAP);              // [32][V]
+  __shared__ float row_lse[kLevelRows];
+  __shared__ uint64_t bounds[kLevelWaves];
+  __shared__ int32_t fin_parent[NEZHA_MAX_BEAM], fin_code[NEZHA_MAX_BEAM];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 4, c = lane & 15;
+  const int b = blockIdx.x;
+  const int V = a.V, K = a.K, K_in = a.K_in, e = a.e;
+  const bool has_beam = a.state_in != nullptr;
+  const int KS = e / 32;
+  const int n_ct = V / 16;
+  const int RT = (K_in + 15) / 16;                                    // 1 or 2 row tiles
+
+  {  // phase A: wave w takes column tiles w, w+16, ... for both row tiles (same W operands)
+    bf16x8 fa16[2][KST];
+    if (has_beam) {
+      const uint16_t* st = static_cast<const uint16_t*>(a.state_in) + (int64_t)b * K_in * e;
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            const float lo = bf16_to_float((uint16_t)ew[u]) + bf16_to_float((uint16_t)sw[u]);
-            const float hi = bf16_to_float((uint16_t)(ew[u] >> 16)) +
-                             bf16_to_float((uint16_t)(sw[u] >> 16));
-            ow[u] = (uint32_t)float_to_bf16(lo) | ((uint32_t)float_to_bf16(hi) << 16);
+      for (int rt = 0; rt < 2; ++rt) {
+        const int row = rt * 16 + c;
+#pragma unroll
+        for (int ks = 0; ks < KST; ++ks) {
+          uint4 v = uint4{0, 0, 0, 0};
+          if (ks < KS && row < K_in)
+            v = *reinterpret_cast<const uint4*>(st + (int64_t)row * e + ks * 32 + 8 * g);
+          fa16[rt][ks] = *reinterpret_cast<bf16x8*>(&v);
+        }
+      }
+    }
+    for (int ct = wave; ct < n_ct; ct += kLevelWaves) {
+      const float start = a.A[(int64_t)b * V + ct * 16 + c];
+      floatx4 acc0 = floatx4{start, start, start, start}, acc1 = acc0;
+      if (has_beam) {
+        const uint4* wp = static_cast<const uint4*>(a.Wbeam) + (int64_t)ct * KS * 64 + lane;
+        uint4 w[KST];
+#pragma unroll
+        for (int ks = 0; ks < KST; ++ks)
+          if (ks < KS) w[ks] = wp[ks * 64];
+#pragma unroll
+        for (int ks = 0; ks < KST; ++ks)
+          if (ks < KS) {
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                fa16[0][ks], *reinterpret_cast<bf16x8*>(&w[ks]), acc0, 0, 0, 0);
+            if (RT > 1)
+              acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                  fa16[1][ks], *reinterpret_cast<bf16x8*>(&w[ks]), acc1, 0, 0, 0);
           }
-          r = uint4{ow[0], ow[1], ow[2], ow[3]};
-        }
-        *reinterpret_cast<uint4*>(out) = r;
-      } else {
-        float* out = static_cast<float*>(a.state_out) + ((int64_t)b * K + j) * e + t * 4;
-        float4 r = float4{0.f, 0.f, 0.f, 0.f};
-        if (par >= 0) {
-          const float4 ev = *reinterpret_cast<const float4*>(static_cast<const float*>(a.E) +
-                                                             (int64_t)code * e + t * 4);
-          float4 sv = float4{0.f, 0.f, 0.f, 0.f};
-          if (a.state_in)
-            sv = *reinterpret_cast<const float4*>(static_cast<const float*>(a.state_in) +
-                                                  ((int64_t)b * K_in + par) * e + t * 4);
-          r = float4{ev.x + sv.x, ev.y + sv.y, ev.z + sv.z, ev.w + sv.w};
-        }
-        *reinterpret_cast<float4*>(out) = r;
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        ztile[(4 * g + i) * V + ct * 16 + c] = acc0[i];
+        if (RT > 1) ztile[(16 + 4 * g + i) * V + ct * 16 + c] = acc1[i];
       }
     }
   }
+  __syncthreads();
+
+  {  // phase B: rows 2*wave and 2*wave+1
+    const int r0 = wave * 2;
+    if (r0 < K_in) {
+      two_rows_topk<NVT, CAP>(ztile + r0 * V, ztile + (r0 + 1) * V, true, r0 + 1 < K_in, V, K,
+                              scratch + wave * CAP, [&](int rr, int p, uint64_t kk, float lse) {
+                                lists[(r0 + rr) * kLevelBeam + p] = kk;
+                                if (p == 0) row_lse[r0 + rr] = lse;
+                              });
+    }
+  }
+  __syncthreads();
+
+  // phase C: candidate (parent p, rank r) -> sort key (ordered score, ~(p*K+r)), 0 if rejected
+  const int n_c = K_in * K;                                           // <= 1024 = one per thread
+  const bool verify = a.set.slots != nullptr;
+  uint64_t sk = 0;
+  if (tid < n_c) {
+    const int p = tid / K;
+    const uint64_t zk = lists[p * kLevelBeam + (tid - p * K)];
+    const uint32_t code = ~(uint32_t)zk;
+    const float logp = unordered_bits((uint32_t)(zk >> 32)) - row_lse[p];
+    const float score = (a.score_in ? a.score_in[b * K_in + p] : 0.f) + logp;
+    bool ok = true;
+    if (verify) {
+      const uint64_t key = (a.key_in ? a.key_in[b * K_in + p] : 0ull) + (uint64_t)code * a.mult;
+      ok = set_contains(a.set, key);
+    }
+    if (ok) sk = ((uint64_t)ordered_bits(score) << 32) | (uint32_t)~(uint32_t)tid;
+    keys2[tid] = sk;
+  }
+  {
+    uint64_t mk[1][1] = {{sk}};
+    sort_desc<1, 1>(mk);                                              // K <= 32 <= 64
+    const uint64_t bound =
+        ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)(mk[0][0] >> 32), K - 1) << 32) |
+        (uint32_t)__builtin_amdgcn_readlane((uint32_t)mk[0][0], K - 1);
+    if (lane == 0) bounds[wave] = bound;
+  }
+  __syncthreads();
+  if (wave == 0) {
+    uint64_t tau = bounds[0];
+#pragma unroll
+    for (int w = 1; w < kLevelWaves; ++w) tau = bounds[w] > tau ? bounds[w] : tau;
+    WaveTopK<CAP> f;
+    f.init(topbuf, K);
+    f.tau = tau ? tau - 1ull : 0ull;                                  // keys >= tau enter
+    for (int base = 0; base < n_c; base += 64) f.push(base + lane < n_c ? keys2[base + lane] : 0ull);
+    f.compact();
+    wave_sync();
+    if (lane < K) {
+      const int64_t o = (int64_t)b * K + lane;
+      if (lane < f.cnt) {
+        const uint64_t s2 = f.buf[lane];
+        const int i = (int)(~(uint32_t)s2);
+        const int par = i / K;
+        const int32_t code = (int32_t)(~(uint32_t)lists[par * kLevelBeam + (i - par * K)]);
+        a.key_out[o] = (a.key_in ? a.key_in[b * K_in + par] : 0ull) + (uint64_t)(uint32_t)code * a.mult;
+        a.score_out[o] = unordered_bits((uint32_t)(s2 >> 32));
+        a.parent_out[o] = par;
+        a.code_out[o] = code;
+        fin_parent[lane] = par;
+        fin_code[lane] = code;
+      } else {
+        a.key_out[o] = kEmpty;
+        a.score_out[o] = -INFINITY;
+        a.parent_out[o] = -1;
+        a.code_out[o] = -1;
+        fin_parent[lane] = -1;
+        fin_code[lane] = -1;
+      }
+    }
+    if (lane == 0 && a.count_out) a.count_out[b] = f.cnt;
+  }
+  __syncthreads();
+  if (a.state_out)
+    update_states<true>(a.state_in, a.E, a.state_out, b, K, K_in, e, fin_parent, fin_code, tid,
+                        64 * kLevelWaves);
 }
 
 // ---- host side ---------------------------------------------------------------------------------
@@ -1440,6 +1629,51 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
   } else {
     rc = launch_user_part(desc, H_l, W_l, Wp, A, stream);
     if (rc != NEZHA_OK) return rc;
+  }
+
+  if (bf16 && K <= kLevelBeam && K_in <= kLevelRows && V <= 512) {
+    // small shapes: the whole level after the projection in one launch, one workgroup per request
+    LevelArgs la;
+    la.state_in = state_in;
+    la.Wbeam = Wp + packed_user_elems(d, V);
+    la.A = A;
+    la.key_in = key_in;
+    la.score_in = score_in;
+    la.E = E_l;
+    la.set = SetView{(set && level == L) ? set->slots : nullptr, set ? set->n_buckets : 0};
+    la.mult = mult[level - 1];
+    la.key_out = key_out;
+    la.score_out = score_out;
+    la.parent_out = parent_out;
+    la.code_out = code_out;
+    la.state_out = state_out;
+    la.count_out = count_out;
+    la.K_in = K_in;
+    la.K = K;
+    la.V = V;
+    la.e = e;
+    const size_t lds = (size_t)(kLevelWaves * 256 + 2 * kLevelRows * kLevelBeam + 256) * 8 +
+                       (size_t)kLevelRows * V * 4;
+    dim3 grid(B), block(64 * kLevelWaves);
+    ProfileScope prof(kLevelFused, stream);
+#define LAUNCH_LEVEL(KSTV, NVTV)                                                           \
+  do {                                                                                     \
+    rc = allow_lds(level_small_kernel<KSTV, NVTV>, lds);                                   \
+    if (rc != NEZHA_OK) return rc;                                                         \
+    hipLaunchKernelGGL((level_small_kernel<KSTV, NVTV>), grid, block, lds, stream, la);    \
+  } while (0)
+    if (V <= 256) {
+      if (e <= 64) LAUNCH_LEVEL(2, 4);
+      else if (e <= 128) LAUNCH_LEVEL(4, 4);
+      else LAUNCH_LEVEL(8, 4);
+    } else {
+      if (e <= 64) LAUNCH_LEVEL(2, 8);
+      else if (e <= 128) LAUNCH_LEVEL(4, 8);
+      else LAUNCH_LEVEL(8, 8);
+    }
+#undef LAUNCH_LEVEL
+    NEZHA_HIP_CHECK(hipGetLastError());
+    return NEZHA_OK;
   }
 
   ExpandArgs ea;
