@@ -36,6 +36,14 @@ PEAK_ALU_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # threshold compare (1)
 EXPAND_SLOTS_PER_LOGIT = 8
 BUCKET_BYTES = 64
+# HBM traffic per launch of the dominant kernel, from the rocprofv3 counter runs whose summaries
+# are in profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB -> bytes; the factors come from the
+# plain-copy calibration in the same runs).  Only workloads that were profiled have an entry.
+MEASURED_TRAFFIC_BYTES = {
+    ("serving", "level_small_kernel"): (2878.7 * 2.0 + 973.3) * 1024,
+    ("stress", "verify_probe_kernel"): (245937.8 * 2.0 + 4065.4) * 1024,
+    ("large", "expand_kernel"): (203763.7 * 2.0 + 214400.0) * 1024,
+}
 
 
 def parse_args():
@@ -177,7 +185,8 @@ def bench_draft(args, cfg):
         unit, peak = "GB/s", PEAK_HBM_GBS
         achieved = kd["work"] / (kd["total_ms"] * 1e-3) / 1e9
     roofline = {"kernel": dom, "bound": kd["bound"], "achieved": achieved, "peak": peak,
-                "unit": unit, "frac": achieved / peak, "traffic": None,
+                "unit": unit, "frac": achieved / peak,
+                "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dom)),
                 "avg_launch_us": kd["avg_us"],
                 "timing": "HIP events by the library around each launch, eager pass of %d steps"
                           % prof_steps}
@@ -323,7 +332,8 @@ def bench_stress(args, cfg):
                    "table_bytes": itemset.info()["n_slots"] * 8, "setup_s": round(setup_s, 1)},
         "roofline": {"kernel": "verify_probe_kernel", "bound": "hbm", "achieved": achieved,
                      "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS,
-                     "traffic": None, "avg_launch_us": 1e3 * ms / launches,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, "verify_probe_kernel")),
+                     "avg_launch_us": 1e3 * ms / launches,
                      "bytes_per_probe": bytes_per_probe,
                      "probes_per_s": n * launches / (ms * 1e-3),
                      "uniform_present_probes_per_s": n * uni_launches / (uni_ms * 1e-3),
