@@ -1161,6 +1161,234 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
     update_states<BF16>(a.state_in, a.E, a.state_out, b, K, K_in, a.e, fin_parent, fin_code, tid, 256);
 }
 
+// ---- the same step for large codebooks: two sweeps over the codes, no running top-K -----------
+// A workgroup of 8 waves owns 16 beams and walks the T_l codes in chunks of 256: phase A puts the
+// chunk's 16 x 256 logits into one of two LDS tiles by MFMA (operands of the next chunk are
+// fetched meanwhile), phase B gives every wave two rows with the row spread over all 64 lanes.
+//   sweep 1: running (max, sum of exponentials) and each lane's two largest logits per row.  The
+//            K-th largest of a row's 128 lane maxima is a lower bound of its K-th largest logit.
+//   sweep 2: the logits are formed again and those at or above the bound (K .. about 1.5 K of them)
+//            are appended to the row's LDS list; one sort per row then gives the K best.
+// The MFMA work is done twice, but nothing is sorted while streaming.  A row whose list would
+// overflow (more than 256 logits tie with the bound) is redone in a third sweep with the
+// general streaming top-K.  K <= 128.
+constexpr int kChunk = 256;
+template <int KST>
+__global__ __launch_bounds__(512, 1) void expand_chunked_kernel(ExpandArgs a) {
+  constexpr int CAP = 256;
+  extern __shared__ __align__(16) uint64_t lds[];
+  uint64_t* lists = lds;                                              // [16 rows][CAP]
+  float* ztile = reinterpret_cast<float*>(lds + 16 * CAP);            // [2][16][kChunk]
+  __shared__ int redo_flag;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int g = lane >> 4, c = lane & 15;
+  const int R0 = blockIdx.x * 16;
+  const int V = a.V, K = a.K, e = a.e;
+  const bool has_beam = a.state != nullptr;
+  const int KS = e / 32;
+  const int n_ct = V / 16;
+  const int n_chunks = (V + kChunk - 1) / kChunk;
+
+  bf16x8 fa16[KST];
+  if (has_beam) {
+    const int row = R0 + c;
+    const uint16_t* st = static_cast<const uint16_t*>(a.state);
+#pragma unroll
+    for (int ks = 0; ks < KST; ++ks) {
+      uint4 v = uint4{0, 0, 0, 0};
+      if (ks < KS && row < a.rows)
+        v = *reinterpret_cast<const uint4*>(st + (int64_t)row * e + ks * 32 + 8 * g);
+      fa16[ks] = *reinterpret_cast<bf16x8*>(&v);
+    }
+  }
+  int64_t a_off[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = R0 + 4 * g + i;
+    a_off[i] = (int64_t)((row < a.rows ? row : 0) / a.K_in) * V;
+  }
+  // operands of this wave's two tiles of a chunk (column tiles 16*ch + wave and + 8)
+  float aq[2][4];
+  uint4 wq[2][KST];
+  auto prefetch = [&](int ch) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      int ct = ch * 16 + wave + 8 * t;
+      ct = ct < n_ct ? ct : n_ct - 1;                                 // clamped; masked at the store
+#pragma unroll
+      for (int i = 0; i < 4; ++i) aq[t][i] = a.A[a_off[i] + ct * 16 + c];
+      if (has_beam) {
+        const uint4* wp = static_cast<const uint4*>(a.Wbeam) + (int64_t)ct * KS * 64 + lane;
+#pragma unroll
+        for (int ks = 0; ks < KST; ++ks)
+          if (ks < KS) wq[t][ks] = wp[ks * 64];
+      }
+    }
+  };
+  auto project = [&](int ch) {                                        // phase A of chunk ch
+    float* zt = ztile + (ch & 1) * 16 * kChunk;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      floatx4 acc = floatx4{aq[t][0], aq[t][1], aq[t][2], aq[t][3]};
+      if (has_beam) {
+#pragma unroll
+        for (int ks = 0; ks < KST; ++ks)
+          if (ks < KS)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                fa16[ks], *reinterpret_cast<bf16x8*>(&wq[t][ks]), acc, 0, 0, 0);
+      }
+      const bool in_range = ch * 16 + wave + 8 * t < n_ct;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        zt[(4 * g + i) * kChunk + (wave + 8 * t) * 16 + c] = in_range ? acc[i] : -INFINITY;
+    }
+  };
+
+  // phase B state of this wave's rows 2*wave, 2*wave+1
+  const int r0 = wave * 2;
+  float m[2] = {-INFINITY, -INFINITY}, ssum[2] = {0.f, 0.f};
+  float top0[2] = {-INFINITY, -INFINITY}, top1[2] = {-INFINITY, -INFINITY};
+  float bound[2] = {INFINITY, INFINITY};
+  int cnt[2] = {0, 0};
+  bool over[2] = {false, false};
+  WaveTopK<CAP> q[2];
+
+  for (int sweep = 0; sweep < 3; ++sweep) {
+    if (sweep == 2) {
+      // third sweep only if some row overflowed (decided for the whole workgroup)
+      if (threadIdx.x == 0) redo_flag = 0;
+      __syncthreads();
+      if (lane == 0 && (over[0] || over[1])) redo_flag = 1;
+      __syncthreads();
+      if (!redo_flag) break;
+#pragma unroll
+      for (int rr = 0; rr < 2; ++rr) q[rr].init(lists + (r0 + rr) * CAP, K);
+    }
+    prefetch(0);
+    for (int ch = 0; ch < n_chunks; ++ch) {
+      project(ch);
+      if (ch + 1 < n_chunks) prefetch(ch + 1);
+      __syncthreads();          // tile ch complete; everyone is past phase B of tile ch-1
+      const float* zt = ztile + (ch & 1) * 16 * kChunk;
+#pragma unroll
+      for (int rr = 0; rr < 2; ++rr) {
+        float z[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) z[j] = zt[(r0 + rr) * kChunk + j * 64 + lane];
+        if (sweep == 0) {
+          const float mx = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
+          const float mn = fmaxf(m[rr], mx);
+          float sum = (m[rr] == mn) ? ssum[rr] : ssum[rr] * __builtin_amdgcn_exp2f((m[rr] - mn) * kLog2e);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            sum += (z[j] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((z[j] - mn) * kLog2e);
+            const float lo = fminf(z[j], top0[rr]);
+            top0[rr] = fmaxf(z[j], top0[rr]);
+            top1[rr] = fmaxf(top1[rr], lo);
+          }
+          ssum[rr] = sum;
+          m[rr] = mn;
+        } else if (sweep == 1) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const bool pass = z[j] >= bound[rr];
+            const uint64_t bal = __ballot(pass);
+            if (bal) {
+              const int pos = cnt[rr] + __builtin_amdgcn_mbcnt_hi(
+                                            (uint32_t)(bal >> 32),
+                                            __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0));
+              const uint32_t code = (uint32_t)(ch * kChunk + j * 64 + lane);
+              if (pass && pos < CAP)
+                lists[(r0 + rr) * CAP + pos] = ((uint64_t)ordered_bits(z[j]) << 32) | (uint32_t)~code;
+              cnt[rr] += __popcll(bal);
+              if (cnt[rr] > CAP) over[rr] = true;
+            }
+          }
+        } else if (over[rr]) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const uint32_t code = (uint32_t)(ch * kChunk + j * 64 + lane);
+            q[rr].push(z[j] == -INFINITY ? 0ull
+                                         : (((uint64_t)ordered_bits(z[j]) << 32) | (uint32_t)~code));
+          }
+        }
+      }
+    }
+    if (sweep == 0) {
+      // log-sum-exp: merge the 64 lanes' (max, sum); bound: K-th largest of the 128 lane maxima
+#pragma unroll
+      for (int rr = 0; rr < 2; ++rr) {
+        float mm = m[rr], ss = ssum[rr];
+        auto merge_with = [&](float om, float os) {
+          const float mn = fmaxf(mm, om);
+          const float wa = (mm == mn) ? 1.f : __builtin_amdgcn_exp2f((mm - mn) * kLog2e);
+          const float wb = (om == mn) ? 1.f : __builtin_amdgcn_exp2f((om - mn) * kLog2e);
+          ss = ss * wa + os * wb;
+          mm = mn;
+        };
+        merge_with(__uint_as_float(lane_xor<1>(__float_as_uint(mm), lane)),
+                   __uint_as_float(lane_xor<1>(__float_as_uint(ss), lane)));
+        merge_with(__uint_as_float(lane_xor<2>(__float_as_uint(mm), lane)),
+                   __uint_as_float(lane_xor<2>(__float_as_uint(ss), lane)));
+        merge_with(__uint_as_float(lane_xor<4>(__float_as_uint(mm), lane)),
+                   __uint_as_float(lane_xor<4>(__float_as_uint(ss), lane)));
+        merge_with(__uint_as_float(lane_xor<8>(__float_as_uint(mm), lane)),
+                   __uint_as_float(lane_xor<8>(__float_as_uint(ss), lane)));
+        merge_with(__uint_as_float(lane_xor<16>(__float_as_uint(mm), lane)),
+                   __uint_as_float(lane_xor<16>(__float_as_uint(ss), lane)));
+        merge_with(__uint_as_float(lane_xor<32>(__float_as_uint(mm), lane)),
+                   __uint_as_float(lane_xor<32>(__float_as_uint(ss), lane)));
+        m[rr] = mm;
+        ssum[rr] = ss;
+      }
+      uint64_t mk[2][2];
+#pragma unroll
+      for (int rr = 0; rr < 2; ++rr) {
+        mk[rr][0] = (uint64_t)ordered_bits(top0[rr]) << 32;
+        mk[rr][1] = (uint64_t)ordered_bits(top1[rr]) << 32;
+      }
+      sort_desc<2, 2>(mk);                                            // position 2*lane + j
+#pragma unroll
+      for (int rr = 0; rr < 2; ++rr) {
+        const uint64_t pick = ((K - 1) & 1) ? mk[rr][1] : mk[rr][0];
+        bound[rr] = unordered_bits(
+            (uint32_t)__builtin_amdgcn_readlane((uint32_t)(pick >> 32), (K - 1) >> 1));
+      }
+    }
+    __syncthreads();            // the tiles are free again before the next sweep's first phase A
+  }
+
+  // the K best of each list, sorted; rows redone in the third sweep take their streaming result
+  if (R0 + r0 >= a.rows) return;
+#pragma unroll
+  for (int rr = 0; rr < 2; ++rr)
+    if (over[rr]) {
+      q[rr].compact();
+      cnt[rr] = q[rr].cnt;
+    }
+  if (!over[0] || !over[1]) {
+    uint64_t* const crows[2] = {lists + r0 * CAP, lists + (r0 + 1) * CAP};
+    int rc[2] = {over[0] ? 0 : cnt[0], over[1] ? 0 : cnt[1]};
+    uint64_t rt[2];
+    compact_rows<CAP, 2>(crows, rc, rt, K);
+    if (!over[0]) cnt[0] = rc[0];
+    if (!over[1]) cnt[1] = rc[1];
+  }
+  wave_sync();
+#pragma unroll
+  for (int rr = 0; rr < 2; ++rr) {
+    const int row = R0 + r0 + rr;
+    if (row < a.rows) {
+      const float lse = m[rr] + __builtin_amdgcn_logf(ssum[rr]) * kLn2;
+      for (int p = lane; p < cnt[rr]; p += 64) {
+        const uint64_t kk = lists[(r0 + rr) * CAP + p];
+        a.cand_code[(int64_t)row * K + p] = (int32_t)(~(uint32_t)kk);
+        a.cand_logp[(int64_t)row * K + p] = unordered_bits((uint32_t)(kk >> 32)) - lse;
+      }
+    }
+  }
+}
+
 // ---- whole level in one kernel for small shapes (bf16, T_l <= 512, K and K_in <= 32) -----------
 // One workgroup of 16 waves per request.  Phase A: the request's K_in x T_l logits by MFMA into
 // LDS (the user-part row is the accumulators' start value).  Phase B: two rows per wave,
@@ -1727,8 +1955,19 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
     else LAUNCH_EXPAND(true, CAPV, 8);                           \
   } while (0)
       if (bf16) {
-        if (plan.cap == 128) LAUNCH_EXPAND_BF16(128);
-        else LAUNCH_EXPAND_BF16(256);
+        // large codebook (or K > 64): two sweeps in chunks of 256 codes, 8 waves per 16 beams
+        const size_t lds2 = (size_t)16 * 256 * 8 + (size_t)2 * 16 * kChunk * 4;
+        dim3 grid2(groups), block2(512);
+#define LAUNCH_CHUNKED(KSTV)                                                              \
+  do {                                                                                    \
+    rc = allow_lds(expand_chunked_kernel<KSTV>, lds2);                                    \
+    if (rc != NEZHA_OK) return rc;                                                        \
+    hipLaunchKernelGGL((expand_chunked_kernel<KSTV>), grid2, block2, lds2, stream, ea);   \
+  } while (0)
+        if (e <= 64) LAUNCH_CHUNKED(2);
+        else if (e <= 128) LAUNCH_CHUNKED(4);
+        else LAUNCH_CHUNKED(8);
+#undef LAUNCH_CHUNKED
       } else {
         if (plan.cap == 128) LAUNCH_EXPAND(false, 128, 64);
         else LAUNCH_EXPAND(false, 256, 64);

@@ -99,6 +99,29 @@ def test_zero_weights_follow_the_tie_rule(oracle):
     assert (want[-1]["key"] == to_np(outs[-1]["key"]).view(np.uint64)).all()
 
 
+def test_zero_weights_with_a_large_codebook(oracle):
+    """All 2048 logits of every row tie: the bound of the two-sweep kernel lets every code
+    through, the lists overflow and the streaming fallback has to give codes 0..K-1."""
+    cfg = synth.StepConfig("ties_large", B=2, d=64, e=32, L=2, V=2048, K=100, N=1000,
+                           dtype="bf16", catalog="uniform")
+    x = synth.draft_inputs(cfg, 1)
+    x["W"] = [np.zeros_like(w) for w in x["W"]]
+    H, W, E = to_device(x, cfg)
+    outs = nz.decode(H, W, E, cfg.radices, cfg.K, None)
+    torch.cuda.synchronize()
+    for l, o in enumerate(outs):
+        g = outputs_to_numpy(o)
+        assert (g["code"] == np.arange(cfg.K)).all() and (g["parent"] == 0).all()
+        assert np.allclose(g["score"], -(l + 1) * np.log(2048), atol=1e-5)
+
+
+def test_large_codebook_odd_sizes(oracle):
+    # T_l not a multiple of the chunk of 256 codes, K between 65 and 128, ragged rows
+    cfg = synth.StepConfig("odd_large", B=3, d=64, e=64, L=2, V=1104, K=70, N=50_000,
+                           dtype="bf16", catalog="uniform", w_std=0.05)
+    run_config(oracle, cfg, 11)
+
+
 def test_results_are_deterministic(oracle):
     cfg = synth.get_config("serving").scaled(B=64)
     x, cat = planted_workload(oracle, cfg, 42, N=200_000)
