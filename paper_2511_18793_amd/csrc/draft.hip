@@ -1174,7 +1174,7 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
 // general streaming top-K.  K <= 128.
 constexpr int kChunk = 256;
 template <int KST>
-__global__ __launch_bounds__(512, 1) void expand_chunked_kernel(ExpandArgs a) {
+__global__ __launch_bounds__(512, 4) void expand_chunked_kernel(ExpandArgs a) {
   constexpr int CAP = 256;
   extern __shared__ __align__(16) uint64_t lds[];
   uint64_t* lists = lds;                                              // [16 rows][CAP]
