@@ -10,6 +10,8 @@
 //                        best surviving candidates, and the additive Transition of Eq. 3
 #include "nezha_internal.h"
 
+#include <type_traits>
+
 namespace nezha {
 namespace {
 
@@ -73,24 +75,29 @@ __device__ __forceinline__ uint32_t lane_xor(uint32_t v, int lane) {
 
 // One compare-exchange step of the bitonic network across lanes at distance LM, for R
 // independent sequences at once (independent work hides the cross-lane latency).
-template <int NPL, int R, int LM>
-__device__ __forceinline__ void cross_step(uint64_t (&key)[R][NPL], int lane, bool keep_max) {
+template <int NPL, int R, int LM, typename T>
+__device__ __forceinline__ void cross_step(T (&key)[R][NPL], int lane, bool keep_max) {
 #pragma unroll
   for (int r = 0; r < R; ++r)
 #pragma unroll
     for (int j = 0; j < NPL; ++j) {
-      const uint32_t lo = lane_xor<LM>((uint32_t)key[r][j], lane);
-      const uint32_t hi = lane_xor<LM>((uint32_t)(key[r][j] >> 32), lane);
-      const uint64_t other = ((uint64_t)hi << 32) | lo;
+      T other;
+      if constexpr (sizeof(T) == 8) {
+        const uint32_t lo = lane_xor<LM>((uint32_t)key[r][j], lane);
+        const uint32_t hi = lane_xor<LM>((uint32_t)(key[r][j] >> 32), lane);
+        other = ((uint64_t)hi << 32) | lo;
+      } else {
+        other = lane_xor<LM>(key[r][j], lane);
+      }
       const bool gt = key[r][j] > other;
       key[r][j] = (gt == keep_max) ? key[r][j] : other;
     }
 }
 
-// Bitonic sort of R sequences of 64*NPL keys, NPL per lane, descending in position
-// p = lane*NPL + j.
-template <int NPL, int R>
-__device__ __forceinline__ void sort_desc(uint64_t (&key)[R][NPL]) {
+// Bitonic sort of R sequences of 64*NPL keys (64- or 32-bit unsigned), NPL per lane, descending
+// in position p = lane*NPL + j.
+template <int NPL, int R, typename T = uint64_t>
+__device__ __forceinline__ void sort_desc(T (&key)[R][NPL]) {
   const int lane = threadIdx.x & 63;
   constexpr int N = 64 * NPL;
 #pragma unroll
@@ -107,7 +114,7 @@ __device__ __forceinline__ void sort_desc(uint64_t (&key)[R][NPL]) {
               // block direction: descending where bit k of the position is clear
               const bool desc = (k < NPL) ? ((j & k) == 0)
                                           : (k == N ? true : ((lane & (k / NPL)) == 0));
-              const uint64_t a = key[r][j], b = key[r][j2];
+              const T a = key[r][j], b = key[r][j2];
               const bool a_gt = a > b;
               const bool swap = desc ? !a_gt : a_gt;
               key[r][j] = swap ? b : a;
@@ -119,12 +126,12 @@ __device__ __forceinline__ void sort_desc(uint64_t (&key)[R][NPL]) {
         const bool is_lo = (lane & lm) == 0;
         const bool desc = (k == N) ? true : ((lane & (k / NPL)) == 0);
         const bool keep_max = (is_lo == desc);
-        if (lm == 1) cross_step<NPL, R, 1>(key, lane, keep_max);
-        else if (lm == 2) cross_step<NPL, R, 2>(key, lane, keep_max);
-        else if (lm == 4) cross_step<NPL, R, 4>(key, lane, keep_max);
-        else if (lm == 8) cross_step<NPL, R, 8>(key, lane, keep_max);
-        else if (lm == 16) cross_step<NPL, R, 16>(key, lane, keep_max);
-        else cross_step<NPL, R, 32>(key, lane, keep_max);
+        if (lm == 1) cross_step<NPL, R, 1, T>(key, lane, keep_max);
+        else if (lm == 2) cross_step<NPL, R, 2, T>(key, lane, keep_max);
+        else if (lm == 4) cross_step<NPL, R, 4, T>(key, lane, keep_max);
+        else if (lm == 8) cross_step<NPL, R, 8, T>(key, lane, keep_max);
+        else if (lm == 16) cross_step<NPL, R, 16, T>(key, lane, keep_max);
+        else cross_step<NPL, R, 32, T>(key, lane, keep_max);
       }
     }
   }
@@ -490,6 +497,7 @@ struct ExpandArgs {
   float* cand_logp;      // [rows, K]
   int rows;              // B * K_in
   int K_in, K, V, d, e;
+  const uint8_t* redo;   // expand_chunked_kernel: only rows with redo[row] != 0 (NULL: every row)
 };
 
 // A workgroup of NW waves owns 16 beams (rows); wave w takes the blocks of 64 codes
@@ -1188,6 +1196,11 @@ __global__ __launch_bounds__(512, 4) void expand_chunked_kernel(ExpandArgs a) {
   const int KS = e / 32;
   const int n_ct = V / 16;
   const int n_chunks = (V + kChunk - 1) / kChunk;
+  if (a.redo) {                      // a pass over the rows another kernel left: most groups leave
+    bool any = false;
+    for (int i = 0; i < 16; ++i) any = any || (R0 + i < a.rows && a.redo[R0 + i] != 0);
+    if (!any) return;
+  }
 
   bf16x8 fa16[KST];
   if (has_beam) {
@@ -1378,7 +1391,7 @@ __global__ __launch_bounds__(512, 4) void expand_chunked_kernel(ExpandArgs a) {
 #pragma unroll
   for (int rr = 0; rr < 2; ++rr) {
     const int row = R0 + r0 + rr;
-    if (row < a.rows) {
+    if (row < a.rows && (!a.redo || a.redo[row] != 0)) {
       const float lse = m[rr] + __builtin_amdgcn_logf(ssum[rr]) * kLn2;
       for (int p = lane; p < cnt[rr]; p += 64) {
         const uint64_t kk = lists[(r0 + rr) * CAP + p];
@@ -1386,6 +1399,332 @@ __global__ __launch_bounds__(512, 4) void expand_chunked_kernel(ExpandArgs a) {
         a.cand_logp[(int64_t)row * K + p] = unordered_bits((uint32_t)(kk >> 32)) - lse;
       }
     }
+  }
+}
+
+// ---- the same step with one workgroup per request (bf16, K_in >= 16) ---------------------------
+// The beams of a request share its user-part row and all beams share W_l: wave w owns the
+// request's beams 16w .. 16w+15 as one MFMA row tile, and the packed beam part of W_l is streamed
+// through LDS in chunks of 128 codes (global_load_lds, two buffers) that every wave reads, so W_l
+// crosses L2 -> CU once per request and sweep instead of once per 16 beams.  Logits stay in the
+// MFMA result layout (register i of lane l: beam 4*(l/16)+i of the tile, code column l%16):
+//   sweep 1: per lane and beam a running sum of exponentials about a reference point and the
+//            maxima of 8 code groups (column tile modulo 8).  A beam's 16 lanes x 8 groups give
+//            128 group maxima; the K-th largest of them is a lower bound of the beam's K-th
+//            largest logit.
+//   sweep 2: logits at or above the bound are appended to the beam's list of 256 (logit, code)
+//            pairs in global scratch, the place taken from a counter in LDS.  The scratch belongs
+//            to the workgroup and is reused for each of its requests, so it lives in L2 / MALL.
+//   Then, per beam, a sort of the listed logits alone (32-bit keys) gives the K-th largest; the
+//   entries above it and the lowest codes among those equal to it are written out, in list order.
+//   (The merge step orders equal scores by parent and code, so the order inside a beam's
+//   candidates carries no meaning.)
+// A beam whose list would overflow (ties, or large logits crowded into few groups) is flagged in
+// redo[] and left to a pass of expand_chunked_kernel.
+constexpr int kReqCap = 256;         // list entries per beam
+constexpr int kReqTiles = 8;         // column tiles per chunk = code groups per lane and beam
+constexpr int kReqMaxGroups = 1024;  // workgroups that own list scratch
+__host__ __device__ inline size_t request_w_region(int e, int n_waves) {
+  const size_t chunks = (size_t)2 * kReqTiles * (e / 32) * 1024;   // two chunk buffers
+  const size_t maxima = (size_t)n_waves * 16 * 128 * 4;            // group maxima between sweeps
+  return chunks > maxima ? chunks : maxima;
+}
+// Element j (wave uniform, 0 <= j < N) of a small register array, without indexing it.
+template <int N>
+__device__ __forceinline__ uint32_t pick_element(const uint32_t (&v)[N], int j) {
+  static_assert(N == 1 || N == 2 || N == 4, "1, 2 or 4 elements");
+  if constexpr (N == 1) {
+    return v[0];
+  } else if constexpr (N == 2) {
+    return v[0] ^ ((v[0] ^ v[1]) & (0u - (uint32_t)(j & 1)));
+  } else {
+    const uint32_t m1 = 0u - (uint32_t)(j & 1), m2 = 0u - (uint32_t)((j >> 1) & 1);
+    const uint32_t lo = v[0] ^ ((v[0] ^ v[1]) & m1), hi = v[2] ^ ((v[2] ^ v[3]) & m1);
+    return lo ^ ((lo ^ hi) & m2);
+  }
+}
+template <int KST>
+__global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
+    ExpandArgs a, uint64_t* __restrict__ lists_all, uint8_t* __restrict__ redo) {
+  extern __shared__ __align__(16) uint8_t req_lds[];
+  // wave-uniform values are made scalar so that what is derived from them needs no vector registers
+  const int lane = threadIdx.x & 63, NW = blockDim.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int V = a.V, K = a.K, K_in = a.K_in, e = a.e;
+  constexpr int KS = KST;                                   // e = 32 * KST exactly
+  const int n_ct = V / 16;
+  const int n_chunks = (n_ct + kReqTiles - 1) / kReqTiles;
+  constexpr int chunk_blocks = kReqTiles * KS;              // 1 KiB operand blocks per chunk
+  const int total_blocks = n_ct * KS;
+  uint8_t* const wbuf = req_lds;                                                  // [2][chunk]
+  float* const abuf = reinterpret_cast<float*>(req_lds + request_w_region(e, NW));   // [2][128]
+  float* const my_info = abuf + 2 * kReqTiles * 16 + wave * 48;   // bound[16], lse[16], count[16]
+  int* const my_cnt = reinterpret_cast<int*>(my_info + 32);
+  uint64_t* const my_lists = lists_all + ((int64_t)blockIdx.x * 128 + wave * 16) * kReqCap;
+  const int B = a.rows / K_in;
+  const uint4* const Wb = static_cast<const uint4*>(a.Wbeam);
+
+  auto stage = [&](int b, int ch) {       // chunk ch of W_l and of the request's user-part row
+    uint8_t* dst = wbuf + (ch & 1) * chunk_blocks * 1024;
+    for (int blk = wave; blk < chunk_blocks; blk += NW) {
+      int gb = ch * chunk_blocks + blk;
+      gb = gb < total_blocks ? gb : total_blocks - 1;       // past the end: a block nobody uses
+      load_block_to_lds(Wb + (int64_t)gb * 64 + lane, dst + blk * 1024);
+    }
+    if (wave == NW - 1 && lane < kReqTiles * 4) {
+      int col = ch * kReqTiles * 16 + lane * 4;
+      col = col < V ? col : 0;
+      load_block_to_lds(a.A + (int64_t)b * V + col, abuf + (ch & 1) * kReqTiles * 16);
+    }
+  };
+
+  for (int b = blockIdx.x; b < B; b += gridDim.x) {
+    bf16x8 fa16[KST];
+    {
+      const int g = lane >> 4, c = lane & 15;
+      const int r = wave * 16 + c;
+      const uint16_t* st = static_cast<const uint16_t*>(a.state);
+#pragma unroll
+      for (int ks = 0; ks < KST; ++ks) {
+        uint4 v = uint4{0, 0, 0, 0};
+        if (st && r < K_in)
+          v = *reinterpret_cast<const uint4*>(st + ((int64_t)b * K_in + r) * e + ks * 32 + 8 * g);
+        fa16[ks] = *reinterpret_cast<bf16x8*>(&v);
+      }
+    }
+    // sweep 1 state: sum of exp(z - m) with the reference m held as nml = -m * log2(e)
+    float gmax[4][kReqTiles], m[4], nml[4], ssum[4], bound[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      m[i] = -INFINITY;
+      nml[i] = 0.f;
+      ssum[i] = 0.f;
+      bound[i] = INFINITY;
+#pragma unroll
+      for (int j = 0; j < kReqTiles; ++j) gmax[i][j] = -INFINITY;
+    }
+    if (lane < 16) my_cnt[lane] = 0;
+
+    auto run_sweep = [&](auto sweep_c) {
+      constexpr int sweep = decltype(sweep_c)::value;
+      // a copy of the lane id the compiler cannot see through: addresses derived from it are
+      // formed here and not kept in registers across the other phases
+      int ln = lane;
+      asm volatile("" : "+v"(ln));
+      const int g = ln >> 4, c = ln & 15;
+      stage(b, 0);
+      for (int ch = 0; ch < n_chunks; ++ch) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of chunk ch has landed
+        __syncthreads();                      // chunk ch is whole; the other buffer is free
+        if (ch + 1 < n_chunks) stage(b, ch + 1);
+        const uint8_t* wb = wbuf + (ch & 1) * chunk_blocks * 1024;
+        const float* ab = abuf + (ch & 1) * kReqTiles * 16;
+        const int tiles = n_ct - ch * kReqTiles;            // >= kReqTiles except in the last chunk
+        auto chunk_body = [&](auto ragged_c) {
+          constexpr bool ragged = decltype(ragged_c)::value;
+          // Operands of tile ct+1 are requested right after the MFMAs of tile ct have been
+          // issued, into the same registers, and arrive under tile ct's vector work.  The
+          // scheduling fences keep the compiler from hoisting a whole chunk's LDS reads at once,
+          // which costs more registers than there are.
+          uint4 w[KST];
+          float a_next = ab[c];
+#pragma unroll
+          for (int ks = 0; ks < KST; ++ks)
+            w[ks] = *reinterpret_cast<const uint4*>(wb + (ks * 64 + ln) * 16);
+#pragma unroll
+          for (int ct = 0; ct < kReqTiles; ++ct) {
+            const float a0 = a_next;
+            floatx4 acc = floatx4{a0, a0, a0, a0};
+#pragma unroll
+            for (int ks = 0; ks < KST; ++ks)
+              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                  fa16[ks], *reinterpret_cast<const bf16x8*>(&w[ks]), acc, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (ct + 1 < kReqTiles) {
+              a_next = ab[(ct + 1) * 16 + c];
+#pragma unroll
+              for (int ks = 0; ks < KST; ++ks)
+                w[ks] = *reinterpret_cast<const uint4*>(
+                    wb + (((ct + 1) * KS + ks) * 64 + ln) * 16);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            const bool live = !ragged || ct < tiles;
+            float z[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) z[i] = live ? acc[i] : -INFINITY;
+            if constexpr (sweep == 0) {
+              // Sum of exp(z - m) about a fixed reference m = (the lane's first logit of the
+              // beam) + 20, held as nml = -m * log2(e): no rescaling while streaming.  A beam with
+              // a logit more than 64 above a lane's reference is redone by the general kernel.
+              if (ct == 0 && ch == 0) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                  m[i] = z[i] + 20.f;
+                  nml[i] = -m[i] * kLog2e;
+                }
+              }
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                gmax[i][ct] = __builtin_amdgcn_fmed3f(gmax[i][ct], z[i], INFINITY);   // max
+                ssum[i] += __builtin_amdgcn_exp2f(fmaf(z[i], kLog2e, nml[i]));
+              }
+            } else {
+              const uint32_t code = (uint32_t)((ch * kReqTiles + ct) * 16 + c);
+              int pos[4];
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                pos[i] = kReqCap;
+                if (live && z[i] >= bound[i]) pos[i] = atomicAdd(&my_cnt[4 * g + i], 1);
+              }
+#pragma unroll
+              for (int i = 0; i < 4; ++i)
+                if (pos[i] < kReqCap)
+                  my_lists[(4 * g + i) * kReqCap + pos[i]] =
+                      ((uint64_t)__float_as_uint(z[i]) << 32) | code;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        };
+        if (tiles >= kReqTiles) chunk_body(std::false_type{});
+        else chunk_body(std::true_type{});
+      }
+      __builtin_amdgcn_s_waitcnt(0x0F70);     // list stores are done before anyone reads them
+      __syncthreads();                        // every wave is done with the chunk buffers
+      if constexpr (sweep == 0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {         // (reference, sum) over the beam's 16 lanes
+          float mm = m[i], ss = ssum[i];
+          auto merge_with = [&](float om, float os) {
+            const float mn = fmaxf(mm, om);
+            ss = ss * __builtin_amdgcn_exp2f((mm - mn) * kLog2e) +
+                 os * __builtin_amdgcn_exp2f((om - mn) * kLog2e);
+            mm = mn;
+          };
+          merge_with(__uint_as_float(lane_xor<1>(__float_as_uint(mm), lane)),
+                     __uint_as_float(lane_xor<1>(__float_as_uint(ss), lane)));
+          merge_with(__uint_as_float(lane_xor<2>(__float_as_uint(mm), lane)),
+                     __uint_as_float(lane_xor<2>(__float_as_uint(ss), lane)));
+          merge_with(__uint_as_float(lane_xor<4>(__float_as_uint(mm), lane)),
+                     __uint_as_float(lane_xor<4>(__float_as_uint(ss), lane)));
+          merge_with(__uint_as_float(lane_xor<8>(__float_as_uint(mm), lane)),
+                     __uint_as_float(lane_xor<8>(__float_as_uint(ss), lane)));
+          if (c == 0) my_info[16 + 4 * g + i] = mm + __builtin_amdgcn_logf(ss) * kLn2;
+          float top = gmax[i][0];
+#pragma unroll
+          for (int j = 1; j < kReqTiles; ++j) top = fmaxf(top, gmax[i][j]);
+          // this lane's sum may have overflowed: push the beam's count past the list size
+          if (top > m[i] + 64.f) atomicAdd(&my_cnt[4 * g + i], kReqCap + 1);
+        }
+        // the beams' 128 group maxima each, through this wave's part of the chunk buffers
+        float* gm = reinterpret_cast<float*>(req_lds) + wave * (16 * 128);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int h = 0; h < 2; ++h)
+            *reinterpret_cast<float4*>(gm + (4 * g + i) * 128 + c * 8 + h * 4) =
+                float4{gmax[i][4 * h], gmax[i][4 * h + 1], gmax[i][4 * h + 2], gmax[i][4 * h + 3]};
+        wave_sync();
+#pragma unroll 1
+        for (int q = 0; q < 4; ++q) {
+          uint32_t mk[4][2];
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) mk[r][j] = ordered_bits(gm[(4 * q + r) * 128 + j * 64 + ln]);
+          sort_desc<2, 4, uint32_t>(mk);                                // position 2*lane + j
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const uint32_t pick = pick_element<2>(mk[r], (K - 1) & 1);
+            const float bnd = unordered_bits((uint32_t)__builtin_amdgcn_readlane((int)pick, (K - 1) >> 1));
+            if (lane == 0) my_info[4 * q + r] = bnd;
+          }
+        }
+        wave_sync();
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          bound[i] = (wave * 16 + 4 * g + i < K_in) ? my_info[4 * g + i] : INFINITY;
+        __syncthreads();                      // maxima read before the next chunk lands on them
+      }
+    };
+    run_sweep(std::integral_constant<int, 0>{});
+    run_sweep(std::integral_constant<int, 1>{});
+
+    // per beam: the K-th largest listed logit, then the entries that belong to the K best
+    auto emit = [&](auto npl_c, int q, const int (&n)[2]) {
+      constexpr int NPL = decltype(npl_c)::value;
+      int ln = lane;
+      asm volatile("" : "+v"(ln));
+      uint32_t zk[2][NPL], code[2][NPL], sk[2][NPL];
+#pragma unroll
+      for (int r = 0; r < 2; ++r)
+#pragma unroll
+        for (int j = 0; j < NPL; ++j) {
+          const int idx = j * 64 + ln;
+          uint64_t ent = 0;
+          if (idx < n[r]) ent = my_lists[(2 * q + r) * kReqCap + idx];
+          zk[r][j] = idx < n[r] ? ordered_bits(__uint_as_float((uint32_t)(ent >> 32))) : 0u;
+          code[r][j] = (uint32_t)ent;
+          sk[r][j] = zk[r][j];
+        }
+      sort_desc<NPL, 2, uint32_t>(sk);                                  // position NPL*lane + j
+#pragma unroll
+      for (int r = 0; r < 2; ++r) {
+        if (n[r] == 0) continue;
+        const uint32_t tau = (uint32_t)__builtin_amdgcn_readlane(
+            (int)pick_element<NPL>(sk[r], (K - 1) % NPL), (K - 1) / NPL);
+        int n_gt = 0, n_eq = 0;
+#pragma unroll
+        for (int j = 0; j < NPL; ++j) {
+          n_gt += __popcll(__ballot(zk[r][j] > tau));
+          n_eq += __popcll(__ballot(zk[r][j] == tau));
+        }
+        const int need = K - n_gt;                                      // >= 1 of the n_eq ties
+        uint32_t cthr = 0;                                              // ~code must reach this
+        if (n_eq > need) {
+          uint32_t ck[1][NPL];
+#pragma unroll
+          for (int j = 0; j < NPL; ++j) ck[0][j] = zk[r][j] == tau ? ~code[r][j] : 0u;
+          sort_desc<NPL, 1, uint32_t>(ck);
+          cthr = (uint32_t)__builtin_amdgcn_readlane(
+              (int)pick_element<NPL>(ck[0], (need - 1) % NPL), (need - 1) / NPL);
+        }
+        const int64_t row = (int64_t)b * K_in + wave * 16 + 2 * q + r;
+        const float lse = my_info[16 + 2 * q + r];
+        int base = 0;
+#pragma unroll
+        for (int j = 0; j < NPL; ++j) {
+          const bool take = zk[r][j] > tau || (zk[r][j] == tau && ~code[r][j] >= cthr);
+          const uint64_t bal = __ballot(take);
+          const int p = base + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32),
+                                                         __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0));
+          if (take && p < K) {
+            a.cand_code[row * K + p] = (int32_t)code[r][j];
+            a.cand_logp[row * K + p] = unordered_bits(zk[r][j]) - lse;
+          }
+          base += __popcll(bal);
+        }
+      }
+    };
+#pragma unroll 1
+    for (int q = 0; q < 8; ++q) {
+      const int ra = wave * 16 + 2 * q;
+      if (ra >= K_in) break;
+      int n[2];
+      n[0] = __builtin_amdgcn_readfirstlane(my_cnt[2 * q]);
+      n[1] = ra + 1 < K_in ? __builtin_amdgcn_readfirstlane(my_cnt[2 * q + 1]) : 0;
+#pragma unroll
+      for (int r = 0; r < 2; ++r) {
+        const bool over = n[r] > kReqCap;
+        if (lane == 0 && ra + r < K_in) redo[(int64_t)b * K_in + ra + r] = over ? 1 : 0;
+        if (over) n[r] = 0;
+      }
+      const int most = n[0] > n[1] ? n[0] : n[1];
+      if (most == 0) continue;
+      if (most <= 64) emit(std::integral_constant<int, 1>{}, q, n);
+      else if (most <= 128) emit(std::integral_constant<int, 2>{}, q, n);
+      else emit(std::integral_constant<int, 4>{}, q, n);
+    }
+    wave_sync();                              // counters and info are rewritten for the next request
   }
 }
 
@@ -1559,9 +1898,21 @@ __global__ __launch_bounds__(64 * kLevelWaves, 1) void level_small_kernel(LevelA
 
 // ---- host side ---------------------------------------------------------------------------------
 struct Plan {
-  size_t wp_off, a_off, code_off, logp_off, total;
+  size_t wp_off, a_off, code_off, logp_off, list_off, redo_off, total;
   int cap;
+  bool per_request;   // expand_request_kernel takes the expansion
 };
+
+// Which kernels take a level is a function of the shape alone, so that the workspace can be sized
+// without the buffers.
+inline bool level_fits_one_launch(bool bf16, int K, int K_in, int V) {
+  return bf16 && K <= kLevelBeam && K_in <= kLevelRows && V <= 512;
+}
+inline bool codebook_fits_lds(bool bf16, int K, int V) { return bf16 && V <= 1024 && K <= 64; }
+inline bool expand_per_request(bool bf16, int K, int K_in, int V, int e) {
+  return bf16 && K_in >= 16 && (e == 32 || e == 64 || e == 128 || e == 256) &&
+         !level_fits_one_launch(bf16, K, K_in, V) && !codebook_fits_lds(bf16, K, V);
+}
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -1608,6 +1959,14 @@ int check_desc(const nezha_step_desc* dsc, Plan* plan) {
     off += align_up(rows * dsc->K * 4, 256);
     plan->logp_off = off;
     off += align_up(rows * dsc->K * 4, 256);
+    plan->per_request = expand_per_request(bf16, dsc->K, dsc->K_in, V, dsc->e);
+    plan->list_off = plan->redo_off = off;
+    if (plan->per_request) {
+      const size_t groups = dsc->B < kReqMaxGroups ? (size_t)dsc->B : (size_t)kReqMaxGroups;
+      off += align_up(groups * 128 * kReqCap * 8, 256);
+      plan->redo_off = off;
+      off += align_up(rows, 256);
+    }
     plan->total = off < 256 ? 256 : off;
     plan->cap = dsc->K <= 32 ? 128 : 256;
   }
@@ -1859,7 +2218,7 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
     if (rc != NEZHA_OK) return rc;
   }
 
-  if (bf16 && K <= kLevelBeam && K_in <= kLevelRows && V <= 512) {
+  if (level_fits_one_launch(bf16, K, K_in, V)) {
     // small shapes: the whole level after the projection in one launch, one workgroup per request
     LevelArgs la;
     la.state_in = state_in;
@@ -1916,10 +2275,43 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
   ea.V = V;
   ea.d = d;
   ea.e = e;
+  ea.redo = nullptr;
+  if (plan.per_request) {
+    // one workgroup per request, resident workgroups walk the batch
+    static int n_cu = 0;
+    if (n_cu == 0) {
+      int dev = 0, v = 0;
+      NEZHA_HIP_CHECK(hipGetDevice(&dev));
+      NEZHA_HIP_CHECK(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev));
+      n_cu = v > 0 ? v : 1;
+    }
+    const int n_waves = (K_in + 15) / 16;
+    int groups = B < 2 * n_cu ? B : 2 * n_cu;
+    groups = groups < kReqMaxGroups ? groups : kReqMaxGroups;
+    const size_t lds = request_w_region(e, n_waves) + (size_t)2 * kReqTiles * 16 * 4 +
+                       (size_t)n_waves * 48 * 4;
+    uint64_t* lists = reinterpret_cast<uint64_t*>(ws + plan.list_off);
+    uint8_t* redo = reinterpret_cast<uint8_t*>(ws + plan.redo_off);
+    ProfileScope prof(kExpand, stream);
+#define LAUNCH_REQUEST(KSTV)                                                                   \
+  do {                                                                                         \
+    rc = allow_lds(expand_request_kernel<KSTV>, lds);                                          \
+    if (rc != NEZHA_OK) return rc;                                                             \
+    hipLaunchKernelGGL((expand_request_kernel<KSTV>), dim3(groups), dim3(64 * n_waves), lds,   \
+                       stream, ea, lists, redo);                                               \
+  } while (0)
+    if (e == 32) LAUNCH_REQUEST(1);
+    else if (e == 64) LAUNCH_REQUEST(2);
+    else if (e == 128) LAUNCH_REQUEST(4);
+    else LAUNCH_REQUEST(8);
+#undef LAUNCH_REQUEST
+    NEZHA_HIP_CHECK(hipGetLastError());
+    ea.redo = redo;   // the chunked kernel below redoes the flagged beams only
+  }
   {
     const int groups = (rows + 15) / 16;
     ProfileScope prof(kExpand, stream);
-    if (bf16 && V <= 1024 && K <= 64) {
+    if (codebook_fits_lds(bf16, K, V)) {
       // small codebook: 16 x T_l logits fit in LDS; 8 waves share 16 beams
       const size_t lds = (size_t)8 * 256 * 8 + (size_t)16 * V * 4;
       dim3 grid(groups), block(512);
