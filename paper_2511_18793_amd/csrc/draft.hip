@@ -1067,19 +1067,22 @@ __device__ __forceinline__ void update_states(const void* state_in, const void* 
   }
 }
 
-// One workgroup (4 waves) per request.  Every candidate (parent p, within-beam rank r) gets the
-// sort key (ordered score, ~(p*K+r)), or 0 if the verifier rejects it; all keys go to LDS.  Each
-// lane remembers its two largest keys; the K-th largest of a wave's lane maxima bounds the
+// One workgroup (4 or 16 waves) per request.  Every candidate (parent p, within-beam rank r) gets
+// the sort key (ordered score, ~(p*K+r)), or 0 if the verifier rejects it; all keys go to LDS.
+// Each lane remembers its two largest keys; the K-th largest of a wave's lane maxima bounds the
 // request's K-th largest key from below, so wave 0 then only has to sort the few keys at or above
-// the best of the four bounds.
+// the best of the waves' bounds.  The keys fill most of a CU's LDS for large K_in * K, so the
+// hash-set probes in flight are what the workgroup's own waves issue: 16 waves then.
+constexpr int kMergeMaxWaves = 16;
 template <bool BF16>
-__global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
+__global__ __launch_bounds__(64 * kMergeMaxWaves) void merge_kernel(MergeArgs a) {
   constexpr int CAP = 256;
   extern __shared__ __align__(16) uint64_t dyn[];   // [n_c keys][CAP top buffer]
-  __shared__ uint64_t bounds[4];
+  __shared__ uint64_t bounds[kMergeMaxWaves];
   __shared__ int32_t fin_parent[NEZHA_MAX_BEAM], fin_code[NEZHA_MAX_BEAM];
   const int b = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n_threads = blockDim.x, n_waves = n_threads >> 6;
   const int K = a.K, K_in = a.K_in;
   const int n_c = K_in * K;
   const bool verify = a.set.slots != nullptr;
@@ -1087,7 +1090,7 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
   uint64_t* topbuf = dyn + ((n_c + 1) & ~1);
 
   uint64_t top0 = 0, top1 = 0;                       // this lane's two largest keys
-  for (int base = wave * 64; base < n_c; base += 256) {   // wave uniform trip count
+  for (int base = wave * 64; base < n_c; base += n_threads) {   // wave uniform trip count
     const int i = base + lane;
     uint64_t sk = 0;
     if (i < n_c) {
@@ -1126,8 +1129,7 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
   __syncthreads();
   if (wave == 0) {
     uint64_t tau = bounds[0];
-#pragma unroll
-    for (int w = 1; w < 4; ++w) tau = bounds[w] > tau ? bounds[w] : tau;
+    for (int w = 1; w < n_waves; ++w) tau = bounds[w] > tau ? bounds[w] : tau;
     WaveTopK<CAP> f;
     f.init(topbuf, K);
     f.tau = tau ? tau - 1ull : 0ull;                 // keys >= tau enter
@@ -1166,7 +1168,8 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
   }
   __syncthreads();
   if (a.state_out)
-    update_states<BF16>(a.state_in, a.E, a.state_out, b, K, K_in, a.e, fin_parent, fin_code, tid, 256);
+    update_states<BF16>(a.state_in, a.E, a.state_out, b, K, K_in, a.e, fin_parent, fin_code, tid,
+                        n_threads);
 }
 
 // ---- the same step for large codebooks: two sweeps over the codes, no running top-K -----------
@@ -2389,7 +2392,7 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
   ma.K = K;
   ma.e = e;
   {
-    dim3 grid(B), block(256);
+    dim3 grid(B), block(K_in * K >= 4096 ? 64 * kMergeMaxWaves : 256);
     const size_t lds = ((size_t)((K_in * K + 1) & ~1) + 256) * sizeof(uint64_t);
     ProfileScope prof(kMerge, stream);
     if (bf16) {
