@@ -40,9 +40,9 @@ BUCKET_BYTES = 64
 # are in profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB -> bytes; the factors come from the
 # plain-copy calibration in the same runs).  Only workloads that were profiled have an entry.
 MEASURED_TRAFFIC_BYTES = {
-    ("serving", "level_small_kernel"): (2878.7 * 2.0 + 973.3) * 1024,
-    ("stress", "verify_probe_kernel"): (245937.8 * 2.0 + 4065.4) * 1024,
-    ("large", "expand_kernel"): (203763.7 * 2.0 + 214400.0) * 1024,
+    ("serving", "level_small_kernel"): (2878.8 * 2.0 + 973.3) * 1024,
+    ("stress", "verify_probe_kernel"): (245832.5 * 2.0 + 4064.6) * 1024,
+    ("large", "expand_request_kernel"): (585420.2 * 2.0 + 1250698.3) * 1024,
 }
 
 
@@ -79,14 +79,20 @@ def kernel_models(cfg):
         K_in = 1 if level == 1 else K
         rows = B * K_in
         probes = rows * K if level == L else 0
+        # which kernel takes the expansion (the library's own rule, from the shape alone)
+        fused = cfg.dtype == "bf16" and K <= 32 and K_in <= 32 and V <= 512
+        per_request = (cfg.dtype == "bf16" and K_in >= 16 and e in (32, 64, 128, 256)
+                       and not fused and not (V <= 1024 and K <= 64))
+        slots = float(EXPAND_SLOTS_PER_LOGIT) * rows * V
         per_level.append({
             "pack_weights_kernel": ("hbm", 2.0 * (d + e) * V * esz),
             "user_gemm_kernel": ("mfma", 2.0 * B * d * V),
-            "expand_kernel": ("alu", float(EXPAND_SLOTS_PER_LOGIT) * rows * V),
+            "expand_kernel": ("alu", 0.0 if per_request else slots),
+            "expand_request_kernel": ("alu", slots if per_request else 0.0),
             "merge_kernel": ("hbm", rows * K * 8.0 + probes * BUCKET_BYTES
                              + B * K * (24.0 + (2 * e * esz if level < L else 0))),
             # expansion, merge, verification and Transition of one level in one launch
-            "level_small_kernel": ("alu", float(EXPAND_SLOTS_PER_LOGIT) * rows * V),
+            "level_small_kernel": ("alu", slots),
         })
     return per_level
 
@@ -190,7 +196,7 @@ def bench_draft(args, cfg):
                 "avg_launch_us": kd["avg_us"],
                 "timing": "HIP events by the library around each launch, eager pass of %d steps"
                           % prof_steps}
-    if dom in ("expand_kernel", "level_small_kernel"):
+    if dom in ("expand_kernel", "expand_request_kernel", "level_small_kernel"):
         flops = sum(2.0 * cfg.B * (1 if l == 0 else cfg.K) * cfg.e * cfg.V * (0 if l == 0 else 1)
                     for l in range(cfg.L)) * prof_steps
         roofline["mfma_tflops"] = flops / (kd["total_ms"] * 1e-3) / 1e12

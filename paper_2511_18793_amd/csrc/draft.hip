@@ -2295,7 +2295,7 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
                        (size_t)n_waves * 48 * 4;
     uint64_t* lists = reinterpret_cast<uint64_t*>(ws + plan.list_off);
     uint8_t* redo = reinterpret_cast<uint8_t*>(ws + plan.redo_off);
-    ProfileScope prof(kExpand, stream);
+    ProfileScope prof(kExpandRequest, stream);
 #define LAUNCH_REQUEST(KSTV)                                                                   \
   do {                                                                                         \
     rc = allow_lds(expand_request_kernel<KSTV>, lds);                                          \
