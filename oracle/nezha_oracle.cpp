@@ -15,6 +15,12 @@
 // sum of log-probabilities; ties go to the lower code, then to the better
 // ranked parent; verification happens at the last level only.
 //
+// Two widenings beyond that path, each behind an argument that defaults to the
+// path above: the recurrent Transition c' = tanh(U c + e_l) (the paper's main
+// variant says "an RNN" without giving the cell; the plain Elman cell without
+// bias is the reading taken), and verification below the last level against a
+// set of valid prefixes (the per-level filter the paper mentions in passing).
+//
 // Arithmetic: inputs are float32 (bf16 workloads pass bf16 values widened to
 // float32); every dot product, the log-sum-exp and the log-probabilities are in
 // double; cumulative scores are stored as float32.
@@ -99,6 +105,8 @@ struct LevelArgs {
   const uint64_t* key_in;
   const float* score_in;
   const ItemSet* set;
+  const float* U;       // [e, e] row major, used when transition == 1
+  int transition;       // 0: c' = c + e_l;  1: c'[j] = tanh(sum_i U[j][i] c[i] + e_l[j])
   int round_state_bf16;
   uint64_t* key_out;
   float* score_out;
@@ -120,6 +128,16 @@ void level_one_request(const LevelArgs& a, int32_t b) {
   cands.reserve((size_t)K_in * K);
 
   for (int32_t k = 0; k < K_in; ++k) {
+    // An empty beam slot (index 2^64-1: fewer than K beams survived the level before)
+    // has no children.
+    const bool empty_slot =
+        a.key_in && a.key_in[(int64_t)b * K_in + k] == std::numeric_limits<uint64_t>::max();
+    if (empty_slot) {
+      if (a.logp_out)
+        for (int32_t v = 0; v < V; ++v)
+          a.logp_out[((int64_t)b * K_in + k) * V + v] = -std::numeric_limits<double>::infinity();
+      continue;
+    }
     // Eq. 2: logits of beam k from the placeholder hidden h_l and the beam's state.
     for (int32_t i = 0; i < d; ++i) x[i] = (double)a.H[(int64_t)b * a.h_row_stride + i];
     for (int32_t i = 0; i < e; ++i)
@@ -154,8 +172,10 @@ void level_one_request(const LevelArgs& a, int32_t b) {
       cands.push_back(c);
     }
   }
-  // Eq. 5 at the last level: drop candidates that are not items, keeping order.
-  if (a.level == a.L && a.set) {
+  // Eq. 5: drop candidates that are not in the set, keeping order.  A set of full tuples
+  // (its L equals the step's L) is consulted at the last level; a set of prefixes of
+  // length `level` at that level.
+  if (a.set && a.set->L == a.level) {
     std::vector<Cand> kept;
     for (const Cand& c : cands)
       if (a.set->keys.count(c.key)) kept.push_back(c);
@@ -180,16 +200,24 @@ void level_one_request(const LevelArgs& a, int32_t b) {
       a.parent_out[o] = -1;
       a.code_out[o] = -1;
     }
-    // Eq. 3 with the additive Transition: state of the survivor.
+    // Eq. 3: state of the survivor, by addition or by the recurrent cell.
     if (a.state_out) {
       float* so = a.state_out + o * e;
       if (j < cnt) {
         const float* erow = a.E + (int64_t)cands[j].code * e;
+        const float* prow =
+            a.state_in ? a.state_in + ((int64_t)b * K_in + cands[j].parent) * e : nullptr;
         for (int32_t i = 0; i < e; ++i) {
-          const float prev =
-              a.state_in ? a.state_in[((int64_t)b * K_in + cands[j].parent) * e + i] : 0.0f;
-          const float sum = prev + erow[i];
-          so[i] = a.round_state_bf16 ? round_bf16(sum) : sum;
+          float next;
+          if (a.transition == 1) {
+            double acc = (double)erow[i];
+            if (prow)
+              for (int32_t t = 0; t < e; ++t) acc += (double)a.U[(int64_t)i * e + t] * (double)prow[t];
+            next = (float)std::tanh(acc);
+          } else {
+            next = (prow ? prow[i] : 0.0f) + erow[i];
+          }
+          so[i] = a.round_state_bf16 ? round_bf16(next) : next;
         }
       } else {
         for (int32_t i = 0; i < e; ++i) so[i] = 0.0f;
@@ -287,23 +315,33 @@ void orc_verify_tuples(const void* h, const int32_t* codes, int64_t n, uint8_t* 
 // One level (1-based `level`) of the inference part of Alg. 3 for B requests.
 // H [B,d] with h_row_stride floats between requests; W [(d+e),T_level]; E
 // [T_level,e] (needed when state_out != NULL); state_in [B,K_in,e] or NULL
-// (zeros); key_in/score_in [B,K_in] or NULL (0 / 0); set or NULL (no
-// verification; only consulted at level == L).  Outputs [B,K] (+ state_out
+// (zeros); key_in/score_in [B,K_in] or NULL (0 / 0), a slot with key 2^64-1 is
+// empty; set or NULL (no verification; consulted when its L equals `level`);
+// U [e,e] with transition == 1, else ignored.  Outputs [B,K] (+ state_out
 // [B,K,e], count_out [B]); slots beyond count hold key 2^64-1, score -inf,
 // parent -1, code -1.  logp_out (optional) [B,K_in,T_level] doubles.
 int orc_draft_level(int32_t B, int32_t L, int32_t level, int32_t K, int32_t K_in, int32_t d,
                     int32_t e, const int32_t* radices, const float* H, int64_t h_row_stride,
                     const float* W, const float* E, const float* state_in,
                     const uint64_t* key_in, const float* score_in, const void* set,
-                    int round_state_bf16, uint64_t* key_out, float* score_out,
+                    const float* U, int transition, int round_state_bf16, uint64_t* key_out,
+                    float* score_out,
                     int32_t* parent_out, int32_t* code_out, float* state_out,
                     int32_t* count_out, double* logp_out, int threads) {
   std::vector<uint64_t> mult;
   if (level < 1 || level > L || K < 1 || K_in < 1 || B < 0) return -1;
   if (!multipliers(L, radices, mult)) return -4;
   if (state_out && !E) return -1;
+  if (transition != 0 && transition != 1) return -1;
+  if (state_out && transition == 1 && !U) return -1;
+  const ItemSet* iset = static_cast<const ItemSet*>(set);
+  if (iset) {
+    if (iset->L != L && iset->L != level) return -1;
+    for (int32_t l = 0; l < iset->L; ++l)
+      if (iset->radices[l] != radices[l]) return -1;
+  }
   LevelArgs a{B, L, level, K, K_in, d, e, radices, H, h_row_stride, W, E, state_in, key_in,
-              score_in, static_cast<const ItemSet*>(set), round_state_bf16, key_out, score_out,
+              score_in, iset, U, transition, round_state_bf16, key_out, score_out,
               parent_out, code_out, state_out, count_out, logp_out, mult[level - 1]};
   const int nt = std::max(1, std::min(threads, (int)B));
   if (nt == 1) {

@@ -103,10 +103,12 @@ class ItemSet:
 
 def draft_level(level, L, radices, K, H_l, W_l, E_l=None, state_in=None, key_in=None,
                 score_in=None, itemset=None, round_state_bf16=False, want_logp=False,
-                want_state=True, threads=None):
+                want_state=True, threads=None, U_l=None):
     """One level (1-based) of the inference part of Alg. 3 for a batch.
 
     H_l [B,d] float32; W_l [(d+e),V]; E_l [V,e]; state_in [B,K_in,e] or None.
+    itemset: full tuples (used at level L) or prefixes of length `level` (used at this level).
+    U_l [e,e]: the recurrent Transition c' = tanh(U_l c + e_l) instead of c' = c + e_l.
     Returns dict(key, score, parent, code, count[, state][, logp])."""
     H_l = np.ascontiguousarray(H_l, dtype=np.float32)
     W_l = np.ascontiguousarray(W_l, dtype=np.float32)
@@ -144,11 +146,15 @@ def draft_level(level, L, radices, K, H_l, W_l, E_l=None, state_in=None, key_in=
     logp = np.empty((B, K_in, V), dtype=np.float64) if want_logp else None
     if threads is None:
         threads = os.cpu_count() or 1
+    if U_l is not None:
+        U_l = np.ascontiguousarray(U_l, dtype=np.float32)
+        assert U_l.shape == (e, e)
     rc = lib().orc_draft_level(
         C.c_int32(B), C.c_int32(L), C.c_int32(level), C.c_int32(K), C.c_int32(K_in),
         C.c_int32(d), C.c_int32(e), _p(rad), _p(H_l), C.c_int64(d), _p(W_l), _p(E_l),
         _p(state_in), _p(key_in), _p(score_in),
         C.c_void_p(itemset._h) if itemset is not None else None,
+        _p(U_l), C.c_int(0 if U_l is None else 1),
         C.c_int(1 if round_state_bf16 else 0), _p(out["key"]), _p(out["score"]),
         _p(out["parent"]), _p(out["code"]), _p(state_out), _p(out["count"]), _p(logp),
         C.c_int(int(threads)))
@@ -161,23 +167,30 @@ def draft_level(level, L, radices, K, H_l, W_l, E_l=None, state_in=None, key_in=
     return out
 
 
-def decode(H, W, E, radices, K, itemset=None, round_state_bf16=False, threads=None):
+def decode(H, W, E, radices, K, itemset=None, round_state_bf16=False, threads=None, U=None,
+           prefix_sets=None):
     """All L levels of Alg. 3 (inference) chained.  H [B,L,d]; W, E lists per
-    level.  Returns the list of per-level outputs; the last one is the answer."""
+    level; U (optional) list of [e,e] per level below L: recurrent Transition;
+    prefix_sets (optional) list of L-1 sets (or None) of valid prefixes of length 1..L-1.
+    Returns the list of per-level outputs; the last one is the answer."""
     L = len(W)
     B_ = H.shape[0]
     outs = []
     state = key = score = None
     for l in range(1, L + 1):
+        s = itemset if l == L else (prefix_sets[l - 1] if prefix_sets else None)
         o = draft_level(l, L, radices, K, H[:, l - 1, :], W[l - 1],
                         E[l - 1] if l < L else None, state, key, score,
-                        itemset if l == L else None, round_state_bf16, threads=threads)
+                        s, round_state_bf16, threads=threads,
+                        U_l=U[l - 1] if (U is not None and l < L) else None)
         outs.append(o)
         state, key, score = o.get("state"), o["key"], o["score"]
-        if l < L:
-            # no verification below the last level, so every request keeps the
-            # same number of beams: min(K, live beams * codes)
-            cnt = int(o["count"][0]) if B_ else 0
-            assert (o["count"] == cnt).all()
+        if l < L and B_:
+            # drop the slots that are empty in every request (without verification below the
+            # last level all requests keep the same number: min(K, live beams * codes))
+            cnt = int(o["count"].max())
+            if not prefix_sets:
+                assert (o["count"] == cnt).all()
+            cnt = max(cnt, 1)
             state, key, score = state[:, :cnt], key[:, :cnt], score[:, :cnt]
     return outs

@@ -1,7 +1,7 @@
 """Independent float64 restatements of what the draft head computes, used only
 to pin the CPU oracle.  Nothing here is shared with the oracle or the GPU
 library: the chain score of a full tuple is written from its definition
-(Eq. 1-3 with the additive Transition, softmax over the level's codes)."""
+(Eq. 1-3 with the additive or the recurrent Transition, softmax over the level's codes)."""
 import itertools
 
 import numpy as np
@@ -13,9 +13,10 @@ def log_softmax(z):
     return z - m - np.log(np.exp(z - m).sum(axis=-1, keepdims=True))
 
 
-def chain_scores_by_definition(h, W, E):
+def chain_scores_by_definition(h, W, E, U=None):
     """All V^L tuples of one request, one at a time, straight from the
-    definition.  h [L,d]; W[l] [(d+e),V]; E[l] [V,e].  Returns dict tuple->score."""
+    definition.  h [L,d]; W[l] [(d+e),V]; E[l] [V,e]; U[l] [e,e] or None (additive
+    Transition).  Returns dict tuple->score."""
     L = len(W)
     V = W[0].shape[1]
     d = h.shape[1]
@@ -29,7 +30,8 @@ def chain_scores_by_definition(h, W, E):
             lp = log_softmax(x @ W[l].astype(np.float64))
             s += lp[t[l]]
             if l < L - 1:
-                c = c + E[l][t[l]].astype(np.float64)
+                emb = E[l][t[l]].astype(np.float64)
+                c = c + emb if U is None else np.tanh(U[l].astype(np.float64) @ c + emb)
         out[t] = s
     return out
 

@@ -192,3 +192,120 @@ def test_state_rounding_to_bf16(oracle):
     want = torch.from_numpy(x["E"][0][o["code"]]).to(torch.bfloat16).float().numpy()
     assert (o["state"] == want).all()
     assert (synth.round_to_bf16(x["E"][0]) == torch.from_numpy(x["E"][0]).to(torch.bfloat16).float().numpy()).all()
+
+
+# ---- recurrent Transition: c' = tanh(U c + e_l) -------------------------------------------------
+def _rnn_weights(seed, L, e, scale=0.6):
+    rng = np.random.default_rng(seed)
+    return [(rng.standard_normal((e, e)) * scale).astype(np.float32) for _ in range(L - 1)]
+
+
+@pytest.mark.parametrize("seed,V,L", [(15, 4, 3), (16, 6, 2)])
+def test_rnn_exhaustive_beam_equals_brute_force(oracle, seed, V, L):
+    cfg, x = _small(seed, B=2, d=6, e=3, V=V, L=L)
+    U = _rnn_weights(seed, L, 3)
+    x["E"] = [em * 20 for em in x["E"]]             # large enough for tanh to bend
+    total = V ** L
+    outs = oracle.decode(x["H"], x["W"], x["E"], cfg.radices, total, U=U)
+    last = outs[-1]
+    for b in range(2):
+        truth = chain_scores_by_definition(x["H"][b], x["W"], x["E"], U=U)
+        plain = chain_scores_by_definition(x["H"][b], x["W"], x["E"])
+        assert abs(sum(np.exp(v) for v in truth.values()) - 1) < 1e-12
+        assert max(abs(truth[t] - plain[t]) for t in truth) > 1e-3   # the cell is not the sum
+        assert last["count"][b] == total
+        got = oracle.unpack(last["key"][b], cfg.radices)
+        for t, sc in zip(got.tolist(), last["score"][b]):
+            assert abs(truth[tuple(t)] - sc) < 2e-6
+        assert (np.diff(last["score"][b]) <= 0).all()
+
+
+def test_rnn_state_closed_forms(oracle):
+    cfg, x = _small(17, B=3, d=8, e=4, V=16)
+    K = 5
+    E1 = x["E"][0] * 30
+    zero = np.zeros((4, 4), np.float32)
+    o1 = oracle.draft_level(1, 3, cfg.radices, K, x["H"][:, 0], x["W"][0], E1, U_l=zero)
+    # level 1 starts from the zero state: c' = tanh(e_l) whatever U is
+    assert np.allclose(o1["state"], np.tanh(E1[o1["code"]].astype(np.float64)), atol=1e-7)
+    U = (np.random.default_rng(17).standard_normal((4, 4)) * 0.7).astype(np.float32)
+    o1u = oracle.draft_level(1, 3, cfg.radices, K, x["H"][:, 0], x["W"][0], E1, U_l=U)
+    assert (o1u["state"] == o1["state"]).all()
+    # level 2: row j of U meets the parent state (a transposed U must be visible)
+    E2 = x["E"][1] * 30
+    o2 = oracle.draft_level(2, 3, cfg.radices, K, x["H"][:, 1], x["W"][1], E2, o1["state"],
+                            o1["key"], o1["score"], U_l=U)
+    par = o1["state"][np.arange(3)[:, None], o2["parent"]].astype(np.float64)      # [B,K,e]
+    want = np.tanh(np.einsum("ji,bki->bkj", U.astype(np.float64), par) + E2[o2["code"]])
+    wrong = np.tanh(np.einsum("ij,bki->bkj", U.astype(np.float64), par) + E2[o2["code"]])
+    assert np.allclose(o2["state"], want, atol=1e-6)
+    assert np.abs(want - wrong).max() > 1e-2
+    # the beams themselves do not depend on the Transition of the same level
+    o2a = oracle.draft_level(2, 3, cfg.radices, K, x["H"][:, 1], x["W"][1], E2, o1["state"],
+                             o1["key"], o1["score"])
+    assert (o2a["key"] == o2["key"]).all() and (o2a["score"] == o2["score"]).all()
+    assert np.allclose(o2a["state"], par + E2[o2["code"]], atol=1e-6)
+    # bf16 rounding of the state applies to the cell's output too
+    o2r = oracle.draft_level(2, 3, cfg.radices, K, x["H"][:, 1], x["W"][1], E2, o1["state"],
+                             o1["key"], o1["score"], U_l=U, round_state_bf16=True)
+    assert (o2r["state"] == synth.round_to_bf16(o2["state"])).all()
+
+
+# ---- verification below the last level against sets of valid prefixes ---------------------------
+def test_prefix_verification_by_definition(oracle):
+    cfg, x = _small(18, B=6, d=10, e=5, V=12)
+    K = 4
+    rng = np.random.default_rng(18)
+    tuples = np.array([t for t in np.ndindex(12, 12, 12)], dtype=np.int32)
+    first_ok = np.isin(tuples[:, 0], [0, 3, 4, 7, 9])             # most first codes start no item
+    cat = tuples[first_ok & (rng.random(len(tuples)) < 0.12)]
+    full = oracle.ItemSet(cat, cfg.radices)
+    p1 = oracle.ItemSet(np.unique(cat[:, :1], axis=0), cfg.radices[:1])
+    p2 = oracle.ItemSet(np.unique(cat[:, :2], axis=0), cfg.radices[:2])
+    outs = oracle.decode(x["H"], x["W"], x["E"], cfg.radices, K, itemset=full,
+                         prefix_sets=[p1, p2])
+    ok1 = set(map(tuple, np.unique(cat[:, :1], axis=0).tolist()))
+    ok2 = set(map(tuple, np.unique(cat[:, :2], axis=0).tolist()))
+    catset = set(map(tuple, cat.tolist()))
+    # level 1 from its definition: the K most probable codes, then those that start an item
+    lp1 = log_softmax(x["H"][:, 0].astype(np.float64) @ x["W"][0][:10].astype(np.float64))
+    for b in range(6):
+        top = np.argsort(-lp1[b], kind="stable")[:K]
+        want = [int(v) for v in top if (int(v),) in ok1]
+        n = int(outs[0]["count"][b])
+        assert outs[0]["code"][b, :n].tolist() == want
+        assert (outs[0]["key"][b, n:] == np.uint64(2**64 - 1)).all()
+    assert (outs[0]["count"] < K).any()                # some slots are empty at level 2's input
+    # level 2 and 3 from their definition, on what the level before handed over
+    for lvl, okset in ((2, ok2), (3, catset)):
+        prev, cur = outs[lvl - 2], outs[lvl - 1]
+        live = int(prev["count"].max())
+        chk = oracle.draft_level(lvl, 3, cfg.radices, K, x["H"][:, lvl - 1], x["W"][lvl - 1], None,
+                                 prev["state"][:, :live], prev["key"][:, :live],
+                                 prev["score"][:, :live], None, want_logp=True)
+        for b in range(6):
+            cands = []
+            for p in range(int(prev["count"][b])):
+                prefix = tuple(oracle.unpack(prev["key"][b, p:p + 1], cfg.radices)[0][:lvl - 1])
+                for v in np.argsort(-chk["logp"][b, p], kind="stable")[:K]:
+                    t = prefix + (int(v),)
+                    if t in okset:
+                        sc = np.float32(np.float64(prev["score"][b, p]) + chk["logp"][b, p, v])
+                        cands.append((-float(sc), p, int(v), t))
+            cands.sort(key=lambda c: (c[0], c[1]))     # stable in (parent, within-beam rank)
+            want = cands[:K]
+            n = int(cur["count"][b])
+            assert n == len(want)
+            got = [tuple(t[:lvl]) for t in oracle.unpack(cur["key"][b, :n], cfg.radices).tolist()]
+            assert got == [c[3] for c in want]
+            assert np.allclose(cur["score"][b, :n], [-c[0] for c in want], atol=1e-6)
+    # prefixes of items only: every emitted item is in the catalog, and an exhaustive search with
+    # the prefix filter returns exactly what it returns without it
+    K_all = 12 ** 3
+    cfg2, y = _small(19, B=1, d=6, e=3, V=12)
+    a = oracle.decode(y["H"], y["W"], y["E"], cfg2.radices, K_all, itemset=full)
+    bb = oracle.decode(y["H"], y["W"], y["E"], cfg2.radices, K_all, itemset=full,
+                       prefix_sets=[p1, p2])
+    n = int(a[-1]["count"][0])
+    assert n == len(cat) == int(bb[-1]["count"][0])
+    assert (a[-1]["key"][0, :n] == bb[-1]["key"][0, :n]).all()
