@@ -61,6 +61,12 @@ def parse_args():
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain elementwise copy of 256 MiB (torch.mul by 1) three "
                          "times, so that hardware counters of a profiler run can be scaled")
+    ap.add_argument("--transition", choices=("add", "rnn"), default="add",
+                    help="Transition of Eq. 3: additive (the measured path) or the recurrent cell "
+                         "c' = tanh(U c + e_l) (variant; U and the embeddings are synthetic)")
+    ap.add_argument("--prefix-sets", action="store_true",
+                    help="variant: also verify each level below L against the set of the "
+                         "catalog's prefixes of that length")
     ap.add_argument("--batch", type=int, default=0, help="override B (debugging)")
     ap.add_argument("--catalog", type=int, default=0, help="override N (debugging)")
     return ap.parse_args()
@@ -106,10 +112,23 @@ def bench_draft(args, cfg):
     W = [torch.from_numpy(w).to(dev).to(dt) for w in x["W"]]
     E = [torch.from_numpy(w).to(dev).to(dt) for w in x["E"]]
     bufs = nz.DraftBuffers(cfg.B, cfg.L, cfg.K, cfg.d, cfg.e, cfg.radices, dt, dev)
+    U = Unp = None
+    if args.transition == "rnn":
+        # variant: recurrent cell.  U_l ~ N(0, 1/e); embeddings scaled so that tanh is not linear
+        rng = np.random.default_rng(args.seed + 1000)
+        Unp = [(rng.standard_normal((cfg.e, cfg.e)) / np.sqrt(cfg.e)).astype(np.float32)
+               for _ in range(cfg.L - 1)]
+        if cfg.dtype == "bf16":
+            Unp = [synth.round_to_bf16(u) for u in Unp]
+            x["E"] = [synth.round_to_bf16(em * 25.0) for em in x["E"]]
+        else:
+            x["E"] = [(em * 25.0).astype(np.float32) for em in x["E"]]
+        E = [torch.from_numpy(w).to(dev).to(dt) for w in x["E"]]
+        U = [torch.from_numpy(u).to(dev).to(dt) for u in Unp]
 
     # Catalog: Zipf / uniform background, with about 70 % of the unverified top-K beams planted
     # so that about 30 % of them are hallucinations (this pass runs without a verifier).
-    free = nz.decode(H, W, E, cfg.radices, cfg.K, None, buffers=bufs)
+    free = nz.decode(H, W, E, cfg.radices, cfg.K, None, buffers=bufs, U=U)
     torch.cuda.synchronize()
     beams = nz.unpack_keys(free[-1]["key"].cpu().numpy().ravel(), cfg.radices)
     if cfg.catalog == "uniform":
@@ -121,6 +140,10 @@ def bench_draft(args, cfg):
     catalog = synth.planted_catalog(cfg.radices, background, beams[keep], beams[~keep], args.seed)
     del background
     itemset = nz.build_itemset(catalog, cfg.radices, cfg.load_factor)
+    prefix_sets = None
+    if args.prefix_sets:
+        prefix_sets = [nz.build_itemset(np.unique(catalog[:, :l], axis=0), cfg.radices[:l],
+                                        cfg.load_factor) for l in range(1, cfg.L)]
     setup_s = time.time() - t0
 
     # The head's weights are static in serving: their operand-order form is made once, here,
@@ -130,7 +153,8 @@ def bench_draft(args, cfg):
         Wrun = [nz.pack_weights(l + 1, cfg.L, cfg.radices, W[l], cfg.d) for l in range(cfg.L)]
 
     def step():
-        nz.decode(H, Wrun, E, cfg.radices, cfg.K, itemset, buffers=bufs)
+        nz.decode(H, Wrun, E, cfg.radices, cfg.K, itemset, buffers=bufs, U=U,
+                  prefix_sets=prefix_sets)
 
     graph = None
     if not args.eager:
@@ -224,22 +248,27 @@ def bench_draft(args, cfg):
                    "launch": "eager" if args.eager else "hip_graph_replay",
                    "weights": "packed per call" if (args.pack_per_call or cfg.dtype != "bf16")
                    else "packed once at set-up",
+                   "transition": args.transition, "prefix_sets": bool(args.prefix_sets),
                    "setup_s": round(setup_s, 1)},
         "accepted_items_per_s": accepted / (ms_per_step * 1e-3),
         "roofline": roofline,
         "kernels": breakdown,
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline_draft(cfg, x, catalog, cands)
+        result["cpu_baseline"] = cpu_baseline_draft(cfg, x, catalog, cands, Unp, args.prefix_sets)
     return result
 
 
-def cpu_baseline_draft(cfg, x, catalog, cands):
+def cpu_baseline_draft(cfg, x, catalog, cands, U=None, prefix_sets=False):
     """The CPU oracle, as it stands, on the host cores: a bounded sample of requests of the same
     workload, scaled to the batch."""
     from oracle import oracle as orc
     threads = os.cpu_count() or 1
     oset = orc.ItemSet(catalog, cfg.radices)
+    opre = None
+    if prefix_sets:
+        opre = [orc.ItemSet(np.unique(catalog[:, :l], axis=0), cfg.radices[:l])
+                for l in range(1, cfg.L)]
     # about 2.2 * B*K*(d+e)*V multiply-adds per decode; keep the sample near 10 s of CPU work
     macs_per_req = (1 + (cfg.L - 1) * cfg.K) * (cfg.d + cfg.e) * cfg.V
     budget = 4e9 * threads
@@ -247,7 +276,7 @@ def cpu_baseline_draft(cfg, x, catalog, cands):
     Hs = x["H"][:n]
     t = time.perf_counter()
     orc.decode(Hs, x["W"], x["E"], cfg.radices, cfg.K, oset,
-               round_state_bf16=cfg.dtype == "bf16", threads=threads)
+               round_state_bf16=cfg.dtype == "bf16", threads=threads, U=U, prefix_sets=opre)
     dt = time.perf_counter() - t
     return {"value": cands * (n / cfg.B) / dt, "unit": "items/s", "cores": min(threads, n),
             "kind": "oracle", "seconds": round(dt, 3),

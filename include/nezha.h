@@ -102,13 +102,19 @@ size_t nezha_verify_workspace(int64_t n);
  *   3. gives each candidate the cumulative score parent_score + logp (float32;
  *      the log of the paper's cumulative probability) and the index
  *      parent_key + code * prod_{j<level} T_j (Eq. 4, one more digit);
- *   4. at level == L and with a set given, drops every candidate whose index is
- *      not in the set (Eq. 5);
+ *   4. with a set given whose tuples have `level` digits (at level == L: the item
+ *      set of Eq. 5; below it: a set of valid prefixes, the per-level filter the
+ *      paper mentions in passing), drops every candidate whose index is not in it;
  *   5. keeps the K candidates of largest score (ties: lower parent rank, then
  *      better within-beam rank), in non-increasing score order;
- *   6. at level < L, forms each survivor's next state by Eq. 3 with the additive
- *      Transition: c' = c_parent + E_l[code].
+ *   6. at level < L, forms each survivor's next state by Eq. 3: with the additive
+ *      Transition c' = c_parent + E_l[code], or with the recurrent one (Sec. 3.2
+ *      "an RNN"; read as a bias-free Elman cell) c' = tanh(U_l c_parent + E_l[code]).
+ * A beam slot whose key_in is 2^64-1 is empty (the level before kept fewer than K beams)
+ * and has no children.
  */
+#define NEZHA_TRANSITION_ADD 0
+#define NEZHA_TRANSITION_RNN 1
 typedef struct {
   int32_t B;              /* requests in the batch, >= 0 */
   int32_t L;              /* levels of the semantic ID */
@@ -124,6 +130,10 @@ typedef struct {
   const float* user_part; /* optional device float32 [B, T_level], 16-byte aligned: h_l W_l[0:d]
                              formed beforehand (nezha_user_projection[_levels]); then H_l is not
                              read.  NULL: the call forms it itself */
+  int32_t transition;     /* NEZHA_TRANSITION_ADD or NEZHA_TRANSITION_RNN (used when level < L) */
+  const void* U_l;        /* NEZHA_TRANSITION_RNN: device [e, e] row major, same dtype as the
+                             states, 16-byte aligned: c'[j] = tanh(sum_i U_l[j][i] c[i] + E_l[code][j]).
+                             Ignored (may be NULL) otherwise */
 } nezha_step_desc;
 
 /* All data pointers are device pointers.
@@ -132,7 +142,9 @@ typedef struct {
  *        (ignored when level == L, may be NULL there); state_in [B, K_in, e]
  *        (NULL = all zero, the initial state); key_in uint64 [B, K_in] and
  *        score_in float32 [B, K_in] (NULL = 0, the empty prefix);
- *        set: consulted only when level == L; NULL = no verification.
+ *        set: NULL = no verification.  Built over all L radices it is consulted when
+ *        level == L (and ignored below); built over the first `level` radices (a set of
+ *        prefixes) it is consulted at this level.  Any other length is NEZHA_EINVAL.
  *   out: key_out uint64 [B, K], score_out float32 [B, K], parent_out int32 [B, K]
  *        (rank of the parent beam), code_out int32 [B, K], state_out [B, K, e]
  *        (NULL allowed when level == L), count_out int32 [B] (NULL allowed):

@@ -168,7 +168,7 @@ def draft_level(level, L, radices, K, H_l, W_l, E_l=None, state_in=None, key_in=
 
 
 def decode(H, W, E, radices, K, itemset=None, round_state_bf16=False, threads=None, U=None,
-           prefix_sets=None):
+           prefix_sets=None, use_state=True):
     """All L levels of Alg. 3 (inference) chained.  H [B,L,d]; W, E lists per
     level; U (optional) list of [e,e] per level below L: recurrent Transition;
     prefix_sets (optional) list of L-1 sets (or None) of valid prefixes of length 1..L-1.
@@ -180,7 +180,7 @@ def decode(H, W, E, radices, K, itemset=None, round_state_bf16=False, threads=No
     for l in range(1, L + 1):
         s = itemset if l == L else (prefix_sets[l - 1] if prefix_sets else None)
         o = draft_level(l, L, radices, K, H[:, l - 1, :], W[l - 1],
-                        E[l - 1] if l < L else None, state, key, score,
+                        E[l - 1] if l < L else None, state if use_state else None, key, score,
                         s, round_state_bf16, threads=threads,
                         U_l=U[l - 1] if (U is not None and l < L) else None)
         outs.append(o)

@@ -10,6 +10,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
 NEZHA_F32, NEZHA_BF16 = 0, 1
+NEZHA_TRANSITION_ADD, NEZHA_TRANSITION_RNN = 0, 1
 MAX_LEVELS = 8
 
 EXPORTS = ["nezha_last_error", "nezha_build_itemset", "nezha_itemset_info", "nezha_free_itemset",
@@ -31,7 +32,7 @@ class _StepDesc(C.Structure):
                 ("K_in", C.c_int32), ("d", C.c_int32), ("e", C.c_int32),
                 ("radices", C.POINTER(C.c_int32)), ("dtype", C.c_int),
                 ("h_row_stride", C.c_int64), ("w_packed", C.c_int32),
-                ("user_part", C.c_void_p)]
+                ("user_part", C.c_void_p), ("transition", C.c_int32), ("U_l", C.c_void_p)]
 
 
 def library_path():
@@ -159,11 +160,13 @@ def verify_tuples(itemset, codes, out_mask=None, out_index=None, out_count=None,
 
 
 def _desc(B, L, level, K, K_in, d, e, radices, dtype, h_row_stride, w_packed=False,
-          user_part=None):
+          user_part=None, U_l=None):
     rad = _radices(radices)
     dsc = _StepDesc(B, L, level, K, K_in, d, e, C.cast(rad, C.POINTER(C.c_int32)),
                     NEZHA_BF16 if dtype == torch.bfloat16 else NEZHA_F32, h_row_stride,
-                    1 if w_packed else 0, None if user_part is None else user_part.data_ptr())
+                    1 if w_packed else 0, None if user_part is None else user_part.data_ptr(),
+                    NEZHA_TRANSITION_ADD if U_l is None else NEZHA_TRANSITION_RNN,
+                    None if U_l is None else U_l.data_ptr())
     dsc._keep = rad
     return dsc
 
@@ -206,11 +209,13 @@ def draft_step_workspace(B, L, level, K, K_in, d, e, radices, dtype, w_packed=Fa
 
 def draft_step(level, L, radices, K, H_l, W_l, E_l=None, state_in=None, key_in=None,
                score_in=None, itemset=None, out=None, workspace=None, stream=None,
-               h_row_stride=None, user_part=None):
+               h_row_stride=None, user_part=None, U_l=None):
     """nezha_draft_step for one level.  H_l [B, d] (a view with a row stride is
     fine), W_l [(d+e), V], E_l [V, e]; state_in [B, K_in, e], key_in int64-as-uint64
-    [B, K_in], score_in float32 [B, K_in].  `out` may hold preallocated tensors
-    key, score, parent, code, state, count.  Returns that dict."""
+    [B, K_in], score_in float32 [B, K_in].  itemset: the items (used at level L) or the
+    valid prefixes of length `level`.  U_l [e, e]: recurrent Transition (NEZHA_TRANSITION_RNN).
+    `out` may hold preallocated tensors key, score, parent, code, state, count.  Returns that
+    dict."""
     B, d = H_l.shape
     V = int(radices[level - 1])
     e = W_l.shape[0] - d
@@ -229,7 +234,7 @@ def draft_step(level, L, radices, K, H_l, W_l, E_l=None, state_in=None, key_in=N
     if level < L and "state" not in out:
         out["state"] = torch.empty((B, K, e), dtype=dt, device=dev)
     dsc = _desc(B, L, level, K, K_in, d, e, radices, dt, h_row_stride,
-                isinstance(W_l, PackedWeights), user_part)
+                isinstance(W_l, PackedWeights), user_part, U_l if level < L else None)
     if workspace is None:
         need = int(load_library().nezha_draft_step_workspace(C.byref(dsc)))
         workspace = torch.empty(max(256, need), dtype=torch.uint8, device=dev)
@@ -304,9 +309,14 @@ class DraftBuffers:
                            for l in range(L)]
 
 
-def decode(H, W, E, radices, K, itemset=None, buffers=None, stream=None):
+def decode(H, W, E, radices, K, itemset=None, buffers=None, stream=None, U=None,
+           prefix_sets=None, use_state=True):
     """All L levels of the inference loop of Alg. 3: L calls of nezha_draft_step on one
-    stream, each level's outputs feeding the next.  H [B, L, d]; W, E lists per level."""
+    stream, each level's outputs feeding the next.  H [B, L, d]; W, E lists per level; U
+    (optional) list of [e, e] per level below L: recurrent Transition; prefix_sets (optional)
+    list of L-1 item sets (or None) of the valid prefixes of length 1..L-1; use_state=False
+    never hands a state to the next level (the head then sees h_l only: the paper's ablation
+    without the autoregressive state, and parallel multi-token heads when all h_l are equal)."""
     L = len(W)
     B, _, d = H.shape
     e = W[0].shape[0] - d
@@ -319,10 +329,13 @@ def decode(H, W, E, radices, K, itemset=None, buffers=None, stream=None):
         parts = user_projection_levels(H, W, radices, buffers.user_parts, stream=stream)
     for level in range(1, L + 1):
         o = draft_step(level, L, radices, K, H[:, level - 1, :], W[level - 1],
-                       E[level - 1] if level < L else None, state, key, score,
-                       itemset if level == L else None, out=buffers.outs[level - 1],
+                       E[level - 1] if level < L else None, state if use_state else None, key,
+                       score,
+                       itemset if level == L else (prefix_sets[level - 1] if prefix_sets else None),
+                       out=buffers.outs[level - 1],
                        workspace=buffers.workspace, stream=stream, h_row_stride=H.stride(0),
-                       user_part=None if parts is None else parts[level - 1])
+                       user_part=None if parts is None else parts[level - 1],
+                       U_l=U[level - 1] if (U is not None and level < L) else None)
         state, key, score = o.get("state"), o["key"], o["score"]
     return buffers.outs
 

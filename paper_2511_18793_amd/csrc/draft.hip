@@ -1013,6 +1013,8 @@ struct MergeArgs {
   void* state_out;          // or NULL
   int32_t* count_out;       // or NULL
   int K_in, K, e;
+  const void* U;            // [e, e] row major (recurrent Transition), else unused
+  int transition;
 };
 
 // Eq. 3 with the additive Transition for the K survivors of request b: c' = c_parent + E[code]
@@ -1067,6 +1069,79 @@ __device__ __forceinline__ void update_states(const void* state_in, const void* 
   }
 }
 
+// Eq. 3 with the recurrent Transition for the K survivors of request b:
+// c'[j] = tanh(sum_i U[j][i] c_parent[i] + E[code][j]) (zero for unused slots).  bf16: 16x16
+// output tiles (16 survivors x 16 state elements) by v_mfma_f32_16x16x32_bf16, spread over the
+// workgroup's waves; the accumulator starts at the code embedding; the A operand is the parent
+// state row, the B operand B[k][n] = U[n][k] is 16 contiguous bytes of row n of U.
+template <bool BF16>
+__device__ __forceinline__ void update_states_rnn(const void* state_in, const void* E, const void* U,
+                                                  void* state_out, int b, int K, int K_in, int e,
+                                                  const int32_t* fin_parent,
+                                                  const int32_t* fin_code, int tid, int nthreads) {
+  if constexpr (BF16) {
+    const int lane = tid & 63, wave = tid >> 6, n_waves = nthreads >> 6;
+    const int g = lane >> 4, c = lane & 15;
+    const int RT = (K + 15) / 16, CT = e / 16, KS = e / 32;
+    const uint16_t* Eh = static_cast<const uint16_t*>(E);
+    const uint16_t* Uh = static_cast<const uint16_t*>(U);
+    const uint16_t* Sh = static_cast<const uint16_t*>(state_in);
+    uint16_t* Oh = static_cast<uint16_t*>(state_out);
+    for (int t = wave; t < RT * CT; t += n_waves) {
+      const int rt = t / CT, ct = t - rt * CT;
+      floatx4 acc;
+      int code[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int j = rt * 16 + 4 * g + i;
+        code[i] = j < K ? fin_code[j] : -1;
+        acc[i] = code[i] >= 0 ? bf16_to_float(Eh[(int64_t)code[i] * e + ct * 16 + c]) : 0.f;
+      }
+      const int ja = rt * 16 + c;
+      const int pa = ja < K ? fin_parent[ja] : -1;
+      if (Sh) {
+        for (int ks = 0; ks < KS; ++ks) {
+          uint4 av = uint4{0, 0, 0, 0};
+          if (pa >= 0)
+            av = *reinterpret_cast<const uint4*>(Sh + ((int64_t)b * K_in + pa) * e + ks * 32 + 8 * g);
+          const uint4 bv =
+              *reinterpret_cast<const uint4*>(Uh + (int64_t)(ct * 16 + c) * e + ks * 32 + 8 * g);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8*>(&av),
+                                                        *reinterpret_cast<const bf16x8*>(&bv), acc,
+                                                        0, 0, 0);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int j = rt * 16 + 4 * g + i;
+        if (j < K)
+          Oh[((int64_t)b * K + j) * e + ct * 16 + c] =
+              code[i] >= 0 ? float_to_bf16(tanhf(acc[i])) : (uint16_t)0;
+      }
+    }
+  } else {
+    const float* Ef = static_cast<const float*>(E);
+    const float* Uf = static_cast<const float*>(U);
+    const float* Sf = static_cast<const float*>(state_in);
+    float* Of = static_cast<float*>(state_out);
+    for (int idx = tid; idx < K * e; idx += nthreads) {
+      const int j = idx / e, col = idx - j * e;
+      const int par = fin_parent[j], code = fin_code[j];
+      float r = 0.f;
+      if (par >= 0) {
+        float acc = Ef[(int64_t)code * e + col];
+        if (Sf) {
+          const float* srow = Sf + ((int64_t)b * K_in + par) * e;
+          const float* urow = Uf + (int64_t)col * e;
+          for (int i = 0; i < e; ++i) acc = fmaf(urow[i], srow[i], acc);
+        }
+        r = tanhf(acc);
+      }
+      Of[((int64_t)b * K + j) * e + col] = r;
+    }
+  }
+}
+
 // One workgroup (4 or 16 waves) per request.  Every candidate (parent p, within-beam rank r) gets
 // the sort key (ordered score, ~(p*K+r)), or 0 if the verifier rejects it; all keys go to LDS.
 // Each lane remembers its two largest keys; the K-th largest of a wave's lane maxima bounds the
@@ -1097,12 +1172,10 @@ __global__ __launch_bounds__(64 * kMergeMaxWaves) void merge_kernel(MergeArgs a)
       const int p = i / K;
       const int64_t o = (int64_t)(b * K_in + p) * K + (i - p * K);
       const float score = (a.score_in ? a.score_in[b * K_in + p] : 0.f) + a.cand_logp[o];
-      bool ok = true;
-      if (verify) {
-        const uint64_t key = (a.key_in ? a.key_in[b * K_in + p] : 0ull) +
-                             (uint64_t)(uint32_t)a.cand_code[o] * a.mult;
-        ok = set_contains(a.set, key);
-      }
+      const uint64_t pkey = a.key_in ? a.key_in[b * K_in + p] : 0ull;
+      bool ok = pkey != kEmpty;                      // an empty beam slot has no children
+      if (verify && ok)
+        ok = set_contains(a.set, pkey + (uint64_t)(uint32_t)a.cand_code[o] * a.mult);
       if (ok) sk = ((uint64_t)ordered_bits(score) << 32) | (uint32_t)~(uint32_t)i;
       keys[i] = sk;
     }
@@ -1167,9 +1240,14 @@ __global__ __launch_bounds__(64 * kMergeMaxWaves) void merge_kernel(MergeArgs a)
     if (lane == 0 && a.count_out) a.count_out[b] = f.cnt;
   }
   __syncthreads();
-  if (a.state_out)
-    update_states<BF16>(a.state_in, a.E, a.state_out, b, K, K_in, a.e, fin_parent, fin_code, tid,
-                        n_threads);
+  if (a.state_out) {
+    if (a.transition == NEZHA_TRANSITION_RNN)
+      update_states_rnn<BF16>(a.state_in, a.E, a.U, a.state_out, b, K, K_in, a.e, fin_parent,
+                              fin_code, tid, n_threads);
+    else
+      update_states<BF16>(a.state_in, a.E, a.state_out, b, K, K_in, a.e, fin_parent, fin_code, tid,
+                          n_threads);
+  }
 }
 
 // ---- the same step for large codebooks: two sweeps over the codes, no running top-K -----------
@@ -1753,6 +1831,8 @@ struct LevelArgs {
   void* state_out;          // or NULL
   int32_t* count_out;       // or NULL
   int K_in, K, V, e;
+  const void* U;            // [e, e] row major (recurrent Transition), else unused
+  int transition;
 };
 constexpr int kLevelWaves = 16, kLevelRows = 32, kLevelBeam = 32;
 template <int KST, int NVT>
@@ -1842,11 +1922,9 @@ __global__ __launch_bounds__(64 * kLevelWaves, 1) void level_small_kernel(LevelA
     const uint32_t code = ~(uint32_t)zk;
     const float logp = unordered_bits((uint32_t)(zk >> 32)) - row_lse[p];
     const float score = (a.score_in ? a.score_in[b * K_in + p] : 0.f) + logp;
-    bool ok = true;
-    if (verify) {
-      const uint64_t key = (a.key_in ? a.key_in[b * K_in + p] : 0ull) + (uint64_t)code * a.mult;
-      ok = set_contains(a.set, key);
-    }
+    const uint64_t pkey = a.key_in ? a.key_in[b * K_in + p] : 0ull;
+    bool ok = pkey != kEmpty;                                         // an empty beam slot has no children
+    if (verify && ok) ok = set_contains(a.set, pkey + (uint64_t)code * a.mult);
     if (ok) sk = ((uint64_t)ordered_bits(score) << 32) | (uint32_t)~(uint32_t)tid;
     keys2[tid] = sk;
   }
@@ -1894,9 +1972,14 @@ __global__ __launch_bounds__(64 * kLevelWaves, 1) void level_small_kernel(LevelA
     if (lane == 0 && a.count_out) a.count_out[b] = f.cnt;
   }
   __syncthreads();
-  if (a.state_out)
-    update_states<true>(a.state_in, a.E, a.state_out, b, K, K_in, e, fin_parent, fin_code, tid,
-                        64 * kLevelWaves);
+  if (a.state_out) {
+    if (a.transition == NEZHA_TRANSITION_RNN)
+      update_states_rnn<true>(a.state_in, a.E, a.U, a.state_out, b, K, K_in, e, fin_parent, fin_code,
+                              tid, 64 * kLevelWaves);
+    else
+      update_states<true>(a.state_in, a.E, a.state_out, b, K, K_in, e, fin_parent, fin_code, tid,
+                          64 * kLevelWaves);
+  }
 }
 
 // ---- host side ---------------------------------------------------------------------------------
@@ -2178,6 +2261,13 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
     return fail(NEZHA_EINVAL, "an output pointer is NULL");
   if (level < L && !state_out) return fail(NEZHA_EINVAL, "state_out is NULL below the last level");
   if (state_out && !E_l) return fail(NEZHA_EINVAL, "E_l is NULL but state_out is wanted");
+  if (desc->transition != NEZHA_TRANSITION_ADD && desc->transition != NEZHA_TRANSITION_RNN)
+    return fail(NEZHA_EINVAL, "unknown transition %d", (int)desc->transition);
+  if (state_out && desc->transition == NEZHA_TRANSITION_RNN) {
+    if (!desc->U_l) return fail(NEZHA_EINVAL, "U_l is NULL with NEZHA_TRANSITION_RNN");
+    if (reinterpret_cast<uintptr_t>(desc->U_l) & 15)
+      return fail(NEZHA_EINVAL, "U_l is not 16-byte aligned");
+  }
   if (!workspace) return fail(NEZHA_EINVAL, "workspace is NULL");
   if (workspace_bytes < plan.total)
     return fail(NEZHA_EINVAL, "workspace has %zu bytes, %zu needed", workspace_bytes, plan.total);
@@ -2192,8 +2282,10 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
     return fail(NEZHA_EINVAL, "E_l and the states must be 16-byte aligned");
   if (set) {
     if (set->magic != kSetMagic) return fail(NEZHA_EINVAL, "not an item set");
-    if (set->L != L) return fail(NEZHA_EINVAL, "item set has L = %d, desc has %d", set->L, L);
-    for (int l = 0; l < L; ++l)
+    if (set->L != L && set->L != level)
+      return fail(NEZHA_EINVAL, "the set's tuples have %d digits; %d (items) or %d (prefixes of this level) expected",
+                  set->L, L, level);
+    for (int l = 0; l < set->L; ++l)
       if (set->radices[l] != desc->radices[l])
         return fail(NEZHA_EINVAL, "item set and desc disagree on radix %d", l + 1);
   }
@@ -2230,7 +2322,9 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
     la.key_in = key_in;
     la.score_in = score_in;
     la.E = E_l;
-    la.set = SetView{(set && level == L) ? set->slots : nullptr, set ? set->n_buckets : 0};
+    la.set = SetView{(set && set->L == level) ? set->slots : nullptr, set ? set->n_buckets : 0};
+    la.U = desc->U_l;
+    la.transition = desc->transition;
     la.mult = mult[level - 1];
     la.key_out = key_out;
     la.score_out = score_out;
@@ -2380,7 +2474,9 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
   ma.score_in = score_in;
   ma.state_in = state_in;
   ma.E = E_l;
-  ma.set = SetView{(set && level == L) ? set->slots : nullptr, set ? set->n_buckets : 0};
+  ma.set = SetView{(set && set->L == level) ? set->slots : nullptr, set ? set->n_buckets : 0};
+  ma.U = desc->U_l;
+  ma.transition = desc->transition;
   ma.mult = mult[level - 1];
   ma.key_out = key_out;
   ma.score_out = score_out;

@@ -49,16 +49,20 @@ def outputs_to_numpy(o):
     return {k: to_np(v.float() if v.dtype == torch.bfloat16 else v) for k, v in o.items()}
 
 
-def check_decode(orc, nz, cfg, x, outs, oset, tol):
-    """Level by level: the oracle is fed what the GPU produced at the level before."""
+def check_decode(orc, nz, cfg, x, outs, oset, tol, U=None, prefix_sets=None, use_state=True):
+    """Level by level: the oracle is fed what the GPU produced at the level before.  U: per-level
+    [e, e] matrices of the recurrent Transition (numpy, the values the GPU read); prefix_sets:
+    oracle sets of the valid prefixes of length 1..L-1."""
     state = key = score = None
     soft_total = 0
     for l in range(1, cfg.L + 1):
         g = outputs_to_numpy(outs[l - 1])
         inp = {"H": x["H"][:, l - 1], "W": x["W"][l - 1],
                "E": x["E"][l - 1] if l < cfg.L else None,
-               "state": state, "key": key, "score": score}
-        soft_total += compare_level(orc, l, cfg.L, cfg.radices, cfg.K, inp, g, oset, tol,
+               "state": state if use_state else None, "key": key, "score": score,
+               "U": U[l - 1] if (U is not None and l < cfg.L) else None}
+        lset = oset if l == cfg.L else (prefix_sets[l - 1] if prefix_sets else None)
+        soft_total += compare_level(orc, l, cfg.L, cfg.radices, cfg.K, inp, g, lset, tol,
                                     cfg.dtype == "bf16")
         state, key, score = g.get("state"), g["key"].view(np.uint64), g["score"]
     return soft_total

@@ -78,6 +78,10 @@ def _call_step(**over):
     a.update(over)
     dsc = api._desc(a["B"], a["L"], a["level"], a["K"], a["K_in"], a["d"], a["e"], a["radices"],
                     a["dtype"], a["stride"])
+    if "transition" in a:
+        dsc.transition = a["transition"]
+    if "U" in a:
+        dsc.U_l = a["U"]
     names = ["H", "W", "E", "state_in", "key_in", "score_in", "set", "key_out", "score_out",
              "parent_out", "code_out", "state_out", "count_out"]
     ptrs = [None if (n in a["null"] or n == "set") else C.c_void_p(a["fake"]) for n in names]
@@ -99,6 +103,17 @@ def test_draft_step_argument_errors(over, code):
     rc, text = _call_step(**over)
     assert rc == code, text
     assert text
+
+
+@pytest.mark.parametrize("over", [
+    dict(transition=2), dict(transition=-1),
+    dict(transition=api.NEZHA_TRANSITION_RNN),                       # no matrix
+    dict(transition=api.NEZHA_TRANSITION_RNN, U=0x1008),             # misaligned matrix
+])
+def test_draft_step_transition_errors(over):
+    rc, text = _call_step(**over)
+    assert rc == -1, text
+    assert "transition" in text or "U_l" in text
 
 
 def test_verify_tuples_rejects_a_non_set():

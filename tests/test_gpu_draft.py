@@ -197,3 +197,127 @@ def test_zero_requests_is_a_no_op():
     o = nz.draft_step(1, 2, [64, 64], 4, H, W, E, h_row_stride=64)
     torch.cuda.synchronize()
     assert o["key"].shape == (0, 4)
+
+
+# ---- recurrent Transition (c' = tanh(U c + e_l)) ------------------------------------------------
+def _rnn_inputs(cfg, seed):
+    """U_l with entries of order 1/sqrt(e) and code embeddings scaled up so that tanh bends:
+    values rounded to the working type, as float32 numpy (for the oracle)."""
+    rng = np.random.default_rng(seed + 1000)
+    U = [(rng.standard_normal((cfg.e, cfg.e)) / np.sqrt(cfg.e)).astype(np.float32)
+         for _ in range(cfg.L - 1)]
+    if cfg.dtype == "bf16":
+        U = [synth.round_to_bf16(u) for u in U]
+    return U
+
+
+@pytest.mark.parametrize("name,B", [("tiny", 64), ("serving", 64), ("wide", 6), ("large", 2)])
+def test_recurrent_transition(oracle, name, B):
+    cfg = synth.get_config(name).scaled(B=B)
+    seed = 61
+    x = synth.draft_inputs(cfg, seed)
+    scale = 25.0                                   # code embeddings of order 0.5: tanh is not linear there
+    x["E"] = [synth.round_to_bf16(em * scale) if cfg.dtype == "bf16" else (em * scale).astype(np.float32)
+              for em in x["E"]]
+    U = _rnn_inputs(cfg, seed)
+    free = oracle.decode(x["H"], x["W"], x["E"], cfg.radices, cfg.K,
+                         round_state_bf16=cfg.dtype == "bf16", U=U)
+    tuples = oracle.unpack(free[-1]["key"].ravel(), cfg.radices)
+    keep = synth.plant_mask(tuples, cfg.radices, seed)
+    cat = synth.planted_catalog(cfg.radices, synth.uniform_catalog(cfg.radices, 20000, seed)[0],
+                                tuples[keep], tuples[~keep], seed)
+    oset = oracle.ItemSet(cat, cfg.radices)
+    gset = nz.build_itemset(cat, cfg.radices, cfg.load_factor)
+    H, W, E = to_device(x, cfg)
+    Ud = [torch.from_numpy(u).to(device()).to(torch_dtype(cfg)) for u in U]
+    outs = nz.decode(H, W, E, cfg.radices, cfg.K, gset, U=Ud)
+    torch.cuda.synchronize()
+    soft = check_decode(oracle, nz, cfg, x, outs, oset, tolerance(cfg), U=U)
+    assert soft <= 8
+    assert int(outs[-1]["count"].sum()) > 0
+    # the cell changes the answer: the additive Transition on the same inputs gives other beams
+    plain = nz.decode(H, W, E, cfg.radices, cfg.K, gset)
+    torch.cuda.synchronize()
+    assert not torch.equal(plain[-1]["key"], outs[-1]["key"])
+
+
+def test_recurrent_transition_needs_its_matrix():
+    cfg = synth.get_config("serving").scaled(B=2)
+    x = synth.draft_inputs(cfg, 1)
+    H, W, E = to_device(x, cfg)
+    U = torch.zeros((cfg.e, cfg.e), dtype=torch.bfloat16, device=device())
+    with pytest.raises(nz.NezhaError):
+        # misaligned matrix (offset by one element)
+        nz.draft_step(1, cfg.L, cfg.radices, cfg.K, H[:, 0], W[0], E[0],
+                      U_l=torch.zeros(cfg.e * cfg.e + 8, dtype=torch.bfloat16, device=device())[1:1 + cfg.e * cfg.e].view(cfg.e, cfg.e))
+    out = nz.draft_step(1, cfg.L, cfg.radices, cfg.K, H[:, 0], W[0], E[0], U_l=U)
+    torch.cuda.synchronize()
+    # zero U and zero initial state: c' = tanh(E[code])
+    want = torch.tanh(E[0].float()[out["code"].long()]).to(torch.bfloat16)
+    assert torch.equal(out["state"], want)
+
+
+# ---- verification below the last level against sets of valid prefixes ---------------------------
+@pytest.mark.parametrize("name,B", [("tiny", 64), ("serving", 64), ("wide", 6), ("large", 2)])
+def test_prefix_verification(oracle, name, B):
+    cfg = synth.get_config(name).scaled(B=B)
+    seed = 71
+    x, cat = planted_workload(oracle, cfg, seed, N=20000)
+    # a catalog whose first-level codes are few, so that level 1 already loses beams
+    first = np.unique(cat[:, 0])
+    cat = cat[np.isin(cat[:, 0], first[: max(2, len(first) // 8)])]
+    oset = oracle.ItemSet(cat, cfg.radices)
+    gset = nz.build_itemset(cat, cfg.radices, cfg.load_factor)
+    opre, gpre = [], []
+    for l in range(1, cfg.L):
+        pre = np.unique(cat[:, :l], axis=0)
+        opre.append(oracle.ItemSet(pre, cfg.radices[:l]))
+        gpre.append(nz.build_itemset(pre, cfg.radices[:l], cfg.load_factor))
+    H, W, E = to_device(x, cfg)
+    outs = nz.decode(H, W, E, cfg.radices, cfg.K, gset, prefix_sets=gpre)
+    torch.cuda.synchronize()
+    soft = check_decode(oracle, nz, cfg, x, outs, oset, tolerance(cfg), prefix_sets=opre)
+    assert soft <= 8
+    c1 = to_np(outs[0]["count"])
+    assert c1.min() < cfg.K                        # empty beam slots did enter level 2
+    # every beam of every level is a prefix of an item
+    for l in range(1, cfg.L + 1):
+        n = to_np(outs[l - 1]["count"])
+        keys = to_np(outs[l - 1]["key"]).view(np.uint64)
+        live = np.concatenate([keys[b, :n[b]] for b in range(cfg.B)])
+        ref = oset if l == cfg.L else opre[l - 1]
+        assert ref.contains_keys(live).all()
+    # a set of the wrong length is refused
+    if cfg.L >= 3:
+        with pytest.raises(nz.NezhaError):
+            nz.draft_step(1, cfg.L, cfg.radices, cfg.K, H[:, 0], W[0], E[0], itemset=gpre[1])
+
+
+# ---- the head without its autoregressive state (ablation / parallel multi-token heads) ----------
+@pytest.mark.parametrize("name,B,shared_hidden", [("serving", 32, False), ("serving", 32, True),
+                                                  ("wide", 4, False), ("tiny", 16, True)])
+def test_head_without_state(oracle, name, B, shared_hidden):
+    cfg = synth.get_config(name).scaled(B=B)
+    x, cat = planted_workload(oracle, cfg, 81, N=20000, plant=False)
+    if shared_hidden:                               # one hidden state for all levels
+        x["H"] = np.repeat(x["H"][:, :1], cfg.L, axis=1).copy()
+    free = oracle.decode(x["H"], x["W"], x["E"], cfg.radices, cfg.K, use_state=False,
+                         round_state_bf16=cfg.dtype == "bf16")
+    tuples = oracle.unpack(free[-1]["key"].ravel(), cfg.radices)
+    keep = synth.plant_mask(tuples, cfg.radices, 81)
+    cat = synth.planted_catalog(cfg.radices, cat, tuples[keep], tuples[~keep], 81)
+    oset = oracle.ItemSet(cat, cfg.radices)
+    gset = nz.build_itemset(cat, cfg.radices, cfg.load_factor)
+    H, W, E = to_device(x, cfg)
+    outs = nz.decode(H, W, E, cfg.radices, cfg.K, gset, use_state=False)
+    torch.cuda.synchronize()
+    soft = check_decode(oracle, nz, cfg, x, outs, oset, tolerance(cfg), use_state=False)
+    assert soft <= 8
+    assert int(outs[-1]["count"].sum()) > 0
+    # without a state every beam of a request sees the same distribution: all parents of a
+    # level pick the same K codes
+    lvl2 = outputs_to_numpy(outs[1])
+    with_state = nz.decode(H, W, E, cfg.radices, cfg.K, gset)
+    torch.cuda.synchronize()
+    assert not torch.equal(with_state[-1]["key"], outs[-1]["key"])
+    assert lvl2["count"].min() > 0

@@ -309,3 +309,21 @@ def test_prefix_verification_by_definition(oracle):
     n = int(a[-1]["count"][0])
     assert n == len(cat) == int(bb[-1]["count"][0])
     assert (a[-1]["key"][0, :n] == bb[-1]["key"][0, :n]).all()
+
+
+# ---- the head without its state: the chain probability is a product of per-level marginals ------
+def test_without_state_the_score_factorizes(oracle):
+    cfg, x = _small(21, B=3, d=7, e=3, V=5, L=3)
+    K = 5 ** 3
+    outs = oracle.decode(x["H"], x["W"], x["E"], cfg.radices, K, use_state=False)
+    last = outs[-1]
+    lp = [log_softmax(x["H"][:, l].astype(np.float64) @ x["W"][l][:7].astype(np.float64))
+          for l in range(3)]
+    for b in range(3):
+        assert last["count"][b] == K
+        got = oracle.unpack(last["key"][b], cfg.radices)
+        want = lp[0][b][got[:, 0]] + lp[1][b][got[:, 1]] + lp[2][b][got[:, 2]]
+        assert np.abs(last["score"][b] - want).max() < 2e-6
+        assert len(set(map(tuple, got.tolist()))) == K
+    with_state = oracle.decode(x["H"], x["W"], x["E"], cfg.radices, K)
+    assert np.abs(with_state[-1]["score"] - last["score"]).max() > 1e-4
