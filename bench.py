@@ -183,6 +183,17 @@ def bench_draft(args, cfg):
     accepted = int(bufs.outs[-1]["count"].sum().item())
     hallucinated = 1.0 - float(keep.mean())
 
+    # Per-level latency: the same steps eager, events around each level's nezha_draft_step.
+    lev_steps = min(args.steps, 50)
+    lev_ev = [[[torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)]
+               for _ in range(cfg.L + 1)] for _ in range(lev_steps)]
+    for i in range(lev_steps):
+        nz.decode(H, Wrun, E, cfg.radices, cfg.K, itemset, buffers=bufs, U=U,
+                  prefix_sets=prefix_sets, level_events=lev_ev[i])
+    torch.cuda.synchronize()
+    level_ms = [[lev_ev[i][l][0].elapsed_time(lev_ev[i][l][1]) for i in range(lev_steps)]
+                for l in range(cfg.L + 1)]
+
     # Per-kernel durations: the same steps again, eager, with the library's event timing on.
     nz.profile_reset()
     nz.profile_enable(True)
@@ -239,6 +250,10 @@ def bench_draft(args, cfg):
         "p50_step_ms": percentile(per_step, 50), "p90_step_ms": percentile(per_step, 90),
         "p99_step_ms": percentile(per_step, 99),
         "wall_ms_per_step": wall_ms / args.steps,
+        # eager launches, events around each call: [projections ahead of the loop, level 1..L]
+        "level_call_ms": {"p50": [round(percentile(v, 50), 5) for v in level_ms],
+                          "p90": [round(percentile(v, 90), 5) for v in level_ms],
+                          "p99": [round(percentile(v, 99), 5) for v in level_ms]},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "B": cfg.B, "d": cfg.d, "e": cfg.e, "L": cfg.L,

@@ -310,13 +310,16 @@ class DraftBuffers:
 
 
 def decode(H, W, E, radices, K, itemset=None, buffers=None, stream=None, U=None,
-           prefix_sets=None, use_state=True):
+           prefix_sets=None, use_state=True, level_events=None):
     """All L levels of the inference loop of Alg. 3: L calls of nezha_draft_step on one
     stream, each level's outputs feeding the next.  H [B, L, d]; W, E lists per level; U
     (optional) list of [e, e] per level below L: recurrent Transition; prefix_sets (optional)
     list of L-1 item sets (or None) of the valid prefixes of length 1..L-1; use_state=False
     never hands a state to the next level (the head then sees h_l only: the paper's ablation
-    without the autoregressive state, and parallel multi-token heads when all h_l are equal)."""
+    without the autoregressive state, and parallel multi-token heads when all h_l are equal).
+    level_events (measurement aid): L+1 pairs of torch.cuda.Event recorded on the current
+    stream around the projections made ahead of the loop (pair 0) and around each level's call
+    (pairs 1..L)."""
     L = len(W)
     B, _, d = H.shape
     e = W[0].shape[0] - d
@@ -324,10 +327,16 @@ def decode(H, W, E, radices, K, itemset=None, buffers=None, stream=None, U=None,
         buffers = DraftBuffers(B, L, K, d, e, radices, H.dtype, H.device)
     state = key = score = None
     parts = None
+    if level_events is not None:
+        level_events[0][0].record()
     if all(isinstance(w, PackedWeights) for w in W):
         # the projections of h_1..h_L do not depend on the beams: one launch before the loop
         parts = user_projection_levels(H, W, radices, buffers.user_parts, stream=stream)
+    if level_events is not None:
+        level_events[0][1].record()
     for level in range(1, L + 1):
+        if level_events is not None:
+            level_events[level][0].record()
         o = draft_step(level, L, radices, K, H[:, level - 1, :], W[level - 1],
                        E[level - 1] if level < L else None, state if use_state else None, key,
                        score,
@@ -336,6 +345,8 @@ def decode(H, W, E, radices, K, itemset=None, buffers=None, stream=None, U=None,
                        workspace=buffers.workspace, stream=stream, h_row_stride=H.stride(0),
                        user_part=None if parts is None else parts[level - 1],
                        U_l=U[level - 1] if (U is not None and level < L) else None)
+        if level_events is not None:
+            level_events[level][1].record()
         state, key, score = o.get("state"), o["key"], o["score"]
     return buffers.outs
 

@@ -777,12 +777,30 @@ __global__ __launch_bounds__(64 * NW) void expand_kernel(ExpandArgs a) {
   }
 }
 
+// Element j (wave uniform, 0 <= j < N) of a small register array, without indexing it.
+template <int N>
+__device__ __forceinline__ uint32_t pick_element(const uint32_t (&v)[N], int j) {
+  static_assert(N == 1 || N == 2 || N == 4, "1, 2 or 4 elements");
+  if constexpr (N == 1) {
+    return v[0];
+  } else if constexpr (N == 2) {
+    return v[0] ^ ((v[0] ^ v[1]) & (0u - (uint32_t)(j & 1)));
+  } else {
+    const uint32_t m1 = 0u - (uint32_t)(j & 1), m2 = 0u - (uint32_t)((j >> 1) & 1);
+    const uint32_t lo = v[0] ^ ((v[0] ^ v[1]) & m1), hi = v[2] ^ ((v[2] ^ v[3]) & m1);
+    return lo ^ ((lo ^ hi) & m2);
+  }
+}
 // Two rows of float32 logits in LDS (T_l = V values each, V/64 per lane): log-sum-exp and the K
-// best (logit, code) keys of each, sorted, handed to emit(row 0|1, rank, key, lse).  The K-th
-// largest of the 64 per-lane maxima is a lower bound of the row's K-th largest key, so only the
-// few keys at or above it are appended to the wave's LDS list (scratch, CAP keys, half per row),
-// which one small sort then cuts to the K best.  The two rows run side by side: independent
-// work hides the cross-lane latency.  K <= 64.  Whole wave.
+// best (logit, code) keys of each, handed to emit(row 0|1, place, key, lse) in code order (not
+// sorted by logit: what follows orders equal scores by parent and code, so the place of a
+// candidate inside its beam's list only has to respect the code order of equal logits).  All
+// sorting is on the 32-bit ordered logits alone.  The K-th largest of the 64 per-lane maxima is
+// a lower bound of the row's K-th largest logit, so only the few logits at or above it are
+// appended, in code order, to the wave's LDS list (scratch, CAP keys, half per row); a sort of
+// those gives the K-th largest logit itself, and the entries above it plus the first (lowest
+// code) of its ties are the K best.  The two rows run side by side: independent work hides the
+// cross-lane latency.  K <= 64.  Whole wave.
 template <int NVT, int CAP, class Emit>
 __device__ __forceinline__ void two_rows_topk(const float* z0, const float* z1, bool live0,
                                               bool live1, int V, int K, uint64_t* scratch,
@@ -792,7 +810,7 @@ __device__ __forceinline__ void two_rows_topk(const float* z0, const float* z1, 
   const float* zrow[2] = {z0, z1};
   bool live[2] = {live0, live1};
   float zv[2][NVT], m[2], ssum[2];
-  uint64_t key[2][NVT], best[2][1];
+  uint32_t zk[2][NVT], best[2][1];
 #pragma unroll
   for (int rr = 0; rr < 2; ++rr) {
     m[rr] = -INFINITY;
@@ -839,34 +857,33 @@ __device__ __forceinline__ void two_rows_topk(const float* z0, const float* z1, 
       const int col = j * 64 + lane;
       const bool ok = j < NV && col < V && live[rr];
       ssum[rr] += ok ? __builtin_amdgcn_exp2f((zv[rr][j] - m[rr]) * kLog2e) : 0.f;
-      key[rr][j] = ok ? (((uint64_t)ordered_bits(zv[rr][j]) << 32) | (uint32_t)~(uint32_t)col) : 0ull;
-      best[rr][0] = key[rr][j] > best[rr][0] ? key[rr][j] : best[rr][0];
+      zk[rr][j] = ok ? ordered_bits(zv[rr][j]) : 0u;       // ordered bits of a finite logit are > 0
+      best[rr][0] = zk[rr][j] > best[rr][0] ? zk[rr][j] : best[rr][0];
     }
   }
   reduce_sum(ssum);
-  // K-th largest of the per-lane maxima: every one of the row's K best keys is >= it
-  sort_desc<1, 2>(best);
+  // K-th largest of the per-lane maxima: every one of the row's K best logits is >= it
+  sort_desc<1, 2, uint32_t>(best);
   uint64_t* rows[2] = {scratch, scratch + CAP / 2};
   int rc[2];
 #pragma unroll
   for (int rr = 0; rr < 2; ++rr) {
-    const uint32_t bound_lo = __builtin_amdgcn_readlane((uint32_t)best[rr][0], K - 1);
-    const uint32_t bound_hi = __builtin_amdgcn_readlane((uint32_t)(best[rr][0] >> 32), K - 1);
-    const uint64_t bound = ((uint64_t)bound_hi << 32) | bound_lo;
-    // append the keys >= bound; a row gets CAP/2 places, which K * T_l/64 keys could exceed only
-    // in contrived cases: then the row falls back to the streaming top-K below
+    const uint32_t bound = (uint32_t)__builtin_amdgcn_readlane((int)best[rr][0], K - 1);
+    // append the logits >= bound in code order; a row gets CAP/2 places, which K * T_l/64 keys
+    // could exceed only in contrived cases: then the row falls back to the streaming top-K below
     int cnt = 0;
     bool overflow = false;
 #pragma unroll
     for (int j = 0; j < NVT; ++j) {
       if (j < NV) {
-        const bool pass = key[rr][j] >= bound && key[rr][j] != 0;
+        const bool pass = zk[rr][j] >= bound && zk[rr][j] != 0;
         const uint64_t bal = __ballot(pass);
         const int pos = cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32),
                                                         __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0));
         const int n = __popcll(bal);
         if (cnt + n > CAP / 2) overflow = true;
-        if (pass && pos < CAP / 2) rows[rr][pos] = key[rr][j];
+        if (pass && pos < CAP / 2)
+          rows[rr][pos] = ((uint64_t)zk[rr][j] << 32) | (uint32_t)~(uint32_t)(j * 64 + lane);
         cnt += n;
       }
     }
@@ -893,16 +910,54 @@ __device__ __forceinline__ void two_rows_topk(const float* z0, const float* z1, 
     }
     return;
   }
-  uint64_t* const crows[2] = {rows[0], rows[1]};
-  uint64_t rt[2];
-  compact_rows<CAP / 2, 2>(crows, rc, rt, K);     // sorts both lists, keeps the K best
+  wave_sync();
+  // the lists hold K .. CAP/2 entries each, in code order: find the K-th largest logit and keep
+  // what is above it and the first of its ties
+  auto select = [&](auto npl_c) {
+    constexpr int NPL = decltype(npl_c)::value;
+    uint64_t ent[2][NPL];
+    uint32_t zz[2][NPL], sk[2][NPL];
 #pragma unroll
-  for (int rr = 0; rr < 2; ++rr) {
-    if (live[rr]) {
+    for (int rr = 0; rr < 2; ++rr)
+#pragma unroll
+      for (int j = 0; j < NPL; ++j) {
+        const int idx = j * 64 + lane;
+        ent[rr][j] = idx < rc[rr] ? rows[rr][idx] : 0ull;
+        zz[rr][j] = (uint32_t)(ent[rr][j] >> 32);
+        sk[rr][j] = zz[rr][j];
+      }
+    sort_desc<NPL, 2, uint32_t>(sk);                                    // position NPL*lane + j
+#pragma unroll
+    for (int rr = 0; rr < 2; ++rr) {
+      if (!live[rr]) continue;
+      const uint32_t tau = (uint32_t)__builtin_amdgcn_readlane(
+          (int)pick_element<NPL>(sk[rr], (K - 1) % NPL), (K - 1) / NPL);
+      int n_gt = 0;
+#pragma unroll
+      for (int j = 0; j < NPL; ++j) n_gt += __popcll(__ballot(zz[rr][j] > tau));
+      const int need = K - n_gt;                                         // ties to take, in list order
       const float lse = m[rr] + __builtin_amdgcn_logf(ssum[rr]) * kLn2;
-      for (int p = lane; p < rc[rr]; p += 64) emit(rr, p, rows[rr][p], lse);
+      int base = 0, ties = 0;
+#pragma unroll
+      for (int j = 0; j < NPL; ++j) {
+        const bool eq = zz[rr][j] == tau;
+        const uint64_t bal_eq = __ballot(eq);
+        const int tie_rank = ties + __builtin_amdgcn_mbcnt_hi(
+                                        (uint32_t)(bal_eq >> 32),
+                                        __builtin_amdgcn_mbcnt_lo((uint32_t)bal_eq, 0));
+        const bool take = zz[rr][j] > tau || (eq && tie_rank < need);
+        const uint64_t bal = __ballot(take);
+        const int p = base + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32),
+                                                       __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0));
+        if (take) emit(rr, p, ent[rr][j], lse);
+        base += __popcll(bal);
+        ties += __popcll(bal_eq);
+      }
     }
-  }
+  };
+  const int most = rc[0] > rc[1] ? rc[0] : rc[1];
+  if (most <= 64) select(std::integral_constant<int, 1>{});
+  else select(std::integral_constant<int, 2>{});
 }
 
 // ---- the same step for small codebooks (T_l <= 1024, K <= 64) ------------------------------------
@@ -1164,7 +1219,7 @@ __global__ __launch_bounds__(64 * kMergeMaxWaves) void merge_kernel(MergeArgs a)
   uint64_t* keys = dyn;
   uint64_t* topbuf = dyn + ((n_c + 1) & ~1);
 
-  uint64_t top0 = 0, top1 = 0;                       // this lane's two largest keys
+  uint32_t top0 = 0, top1 = 0;                       // this lane's two largest scores (ordered bits)
   for (int base = wave * 64; base < n_c; base += n_threads) {   // wave uniform trip count
     const int i = base + lane;
     uint64_t sk = 0;
@@ -1179,25 +1234,25 @@ __global__ __launch_bounds__(64 * kMergeMaxWaves) void merge_kernel(MergeArgs a)
       if (ok) sk = ((uint64_t)ordered_bits(score) << 32) | (uint32_t)~(uint32_t)i;
       keys[i] = sk;
     }
-    const uint64_t lo = sk > top0 ? top0 : sk;       // the smaller of (sk, top0)
-    top0 = sk > top0 ? sk : top0;
+    const uint32_t s32 = (uint32_t)(sk >> 32);
+    const uint32_t lo = s32 > top0 ? top0 : s32;     // the smaller of (score, top0)
+    top0 = s32 > top0 ? s32 : top0;
     top1 = lo > top1 ? lo : top1;
   }
   {
-    uint64_t bound;
+    // scores alone: a lower bound of the K-th largest key may ignore how ties are ordered
+    uint32_t b32;
     if (K <= 64) {
-      uint64_t mk[1][1] = {{top0}};
-      sort_desc<1, 1>(mk);
-      bound = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)(mk[0][0] >> 32), K - 1) << 32) |
-              (uint32_t)__builtin_amdgcn_readlane((uint32_t)mk[0][0], K - 1);
+      uint32_t mk[1][1] = {{top0}};
+      sort_desc<1, 1, uint32_t>(mk);
+      b32 = (uint32_t)__builtin_amdgcn_readlane((int)mk[0][0], K - 1);
     } else {
-      uint64_t mk[1][2] = {{top0, top1}};
-      sort_desc<2, 1>(mk);                           // position 2*lane + j
-      const uint64_t pick = ((K - 1) & 1) ? mk[0][1] : mk[0][0];
-      bound = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)(pick >> 32), (K - 1) >> 1) << 32) |
-              (uint32_t)__builtin_amdgcn_readlane((uint32_t)pick, (K - 1) >> 1);
+      uint32_t mk[1][2] = {{top0, top1}};
+      sort_desc<2, 1, uint32_t>(mk);                 // position 2*lane + j
+      b32 = (uint32_t)__builtin_amdgcn_readlane((int)pick_element<2>(mk[0], (K - 1) & 1),
+                                                (K - 1) >> 1);
     }
-    if (lane == 0) bounds[wave] = bound;
+    if (lane == 0) bounds[wave] = (uint64_t)b32 << 32;
   }
   __syncthreads();
   if (wave == 0) {
@@ -1509,20 +1564,6 @@ __host__ __device__ inline size_t request_w_region(int e, int n_waves) {
   const size_t chunks = (size_t)2 * kReqTiles * (e / 32) * 1024;   // two chunk buffers
   const size_t maxima = (size_t)n_waves * 16 * 128 * 4;            // group maxima between sweeps
   return chunks > maxima ? chunks : maxima;
-}
-// Element j (wave uniform, 0 <= j < N) of a small register array, without indexing it.
-template <int N>
-__device__ __forceinline__ uint32_t pick_element(const uint32_t (&v)[N], int j) {
-  static_assert(N == 1 || N == 2 || N == 4, "1, 2 or 4 elements");
-  if constexpr (N == 1) {
-    return v[0];
-  } else if constexpr (N == 2) {
-    return v[0] ^ ((v[0] ^ v[1]) & (0u - (uint32_t)(j & 1)));
-  } else {
-    const uint32_t m1 = 0u - (uint32_t)(j & 1), m2 = 0u - (uint32_t)((j >> 1) & 1);
-    const uint32_t lo = v[0] ^ ((v[0] ^ v[1]) & m1), hi = v[2] ^ ((v[2] ^ v[3]) & m1);
-    return lo ^ ((lo ^ hi) & m2);
-  }
 }
 template <int KST>
 __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
@@ -1929,11 +1970,10 @@ __global__ __launch_bounds__(64 * kLevelWaves, 1) void level_small_kernel(LevelA
     keys2[tid] = sk;
   }
   {
-    uint64_t mk[1][1] = {{sk}};
-    sort_desc<1, 1>(mk);                                              // K <= 32 <= 64
-    const uint64_t bound =
-        ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)(mk[0][0] >> 32), K - 1) << 32) |
-        (uint32_t)__builtin_amdgcn_readlane((uint32_t)mk[0][0], K - 1);
+    // K-th largest score of this wave's 64 candidates (scores alone: a bound may ignore ties)
+    uint32_t mk[1][1] = {{(uint32_t)(sk >> 32)}};
+    sort_desc<1, 1, uint32_t>(mk);                                    // K <= 32 <= 64
+    const uint64_t bound = (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)mk[0][0], K - 1) << 32;
     if (lane == 0) bounds[wave] = bound;
   }
   __syncthreads();
