@@ -165,6 +165,36 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
                      size_t workspace_bytes, void* hip_stream);
 size_t nezha_draft_step_workspace(const nezha_step_desc* desc); /* 0 if desc is invalid */
 
+/* All L levels of the inference loop of Alg. 3 in one call: exactly what L calls of
+ * nezha_draft_step do with level = 1..L, K_in = 1 at level 1 and K after it, each level's
+ * key_out / score_out / state_out feeding the next level's key_in / score_in / state_in.
+ * desc gives B, L, K, d, e, radices, dtype, h_row_stride, w_packed and transition for all
+ * levels; its level, K_in, user_part and U_l are not read (they come from io[l-1]).  io: host
+ * array of L entries; the pointers in it follow the rules of the like-named arguments of
+ * nezha_draft_step (device memory; set = items at level L or prefixes of length l below it or
+ * NULL; user_part and U_l optional).  When every level is small enough for the single-launch
+ * level kernel (NEZHA_BF16, packed weights, K <= 32, T_l <= 512) and every io[l-1].user_part is
+ * given, one kernel launch runs all levels; otherwise the levels are launched one after the
+ * other.  workspace: at least nezha_draft_levels_workspace(desc) bytes, 256-byte aligned.
+ * Asynchronous on hip_stream; allocates nothing. */
+typedef struct {
+  const void* H_l;            /* [B, d] hidden states of this level (may be NULL with user_part) */
+  const void* W_l;            /* weights of this level (packed when desc->w_packed) */
+  const void* E_l;            /* code embeddings (NULL allowed at level L) */
+  const nezha_itemset* set;   /* or NULL */
+  const float* user_part;     /* or NULL */
+  const void* U_l;            /* NEZHA_TRANSITION_RNN: [e, e]; else NULL */
+  uint64_t* key_out;
+  float* score_out;
+  int32_t* parent_out;
+  int32_t* code_out;
+  void* state_out;            /* NULL allowed at level L */
+  int32_t* count_out;         /* or NULL */
+} nezha_level_io;
+int nezha_draft_levels(const nezha_step_desc* desc, const nezha_level_io* io, void* workspace,
+                       size_t workspace_bytes, void* hip_stream);
+size_t nezha_draft_levels_workspace(const nezha_step_desc* desc); /* 0 if desc is invalid */
+
 /* The user parts of levels 1..n_levels in one launch.  They do not depend on the beams, and all
  * hidden states h_1..h_L come out of the same prefill, so they can be formed before the level
  * loop and handed to nezha_draft_step through desc->user_part.  H, W_packed, A_out: host arrays

@@ -18,7 +18,8 @@ EXPORTS = ["nezha_last_error", "nezha_build_itemset", "nezha_itemset_info", "nez
            "nezha_draft_step_workspace", "nezha_unpack_keys", "nezha_profile_enable",
            "nezha_profile_reset", "nezha_profile_kinds", "nezha_profile_read",
            "nezha_bench_random_gather", "nezha_user_projection", "nezha_pack_weights",
-           "nezha_packed_weights_bytes", "nezha_user_projection_levels"]
+           "nezha_packed_weights_bytes", "nezha_user_projection_levels", "nezha_draft_levels",
+           "nezha_draft_levels_workspace"]
 
 
 class NezhaError(RuntimeError):
@@ -33,6 +34,13 @@ class _StepDesc(C.Structure):
                 ("radices", C.POINTER(C.c_int32)), ("dtype", C.c_int),
                 ("h_row_stride", C.c_int64), ("w_packed", C.c_int32),
                 ("user_part", C.c_void_p), ("transition", C.c_int32), ("U_l", C.c_void_p)]
+
+
+class _LevelIO(C.Structure):
+    _fields_ = [("H_l", C.c_void_p), ("W_l", C.c_void_p), ("E_l", C.c_void_p), ("set", C.c_void_p),
+                ("user_part", C.c_void_p), ("U_l", C.c_void_p), ("key_out", C.c_void_p),
+                ("score_out", C.c_void_p), ("parent_out", C.c_void_p), ("code_out", C.c_void_p),
+                ("state_out", C.c_void_p), ("count_out", C.c_void_p)]
 
 
 def library_path():
@@ -309,6 +317,43 @@ class DraftBuffers:
                            for l in range(L)]
 
 
+def _dp(t):
+    return None if t is None else t.data_ptr()
+
+
+def draft_levels(H, W, E, radices, K, itemset=None, buffers=None, stream=None, U=None,
+                 prefix_sets=None, user_parts=None):
+    """nezha_draft_levels: all L levels in one C call (one kernel launch when every level is
+    small and `user_parts` are given).  Arguments as for decode()."""
+    L = len(W)
+    B, _, d = H.shape
+    e = W[0].shape[0] - d
+    if buffers is None:
+        buffers = DraftBuffers(B, L, K, d, e, radices, H.dtype, H.device)
+    packed = all(isinstance(w, PackedWeights) for w in W)
+    if not packed and any(isinstance(w, PackedWeights) for w in W):
+        raise ValueError("either all or none of the W_l may be packed")
+    dsc = _desc(B, L, 1, K, 1, d, e, radices, H.dtype, H.stride(0), packed, None,
+                U[0] if U is not None else None)
+    esz = H.element_size()
+    io = (_LevelIO * L)()
+    for l in range(L):
+        o = buffers.outs[l]
+        s = itemset if l == L - 1 else (prefix_sets[l] if prefix_sets else None)
+        io[l] = _LevelIO(H.data_ptr() + l * H.stride(1) * esz, W[l].data_ptr(),
+                         _dp(E[l]) if l < L - 1 else None, s._h if s is not None else None,
+                         _dp(user_parts[l]) if user_parts is not None else None,
+                         _dp(U[l]) if (U is not None and l < L - 1) else None,
+                         o["key"].data_ptr(), o["score"].data_ptr(), o["parent"].data_ptr(),
+                         o["code"].data_ptr(), _dp(o.get("state")), o["count"].data_ptr())
+    lib = load_library()
+    lib.nezha_draft_levels.argtypes = [C.POINTER(_StepDesc), C.POINTER(_LevelIO), C.c_void_p,
+                                       C.c_size_t, C.c_void_p]
+    _check(lib.nezha_draft_levels(C.byref(dsc), io, _ptr(buffers.workspace),
+                                  buffers.workspace.numel(), _stream(stream)))
+    return buffers.outs
+
+
 def decode(H, W, E, radices, K, itemset=None, buffers=None, stream=None, U=None,
            prefix_sets=None, use_state=True, level_events=None):
     """All L levels of the inference loop of Alg. 3: L calls of nezha_draft_step on one
@@ -334,6 +379,9 @@ def decode(H, W, E, radices, K, itemset=None, buffers=None, stream=None, U=None,
         parts = user_projection_levels(H, W, radices, buffers.user_parts, stream=stream)
     if level_events is not None:
         level_events[0][1].record()
+    if parts is not None and use_state and level_events is None:
+        # the level loop itself in one call (one launch when every level is small)
+        return draft_levels(H, W, E, radices, K, itemset, buffers, stream, U, prefix_sets, parts)
     for level in range(1, L + 1):
         if level_events is not None:
             level_events[level][0].record()

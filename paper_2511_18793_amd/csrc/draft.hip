@@ -1877,9 +1877,8 @@ struct LevelArgs {
 };
 constexpr int kLevelWaves = 16, kLevelRows = 32, kLevelBeam = 32;
 template <int KST, int NVT>
-__global__ __launch_bounds__(64 * kLevelWaves, 1) void level_small_kernel(LevelArgs a) {
+__device__ __forceinline__ void level_small_body(const LevelArgs& a, uint64_t* lds) {
   constexpr int CAP = 256;
-  extern __shared__ __align__(16) uint64_t lds[];
   uint64_t* scratch = lds;                                            // [16 waves][CAP]
   uint64_t* lists = scratch + kLevelWaves * CAP;                      // [32 rows][32]
   uint64_t* keys2 = lists + kLevelRows * kLevelBeam;                  // [32*32]
@@ -2019,6 +2018,29 @@ __global__ __launch_bounds__(64 * kLevelWaves, 1) void level_small_kernel(LevelA
     else
       update_states<true>(a.state_in, a.E, a.state_out, b, K, K_in, e, fin_parent, fin_code, tid,
                           64 * kLevelWaves);
+  }
+}
+
+template <int KST, int NVT>
+__global__ __launch_bounds__(64 * kLevelWaves, 1) void level_small_kernel(LevelArgs a) {
+  extern __shared__ __align__(16) uint64_t lds[];
+  level_small_body<KST, NVT>(a, lds);
+}
+
+// All levels of a decode in one launch: the workgroup of request b runs level 1, 2, ... in turn;
+// what a level hands to the next (keys, scores, states) is written to and read back from the
+// level's output arrays in global memory by the same workgroup.
+struct DecodeArgs {
+  LevelArgs lv[NEZHA_MAX_LEVELS];
+  int L;
+};
+template <int KST, int NVT>
+__global__ __launch_bounds__(64 * kLevelWaves, 1) void decode_small_kernel(DecodeArgs d) {
+  extern __shared__ __align__(16) uint64_t lds[];
+  for (int l = 0; l < d.L; ++l) {
+    level_small_body<KST, NVT>(d.lv[l], lds);
+    __threadfence_block();      // this level's outputs are the next level's inputs
+    __syncthreads();
   }
 }
 
@@ -2280,18 +2302,54 @@ size_t nezha_draft_step_workspace(const nezha_step_desc* desc) {
   return p.total;
 }
 
-int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W_l,
-                     const void* E_l, const void* state_in, const uint64_t* key_in,
-                     const float* score_in, const nezha_itemset* set, uint64_t* key_out,
-                     float* score_out, int32_t* parent_out, int32_t* code_out,
-                     void* state_out, int32_t* count_out, void* workspace,
-                     size_t workspace_bytes, void* hip_stream) {
+// Arguments of the single-launch level kernel from those of nezha_draft_step.
+static LevelArgs make_level_args(const nezha_step_desc* desc, const uint16_t* Wp, const float* A,
+                                 const void* E_l, const void* state_in, const uint64_t* key_in,
+                                 const float* score_in, const nezha_itemset* set, uint64_t* key_out,
+                                 float* score_out, int32_t* parent_out, int32_t* code_out,
+                                 void* state_out, int32_t* count_out, uint64_t mult) {
+  const int level = desc->level;
+  const int V = desc->radices[level - 1];
+  LevelArgs la;
+  la.state_in = state_in;
+  la.Wbeam = Wp + packed_user_elems(desc->d, V);
+  la.A = A;
+  la.key_in = key_in;
+  la.score_in = score_in;
+  la.E = E_l;
+  la.set = SetView{(set && set->L == level) ? set->slots : nullptr, set ? set->n_buckets : 0};
+  la.U = desc->U_l;
+  la.transition = desc->transition;
+  la.mult = mult;
+  la.key_out = key_out;
+  la.score_out = score_out;
+  la.parent_out = parent_out;
+  la.code_out = code_out;
+  la.state_out = state_out;
+  la.count_out = count_out;
+  la.K_in = desc->K_in;
+  la.K = desc->K;
+  la.V = V;
+  la.e = desc->e;
+  return la;
+}
+static size_t level_small_lds(int V) {
+  return (size_t)(kLevelWaves * 256 + 2 * kLevelRows * kLevelBeam + 256) * 8 +
+         (size_t)kLevelRows * V * 4;
+}
+
+// Argument checks of one level (everything nezha_draft_step refuses); fills the workspace plan.
+static int validate_step(const nezha_step_desc* desc, const void* H_l, const void* W_l,
+                         const void* E_l, const void* state_in, const nezha_itemset* set,
+                         const uint64_t* key_out, const float* score_out,
+                         const int32_t* parent_out, const int32_t* code_out,
+                         const void* state_out, const void* workspace, size_t workspace_bytes,
+                         Plan* plan_out) {
   Plan plan;
   int rc = check_desc(desc, &plan);
   if (rc != NEZHA_OK) return rc;
-  const int B = desc->B, K = desc->K, K_in = desc->K_in, d = desc->d, e = desc->e;
+  *plan_out = plan;
   const int level = desc->level, L = desc->L;
-  const int V = desc->radices[level - 1];
   const bool bf16 = desc->dtype == NEZHA_BF16;
   if (desc->B == 0) return NEZHA_OK;  // an empty batch has nothing to read or write
   if ((!H_l && !desc->user_part) || !W_l) return fail(NEZHA_EINVAL, "H_l or W_l is NULL");
@@ -2329,6 +2387,24 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
       if (set->radices[l] != desc->radices[l])
         return fail(NEZHA_EINVAL, "item set and desc disagree on radix %d", l + 1);
   }
+  return NEZHA_OK;
+}
+
+int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W_l,
+                     const void* E_l, const void* state_in, const uint64_t* key_in,
+                     const float* score_in, const nezha_itemset* set, uint64_t* key_out,
+                     float* score_out, int32_t* parent_out, int32_t* code_out,
+                     void* state_out, int32_t* count_out, void* workspace,
+                     size_t workspace_bytes, void* hip_stream) {
+  Plan plan;
+  int rc = validate_step(desc, H_l, W_l, E_l, state_in, set, key_out, score_out, parent_out,
+                         code_out, state_out, workspace, workspace_bytes, &plan);
+  if (rc != NEZHA_OK) return rc;
+  const int B = desc->B, K = desc->K, K_in = desc->K_in, d = desc->d, e = desc->e;
+  const int level = desc->level, L = desc->L;
+  const int V = desc->radices[level - 1];
+  const bool bf16 = desc->dtype == NEZHA_BF16;
+  if (desc->B == 0) return NEZHA_OK;
   uint64_t mult[NEZHA_MAX_LEVELS];
   radix_multipliers(L, desc->radices, mult);
 
@@ -2355,29 +2431,10 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
 
   if (level_fits_one_launch(bf16, K, K_in, V)) {
     // small shapes: the whole level after the projection in one launch, one workgroup per request
-    LevelArgs la;
-    la.state_in = state_in;
-    la.Wbeam = Wp + packed_user_elems(d, V);
-    la.A = A;
-    la.key_in = key_in;
-    la.score_in = score_in;
-    la.E = E_l;
-    la.set = SetView{(set && set->L == level) ? set->slots : nullptr, set ? set->n_buckets : 0};
-    la.U = desc->U_l;
-    la.transition = desc->transition;
-    la.mult = mult[level - 1];
-    la.key_out = key_out;
-    la.score_out = score_out;
-    la.parent_out = parent_out;
-    la.code_out = code_out;
-    la.state_out = state_out;
-    la.count_out = count_out;
-    la.K_in = K_in;
-    la.K = K;
-    la.V = V;
-    la.e = e;
-    const size_t lds = (size_t)(kLevelWaves * 256 + 2 * kLevelRows * kLevelBeam + 256) * 8 +
-                       (size_t)kLevelRows * V * 4;
+    const LevelArgs la = make_level_args(desc, Wp, A, E_l, state_in, key_in, score_in, set, key_out,
+                                         score_out, parent_out, code_out, state_out, count_out,
+                                         mult[level - 1]);
+    const size_t lds = level_small_lds(V);
     dim3 grid(B), block(64 * kLevelWaves);
     ProfileScope prof(kLevelFused, stream);
 #define LAUNCH_LEVEL(KSTV, NVTV)                                                           \
@@ -2542,6 +2599,98 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
     }
     NEZHA_HIP_CHECK(hipGetLastError());
   }
+  return NEZHA_OK;
+}
+
+size_t nezha_draft_levels_workspace(const nezha_step_desc* desc) {
+  if (!desc || desc->L < 1 || desc->L > NEZHA_MAX_LEVELS) return 0;
+  size_t most = 0;
+  nezha_step_desc dl = *desc;
+  for (int l = 1; l <= desc->L; ++l) {
+    dl.level = l;
+    dl.K_in = l == 1 ? 1 : desc->K;
+    const size_t n = nezha_draft_step_workspace(&dl);
+    if (n == 0) return 0;
+    most = n > most ? n : most;
+  }
+  return most;
+}
+
+int nezha_draft_levels(const nezha_step_desc* desc, const nezha_level_io* io, void* workspace,
+                       size_t workspace_bytes, void* hip_stream) {
+  if (!desc || !io) return fail(NEZHA_EINVAL, "desc or io is NULL");
+  const int L = desc->L;
+  if (L < 1 || L > NEZHA_MAX_LEVELS)
+    return fail(NEZHA_EINVAL, "L = %d outside 1..%d", L, NEZHA_MAX_LEVELS);
+  if (!desc->radices) return fail(NEZHA_EINVAL, "radices is NULL");
+  const bool bf16 = desc->dtype == NEZHA_BF16;
+  const int K = desc->K;
+  // one launch for all levels when every level fits the single-launch kernel and has its user part
+  bool one_launch = bf16 && desc->w_packed == 1 && desc->B > 0;
+  int max_v = 0;
+  for (int l = 1; l <= L && one_launch; ++l) {
+    const int V = desc->radices[l - 1];
+    one_launch = level_fits_one_launch(bf16, K, l == 1 ? 1 : K, V) && io[l - 1].user_part != nullptr;
+    max_v = V > max_v ? V : max_v;
+  }
+  nezha_step_desc dl = *desc;
+  const void* state = nullptr;
+  const uint64_t* key = nullptr;
+  const float* score = nullptr;
+  DecodeArgs da;
+  da.L = L;
+  uint64_t mult[NEZHA_MAX_LEVELS];
+  if (one_launch && !radix_multipliers(L, desc->radices, mult))
+    return fail(NEZHA_ERANGE, "radices must be >= 1 with a product of at most 2^64-1");
+  for (int l = 1; l <= L; ++l) {
+    const nezha_level_io& x = io[l - 1];
+    dl.level = l;
+    dl.K_in = l == 1 ? 1 : K;
+    dl.user_part = x.user_part;
+    dl.U_l = x.U_l;
+    if (one_launch) {
+      Plan plan;
+      int rc = validate_step(&dl, x.H_l, x.W_l, x.E_l, state, x.set, x.key_out, x.score_out,
+                             x.parent_out, x.code_out, x.state_out, workspace, workspace_bytes, &plan);
+      if (rc != NEZHA_OK) return rc;
+      da.lv[l - 1] = make_level_args(&dl, static_cast<const uint16_t*>(x.W_l), x.user_part, x.E_l,
+                                     state, key, score, x.set, x.key_out, x.score_out, x.parent_out,
+                                     x.code_out, x.state_out, x.count_out, mult[l - 1]);
+    } else {
+      int rc = nezha_draft_step(&dl, x.H_l, x.W_l, x.E_l, state, key, score, x.set, x.key_out,
+                                x.score_out, x.parent_out, x.code_out, x.state_out, x.count_out,
+                                workspace, workspace_bytes, hip_stream);
+      if (rc != NEZHA_OK) return rc;
+    }
+    state = x.state_out;
+    key = x.key_out;
+    score = x.score_out;
+  }
+  if (!one_launch) return NEZHA_OK;
+  for (int l = L; l < NEZHA_MAX_LEVELS; ++l) da.lv[l] = da.lv[L - 1];
+  hipStream_t stream = (hipStream_t)hip_stream;
+  const size_t lds = level_small_lds(max_v);
+  const int e = desc->e;
+  int rc = NEZHA_OK;
+  dim3 grid(desc->B), block(64 * kLevelWaves);
+  ProfileScope prof(kLevelFused, stream);
+#define LAUNCH_DECODE(KSTV, NVTV)                                                           \
+  do {                                                                                      \
+    rc = allow_lds(decode_small_kernel<KSTV, NVTV>, lds);                                   \
+    if (rc != NEZHA_OK) return rc;                                                          \
+    hipLaunchKernelGGL((decode_small_kernel<KSTV, NVTV>), grid, block, lds, stream, da);    \
+  } while (0)
+  if (max_v <= 256) {
+    if (e <= 64) LAUNCH_DECODE(2, 4);
+    else if (e <= 128) LAUNCH_DECODE(4, 4);
+    else LAUNCH_DECODE(8, 4);
+  } else {
+    if (e <= 64) LAUNCH_DECODE(2, 8);
+    else if (e <= 128) LAUNCH_DECODE(4, 8);
+    else LAUNCH_DECODE(8, 8);
+  }
+#undef LAUNCH_DECODE
+  NEZHA_HIP_CHECK(hipGetLastError());
   return NEZHA_OK;
 }
 

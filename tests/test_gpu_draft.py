@@ -321,3 +321,59 @@ def test_head_without_state(oracle, name, B, shared_hidden):
     torch.cuda.synchronize()
     assert not torch.equal(with_state[-1]["key"], outs[-1]["key"])
     assert lvl2["count"].min() > 0
+
+
+# ---- all levels in one call ---------------------------------------------------------------------
+@pytest.mark.parametrize("name,B,variant", [("serving", 256, "plain"), ("serving", 40, "rnn"),
+                                            ("serving", 40, "prefix"), ("paper_yelp", 64, "plain"),
+                                            ("wide", 8, "plain")])
+def test_draft_levels_equals_the_level_loop(oracle, name, B, variant):
+    """nezha_draft_levels (one launch for all levels where the shapes allow) against L calls of
+    nezha_draft_step on the same inputs: identical outputs, and parity with the oracle."""
+    cfg = synth.get_config(name).scaled(B=B)
+    x, cat = planted_workload(oracle, cfg, 91, N=20000)
+    if variant == "prefix":
+        first = np.unique(cat[:, 0])
+        cat = cat[np.isin(cat[:, 0], first[: max(2, len(first) // 8)])]
+    oset = oracle.ItemSet(cat, cfg.radices)
+    gset = nz.build_itemset(cat, cfg.radices, cfg.load_factor)
+    H, W, E = to_device(x, cfg)
+    U = Ud = opre = gpre = None
+    if variant == "rnn":
+        U = _rnn_inputs(cfg, 91)
+        Ud = [torch.from_numpy(u).to(device()).to(torch_dtype(cfg)) for u in U]
+    if variant == "prefix":
+        opre, gpre = [], []
+        for l in range(1, cfg.L):
+            pre = np.unique(cat[:, :l], axis=0)
+            opre.append(oracle.ItemSet(pre, cfg.radices[:l]))
+            gpre.append(nz.build_itemset(pre, cfg.radices[:l], cfg.load_factor))
+    Wp = [nz.pack_weights(l + 1, cfg.L, cfg.radices, W[l], cfg.d) for l in range(cfg.L)]
+    b1 = nz.DraftBuffers(cfg.B, cfg.L, cfg.K, cfg.d, cfg.e, cfg.radices, H.dtype, H.device)
+    b2 = nz.DraftBuffers(cfg.B, cfg.L, cfg.K, cfg.d, cfg.e, cfg.radices, H.dtype, H.device)
+    parts = nz.user_projection_levels(H, Wp, cfg.radices, b1.user_parts)
+    one = nz.draft_levels(H, Wp, E, cfg.radices, cfg.K, gset, b1, U=Ud, prefix_sets=gpre,
+                          user_parts=parts)
+    torch.cuda.synchronize()
+    state = key = score = None
+    for level in range(1, cfg.L + 1):
+        s = gset if level == cfg.L else (gpre[level - 1] if gpre else None)
+        o = nz.draft_step(level, cfg.L, cfg.radices, cfg.K, H[:, level - 1, :], Wp[level - 1],
+                          E[level - 1] if level < cfg.L else None, state, key, score, s,
+                          out=b2.outs[level - 1], workspace=b2.workspace,
+                          h_row_stride=H.stride(0), user_part=parts[level - 1],
+                          U_l=Ud[level - 1] if (Ud and level < cfg.L) else None)
+        state, key, score = o.get("state"), o["key"], o["score"]
+    torch.cuda.synchronize()
+    for l in range(cfg.L):
+        for k in b2.outs[l]:
+            assert torch.equal(one[l][k], b2.outs[l][k]), (l, k)
+    soft = check_decode(oracle, nz, cfg, x, one, oset, tolerance(cfg), U=U, prefix_sets=opre)
+    assert soft <= 8
+    # without the user parts the call falls back to the level loop and still agrees
+    b3 = nz.DraftBuffers(cfg.B, cfg.L, cfg.K, cfg.d, cfg.e, cfg.radices, H.dtype, H.device)
+    loop = nz.draft_levels(H, Wp, E, cfg.radices, cfg.K, gset, b3, U=Ud, prefix_sets=gpre)
+    torch.cuda.synchronize()
+    for l in range(cfg.L):
+        for k in ("key", "score", "parent", "code", "count"):
+            assert torch.equal(loop[l][k], one[l][k]), (l, k)
