@@ -86,7 +86,8 @@ def kernel_models(cfg):
         rows = B * K_in
         probes = rows * K if level == L else 0
         # which kernel takes the expansion (the library's own rule, from the shape alone)
-        fused = cfg.dtype == "bf16" and K <= 32 and K_in <= 32 and V <= 512
+        fused = (cfg.dtype == "bf16" and K <= 32 and K_in <= 32 and V <= 512
+                 and e in (32, 64, 128, 256))
         per_request = (cfg.dtype == "bf16" and K_in >= 16 and e in (32, 64, 128, 256)
                        and not fused and not (V <= 1024 and K <= 64))
         slots = float(EXPAND_SLOTS_PER_LOGIT) * rows * V

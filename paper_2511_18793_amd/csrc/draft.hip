@@ -1074,11 +1074,15 @@ struct MergeArgs {
 
 // Eq. 3 with the additive Transition for the K survivors of request b: c' = c_parent + E[code]
 // (zero for unused slots); 8 (bf16) or 4 (f32) elements per thread and step.
+// lds_in / lds_out (bf16 only, may be NULL): the parents' states [K_in, e] and a second copy of
+// the new states [K, e] in LDS, for a caller that runs the next level in the same workgroup.
 template <bool BF16>
 __device__ __forceinline__ void update_states(const void* state_in, const void* E, void* state_out,
                                               int b, int K, int K_in, int e,
                                               const int32_t* fin_parent, const int32_t* fin_code,
-                                              int tid, int nthreads) {
+                                              int tid, int nthreads,
+                                              const uint16_t* lds_in = nullptr,
+                                              uint16_t* lds_out = nullptr) {
   {
     const int per = e / (BF16 ? 8 : 4);
     for (int idx = tid; idx < K * per; idx += nthreads) {
@@ -1088,12 +1092,13 @@ __device__ __forceinline__ void update_states(const void* state_in, const void* 
         uint16_t* out = static_cast<uint16_t*>(state_out) + ((int64_t)b * K + j) * e + t * 8;
         uint4 r = uint4{0, 0, 0, 0};
         if (par >= 0) {
-          const uint4 ev = *reinterpret_cast<const uint4*>(
-              static_cast<const uint16_t*>(E) + (int64_t)code * e + t * 8);
+          const uint4 ev = load_global_u4(static_cast<const uint16_t*>(E) + (int64_t)code * e + t * 8);
           uint4 sv = uint4{0, 0, 0, 0};
-          if (state_in)
-            sv = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(state_in) +
-                                                 ((int64_t)b * K_in + par) * e + t * 8);
+          if (lds_in)
+            sv = *reinterpret_cast<const uint4*>(lds_in + par * e + t * 8);
+          else if (state_in)
+            sv = load_global_u4(static_cast<const uint16_t*>(state_in) +
+                                ((int64_t)b * K_in + par) * e + t * 8);
           const uint32_t ew[4] = {ev.x, ev.y, ev.z, ev.w}, sw[4] = {sv.x, sv.y, sv.z, sv.w};
           uint32_t ow[4];
 #pragma unroll
@@ -1105,7 +1110,8 @@ __device__ __forceinline__ void update_states(const void* state_in, const void* 
           }
           r = uint4{ow[0], ow[1], ow[2], ow[3]};
         }
-        *reinterpret_cast<uint4*>(out) = r;
+        store_global_u4(out, r);
+        if (lds_out) *reinterpret_cast<uint4*>(lds_out + j * e + t * 8) = r;
       } else {
         float* out = static_cast<float*>(state_out) + ((int64_t)b * K + j) * e + t * 4;
         float4 r = float4{0.f, 0.f, 0.f, 0.f};
@@ -1133,7 +1139,9 @@ template <bool BF16>
 __device__ __forceinline__ void update_states_rnn(const void* state_in, const void* E, const void* U,
                                                   void* state_out, int b, int K, int K_in, int e,
                                                   const int32_t* fin_parent,
-                                                  const int32_t* fin_code, int tid, int nthreads) {
+                                                  const int32_t* fin_code, int tid, int nthreads,
+                                                  const uint16_t* lds_in = nullptr,
+                                                  uint16_t* lds_out = nullptr) {
   if constexpr (BF16) {
     const int lane = tid & 63, wave = tid >> 6, n_waves = nthreads >> 6;
     const int g = lane >> 4, c = lane & 15;
@@ -1150,17 +1158,20 @@ __device__ __forceinline__ void update_states_rnn(const void* state_in, const vo
       for (int i = 0; i < 4; ++i) {
         const int j = rt * 16 + 4 * g + i;
         code[i] = j < K ? fin_code[j] : -1;
-        acc[i] = code[i] >= 0 ? bf16_to_float(Eh[(int64_t)code[i] * e + ct * 16 + c]) : 0.f;
+        acc[i] = code[i] >= 0 ? bf16_to_float(as_global(Eh)[(int64_t)code[i] * e + ct * 16 + c]) : 0.f;
       }
       const int ja = rt * 16 + c;
       const int pa = ja < K ? fin_parent[ja] : -1;
-      if (Sh) {
+      if (Sh || lds_in) {
         for (int ks = 0; ks < KS; ++ks) {
           uint4 av = uint4{0, 0, 0, 0};
-          if (pa >= 0)
-            av = *reinterpret_cast<const uint4*>(Sh + ((int64_t)b * K_in + pa) * e + ks * 32 + 8 * g);
-          const uint4 bv =
-              *reinterpret_cast<const uint4*>(Uh + (int64_t)(ct * 16 + c) * e + ks * 32 + 8 * g);
+          if (pa >= 0) {
+            if (lds_in)
+              av = *reinterpret_cast<const uint4*>(lds_in + pa * e + ks * 32 + 8 * g);
+            else
+              av = load_global_u4(Sh + ((int64_t)b * K_in + pa) * e + ks * 32 + 8 * g);
+          }
+          const uint4 bv = load_global_u4(Uh + (int64_t)(ct * 16 + c) * e + ks * 32 + 8 * g);
           acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8*>(&av),
                                                         *reinterpret_cast<const bf16x8*>(&bv), acc,
                                                         0, 0, 0);
@@ -1169,9 +1180,11 @@ __device__ __forceinline__ void update_states_rnn(const void* state_in, const vo
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int j = rt * 16 + 4 * g + i;
-        if (j < K)
-          Oh[((int64_t)b * K + j) * e + ct * 16 + c] =
-              code[i] >= 0 ? float_to_bf16(tanhf(acc[i])) : (uint16_t)0;
+        if (j < K) {
+          const uint16_t v = code[i] >= 0 ? float_to_bf16(tanhf(acc[i])) : (uint16_t)0;
+          as_global(Oh)[((int64_t)b * K + j) * e + ct * 16 + c] = v;
+          if (lds_out) lds_out[j * e + ct * 16 + c] = v;
+        }
       }
     }
   } else {
@@ -1211,7 +1224,9 @@ __global__ __launch_bounds__(64 * kMergeMaxWaves) void merge_kernel(MergeArgs a)
   __shared__ uint64_t bounds[kMergeMaxWaves];
   __shared__ int32_t fin_parent[NEZHA_MAX_BEAM], fin_code[NEZHA_MAX_BEAM];
   const int b = blockIdx.x;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // the wave id is made scalar: loops and branches on it are then uniform for the compiler
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n_threads = blockDim.x, n_waves = n_threads >> 6;
   const int K = a.K, K_in = a.K_in;
   const int n_c = K_in * K;
@@ -1876,65 +1891,92 @@ struct LevelArgs {
   int transition;
 };
 constexpr int kLevelWaves = 16, kLevelRows = 32, kLevelBeam = 32;
+// What a workgroup that runs several levels in one launch carries from one level to the next:
+// which of the two LDS state buffers holds the states of the entering beams.  (Requesting the
+// next level's weight operands a level ahead into registers was tried and lost: the kernel is
+// bound by instruction issue with four waves per SIMD, and the extra live registers cost more
+// than the hidden latency gained.)
+struct LevelCarry {
+  int state_buf;        // 0 / 1: that LDS buffer; -1: the states are read from global memory
+};
+constexpr int kLevelStateElems = kLevelBeam * 256;     // one LDS state buffer: 32 beams x e <= 256
+
 template <int KST, int NVT>
-__device__ __forceinline__ void level_small_body(const LevelArgs& a, uint64_t* lds) {
+__device__ __forceinline__ void level_small_body(const LevelArgs& a, uint64_t* lds, bool has_next,
+                                                 LevelCarry& carry) {
   constexpr int CAP = 256;
   uint64_t* scratch = lds;                                            // [16 waves][CAP]
   uint64_t* lists = scratch + kLevelWaves * CAP;                      // [32 rows][32]
   uint64_t* keys2 = lists + kLevelRows * kLevelBeam;                  // [32*32]
   uint64_t* topbuf = keys2 + kLevelRows * kLevelBeam;                 // [CAP]
-  float* ztile = reinterpret_cast<float*>(topbuf + CAP);              // [32][V]
+  uint16_t* state_lds = reinterpret_cast<uint16_t*>(topbuf + CAP);    // [2][32 beams][e]
+  float* ztile = reinterpret_cast<float*>(state_lds + 2 * kLevelStateElems);   // [32][V]
   __shared__ float row_lse[kLevelRows];
   __shared__ uint64_t bounds[kLevelWaves];
   __shared__ int32_t fin_parent[NEZHA_MAX_BEAM], fin_code[NEZHA_MAX_BEAM];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // the wave id is made scalar: loops and branches on it are then uniform for the compiler
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, c = lane & 15;
   const int b = blockIdx.x;
   const int V = a.V, K = a.K, K_in = a.K_in, e = a.e;
   const bool has_beam = a.state_in != nullptr;
-  const int KS = e / 32;
   const int n_ct = V / 16;
   const int RT = (K_in + 15) / 16;                                    // 1 or 2 row tiles
 
-  {  // phase A: wave w takes column tiles w, w+16, ... for both row tiles (same W operands)
+  {  // phase A: wave w takes column tiles w, w+16, ... for both row tiles (same W operands).
+     // Every load of the first tile is issued before anything waits: one memory round trip.
+    constexpr int KS = KST;                                           // e = 32 * KST exactly
+    uint4 w[KST];
+    float start = 0.f;
+    int ct = wave;
+    auto fetch = [&](int t) {
+      if (has_beam) {
+        const uint4* wp = static_cast<const uint4*>(a.Wbeam) + (int64_t)t * KS * 64 + lane;
+#pragma unroll
+        for (int ks = 0; ks < KST; ++ks) w[ks] = load_global_u4(wp + ks * 64);
+      }
+      start = as_global(a.A)[(int64_t)b * V + t * 16 + c];
+    };
+    if (ct < n_ct) fetch(ct);
     bf16x8 fa16[2][KST];
     if (has_beam) {
       const uint16_t* st = static_cast<const uint16_t*>(a.state_in) + (int64_t)b * K_in * e;
+      const uint16_t* sl = state_lds + (carry.state_buf > 0 ? kLevelStateElems : 0);
 #pragma unroll
       for (int rt = 0; rt < 2; ++rt) {
         const int row = rt * 16 + c;
 #pragma unroll
         for (int ks = 0; ks < KST; ++ks) {
           uint4 v = uint4{0, 0, 0, 0};
-          if (ks < KS && row < K_in)
-            v = *reinterpret_cast<const uint4*>(st + (int64_t)row * e + ks * 32 + 8 * g);
+          if (row < K_in) {
+            if (carry.state_buf >= 0)     // (two loads, not one load through a chosen pointer)
+              v = *reinterpret_cast<const uint4*>(sl + row * e + ks * 32 + 8 * g);
+            else
+              v = load_global_u4(st + (int64_t)row * e + ks * 32 + 8 * g);
+          }
           fa16[rt][ks] = *reinterpret_cast<bf16x8*>(&v);
         }
       }
     }
-    for (int ct = wave; ct < n_ct; ct += kLevelWaves) {
-      const float start = a.A[(int64_t)b * V + ct * 16 + c];
+    for (; ct < n_ct; ct += kLevelWaves) {
       floatx4 acc0 = floatx4{start, start, start, start}, acc1 = acc0;
       if (has_beam) {
-        const uint4* wp = static_cast<const uint4*>(a.Wbeam) + (int64_t)ct * KS * 64 + lane;
-        uint4 w[KST];
 #pragma unroll
-        for (int ks = 0; ks < KST; ++ks)
-          if (ks < KS) w[ks] = wp[ks * 64];
-#pragma unroll
-        for (int ks = 0; ks < KST; ++ks)
-          if (ks < KS) {
-            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                fa16[0][ks], *reinterpret_cast<bf16x8*>(&w[ks]), acc0, 0, 0, 0);
-            if (RT > 1)
-              acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                  fa16[1][ks], *reinterpret_cast<bf16x8*>(&w[ks]), acc1, 0, 0, 0);
-          }
+        for (int ks = 0; ks < KST; ++ks) {
+          acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+              fa16[0][ks], *reinterpret_cast<bf16x8*>(&w[ks]), acc0, 0, 0, 0);
+          if (RT > 1)
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                fa16[1][ks], *reinterpret_cast<bf16x8*>(&w[ks]), acc1, 0, 0, 0);
+        }
       }
+      const int here = ct;
+      if (ct + kLevelWaves < n_ct) fetch(ct + kLevelWaves);           // next tile's operands
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        ztile[(4 * g + i) * V + ct * 16 + c] = acc0[i];
-        if (RT > 1) ztile[(16 + 4 * g + i) * V + ct * 16 + c] = acc1[i];
+        ztile[(4 * g + i) * V + here * 16 + c] = acc0[i];
+        if (RT > 1) ztile[(16 + 4 * g + i) * V + here * 16 + c] = acc1[i];
       }
     }
   }
@@ -1961,8 +2003,8 @@ __device__ __forceinline__ void level_small_body(const LevelArgs& a, uint64_t* l
     const uint64_t zk = lists[p * kLevelBeam + (tid - p * K)];
     const uint32_t code = ~(uint32_t)zk;
     const float logp = unordered_bits((uint32_t)(zk >> 32)) - row_lse[p];
-    const float score = (a.score_in ? a.score_in[b * K_in + p] : 0.f) + logp;
-    const uint64_t pkey = a.key_in ? a.key_in[b * K_in + p] : 0ull;
+    const float score = (a.score_in ? as_global(a.score_in)[b * K_in + p] : 0.f) + logp;
+    const uint64_t pkey = a.key_in ? as_global(a.key_in)[b * K_in + p] : 0ull;
     bool ok = pkey != kEmpty;                                         // an empty beam slot has no children
     if (verify && ok) ok = set_contains(a.set, pkey + (uint64_t)code * a.mult);
     if (ok) sk = ((uint64_t)ordered_bits(score) << 32) | (uint32_t)~(uint32_t)tid;
@@ -1993,43 +2035,53 @@ __device__ __forceinline__ void level_small_body(const LevelArgs& a, uint64_t* l
         const int i = (int)(~(uint32_t)s2);
         const int par = i / K;
         const int32_t code = (int32_t)(~(uint32_t)lists[par * kLevelBeam + (i - par * K)]);
-        a.key_out[o] = (a.key_in ? a.key_in[b * K_in + par] : 0ull) + (uint64_t)(uint32_t)code * a.mult;
-        a.score_out[o] = unordered_bits((uint32_t)(s2 >> 32));
-        a.parent_out[o] = par;
-        a.code_out[o] = code;
+        as_global(a.key_out)[o] =
+            (a.key_in ? as_global(a.key_in)[b * K_in + par] : 0ull) + (uint64_t)(uint32_t)code * a.mult;
+        as_global(a.score_out)[o] = unordered_bits((uint32_t)(s2 >> 32));
+        as_global(a.parent_out)[o] = par;
+        as_global(a.code_out)[o] = code;
         fin_parent[lane] = par;
         fin_code[lane] = code;
       } else {
-        a.key_out[o] = kEmpty;
-        a.score_out[o] = -INFINITY;
-        a.parent_out[o] = -1;
-        a.code_out[o] = -1;
+        as_global(a.key_out)[o] = kEmpty;
+        as_global(a.score_out)[o] = -INFINITY;
+        as_global(a.parent_out)[o] = -1;
+        as_global(a.code_out)[o] = -1;
         fin_parent[lane] = -1;
         fin_code[lane] = -1;
       }
     }
-    if (lane == 0 && a.count_out) a.count_out[b] = f.cnt;
+    if (lane == 0 && a.count_out) as_global(a.count_out)[b] = f.cnt;
   }
   __syncthreads();
   if (a.state_out) {
+    // with a next level in the same launch the new states also go to the other LDS buffer
+    const uint16_t* lds_in =
+        (has_beam && carry.state_buf >= 0) ? state_lds + (carry.state_buf > 0 ? kLevelStateElems : 0)
+                                           : nullptr;
+    const int out_buf = carry.state_buf > 0 ? 0 : 1;
+    uint16_t* lds_out = has_next ? state_lds + (out_buf > 0 ? kLevelStateElems : 0) : nullptr;
     if (a.transition == NEZHA_TRANSITION_RNN)
       update_states_rnn<true>(a.state_in, a.E, a.U, a.state_out, b, K, K_in, e, fin_parent, fin_code,
-                              tid, 64 * kLevelWaves);
+                              tid, 64 * kLevelWaves, lds_in, lds_out);
     else
       update_states<true>(a.state_in, a.E, a.state_out, b, K, K_in, e, fin_parent, fin_code, tid,
-                          64 * kLevelWaves);
+                          64 * kLevelWaves, lds_in, lds_out);
+    carry.state_buf = has_next ? out_buf : -1;
   }
 }
 
 template <int KST, int NVT>
 __global__ __launch_bounds__(64 * kLevelWaves, 1) void level_small_kernel(LevelArgs a) {
   extern __shared__ __align__(16) uint64_t lds[];
-  level_small_body<KST, NVT>(a, lds);
+  LevelCarry carry;
+  carry.state_buf = -1;
+  level_small_body<KST, NVT>(a, lds, false, carry);
 }
 
-// All levels of a decode in one launch: the workgroup of request b runs level 1, 2, ... in turn;
-// what a level hands to the next (keys, scores, states) is written to and read back from the
-// level's output arrays in global memory by the same workgroup.
+// All levels of a decode in one launch: the workgroup of request b runs level 1, 2, ... in turn.
+// Keys and scores of the beams are read back from the level's output arrays in global memory
+// (written by the same workgroup); the states stay in LDS.
 struct DecodeArgs {
   LevelArgs lv[NEZHA_MAX_LEVELS];
   int L;
@@ -2037,8 +2089,10 @@ struct DecodeArgs {
 template <int KST, int NVT>
 __global__ __launch_bounds__(64 * kLevelWaves, 1) void decode_small_kernel(DecodeArgs d) {
   extern __shared__ __align__(16) uint64_t lds[];
+  LevelCarry carry;
+  carry.state_buf = -1;
   for (int l = 0; l < d.L; ++l) {
-    level_small_body<KST, NVT>(d.lv[l], lds);
+    level_small_body<KST, NVT>(d.lv[l], lds, l + 1 < d.L, carry);
     __threadfence_block();      // this level's outputs are the next level's inputs
     __syncthreads();
   }
@@ -2053,13 +2107,14 @@ struct Plan {
 
 // Which kernels take a level is a function of the shape alone, so that the workspace can be sized
 // without the buffers.
-inline bool level_fits_one_launch(bool bf16, int K, int K_in, int V) {
-  return bf16 && K <= kLevelBeam && K_in <= kLevelRows && V <= 512;
+inline bool level_fits_one_launch(bool bf16, int K, int K_in, int V, int e) {
+  return bf16 && K <= kLevelBeam && K_in <= kLevelRows && V <= 512 &&
+         (e == 32 || e == 64 || e == 128 || e == 256);
 }
 inline bool codebook_fits_lds(bool bf16, int K, int V) { return bf16 && V <= 1024 && K <= 64; }
 inline bool expand_per_request(bool bf16, int K, int K_in, int V, int e) {
   return bf16 && K_in >= 16 && (e == 32 || e == 64 || e == 128 || e == 256) &&
-         !level_fits_one_launch(bf16, K, K_in, V) && !codebook_fits_lds(bf16, K, V);
+         !level_fits_one_launch(bf16, K, K_in, V, e) && !codebook_fits_lds(bf16, K, V);
 }
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -2335,7 +2390,7 @@ static LevelArgs make_level_args(const nezha_step_desc* desc, const uint16_t* Wp
 }
 static size_t level_small_lds(int V) {
   return (size_t)(kLevelWaves * 256 + 2 * kLevelRows * kLevelBeam + 256) * 8 +
-         (size_t)kLevelRows * V * 4;
+         (size_t)2 * kLevelStateElems * 2 + (size_t)kLevelRows * V * 4;
 }
 
 // Argument checks of one level (everything nezha_draft_step refuses); fills the workspace plan.
@@ -2429,7 +2484,7 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
     if (rc != NEZHA_OK) return rc;
   }
 
-  if (level_fits_one_launch(bf16, K, K_in, V)) {
+  if (level_fits_one_launch(bf16, K, K_in, V, e)) {
     // small shapes: the whole level after the projection in one launch, one workgroup per request
     const LevelArgs la = make_level_args(desc, Wp, A, E_l, state_in, key_in, score_in, set, key_out,
                                          score_out, parent_out, code_out, state_out, count_out,
@@ -2444,12 +2499,14 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
     hipLaunchKernelGGL((level_small_kernel<KSTV, NVTV>), grid, block, lds, stream, la);    \
   } while (0)
     if (V <= 256) {
-      if (e <= 64) LAUNCH_LEVEL(2, 4);
-      else if (e <= 128) LAUNCH_LEVEL(4, 4);
+      if (e == 32) LAUNCH_LEVEL(1, 4);
+      else if (e == 64) LAUNCH_LEVEL(2, 4);
+      else if (e == 128) LAUNCH_LEVEL(4, 4);
       else LAUNCH_LEVEL(8, 4);
     } else {
-      if (e <= 64) LAUNCH_LEVEL(2, 8);
-      else if (e <= 128) LAUNCH_LEVEL(4, 8);
+      if (e == 32) LAUNCH_LEVEL(1, 8);
+      else if (e == 64) LAUNCH_LEVEL(2, 8);
+      else if (e == 128) LAUNCH_LEVEL(4, 8);
       else LAUNCH_LEVEL(8, 8);
     }
 #undef LAUNCH_LEVEL
@@ -2630,7 +2687,8 @@ int nezha_draft_levels(const nezha_step_desc* desc, const nezha_level_io* io, vo
   int max_v = 0;
   for (int l = 1; l <= L && one_launch; ++l) {
     const int V = desc->radices[l - 1];
-    one_launch = level_fits_one_launch(bf16, K, l == 1 ? 1 : K, V) && io[l - 1].user_part != nullptr;
+    one_launch = level_fits_one_launch(bf16, K, l == 1 ? 1 : K, V, desc->e) &&
+                 io[l - 1].user_part != nullptr;
     max_v = V > max_v ? V : max_v;
   }
   nezha_step_desc dl = *desc;
@@ -2681,12 +2739,14 @@ int nezha_draft_levels(const nezha_step_desc* desc, const nezha_level_io* io, vo
     hipLaunchKernelGGL((decode_small_kernel<KSTV, NVTV>), grid, block, lds, stream, da);    \
   } while (0)
   if (max_v <= 256) {
-    if (e <= 64) LAUNCH_DECODE(2, 4);
-    else if (e <= 128) LAUNCH_DECODE(4, 4);
+    if (e == 32) LAUNCH_DECODE(1, 4);
+    else if (e == 64) LAUNCH_DECODE(2, 4);
+    else if (e == 128) LAUNCH_DECODE(4, 4);
     else LAUNCH_DECODE(8, 4);
   } else {
-    if (e <= 64) LAUNCH_DECODE(2, 8);
-    else if (e <= 128) LAUNCH_DECODE(4, 8);
+    if (e == 32) LAUNCH_DECODE(1, 8);
+    else if (e == 64) LAUNCH_DECODE(2, 8);
+    else if (e == 128) LAUNCH_DECODE(4, 8);
     else LAUNCH_DECODE(8, 8);
   }
 #undef LAUNCH_DECODE

@@ -58,13 +58,38 @@ __device__ __forceinline__ uint64_t home_bucket(uint64_t key, uint64_t n_buckets
   return __umul64hi(hash64(key), n_buckets);  // range reduction without a modulo
 }
 
+// A pointer known to address global memory, typed so: loads and stores through it are global
+// instructions even where the compiler cannot trace the pointer back to a kernel argument
+// (a generic access is a flat instruction, which also counts as an LDS access at every barrier).
+template <typename T>
+using global_ptr = __attribute__((address_space(1))) T*;
+template <typename T>
+__device__ __forceinline__ global_ptr<T> as_global(T* p) {
+  return (global_ptr<T>)p;
+}
+// 16-byte global loads / stores (the HIP vector classes cannot be read through such a pointer)
+typedef uint32_t nezha_u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned long long nezha_u64x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint4 load_global_u4(const void* p) {
+  const nezha_u32x4 v = *(global_ptr<const nezha_u32x4>)p;
+  return uint4{v.x, v.y, v.z, v.w};
+}
+__device__ __forceinline__ void store_global_u4(void* p, uint4 v) {
+  *(global_ptr<nezha_u32x4>)p = nezha_u32x4{v.x, v.y, v.z, v.w};
+}
+__device__ __forceinline__ ulonglong2 load_global_u64x2(const void* p) {
+  const nezha_u64x2 v = *(global_ptr<const nezha_u64x2>)p;
+  return ulonglong2{v.x, v.y};
+}
+
 // Membership of one key: scan the home bucket, then following buckets, until the key or an
 // empty slot is seen.  The table is never full, so the scan ends; it is bounded anyway.
 __device__ __forceinline__ bool set_contains(const SetView& s, uint64_t key) {
   uint64_t b = home_bucket(key, s.n_buckets);
   for (uint64_t step = 0; step < s.n_buckets; ++step) {
-    const ulonglong2* p = reinterpret_cast<const ulonglong2*>(s.slots + b * kBucketSlots);
-    ulonglong2 q0 = p[0], q1 = p[1], q2 = p[2], q3 = p[3];
+    const uint64_t* p = s.slots + b * kBucketSlots;
+    const ulonglong2 q0 = load_global_u64x2(p), q1 = load_global_u64x2(p + 2),
+                     q2 = load_global_u64x2(p + 4), q3 = load_global_u64x2(p + 6);
     bool hit = (q0.x == key) | (q0.y == key) | (q1.x == key) | (q1.y == key) |
                (q2.x == key) | (q2.y == key) | (q3.x == key) | (q3.y == key);
     if (hit) return true;
