@@ -40,7 +40,7 @@ BUCKET_BYTES = 64
 # are in profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB -> bytes; the factors come from the
 # plain-copy calibration in the same runs).  Only workloads that were profiled have an entry.
 MEASURED_TRAFFIC_BYTES = {
-    ("serving", "level_small_kernel"): (2878.8 * 2.0 + 973.3) * 1024,
+    ("serving", "decode_small_kernel"): (7826.3 * 2.0 + 2920.0) * 1024,
     ("stress", "verify_probe_kernel"): (245832.5 * 2.0 + 4064.6) * 1024,
     ("large", "expand_request_kernel"): (585420.2 * 2.0 + 1250698.3) * 1024,
 }
@@ -81,6 +81,8 @@ def kernel_models(cfg):
     B, K, V, d, e, L = cfg.B, cfg.K, cfg.V, cfg.d, cfg.e, cfg.L
     esz = 2 if cfg.dtype == "bf16" else 4
     per_level = []
+    # all levels in one launch (nezha_draft_levels) when every level fits the single-launch kernel
+    one_launch = (cfg.dtype == "bf16" and K <= 32 and V <= 512 and e in (32, 64, 128, 256))
     for level in range(1, L + 1):
         K_in = 1 if level == 1 else K
         rows = B * K_in
@@ -99,7 +101,8 @@ def kernel_models(cfg):
             "merge_kernel": ("hbm", rows * K * 8.0 + probes * BUCKET_BYTES
                              + B * K * (24.0 + (2 * e * esz if level < L else 0))),
             # expansion, merge, verification and Transition of one level in one launch
-            "level_small_kernel": ("alu", slots),
+            "level_small_kernel": ("alu", 0.0 if one_launch else slots),
+            "decode_small_kernel": ("alu", slots if one_launch else 0.0),
         })
     return per_level
 
@@ -232,7 +235,8 @@ def bench_draft(args, cfg):
                 "avg_launch_us": kd["avg_us"],
                 "timing": "HIP events by the library around each launch, eager pass of %d steps"
                           % prof_steps}
-    if dom in ("expand_kernel", "expand_request_kernel", "level_small_kernel"):
+    if dom in ("expand_kernel", "expand_request_kernel", "level_small_kernel",
+               "decode_small_kernel"):
         flops = sum(2.0 * cfg.B * (1 if l == 0 else cfg.K) * cfg.e * cfg.V * (0 if l == 0 else 1)
                     for l in range(cfg.L)) * prof_steps
         roofline["mfma_tflops"] = flops / (kd["total_ms"] * 1e-3) / 1e12

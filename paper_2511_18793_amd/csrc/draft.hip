@@ -2731,7 +2731,7 @@ int nezha_draft_levels(const nezha_step_desc* desc, const nezha_level_io* io, vo
   const int e = desc->e;
   int rc = NEZHA_OK;
   dim3 grid(desc->B), block(64 * kLevelWaves);
-  ProfileScope prof(kLevelFused, stream);
+  ProfileScope prof(kDecodeFused, stream);
 #define LAUNCH_DECODE(KSTV, NVTV)                                                           \
   do {                                                                                      \
     rc = allow_lds(decode_small_kernel<KSTV, NVTV>, lds);                                   \
