@@ -377,3 +377,48 @@ def test_draft_levels_equals_the_level_loop(oracle, name, B, variant):
     for l in range(cfg.L):
         for k in ("key", "score", "parent", "code", "count"):
             assert torch.equal(loop[l][k], one[l][k]), (l, k)
+
+
+# ---- the one-workgroup-per-request expansion (bf16, K_in >= 16, large codebooks) -----------------
+@pytest.mark.parametrize("B,d,e,V,K,L", [
+    (3, 64, 32, 1104, 70, 2),      # one MFMA step over the state, ragged last chunk
+    (2, 64, 64, 2048, 17, 3),      # the smallest beam that takes this path (two waves, one nearly empty)
+    (2, 64, 256, 1536, 100, 2),    # widest state
+    (2, 128, 128, 4096, 128, 2),   # the largest beam, eight full waves
+    (5, 64, 128, 80, 70, 2),       # fewer codes than one chunk: most code groups are empty
+])
+def test_request_kernel_shapes(oracle, B, d, e, V, K, L):
+    cfg = synth.StepConfig("req", B=B, d=d, e=e, L=L, V=V, K=K, N=min(V ** L // 4, 50_000),
+                           dtype="bf16", catalog="uniform", w_std=0.05)
+    outs, soft = run_config(oracle, cfg, 13)
+    assert soft <= 8
+
+
+def test_request_kernel_hands_hard_rows_to_the_general_kernel(oracle):
+    """Logits with a spread of several hundred (a lane's first logit can lie far below the rest,
+    so the fixed reference of the sum of exponentials is unusable) and logits crowded into one
+    code group (the group-maxima bound lets too many through): both must end in the flagged
+    beams being redone, with the same results as everywhere else."""
+    cfg = synth.StepConfig("hard", B=4, d=64, e=64, L=2, V=2048, K=40, N=50_000, dtype="bf16",
+                           catalog="uniform", w_std=0.05)
+    x, cat = planted_workload(oracle, cfg, 17, plant=False)
+    # (1) requests 0, 1: huge spread (the hidden state of level 2 scaled up)
+    x["H"][:2, 1] = synth.round_to_bf16(x["H"][:2, 1] * 400.0)
+    # (2) requests 2, 3: 480 codes lifted far above the rest, all of them in 30 of the 128 code
+    #     groups (a code's group is its value modulo 128), through a constant input component
+    x["H"][2:, 1, 0] = 1.0
+    lifted = (np.arange(cfg.V) % 128) < 30
+    x["W"][1][0, :] = np.where(lifted, 30.0, 0.0).astype(np.float32)
+    free = oracle.decode(x["H"], x["W"], x["E"], cfg.radices, cfg.K, round_state_bf16=True)
+    tuples = oracle.unpack(free[-1]["key"].ravel(), cfg.radices)
+    keep = synth.plant_mask(tuples, cfg.radices, 17)
+    cat = synth.planted_catalog(cfg.radices, cat, tuples[keep], tuples[~keep], 17)
+    oset = oracle.ItemSet(cat, cfg.radices)
+    gset = nz.build_itemset(cat, cfg.radices, cfg.load_factor)
+    H, W, E = to_device(x, cfg)
+    outs = nz.decode(H, W, E, cfg.radices, cfg.K, gset)
+    torch.cuda.synchronize()
+    # logits of the order of 1000 formed by float32 sums of 64 products: a few 1e-3 of rounding
+    # (the bf16 allowance is 2e-2)
+    soft = check_decode(oracle, nz, cfg, x, outs, oset, 4e-3)
+    assert soft <= 8
