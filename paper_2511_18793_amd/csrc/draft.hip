@@ -1070,6 +1070,7 @@ struct MergeArgs {
   int K_in, K, e;
   const void* U;            // [e, e] row major (recurrent Transition), else unused
   int transition;
+  const uint8_t* redo_req;  // only requests with redo_req[b] != 0 (NULL: every request)
 };
 
 // Eq. 3 with the additive Transition for the K survivors of request b: c' = c_parent + E[code]
@@ -1224,6 +1225,7 @@ __global__ __launch_bounds__(64 * kMergeMaxWaves) void merge_kernel(MergeArgs a)
   __shared__ uint64_t bounds[kMergeMaxWaves];
   __shared__ int32_t fin_parent[NEZHA_MAX_BEAM], fin_code[NEZHA_MAX_BEAM];
   const int b = blockIdx.x;
+  if (a.redo_req && a.redo_req[b] == 0) return;      // a pass over what another kernel left
   // the wave id is made scalar: loops and branches on it are then uniform for the compiler
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1580,9 +1582,40 @@ __host__ __device__ inline size_t request_w_region(int e, int n_waves) {
   const size_t maxima = (size_t)n_waves * 16 * 128 * 4;            // group maxima between sweeps
   return chunks > maxima ? chunks : maxima;
 }
-template <int KST>
+// WHOLE = true (a level without verification): the per-beam lists and the merge step are skipped.
+// The K best of the request's K_in * T_l candidates are the same set whether or not each beam is
+// first cut to its own K best, so the selection is done on cumulative scores for the request as a
+// whole: after sweep 1 every wave turns the 16 largest group maxima of each of its beams into
+// scores (parent score + logit - log-sum-exp, formed exactly as the final scores are), and the
+// K-th largest of a wave's 256 such scores bounds the request's K-th best score from below; the
+// best of the waves' bounds is the threshold.  Sweep 2 appends the few candidates at or above it
+// (about 1.5 K .. 6 K per request instead of 1.3 K per beam) to one list in LDS as final sort keys
+// (score, parent, code); wave 0 sorts them, writes the level's outputs, and the workgroup applies
+// the Transition.  A request whose list overflows is flagged and left to the general kernels.
+struct RequestLevelArgs {
+  const uint64_t* key_in;   // [B, K_in] or NULL
+  const float* score_in;    // [B, K_in] or NULL
+  const void* E;            // [V, e] (used when state_out != NULL)
+  const void* U;            // recurrent Transition, else unused
+  uint64_t mult;            // prod_{j<level} T_j
+  uint64_t* key_out;
+  float* score_out;
+  int32_t* parent_out;
+  int32_t* code_out;
+  void* state_out;          // or NULL
+  int32_t* count_out;       // or NULL
+  uint8_t* redo_req;        // [B]: 1 = the request is left to the general kernels
+  int transition;
+};
+constexpr int kReqListCap = 768;     // WHOLE: candidates per request kept for the final sort
+__host__ __device__ inline size_t request_whole_lds() {
+  // request list, wave 0's sorting buffer, per-wave bounds + counter, survivors' parents / codes
+  return (size_t)kReqListCap * 8 + 256 * 8 + 16 * 4 + 2 * NEZHA_MAX_BEAM * 4;
+}
+template <int KST, bool WHOLE>
 __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
-    ExpandArgs a, uint64_t* __restrict__ lists_all, uint8_t* __restrict__ redo) {
+    ExpandArgs a, uint64_t* __restrict__ lists_all, uint8_t* __restrict__ redo,
+    RequestLevelArgs la) {
   extern __shared__ __align__(16) uint8_t req_lds[];
   // wave-uniform values are made scalar so that what is derived from them needs no vector registers
   const int lane = threadIdx.x & 63, NW = blockDim.x >> 6;
@@ -1595,9 +1628,17 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
   const int total_blocks = n_ct * KS;
   uint8_t* const wbuf = req_lds;                                                  // [2][chunk]
   float* const abuf = reinterpret_cast<float*>(req_lds + request_w_region(e, NW));   // [2][128]
-  float* const my_info = abuf + 2 * kReqTiles * 16 + wave * 48;   // bound[16], lse[16], count[16]
+  // per wave: bound[16], lse[16], count[16] (WHOLE: the parents' scores instead of the counts)
+  float* const my_info = abuf + 2 * kReqTiles * 16 + wave * 48;
   int* const my_cnt = reinterpret_cast<int*>(my_info + 32);
   uint64_t* const my_lists = lists_all + ((int64_t)blockIdx.x * 128 + wave * 16) * kReqCap;
+  // WHOLE only (after the NW waves' info):
+  uint64_t* const req_list = reinterpret_cast<uint64_t*>(abuf + 2 * kReqTiles * 16 + NW * 48);
+  uint64_t* const topbuf = req_list + kReqListCap;
+  uint32_t* const tau_s = reinterpret_cast<uint32_t*>(topbuf + 256);   // [8] bounds, [8] = counter
+  int* const req_cnt = reinterpret_cast<int*>(tau_s + 8);
+  int32_t* const fin_parent = reinterpret_cast<int32_t*>(tau_s + 16);
+  int32_t* const fin_code = fin_parent + NEZHA_MAX_BEAM;
   const int B = a.rows / K_in;
   const uint4* const Wb = static_cast<const uint4*>(a.Wbeam);
 
@@ -1631,16 +1672,36 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
     }
     // sweep 1 state: sum of exp(z - m) with the reference m held as nml = -m * log2(e)
     float gmax[4][kReqTiles], m[4], nml[4], ssum[4], bound[4];
+    float sp[4], lse_r[4];                    // WHOLE: parent score (-inf: no such beam), log-sum-exp
+    uint32_t tau = 0;                         // WHOLE: ordered bits of the score threshold
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       m[i] = -INFINITY;
       nml[i] = 0.f;
       ssum[i] = 0.f;
       bound[i] = INFINITY;
+      sp[i] = 0.f;
+      lse_r[i] = 0.f;
 #pragma unroll
       for (int j = 0; j < kReqTiles; ++j) gmax[i][j] = -INFINITY;
     }
-    if (lane < 16) my_cnt[lane] = 0;
+    if constexpr (WHOLE) {
+      const int g = lane >> 4, c = lane & 15;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = wave * 16 + 4 * g + i;
+        float v = -INFINITY;
+        if (row < K_in) {
+          const bool dead = la.key_in && la.key_in[(int64_t)b * K_in + row] == kEmpty;
+          if (!dead) v = la.score_in ? la.score_in[(int64_t)b * K_in + row] : 0.f;
+        }
+        sp[i] = v;
+        if (c == 0) my_info[32 + 4 * g + i] = v;
+      }
+      if (threadIdx.x == 0) *req_cnt = 0;
+    } else {
+      if (lane < 16) my_cnt[lane] = 0;
+    }
 
     auto run_sweep = [&](auto sweep_c) {
       constexpr int sweep = decltype(sweep_c)::value;
@@ -1705,6 +1766,19 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
                 gmax[i][ct] = __builtin_amdgcn_fmed3f(gmax[i][ct], z[i], INFINITY);   // max
                 ssum[i] += __builtin_amdgcn_exp2f(fmaf(z[i], kLog2e, nml[i]));
               }
+            } else if constexpr (WHOLE) {
+              const uint32_t code = (uint32_t)((ch * kReqTiles + ct) * 16 + c);
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                if (live && z[i] >= bound[i]) {             // bound: a logit that cannot be missed
+                  const uint32_t key = ordered_bits(sp[i] + (z[i] - lse_r[i]));   // the final score
+                  if (key >= tau) {
+                    const int pos = atomicAdd(req_cnt, 1);
+                    const uint32_t who = ((uint32_t)(wave * 16 + 4 * g + i) << 24) | code;
+                    if (pos < kReqListCap) req_list[pos] = ((uint64_t)key << 32) | (uint32_t)~who;
+                  }
+                }
+              }
             } else {
               const uint32_t code = (uint32_t)((ch * kReqTiles + ct) * 16 + c);
               int pos[4];
@@ -1745,12 +1819,17 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
                      __uint_as_float(lane_xor<4>(__float_as_uint(ss), lane)));
           merge_with(__uint_as_float(lane_xor<8>(__float_as_uint(mm), lane)),
                      __uint_as_float(lane_xor<8>(__float_as_uint(ss), lane)));
-          if (c == 0) my_info[16 + 4 * g + i] = mm + __builtin_amdgcn_logf(ss) * kLn2;
+          lse_r[i] = mm + __builtin_amdgcn_logf(ss) * kLn2;
+          if (c == 0) my_info[16 + 4 * g + i] = lse_r[i];
           float top = gmax[i][0];
 #pragma unroll
           for (int j = 1; j < kReqTiles; ++j) top = fmaxf(top, gmax[i][j]);
-          // this lane's sum may have overflowed: push the beam's count past the list size
-          if (top > m[i] + 64.f) atomicAdd(&my_cnt[4 * g + i], kReqCap + 1);
+          // this lane's sum may have overflowed: push the beam's (the request's) count past
+          // the list size
+          if (top > m[i] + 64.f) {
+            if constexpr (WHOLE) atomicAdd(req_cnt, kReqListCap + 1);
+            else atomicAdd(&my_cnt[4 * g + i], kReqCap + 1);
+          }
         }
         // the beams' 128 group maxima each, through this wave's part of the chunk buffers
         float* gm = reinterpret_cast<float*>(req_lds) + wave * (16 * 128);
@@ -1769,23 +1848,118 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
 #pragma unroll
             for (int j = 0; j < 2; ++j) mk[r][j] = ordered_bits(gm[(4 * q + r) * 128 + j * 64 + ln]);
           sort_desc<2, 4, uint32_t>(mk);                                // position 2*lane + j
+          if constexpr (WHOLE) {
+            // the 16 largest group maxima of each of the 4 beams as scores: 64 keys, parked in
+            // the (already read) first row of this quad's maxima
+            wave_sync();
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const uint32_t pick = pick_element<2>(mk[r], (K - 1) & 1);
-            const float bnd = unordered_bits((uint32_t)__builtin_amdgcn_readlane((int)pick, (K - 1) >> 1));
-            if (lane == 0) my_info[4 * q + r] = bnd;
+            for (int r = 0; r < 4; ++r) {
+              const float p_sc = my_info[32 + 4 * q + r], p_lse = my_info[16 + 4 * q + r];
+#pragma unroll
+              for (int j = 0; j < 2; ++j) {
+                const uint32_t key = ordered_bits(p_sc + (unordered_bits(mk[r][j]) - p_lse));
+                if (ln < 8) reinterpret_cast<uint32_t*>(gm)[(4 * q) * 128 + r * 16 + 2 * ln + j] = key;
+              }
+            }
+          } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const uint32_t pick = pick_element<2>(mk[r], (K - 1) & 1);
+              const float bnd =
+                  unordered_bits((uint32_t)__builtin_amdgcn_readlane((int)pick, (K - 1) >> 1));
+              if (lane == 0) my_info[4 * q + r] = bnd;
+            }
           }
         }
         wave_sync();
+        if constexpr (WHOLE) {
+          uint32_t uk[1][4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-          bound[i] = (wave * 16 + 4 * g + i < K_in) ? my_info[4 * g + i] : INFINITY;
-        __syncthreads();                      // maxima read before the next chunk lands on them
+          for (int t = 0; t < 4; ++t) uk[0][t] = reinterpret_cast<const uint32_t*>(gm)[(4 * t) * 128 + ln];
+          sort_desc<4, 1, uint32_t>(uk);                                // position 4*lane + j
+          const uint32_t tw = (uint32_t)__builtin_amdgcn_readlane(
+              (int)pick_element<4>(uk[0], (K - 1) & 3), (K - 1) >> 2);
+          if (lane == 0) tau_s[wave] = tw;
+          __syncthreads();                    // all bounds are in; maxima have been read
+          tau = tau_s[0];
+          for (int w2 = 1; w2 < NW; ++w2) tau = tau_s[w2] > tau ? tau_s[w2] : tau;
+          tau = (uint32_t)__builtin_amdgcn_readfirstlane((int)tau);
+          // a logit bound per beam that no candidate with score >= tau can fall below: the
+          // threshold moved back through the (rounded) score formula, minus a margin far above
+          // the rounding of two float32 additions
+          const float tf = unordered_bits(tau);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float margin = 1e-5f * (fabsf(tf) + fabsf(sp[i]) + fabsf(lse_r[i]) + 1.f);
+            bound[i] = (sp[i] == -INFINITY) ? INFINITY : (tf - sp[i]) + lse_r[i] - margin;
+            if (!(tf > -INFINITY)) bound[i] = (sp[i] == -INFINITY) ? INFINITY : -INFINITY;
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            bound[i] = (wave * 16 + 4 * g + i < K_in) ? my_info[4 * g + i] : INFINITY;
+          __syncthreads();                    // maxima read before the next chunk lands on them
+        }
       }
     };
     run_sweep(std::integral_constant<int, 0>{});
     run_sweep(std::integral_constant<int, 1>{});
 
+    if constexpr (WHOLE) {
+      const int n = *req_cnt;                 // (the sweep ended with a barrier)
+      const bool over = n > kReqListCap;
+      if (threadIdx.x < K_in) redo[(int64_t)b * K_in + threadIdx.x] = over ? 1 : 0;
+      if (threadIdx.x == 0) la.redo_req[b] = over ? 1 : 0;
+      if (!over) {
+        if (wave == 0) {
+          WaveTopK<256> f;
+          f.init(topbuf, K);
+          for (int base = 0; base < n; base += 64) f.push(base + lane < n ? req_list[base + lane] : 0ull);
+          f.compact();
+          wave_sync();
+          constexpr int NPLK = (NEZHA_MAX_BEAM + 63) / 64;
+#pragma unroll
+          for (int j = 0; j < NPLK; ++j) {
+            const int p = lane + 64 * j;
+            if (p < K) {
+              const int64_t o = (int64_t)b * K + p;
+              if (p < f.cnt) {
+                const uint64_t sk = f.buf[p];
+                const uint32_t who = ~(uint32_t)sk;
+                const int par = (int)(who >> 24);
+                const int32_t code = (int32_t)(who & 0xFFFFFFu);
+                la.key_out[o] = (la.key_in ? la.key_in[(int64_t)b * K_in + par] : 0ull) +
+                                (uint64_t)(uint32_t)code * la.mult;
+                la.score_out[o] = unordered_bits((uint32_t)(sk >> 32));
+                la.parent_out[o] = par;
+                la.code_out[o] = code;
+                fin_parent[p] = par;
+                fin_code[p] = code;
+              } else {
+                la.key_out[o] = kEmpty;
+                la.score_out[o] = -INFINITY;
+                la.parent_out[o] = -1;
+                la.code_out[o] = -1;
+                fin_parent[p] = -1;
+                fin_code[p] = -1;
+              }
+            }
+          }
+          if (lane == 0 && la.count_out) la.count_out[b] = f.cnt;
+        }
+        __syncthreads();
+        if (la.state_out) {
+          if (la.transition == NEZHA_TRANSITION_RNN)
+            update_states_rnn<true>(a.state, la.E, la.U, la.state_out, b, K, K_in, e, fin_parent,
+                                    fin_code, threadIdx.x, blockDim.x);
+          else
+            update_states<true>(a.state, la.E, la.state_out, b, K, K_in, e, fin_parent, fin_code,
+                                threadIdx.x, blockDim.x);
+        }
+      }
+      __syncthreads();                        // the request's LDS state is reused by the next one
+      continue;
+    }
     // per beam: the K-th largest listed logit, then the entries that belong to the K best
     auto emit = [&](auto npl_c, int q, const int (&n)[2]) {
       constexpr int NPL = decltype(npl_c)::value;
@@ -2100,7 +2274,7 @@ __global__ __launch_bounds__(64 * kLevelWaves, 1) void decode_small_kernel(Decod
 
 // ---- host side ---------------------------------------------------------------------------------
 struct Plan {
-  size_t wp_off, a_off, code_off, logp_off, list_off, redo_off, total;
+  size_t wp_off, a_off, code_off, logp_off, list_off, redo_off, redo_req_off, total;
   int cap;
   bool per_request;   // expand_request_kernel takes the expansion
 };
@@ -2113,7 +2287,7 @@ inline bool level_fits_one_launch(bool bf16, int K, int K_in, int V, int e) {
 }
 inline bool codebook_fits_lds(bool bf16, int K, int V) { return bf16 && V <= 1024 && K <= 64; }
 inline bool expand_per_request(bool bf16, int K, int K_in, int V, int e) {
-  return bf16 && K_in >= 16 && (e == 32 || e == 64 || e == 128 || e == 256) &&
+  return bf16 && K_in >= 16 && V <= (1 << 24) && (e == 32 || e == 64 || e == 128 || e == 256) &&
          !level_fits_one_launch(bf16, K, K_in, V, e) && !codebook_fits_lds(bf16, K, V);
 }
 
@@ -2163,12 +2337,14 @@ int check_desc(const nezha_step_desc* dsc, Plan* plan) {
     plan->logp_off = off;
     off += align_up(rows * dsc->K * 4, 256);
     plan->per_request = expand_per_request(bf16, dsc->K, dsc->K_in, V, dsc->e);
-    plan->list_off = plan->redo_off = off;
+    plan->list_off = plan->redo_off = plan->redo_req_off = off;
     if (plan->per_request) {
       const size_t groups = dsc->B < kReqMaxGroups ? (size_t)dsc->B : (size_t)kReqMaxGroups;
       off += align_up(groups * 128 * kReqCap * 8, 256);
       plan->redo_off = off;
       off += align_up(rows, 256);
+      plan->redo_req_off = off;
+      off += align_up((size_t)dsc->B, 256);
     }
     plan->total = off < 256 ? 256 : off;
     plan->cap = dsc->K <= 32 ? 128 : 256;
@@ -2527,6 +2703,7 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
   ea.d = d;
   ea.e = e;
   ea.redo = nullptr;
+  const uint8_t* redo_req = nullptr;   // set when a kernel above has already finished most requests
   if (plan.per_request) {
     // one workgroup per request, resident workgroups walk the batch
     static int n_cu = 0;
@@ -2539,24 +2716,47 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
     const int n_waves = (K_in + 15) / 16;
     int groups = B < 2 * n_cu ? B : 2 * n_cu;
     groups = groups < kReqMaxGroups ? groups : kReqMaxGroups;
+    // without verification at this level the kernel also does the merge and the Transition
+    const bool whole = !(set && set->L == level);
     const size_t lds = request_w_region(e, n_waves) + (size_t)2 * kReqTiles * 16 * 4 +
-                       (size_t)n_waves * 48 * 4;
+                       (size_t)n_waves * 48 * 4 + (whole ? request_whole_lds() : 0);
     uint64_t* lists = reinterpret_cast<uint64_t*>(ws + plan.list_off);
     uint8_t* redo = reinterpret_cast<uint8_t*>(ws + plan.redo_off);
+    RequestLevelArgs rl;
+    rl.key_in = key_in;
+    rl.score_in = score_in;
+    rl.E = E_l;
+    rl.U = desc->U_l;
+    rl.mult = mult[level - 1];
+    rl.key_out = key_out;
+    rl.score_out = score_out;
+    rl.parent_out = parent_out;
+    rl.code_out = code_out;
+    rl.state_out = state_out;
+    rl.count_out = count_out;
+    rl.redo_req = reinterpret_cast<uint8_t*>(ws + plan.redo_req_off);
+    rl.transition = desc->transition;
     ProfileScope prof(kExpandRequest, stream);
-#define LAUNCH_REQUEST(KSTV)                                                                   \
-  do {                                                                                         \
-    rc = allow_lds(expand_request_kernel<KSTV>, lds);                                          \
-    if (rc != NEZHA_OK) return rc;                                                             \
-    hipLaunchKernelGGL((expand_request_kernel<KSTV>), dim3(groups), dim3(64 * n_waves), lds,   \
-                       stream, ea, lists, redo);                                               \
+#define LAUNCH_REQUEST(KSTV, WHOLEV)                                                               \
+  do {                                                                                             \
+    rc = allow_lds(expand_request_kernel<KSTV, WHOLEV>, lds);                                      \
+    if (rc != NEZHA_OK) return rc;                                                                 \
+    hipLaunchKernelGGL((expand_request_kernel<KSTV, WHOLEV>), dim3(groups), dim3(64 * n_waves),    \
+                       lds, stream, ea, lists, redo, rl);                                          \
   } while (0)
-    if (e == 32) LAUNCH_REQUEST(1);
-    else if (e == 64) LAUNCH_REQUEST(2);
-    else if (e == 128) LAUNCH_REQUEST(4);
-    else LAUNCH_REQUEST(8);
+#define LAUNCH_REQUEST_E(WHOLEV)                  \
+  do {                                            \
+    if (e == 32) LAUNCH_REQUEST(1, WHOLEV);       \
+    else if (e == 64) LAUNCH_REQUEST(2, WHOLEV);  \
+    else if (e == 128) LAUNCH_REQUEST(4, WHOLEV); \
+    else LAUNCH_REQUEST(8, WHOLEV);               \
+  } while (0)
+    if (whole) LAUNCH_REQUEST_E(true);
+    else LAUNCH_REQUEST_E(false);
+#undef LAUNCH_REQUEST_E
 #undef LAUNCH_REQUEST
     NEZHA_HIP_CHECK(hipGetLastError());
+    redo_req = whole ? rl.redo_req : nullptr;
     ea.redo = redo;   // the chunked kernel below redoes the flagged beams only
   }
   {
@@ -2631,6 +2831,7 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
   ma.set = SetView{(set && set->L == level) ? set->slots : nullptr, set ? set->n_buckets : 0};
   ma.U = desc->U_l;
   ma.transition = desc->transition;
+  ma.redo_req = redo_req;
   ma.mult = mult[level - 1];
   ma.key_out = key_out;
   ma.score_out = score_out;
