@@ -1671,17 +1671,14 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
       }
     }
     // sweep 1 state: sum of exp(z - m) with the reference m held as nml = -m * log2(e)
-    float gmax[4][kReqTiles], m[4], nml[4], ssum[4], bound[4];
-    float sp[4], lse_r[4];                    // WHOLE: parent score (-inf: no such beam), log-sum-exp
-    uint32_t tau = 0;                         // WHOLE: ordered bits of the score threshold
+    // (as few values as possible live through the first sweep: it is the one short of registers)
+    // What the second sweep needs (bounds, parent scores, log-sum-exps, threshold) is handed over
+    // through LDS and read at its start, so that nothing but this lives through the first sweep.
+    float gmax[4][kReqTiles], nml[4], ssum[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      m[i] = -INFINITY;
       nml[i] = 0.f;
       ssum[i] = 0.f;
-      bound[i] = INFINITY;
-      sp[i] = 0.f;
-      lse_r[i] = 0.f;
 #pragma unroll
       for (int j = 0; j < kReqTiles; ++j) gmax[i][j] = -INFINITY;
     }
@@ -1695,8 +1692,7 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
           const bool dead = la.key_in && la.key_in[(int64_t)b * K_in + row] == kEmpty;
           if (!dead) v = la.score_in ? la.score_in[(int64_t)b * K_in + row] : 0.f;
         }
-        sp[i] = v;
-        if (c == 0) my_info[32 + 4 * g + i] = v;
+        if (c == 0) my_info[32 + 4 * g + i] = v;   // read back after the first sweep
       }
       if (threadIdx.x == 0) *req_cnt = 0;
     } else {
@@ -1710,6 +1706,39 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
       int ln = lane;
       asm volatile("" : "+v"(ln));
       const int g = ln >> 4, c = ln & 15;
+      // second sweep: per-beam logit bounds (and, WHOLE, what turns a logit into its final score)
+      float bound[4], sp[4], lse_r[4];
+      uint32_t tau = 0;                       // WHOLE: ordered bits of the score threshold
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        bound[i] = INFINITY;
+        sp[i] = 0.f;
+        lse_r[i] = 0.f;
+      }
+      if constexpr (sweep == 1) {
+        if constexpr (WHOLE) {
+          tau = tau_s[0];
+          for (int w2 = 1; w2 < NW; ++w2) tau = tau_s[w2] > tau ? tau_s[w2] : tau;
+          tau = (uint32_t)__builtin_amdgcn_readfirstlane((int)tau);
+          // a logit bound per beam that no candidate with score >= tau can fall below: the
+          // threshold moved back through the (rounded) score formula, minus a margin far above
+          // the rounding of two float32 additions
+          const float tf = unordered_bits(tau);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            sp[i] = my_info[32 + 4 * g + i];
+            lse_r[i] = my_info[16 + 4 * g + i];
+            const float margin = 1e-5f * (fabsf(tf) + fabsf(sp[i]) + fabsf(lse_r[i]) + 1.f);
+            float bz = (tf - sp[i]) + lse_r[i] - margin;
+            if (!(tf > -INFINITY)) bz = -INFINITY;
+            bound[i] = (sp[i] == -INFINITY) ? INFINITY : bz;
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            bound[i] = (wave * 16 + 4 * g + i < K_in) ? my_info[4 * g + i] : INFINITY;
+        }
+      }
       stage(b, 0);
       for (int ch = 0; ch < n_chunks; ++ch) {
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of chunk ch has landed
@@ -1756,10 +1785,7 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
               // a logit more than 64 above a lane's reference is redone by the general kernel.
               if (ct == 0 && ch == 0) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                  m[i] = z[i] + 20.f;
-                  nml[i] = -m[i] * kLog2e;
-                }
+                for (int i = 0; i < 4; ++i) nml[i] = -(z[i] + 20.f) * kLog2e;
               }
 #pragma unroll
               for (int i = 0; i < 4; ++i) {
@@ -1804,7 +1830,8 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
       if constexpr (sweep == 0) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {         // (reference, sum) over the beam's 16 lanes
-          float mm = m[i], ss = ssum[i];
+          const float m_ref = -nml[i] * kLn2;                // the reference the sum was taken about
+          float mm = m_ref, ss = ssum[i];
           auto merge_with = [&](float om, float os) {
             const float mn = fmaxf(mm, om);
             ss = ss * __builtin_amdgcn_exp2f((mm - mn) * kLog2e) +
@@ -1819,14 +1846,13 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
                      __uint_as_float(lane_xor<4>(__float_as_uint(ss), lane)));
           merge_with(__uint_as_float(lane_xor<8>(__float_as_uint(mm), lane)),
                      __uint_as_float(lane_xor<8>(__float_as_uint(ss), lane)));
-          lse_r[i] = mm + __builtin_amdgcn_logf(ss) * kLn2;
-          if (c == 0) my_info[16 + 4 * g + i] = lse_r[i];
+          if (c == 0) my_info[16 + 4 * g + i] = mm + __builtin_amdgcn_logf(ss) * kLn2;
           float top = gmax[i][0];
 #pragma unroll
           for (int j = 1; j < kReqTiles; ++j) top = fmaxf(top, gmax[i][j]);
           // this lane's sum may have overflowed: push the beam's (the request's) count past
           // the list size
-          if (top > m[i] + 64.f) {
+          if (top > m_ref + 64.f) {
             if constexpr (WHOLE) atomicAdd(req_cnt, kReqListCap + 1);
             else atomicAdd(&my_cnt[4 * g + i], kReqCap + 1);
           }
@@ -1881,23 +1907,7 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
               (int)pick_element<4>(uk[0], (K - 1) & 3), (K - 1) >> 2);
           if (lane == 0) tau_s[wave] = tw;
           __syncthreads();                    // all bounds are in; maxima have been read
-          tau = tau_s[0];
-          for (int w2 = 1; w2 < NW; ++w2) tau = tau_s[w2] > tau ? tau_s[w2] : tau;
-          tau = (uint32_t)__builtin_amdgcn_readfirstlane((int)tau);
-          // a logit bound per beam that no candidate with score >= tau can fall below: the
-          // threshold moved back through the (rounded) score formula, minus a margin far above
-          // the rounding of two float32 additions
-          const float tf = unordered_bits(tau);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const float margin = 1e-5f * (fabsf(tf) + fabsf(sp[i]) + fabsf(lse_r[i]) + 1.f);
-            bound[i] = (sp[i] == -INFINITY) ? INFINITY : (tf - sp[i]) + lse_r[i] - margin;
-            if (!(tf > -INFINITY)) bound[i] = (sp[i] == -INFINITY) ? INFINITY : -INFINITY;
-          }
         } else {
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            bound[i] = (wave * 16 + 4 * g + i < K_in) ? my_info[4 * g + i] : INFINITY;
           __syncthreads();                    // maxima read before the next chunk lands on them
         }
       }
