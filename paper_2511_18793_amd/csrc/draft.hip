@@ -1753,27 +1753,21 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
           // issued, into the same registers, and arrive under tile ct's vector work.  The
           // scheduling fences keep the compiler from hoisting a whole chunk's LDS reads at once,
           // which costs more registers than there are.
-          uint4 w[KST];
-          float a_next = ab[c];
-#pragma unroll
-          for (int ks = 0; ks < KST; ++ks)
-            w[ks] = *reinterpret_cast<const uint4*>(wb + (ks * 64 + ln) * 16);
 #pragma unroll
           for (int ct = 0; ct < kReqTiles; ++ct) {
-            const float a0 = a_next;
+            // (operands are read tile by tile, not a tile ahead: the other waves of the SIMD
+            // cover the LDS latency, and the registers a second operand set would take are the
+            // ones this loop is short of)
+            uint4 w[KST];
+#pragma unroll
+            for (int ks = 0; ks < KST; ++ks)
+              w[ks] = *reinterpret_cast<const uint4*>(wb + ((ct * KS + ks) * 64 + ln) * 16);
+            const float a0 = ab[ct * 16 + c];
             floatx4 acc = floatx4{a0, a0, a0, a0};
 #pragma unroll
             for (int ks = 0; ks < KST; ++ks)
               acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
                   fa16[ks], *reinterpret_cast<const bf16x8*>(&w[ks]), acc, 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            if (ct + 1 < kReqTiles) {
-              a_next = ab[(ct + 1) * 16 + c];
-#pragma unroll
-              for (int ks = 0; ks < KST; ++ks)
-                w[ks] = *reinterpret_cast<const uint4*>(
-                    wb + (((ct + 1) * KS + ks) * 64 + ln) * 16);
-            }
             __builtin_amdgcn_sched_barrier(0);
             const bool live = !ragged || ct < tiles;
             float z[4];
