@@ -327,3 +327,42 @@ def test_without_state_the_score_factorizes(oracle):
         assert len(set(map(tuple, got.tolist()))) == K
     with_state = oracle.decode(x["H"], x["W"], x["E"], cfg.radices, K)
     assert np.abs(with_state[-1]["score"] - last["score"]).max() > 1e-4
+
+
+def test_wide_beam_against_the_grid_of_all_tuples(oracle):
+    """A beam wider than 128 (the recall setting of the paper: beam 512 to 1000), checked against
+    beam search restated on the array of all V^3 chain scores: level 1 keeps the K most probable
+    codes, level 2 the K best (t1, t2) pairs among the kept t1, level 3 cuts every beam to its K
+    most probable codes, drops what is not in the catalog and keeps the K best."""
+    V, K = 144, 136
+    cfg, x = _small(21, B=2, d=10, e=6, V=V, w_std=0.5)
+    rng = np.random.default_rng(21)
+    bitmap = rng.random((V, V, V)) < 0.05
+    cat = np.argwhere(bitmap).astype(np.int32)
+    s = oracle.ItemSet(cat, cfg.radices)
+    outs = oracle.decode(x["H"], x["W"], x["E"], cfg.radices, K, itemset=s)
+    for b in range(2):
+        grid, lp1 = chain_scores_grid_L3(x["H"][b], x["W"], x["E"])
+        t1 = np.argsort(-lp1, kind="stable")[:K]
+        assert (outs[0]["code"][b] == t1).all()
+        # level 2: all K*V pairs, order (score, parent rank, code)
+        d = cfg.d
+        lp2 = log_softmax((x["H"][b, 1].astype(np.float64) @ x["W"][1][:d].astype(np.float64))[None, :]
+                          + x["E"][0][t1].astype(np.float64) @ x["W"][1][d:].astype(np.float64))
+        s2 = (lp1[t1][:, None] + lp2).ravel()
+        pick = np.argsort(-s2, kind="stable")[:K]
+        assert (outs[1]["parent"][b] == pick // V).all() and (outs[1]["code"][b] == pick % V).all()
+        assert np.abs(outs[1]["score"][b] - s2[pick]).max() < 2e-6
+        pairs = np.stack([t1[pick // V], pick % V], axis=1)
+        # level 3
+        cands = []
+        for r, (a1, a2) in enumerate(pairs.tolist()):
+            lp3 = grid[a1, a2] - s2[pick[r]]
+            top = np.argsort(-lp3, kind="stable")[:K]
+            cands += [(-grid[a1, a2, v], r, int(v)) for v in top if bitmap[a1, a2, v]]
+        cands.sort()
+        n = int(outs[2]["count"][b])
+        assert n == min(K, len(cands)) and n > 128
+        assert [(c[1], c[2]) for c in cands[:n]] == list(zip(outs[2]["parent"][b, :n].tolist(),
+                                                             outs[2]["code"][b, :n].tolist()))
+        assert np.abs(outs[2]["score"][b, :n] + np.array([c[0] for c in cands[:n]])).max() < 3e-6
