@@ -48,7 +48,9 @@ enum {
 
 /* Limits of this implementation. */
 #define NEZHA_MAX_LEVELS 8
-#define NEZHA_MAX_BEAM 128 /* K and K_in */
+#define NEZHA_MAX_BEAM 128       /* K and K_in of the in-register / in-LDS kernels */
+#define NEZHA_MAX_WIDE_BEAM 1024 /* K and K_in overall: wider beams than NEZHA_MAX_BEAM take a path
+                                    that keeps the level's logits in the workspace */
 
 const char* nezha_last_error(void); /* thread local, never NULL */
 
@@ -119,7 +121,7 @@ typedef struct {
   int32_t B;              /* requests in the batch, >= 0 */
   int32_t L;              /* levels of the semantic ID */
   int32_t level;          /* this call's level, 1..L */
-  int32_t K;              /* beams kept, 1 <= K <= min(T_level, NEZHA_MAX_BEAM) */
+  int32_t K;              /* beams kept, 1 <= K <= min(T_level, NEZHA_MAX_WIDE_BEAM) */
   int32_t K_in;           /* live beams entering: 1 at level 1, else K of the previous call */
   int32_t d;              /* width of h_l */
   int32_t e;              /* width of the state c and of the code embeddings */
@@ -154,7 +156,9 @@ typedef struct {
  *        256-byte aligned; scratch.
  * Alignment: E_l and the states 16 bytes; H_l (every row) and W_l 16 bytes with NEZHA_BF16,
  * 4 bytes with NEZHA_F32.
- * Shape limits: K, K_in <= NEZHA_MAX_BEAM; T_level a multiple of 16; with
+ * Shape limits: K, K_in <= NEZHA_MAX_WIDE_BEAM (the recall setting of Sec. 1: beam 512 to
+ * 1000; above NEZHA_MAX_BEAM the workspace also holds 4 * B * K_in * T_level bytes of logits
+ * and K_in * T_level must stay below 2^31); T_level a multiple of 16; with
  * NEZHA_BF16 d and e multiples of 32, with NEZHA_F32 d >= 1 and e a multiple
  * of 4; e <= 256.  Anything else gives NEZHA_EINVAL. */
 int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W_l,

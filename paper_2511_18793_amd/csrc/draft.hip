@@ -2277,11 +2277,15 @@ __global__ __launch_bounds__(64 * kLevelWaves, 1) void decode_small_kernel(Decod
 }
 
 // ---- host side ---------------------------------------------------------------------------------
+#include "wide_beam.h"
+
 struct Plan {
   size_t wp_off, a_off, code_off, logp_off, list_off, redo_off, redo_req_off, total;
   int cap;
   bool per_request;   // expand_request_kernel takes the expansion
+  bool wide;          // beams wider than NEZHA_MAX_BEAM: code_off is where the level's logits go
 };
+inline bool wide_beam(int K, int K_in) { return K > NEZHA_MAX_BEAM || K_in > NEZHA_MAX_BEAM; }
 
 // Which kernels take a level is a function of the shape alone, so that the workspace can be sized
 // without the buffers.
@@ -2309,10 +2313,11 @@ int check_desc(const nezha_step_desc* dsc, Plan* plan) {
   if (!radix_multipliers(dsc->L, dsc->radices, mult))
     return fail(NEZHA_ERANGE, "radices must be >= 1 with a product of at most 2^64-1");
   const int V = dsc->radices[dsc->level - 1];
-  if (dsc->K < 1 || dsc->K > NEZHA_MAX_BEAM || dsc->K > V)
-    return fail(NEZHA_EINVAL, "K = %d outside 1..min(T_level = %d, %d)", dsc->K, V, NEZHA_MAX_BEAM);
-  if (dsc->K_in < 1 || dsc->K_in > NEZHA_MAX_BEAM)
-    return fail(NEZHA_EINVAL, "K_in = %d outside 1..%d", dsc->K_in, NEZHA_MAX_BEAM);
+  if (dsc->K < 1 || dsc->K > NEZHA_MAX_WIDE_BEAM || dsc->K > V)
+    return fail(NEZHA_EINVAL, "K = %d outside 1..min(T_level = %d, %d)", dsc->K, V,
+                NEZHA_MAX_WIDE_BEAM);
+  if (dsc->K_in < 1 || dsc->K_in > NEZHA_MAX_WIDE_BEAM)
+    return fail(NEZHA_EINVAL, "K_in = %d outside 1..%d", dsc->K_in, NEZHA_MAX_WIDE_BEAM);
   if (dsc->dtype != NEZHA_F32 && dsc->dtype != NEZHA_BF16)
     return fail(NEZHA_EINVAL, "unknown dtype %d", (int)dsc->dtype);
   if (dsc->w_packed != 0 && (dsc->w_packed != 1 || dsc->dtype != NEZHA_BF16))
@@ -2328,6 +2333,10 @@ int check_desc(const nezha_step_desc* dsc, Plan* plan) {
                 (long long)dsc->h_row_stride);
   if ((int64_t)dsc->B * dsc->K_in > 0x7FFFFFFF / NEZHA_MAX_BEAM)
     return fail(NEZHA_EINVAL, "B * K_in too large");
+  const bool wide = wide_beam(dsc->K, dsc->K_in);
+  if (wide && (int64_t)dsc->K_in * V > 0x7FFFFFFF)
+    return fail(NEZHA_EINVAL, "K_in * T_level = %lld exceeds 2^31-1 (beams wider than %d)",
+                (long long)dsc->K_in * V, NEZHA_MAX_BEAM);
   if (plan) {
     const size_t rows = (size_t)dsc->B * dsc->K_in;
     size_t off = 0;
@@ -2337,6 +2346,15 @@ int check_desc(const nezha_step_desc* dsc, Plan* plan) {
     plan->a_off = off;
     off += align_up((size_t)dsc->B * V * 4, 256);
     plan->code_off = off;
+    plan->wide = wide;
+    if (wide) {
+      off += align_up(rows * (size_t)V * 4, 256);
+      plan->logp_off = plan->list_off = plan->redo_off = plan->redo_req_off = off;
+      plan->per_request = false;
+      plan->total = off;
+      plan->cap = 0;
+      return NEZHA_OK;
+    }
     off += align_up(rows * dsc->K * 4, 256);
     plan->logp_off = off;
     off += align_up(rows * dsc->K * 4, 256);
@@ -2662,6 +2680,96 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
   } else {
     rc = launch_user_part(desc, H_l, W_l, Wp, A, stream);
     if (rc != NEZHA_OK) return rc;
+  }
+
+  if (plan.wide) {
+    // beams wider than 128: the level's logits go through HBM (wide_beam.h)
+    WideArgs wa;
+    wa.state = state_in;
+    wa.Wbeam = bf16 ? static_cast<const void*>(Wp + packed_user_elems(d, V)) : W_l;
+    wa.A = A;
+    wa.zk = reinterpret_cast<uint32_t*>(ws + plan.code_off);
+    wa.key_in = key_in;
+    wa.score_in = score_in;
+    const bool verify = set && set->L == level;
+    wa.set = SetView{verify ? set->slots : nullptr, set ? set->n_buckets : 0};
+    wa.mult = mult[level - 1];
+    wa.rows = rows;
+    wa.K_in = K_in;
+    wa.K = K;
+    wa.V = V;
+    wa.d = d;
+    wa.e = e;
+    wa.col_splits = 1;
+    {
+      ProfileScope prof(kWideLogits, stream);
+      if (bf16) {
+        const int64_t row_groups = ((int64_t)rows + 31) / 32;
+        int64_t cs = (4096 + row_groups - 1) / row_groups;       // enough waves to fill the chip
+        cs = cs < 1 ? 1 : cs > V / 16 ? V / 16 : cs;
+        wa.col_splits = (int)cs;
+        const int64_t blocks = (row_groups * cs + 3) / 4;
+        if (e <= 64)
+          hipLaunchKernelGGL((wide_logits_bf16_kernel<2>), dim3((unsigned)blocks), dim3(256), 0,
+                             stream, wa);
+        else if (e <= 128)
+          hipLaunchKernelGGL((wide_logits_bf16_kernel<4>), dim3((unsigned)blocks), dim3(256), 0,
+                             stream, wa);
+        else
+          hipLaunchKernelGGL((wide_logits_bf16_kernel<8>), dim3((unsigned)blocks), dim3(256), 0,
+                             stream, wa);
+      } else {
+        const int64_t blocks = (((int64_t)rows + 15) / 16) * ((V + 255) / 256);
+        hipLaunchKernelGGL(wide_logits_f32_kernel, dim3((unsigned)blocks), dim3(256),
+                           (size_t)16 * e * 4, stream, wa);
+      }
+      NEZHA_HIP_CHECK(hipGetLastError());
+    }
+    {
+      ProfileScope prof(kWideRows, stream);
+      if (verify)
+        hipLaunchKernelGGL((wide_rows_kernel<true>), dim3((unsigned)rows), dim3(kWideRowThreads), 0,
+                           stream, wa);
+      else
+        hipLaunchKernelGGL((wide_rows_kernel<false>), dim3((unsigned)rows), dim3(kWideRowThreads),
+                           0, stream, wa);
+      NEZHA_HIP_CHECK(hipGetLastError());
+    }
+    WideSelectArgs sa;
+    sa.zk = wa.zk;
+    sa.key_in = key_in;
+    sa.score_in = score_in;
+    sa.state_in = state_in;
+    sa.E = E_l;
+    sa.U = desc->U_l;
+    sa.mult = mult[level - 1];
+    sa.key_out = key_out;
+    sa.score_out = score_out;
+    sa.parent_out = parent_out;
+    sa.code_out = code_out;
+    sa.state_out = state_out;
+    sa.count_out = count_out;
+    sa.K_in = K_in;
+    sa.K = K;
+    sa.V = V;
+    sa.e = e;
+    sa.transition = desc->transition;
+    {
+      const size_t lds = wide_select_lds();
+      ProfileScope prof(kWideSelect, stream);
+      if (bf16) {
+        rc = allow_lds(wide_select_kernel<true>, lds);
+        if (rc != NEZHA_OK) return rc;
+        hipLaunchKernelGGL((wide_select_kernel<true>), dim3(B), dim3(kWideThreads), lds, stream, sa);
+      } else {
+        rc = allow_lds(wide_select_kernel<false>, lds);
+        if (rc != NEZHA_OK) return rc;
+        hipLaunchKernelGGL((wide_select_kernel<false>), dim3(B), dim3(kWideThreads), lds, stream,
+                           sa);
+      }
+      NEZHA_HIP_CHECK(hipGetLastError());
+    }
+    return NEZHA_OK;
   }
 
   if (level_fits_one_launch(bf16, K, K_in, V, e)) {

@@ -34,7 +34,7 @@ const char* const kKernelNames[kKernelKinds] = {
     "pack_weights_kernel", "user_gemm_kernel", "expand_kernel", "merge_kernel",
     "verify_probe_kernel", "verify_scan_kernel", "verify_scatter_kernel", "insert_kernel",
     "random_gather_kernel", "level_small_kernel", "expand_request_kernel",
-    "decode_small_kernel"};
+    "decode_small_kernel", "wide_logits_kernel", "wide_rows_kernel", "wide_select_kernel"};
 }  // namespace
 
 ProfileScope::ProfileScope(KernelKind kind, hipStream_t s) : slot(-1), stream(s) {

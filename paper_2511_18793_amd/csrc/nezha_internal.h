@@ -28,7 +28,8 @@ bool radix_multipliers(int32_t L, const int32_t* radices, uint64_t* mult);
 // ---- optional per-kernel timing with HIP events (off by default) ------------------------
 enum KernelKind {
   kPackWeights = 0, kUserGemm, kExpand, kMerge, kVerifyProbe, kVerifyScan, kVerifyScatter,
-  kInsert, kGather, kLevelFused, kExpandRequest, kDecodeFused, kKernelKinds
+  kInsert, kGather, kLevelFused, kExpandRequest, kDecodeFused, kWideLogits, kWideRows, kWideSelect,
+  kKernelKinds
 };
 // Brackets the launches made while it is alive with two events on `stream` when timing is on.
 struct ProfileScope {

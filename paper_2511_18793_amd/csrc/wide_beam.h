@@ -1,0 +1,532 @@
+// Beams wider than NEZHA_MAX_BEAM (the recall setting of Sec. 1 and Table 1: beam 512, up to
+// 1000 in item retrieval): one level of Alg. 3 with up to 1024 beams in and out.
+//
+// K * K reaches 10^6 candidates per request here, so nothing of a request fits in registers or
+// LDS any more.  The level's logits go through HBM once instead:
+//   wide_logits_*_kernel  z = A_l + c * W_l[d:d+e] for all B*K_in beams        -> zk (float32)
+//   wide_rows_kernel      per beam: log-sum-exp, cumulative score of every code as a 32-bit sort
+//                         key (in place).  Where a set is consulted: the beam's K best codes
+//                         (exact radix selection, ties to the lower code) are probed (Eq. 4-5);
+//                         every other code gets key 0 = not a candidate
+//   wide_select_kernel    per request: the K best keys of its K_in * T_l, ordered by (score,
+//                         parent, code); outputs and the Transition of Eq. 3
+// Included by draft.hip only (inside its unnamed namespace).
+#pragma once
+
+constexpr int kWideThreads = 1024;          // wide_select_kernel
+constexpr int kWideListCap = 8192;          // keys at or above the first bound that LDS can take
+constexpr int kWideRowThreads = 256;        // wide_rows_kernel
+
+struct WideArgs {
+  const void* state;        // [B*K_in, e] or NULL
+  const void* Wbeam;        // bf16: packed beam part of W_l; float32: W_l itself, row major
+  const float* A;           // [B, T_l] user part
+  uint32_t* zk;             // [B*K_in, T_l]: logits as float bits, then sort keys, in place
+  const uint64_t* key_in;   // [B*K_in] or NULL
+  const float* score_in;    // [B*K_in] or NULL
+  SetView set;              // slots == NULL: no set is consulted at this level
+  uint64_t mult;
+  int64_t rows;
+  int K_in, K, V, d, e;
+  int col_splits;           // wide_logits_bf16_kernel: waves sharing one group of 32 beams
+};
+
+// ---- logits --------------------------------------------------------------------------------
+// bf16: one wave = 32 beams (two 16-row MFMA tiles) x a contiguous share of the code tiles; the
+// packed operands of W_l are read straight from L2 (every wave walks them in the same order),
+// one tile ahead of the MFMAs.
+template <int KST>
+__global__ __launch_bounds__(256) void wide_logits_bf16_kernel(WideArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int g = lane >> 4, c = lane & 15;
+  const int64_t unit = (int64_t)blockIdx.x * 4 + wave;
+  const int64_t rg = unit / a.col_splits;
+  const int cs = (int)(unit - rg * a.col_splits);
+  const int64_t row0 = rg * 32;
+  if (row0 >= a.rows) return;
+  const int V = a.V, e = a.e, KS = e >> 5;
+  const int n_tiles = V >> 4;
+  const int t_begin = (int)((int64_t)n_tiles * cs / a.col_splits);
+  const int t_end = (int)((int64_t)n_tiles * (cs + 1) / a.col_splits);
+  const uint16_t* S = static_cast<const uint16_t*>(a.state);
+  const uint16_t* Wb = static_cast<const uint16_t*>(a.Wbeam);
+
+  uint4 fa[2][KST];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const int64_t r = row0 + 16 * t + c;
+#pragma unroll
+    for (int ks = 0; ks < KST; ++ks) {
+      fa[t][ks] = uint4{0, 0, 0, 0};
+      if (S && r < a.rows && ks < KS) fa[t][ks] = load_global_u4(S + r * e + ks * 32 + 8 * g);
+    }
+  }
+  int64_t arow[2][4], zrow[2][4];
+  bool live[2][4];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int64_t r = row0 + 16 * t + 4 * g + i;
+      live[t][i] = r < a.rows;
+      arow[t][i] = live[t][i] ? (r / a.K_in) * V : 0;
+      zrow[t][i] = live[t][i] ? r * V : 0;
+    }
+  uint4 w[KST], wn[KST];
+  auto fetch = [&](uint4 (&dst)[KST], int ct) {
+#pragma unroll
+    for (int ks = 0; ks < KST; ++ks) {
+      dst[ks] = uint4{0, 0, 0, 0};
+      if (ks < KS) dst[ks] = load_global_u4(Wb + ((int64_t)(ct * KS + ks) * 64 + lane) * 8);
+    }
+  };
+  if (t_begin < t_end) fetch(w, t_begin);
+  for (int ct = t_begin; ct < t_end; ++ct) {
+    if (ct + 1 < t_end) fetch(wn, ct + 1);
+    const int col = ct * 16 + c;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      floatx4 acc;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] = as_global(a.A)[arow[t][i] + col];
+#pragma unroll
+      for (int ks = 0; ks < KST; ++ks)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8*>(&fa[t][ks]),
+                                                      *reinterpret_cast<const bf16x8*>(&w[ks]), acc,
+                                                      0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (live[t][i]) as_global(a.zk)[zrow[t][i] + col] = __float_as_uint(acc[i]);
+    }
+#pragma unroll
+    for (int ks = 0; ks < KST; ++ks) w[ks] = wn[ks];
+  }
+}
+
+// float32: a workgroup forms 16 beams x 256 codes; the beams' states sit in LDS, a thread owns
+// one code column and walks the e rows of the beam part of W_l (coalesced across the threads).
+__global__ __launch_bounds__(256) void wide_logits_f32_kernel(WideArgs a) {
+  extern __shared__ float wide_states[];   // [16][e]
+  const int V = a.V, e = a.e;
+  const int col_tiles = (V + 255) / 256;
+  const int64_t rt = blockIdx.x / col_tiles;
+  const int vt = (int)(blockIdx.x - rt * col_tiles);
+  const int64_t row0 = rt * 16;
+  const float* S = static_cast<const float*>(a.state);
+  const float* W = static_cast<const float*>(a.Wbeam);
+  for (int idx = threadIdx.x; idx < 16 * e; idx += 256) {
+    const int r = idx / e, i = idx - r * e;
+    wide_states[idx] = (S && row0 + r < a.rows) ? S[(row0 + r) * e + i] : 0.f;
+  }
+  __syncthreads();
+  const int v = vt * 256 + (int)threadIdx.x;
+  if (v >= V) return;
+  float acc[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r)
+    acc[r] = row0 + r < a.rows ? a.A[((row0 + r) / a.K_in) * V + v] : 0.f;
+  if (S) {
+    for (int i = 0; i < e; ++i) {
+      const float wv = W[(int64_t)(a.d + i) * V + v];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] = fmaf(wide_states[r * e + i], wv, acc[r]);
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r)
+    if (row0 + r < a.rows) a.zk[(row0 + r) * V + v] = __float_as_uint(acc[r]);
+}
+
+// ---- workgroup-wide helpers ------------------------------------------------------------------
+template <int NT>
+__device__ __forceinline__ float block_max(float v, float* red) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m));
+  __syncthreads();                                   // red may still be read from a call before
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = red[0];
+#pragma unroll
+  for (int w = 1; w < NT / 64; ++w) r = fmaxf(r, red[w]);
+  return r;
+}
+template <int NT>
+__device__ __forceinline__ float block_sum(float v, float* red) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = red[0];
+#pragma unroll
+  for (int w = 1; w < NT / 64; ++w) r += red[w];
+  return r;
+}
+
+// Where the K-th largest nonzero key of keys[0..n) lies: keys above tau are among the K largest,
+// and so are `need` of the n_eq keys equal to tau (need >= 1).  all == true: there are at most K
+// nonzero keys, all of them count (tau, need, n_eq unset).
+struct RadixPick {
+  uint32_t tau;
+  int need, n_eq;
+  bool all;
+};
+// Exact radix selection by a workgroup of NT threads: three passes over the keys (12, 12 and 8
+// bits from the top), each a histogram in LDS of the keys that match the digits found so far.
+// hist: 4096 words of LDS, bc: 4 words of LDS.  Every thread gets the result.
+template <int NT>
+__device__ RadixPick block_radix_select(const uint32_t* keys, int64_t n, int K, uint32_t* hist,
+                                        uint32_t* bc) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  RadixPick r;
+  r.tau = 0;
+  r.need = K;
+  r.n_eq = 0;
+  r.all = false;
+  uint32_t prefix = 0;
+  int need = K;
+#pragma unroll 1
+  for (int pass = 0; pass < 3; ++pass) {
+    const int shift = pass == 0 ? 20 : pass == 1 ? 8 : 0;
+    const int bits = pass == 2 ? 8 : 12;
+    const int nb = 1 << bits;
+    for (int i = tid; i < nb; i += NT) hist[i] = 0;
+    __syncthreads();
+    for (int64_t i = tid; i < n; i += NT) {
+      const uint32_t k = as_global(keys)[i];
+      if (k != 0 && (pass == 0 || (k >> (shift + bits)) == prefix))
+        atomicAdd(&hist[(k >> shift) & (uint32_t)(nb - 1)], 1u);
+    }
+    __syncthreads();
+    if (tid < 64) {
+      // lane l owns the bins nb-1 - (l*per .. l*per+per-1), i.e. walks down from the top
+      const int per = nb / 64;
+      uint32_t mine = 0;
+      for (int i = 0; i < per; ++i) {
+        const int j = (i + lane) % per;                 // skewed: the lanes hit different banks
+        mine += hist[nb - 1 - (lane * per + j)];
+      }
+      uint32_t incl = mine;
+#pragma unroll
+      for (int m = 1; m < 64; m <<= 1) {
+        const uint32_t up = __shfl_up(incl, m);
+        if (lane >= m) incl += up;
+      }
+      const uint32_t total = __shfl(incl, 63);
+      const uint64_t reach = __ballot(incl >= (uint32_t)need);
+      if (total < (uint32_t)need) {
+        if (lane == 0) bc[0] = 0xFFFFFFFFu;             // fewer than `need` keys (first pass only)
+      } else {
+        const int first = __ffsll((unsigned long long)reach) - 1;
+        if (lane == first) {
+          uint32_t above = incl - mine;                 // keys in bins above this lane's
+          int digit = nb - 1 - lane * per;
+          for (int i = 0; i < per; ++i, --digit) {
+            const uint32_t h = hist[digit];
+            if (above + h >= (uint32_t)need) {
+              bc[0] = (uint32_t)digit;
+              bc[1] = above;
+              bc[2] = h;
+              break;
+            }
+            above += h;
+          }
+        }
+      }
+    }
+    __syncthreads();
+    const uint32_t digit = bc[0];
+    if (digit == 0xFFFFFFFFu) {
+      r.all = true;
+      return r;
+    }
+    need -= (int)bc[1];
+    r.n_eq = (int)bc[2];
+    prefix = (prefix << bits) | digit;
+    __syncthreads();                                    // bc and hist are reused by the next pass
+  }
+  r.tau = prefix;
+  r.need = need;
+  return r;
+}
+
+// Which of the keys equal to tau are taken: the first `need` in index order.  Calls visit(i,
+// taken) for every i in [0, n) with keys[i] == tau, in chunks of NT consecutive indices.
+// cnt: NT/64 words of LDS.
+template <int NT, class Visit>
+__device__ __forceinline__ void block_take_ties(const uint32_t* keys, int64_t n, uint32_t tau,
+                                                int need, int* cnt, Visit visit) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int running = 0;
+  for (int64_t base = 0; base < n; base += NT) {        // uniform trip count
+    const int64_t i = base + tid;
+    const bool tie = i < n && as_global(keys)[i] == tau;
+    const uint64_t bal = __ballot(tie);
+    const int rank = __popcll(bal & ((1ull << lane) - 1ull));
+    __syncthreads();
+    if (lane == 0) cnt[wave] = __popcll(bal);
+    __syncthreads();
+    int before = running, total = 0;
+#pragma unroll
+    for (int w = 0; w < NT / 64; ++w) {
+      const int cw = cnt[w];
+      if (w < wave) before += cw;
+      total += cw;
+    }
+    if (tie) visit(i, before + rank < need);
+    running += total;
+  }
+}
+
+// Bitonic sort, descending, of P (a power of two) 64-bit keys in LDS by NT threads.
+template <int NT>
+__device__ __forceinline__ void block_sort_desc(uint64_t* v, int P) {
+  const int tid = threadIdx.x;
+  for (int k = 2; k <= P; k <<= 1)
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int t = tid; t < (P >> 1); t += NT) {
+        const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+        const int l = i | j;
+        const bool desc = (i & k) == 0;
+        const uint64_t x = v[i], y = v[l];
+        if ((x < y) == desc) {
+          v[i] = y;
+          v[l] = x;
+        }
+      }
+      __syncthreads();
+    }
+}
+template <int NT>
+__device__ __forceinline__ void block_sort_desc(uint32_t* v, int P) {
+  const int tid = threadIdx.x;
+  for (int k = 2; k <= P; k <<= 1)
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int t = tid; t < (P >> 1); t += NT) {
+        const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+        const int l = i | j;
+        const bool desc = (i & k) == 0;
+        const uint32_t x = v[i], y = v[l];
+        if ((x < y) == desc) {
+          v[i] = y;
+          v[l] = x;
+        }
+      }
+      __syncthreads();
+    }
+}
+
+// ---- per beam: scores as sort keys, per-beam cut and probes -------------------------------------
+// One workgroup per beam.  VERIFY: a set is consulted at this level, so the beam is cut to its K
+// most probable codes first (that cut decides which candidates are verified; without a set the
+// request-level selection alone gives the same result) and the survivors are probed.
+template <bool VERIFY>
+__global__ __launch_bounds__(kWideRowThreads) void wide_rows_kernel(WideArgs a) {
+  constexpr int NT = kWideRowThreads;
+  __shared__ float red[NT / 64];
+  __shared__ uint32_t hist[VERIFY ? 4096 : 1];
+  __shared__ uint32_t bc[4];
+  __shared__ int cnt[NT / 64];
+  const int64_t row = blockIdx.x;
+  const int V = a.V, tid = threadIdx.x;
+  uint32_t* zk = a.zk + row * V;
+  const uint64_t pkey = a.key_in ? a.key_in[row] : 0ull;
+  const float sp = a.score_in ? a.score_in[row] : 0.f;
+  if (pkey == kEmpty) {                                  // an empty beam slot has no children
+    for (int v = tid; v < V; v += NT) as_global(zk)[v] = 0u;
+    return;
+  }
+  float m = -INFINITY;
+  for (int v = tid; v < V; v += NT) m = fmaxf(m, __uint_as_float(as_global(zk)[v]));
+  m = block_max<NT>(m, red);
+  float s = 0.f;
+  for (int v = tid; v < V; v += NT) s += expf(__uint_as_float(as_global(zk)[v]) - m);
+  s = block_sum<NT>(s, red);
+  const float lse = m + logf(s);
+  for (int v = tid; v < V; v += NT) {
+    const float z = __uint_as_float(as_global(zk)[v]);
+    as_global(zk)[v] = ordered_bits(sp + (z - lse));
+  }
+  if constexpr (VERIFY) {
+    __syncthreads();                                     // the keys are read back by other threads
+    uint32_t tau = 0;
+    if (a.K < V) {
+      const RadixPick p = block_radix_select<NT>(zk, V, a.K, hist, bc);
+      if (!p.all) {
+        tau = p.tau;
+        if (p.need < p.n_eq) {
+          // more codes tie with the K-th than fit: the lower codes stay
+          block_take_ties<NT>(zk, V, tau, p.need, cnt, [&](int64_t i, bool taken) {
+            if (!taken) as_global(zk)[i] = 0u;
+          });
+          __syncthreads();
+        }
+      }
+    }
+    for (int v = tid; v < V; v += NT) {
+      const uint32_t k = as_global(zk)[v];
+      if (k == 0u) continue;
+      const bool in = k >= tau && set_contains(a.set, pkey + (uint64_t)(uint32_t)v * a.mult);
+      if (!in) as_global(zk)[v] = 0u;
+    }
+  }
+}
+
+// ---- per request: the K best keys --------------------------------------------------------------
+struct WideSelectArgs {
+  const uint32_t* zk;       // [B, K_in * T_l] sort keys, 0 = not a candidate
+  const uint64_t* key_in;
+  const float* score_in;
+  const void* state_in;
+  const void* E;
+  const void* U;
+  uint64_t mult;
+  uint64_t* key_out;
+  float* score_out;
+  int32_t* parent_out;
+  int32_t* code_out;
+  void* state_out;
+  int32_t* count_out;
+  int K_in, K, V, e, transition;
+};
+inline size_t wide_select_lds() {
+  return (size_t)kWideListCap * 8 + (size_t)2 * kWideThreads * 4 + (size_t)2 * 1024 * 4 + 64;
+}
+
+// One workgroup of 1024 threads per request.  First pass over the request's K_in * T_l keys:
+// every thread keeps the two largest keys of the indices it visits; the K-th largest of those
+// 2048 keys is a lower bound of the K-th largest key (they are K distinct candidates).  Second
+// pass: keys at or above the bound go to an LDS list as (key, ~index); the list is sorted, which
+// orders equal scores by parent and code, and its first K entries are the level's beams.  When
+// the list would overflow (scores crowded into the indices of few threads, massive ties) the
+// selection is done exactly by radix passes instead.
+template <bool BF16>
+__global__ __launch_bounds__(kWideThreads) void wide_select_kernel(WideSelectArgs a) {
+  constexpr int NT = kWideThreads;
+  extern __shared__ __align__(16) uint64_t wide_lds[];
+  uint64_t* list = wide_lds;                                            // [kWideListCap]
+  uint32_t* top = reinterpret_cast<uint32_t*>(list + kWideListCap);     // [2 * NT]
+  int32_t* fin_parent = reinterpret_cast<int32_t*>(top + 2 * NT);       // [1024]
+  int32_t* fin_code = fin_parent + 1024;                                // [1024]
+  uint32_t* bc = reinterpret_cast<uint32_t*>(fin_code + 1024);          // [4]
+  int* n_list = reinterpret_cast<int*>(bc + 4);                         // [1]
+  int* tie_cnt = reinterpret_cast<int*>(top);                           // [NT / 64], after top's use
+  uint32_t* hist = reinterpret_cast<uint32_t*>(list + 2048);            // 4096 words inside list
+
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+  const int K = a.K, V = a.V;
+  const int64_t n = (int64_t)a.K_in * V;                 // a multiple of 16
+  const uint32_t* keys = a.zk + (int64_t)b * n;
+
+  uint32_t t0 = 0, t1 = 0;
+  for (int64_t q = tid; q < (n >> 2); q += NT) {
+    const uint4 k4 = load_global_u4(keys + 4 * q);
+    const uint32_t kk[4] = {k4.x, k4.y, k4.z, k4.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t lo = kk[j] > t0 ? t0 : kk[j];
+      t0 = kk[j] > t0 ? kk[j] : t0;
+      t1 = lo > t1 ? lo : t1;
+    }
+  }
+  top[2 * tid] = t0;
+  top[2 * tid + 1] = t1;
+  if (tid == 0) *n_list = 0;
+  __syncthreads();
+  block_sort_desc<NT>(top, 2 * NT);
+  uint32_t tau0 = top[K - 1];
+  if (tau0 == 0u) tau0 = 1u;                             // fewer than K candidates seen: take all
+  __syncthreads();
+
+  for (int64_t q0 = 0; q0 < (n >> 2); q0 += NT) {        // uniform trip count
+    const int64_t q = q0 + tid;
+    uint4 k4 = uint4{0, 0, 0, 0};
+    if (q < (n >> 2)) k4 = load_global_u4(keys + 4 * q);
+    const uint32_t kk[4] = {k4.x, k4.y, k4.z, k4.w};
+    const bool any = (kk[0] >= tau0) | (kk[1] >= tau0) | (kk[2] >= tau0) | (kk[3] >= tau0);
+    if (__ballot(any) == 0ull) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const bool in = kk[j] >= tau0;
+      const uint64_t bal = __ballot(in);
+      if (bal == 0ull) continue;
+      int base = 0;
+      if (lane == 0) base = atomicAdd(n_list, __popcll(bal));
+      base = __shfl(base, 0);
+      const int pos = base + __popcll(bal & ((1ull << lane) - 1ull));
+      if (in && pos < kWideListCap)
+        list[pos] = ((uint64_t)kk[j] << 32) | (uint32_t)~(uint32_t)(4 * q + j);
+    }
+  }
+  __syncthreads();
+  int n_in = *n_list;
+  __syncthreads();
+  if (n_in > kWideListCap) {
+    // exact selection; the list is rebuilt from the keys above the K-th and its first ties
+    const RadixPick p = block_radix_select<NT>(keys, n, K, hist, bc);
+    if (tid == 0) *n_list = 0;
+    __syncthreads();
+    const uint32_t tau = p.all ? 1u : p.tau;
+    for (int64_t i0 = 0; i0 < n; i0 += NT) {
+      const int64_t i = i0 + tid;
+      const uint32_t k = i < n ? as_global(keys)[i] : 0u;
+      const bool in = p.all ? (k != 0u) : (k > tau);
+      const uint64_t bal = __ballot(in);
+      if (bal == 0ull) continue;
+      int base = 0;
+      if (lane == 0) base = atomicAdd(n_list, __popcll(bal));
+      base = __shfl(base, 0);
+      const int pos = base + __popcll(bal & ((1ull << lane) - 1ull));
+      if (in) list[pos] = ((uint64_t)k << 32) | (uint32_t)~(uint32_t)i;   // at most K entries
+    }
+    if (!p.all) {
+      block_take_ties<NT>(keys, n, tau, p.need, tie_cnt, [&](int64_t i, bool taken) {
+        if (taken) list[atomicAdd(n_list, 1)] = ((uint64_t)tau << 32) | (uint32_t)~(uint32_t)i;
+      });
+    }
+    __syncthreads();
+    n_in = *n_list;
+    __syncthreads();
+  }
+  int P = 2;
+  while (P < n_in) P <<= 1;
+  for (int i = n_in + tid; i < P; i += NT) list[i] = 0ull;
+  __syncthreads();
+  block_sort_desc<NT>(list, P);
+
+  const int cnt = n_in < K ? n_in : K;
+  for (int j = tid; j < K; j += NT) {
+    const int64_t o = (int64_t)b * K + j;
+    if (j < cnt) {
+      const uint64_t sk = list[j];
+      const uint32_t idx = ~(uint32_t)sk;
+      const int par = (int)(idx / (uint32_t)V);
+      const int code = (int)(idx - (uint32_t)par * (uint32_t)V);
+      a.key_out[o] = (a.key_in ? a.key_in[(int64_t)b * a.K_in + par] : 0ull) +
+                     (uint64_t)(uint32_t)code * a.mult;
+      a.score_out[o] = unordered_bits((uint32_t)(sk >> 32));
+      a.parent_out[o] = par;
+      a.code_out[o] = code;
+      fin_parent[j] = par;
+      fin_code[j] = code;
+    } else {
+      a.key_out[o] = kEmpty;
+      a.score_out[o] = -INFINITY;
+      a.parent_out[o] = -1;
+      a.code_out[o] = -1;
+      fin_parent[j] = -1;
+      fin_code[j] = -1;
+    }
+  }
+  if (tid == 0 && a.count_out) a.count_out[b] = cnt;
+  __syncthreads();
+  if (a.state_out) {
+    if (a.transition == NEZHA_TRANSITION_RNN)
+      update_states_rnn<BF16>(a.state_in, a.E, a.U, a.state_out, b, K, a.K_in, a.e, fin_parent,
+                              fin_code, tid, NT);
+    else
+      update_states<BF16>(a.state_in, a.E, a.state_out, b, K, a.K_in, a.e, fin_parent, fin_code,
+                          tid, NT);
+  }
+}

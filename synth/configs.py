@@ -1,4 +1,4 @@
-"""The workload shapes: the five configurations of this build plus the
+"""The workload shapes: the five configurations of this build, the wide-beam recall shape, plus the
 public-dataset shape of the paper (Implementation Details and Table 2)."""
 from dataclasses import dataclass, replace
 
@@ -40,6 +40,10 @@ CONFIGS = {
                          queries=4_000_000),
     "large": StepConfig("large", B=4096, d=2048, e=128, L=3, V=4096, K=100,
                         N=50_000_000, dtype="bf16", catalog="zipf1", zipf_s=1.1),
+    # recall setting (Sec. 1, Table 1: beam 512; up to 1000 in item retrieval): the beam is wider
+    # than anything that stays on chip, K*K = 262144 candidates per request are verified
+    "recall": StepConfig("recall", B=64, d=1024, e=128, L=3, V=4096, K=512,
+                         N=20_000_000, dtype="bf16", catalog="zipf1", zipf_s=1.1),
     # paper's public setting: L=3, T_l=512, beam 10, logit head 1024 wide; the
     # catalog sizes are the item counts of its three datasets (Table 2).
     "paper_yelp": StepConfig("paper_yelp", B=64, d=1024, e=128, L=3, V=512, K=10,

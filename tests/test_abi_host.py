@@ -90,7 +90,9 @@ def _call_step(**over):
 
 
 @pytest.mark.parametrize("over,code", [
-    (dict(level=0), -1), (dict(level=4), -1), (dict(K=0), -1), (dict(K=129), -1),
+    (dict(level=0), -1), (dict(level=4), -1), (dict(K=0), -1), (dict(K=1025, radices=[2048] * 3), -1),
+    (dict(K_in=1025, radices=[2048] * 3), -1),
+    (dict(K=129, K_in=129, radices=[1 << 24, 1 << 24, 4]), -1),   # wide beam: K_in * T_level >= 2^31
     (dict(K=4, radices=[256, 2, 256]), -1),            # K > T_level
     (dict(K_in=0), -1), (dict(e=6), -1), (dict(e=512), -1), (dict(stride=32), -1),
     (dict(radices=[1 << 30] * 3), -4), (dict(null=("H",)), -1), (dict(null=("key_out",)), -1),
