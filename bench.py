@@ -96,12 +96,22 @@ def kernel_models(cfg):
         per_request = (cfg.dtype == "bf16" and K_in >= 16 and e in (32, 64, 128, 256)
                        and not fused and not (V <= 1024 and K <= 64))
         slots = float(EXPAND_SLOTS_PER_LOGIT) * rows * V
+        # beams wider than 128: the level's logits go through HBM (three kernels per level)
+        wide = K > 128 or K_in > 128
+        if wide:
+            fused = per_request = False
+            slots = 0.0
+        wide_probes = rows * min(K, V) if level == L else 0
         per_level.append({
+            "wide_logits_kernel": ("hbm", (4.0 * rows * V + rows * e * esz + 4.0 * B * V) if wide else 0.0),
+            "wide_rows_kernel": ("hbm", (8.0 * rows * V + wide_probes * BUCKET_BYTES) if wide else 0.0),
+            "wide_select_kernel": ("hbm", (4.0 * rows * V + B * K * (24.0 + (2 * e * esz if level < L else 0)))
+                                   if wide else 0.0),
             "pack_weights_kernel": ("hbm", 2.0 * (d + e) * V * esz),
             "user_gemm_kernel": ("mfma", 2.0 * B * d * V),
             "expand_kernel": ("alu", 0.0 if per_request else slots),
             "expand_request_kernel": ("alu", slots if per_request else 0.0),
-            "merge_kernel": ("hbm", rows * K * 8.0 + probes * BUCKET_BYTES
+            "merge_kernel": ("hbm", 0.0 if wide else rows * K * 8.0 + probes * BUCKET_BYTES
                              + B * K * (24.0 + (2 * e * esz if level < L else 0))),
             # expansion, merge, verification and Transition of one level in one launch
             "level_small_kernel": ("alu", 0.0 if one_launch else slots),

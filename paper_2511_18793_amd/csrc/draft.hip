@@ -2727,12 +2727,17 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
     }
     {
       ProfileScope prof(kWideRows, stream);
-      if (verify)
-        hipLaunchKernelGGL((wide_rows_kernel<true>), dim3((unsigned)rows), dim3(kWideRowThreads), 0,
-                           stream, wa);
-      else
-        hipLaunchKernelGGL((wide_rows_kernel<false>), dim3((unsigned)rows), dim3(kWideRowThreads),
-                           0, stream, wa);
+#define LAUNCH_ROWS(VERIFYV, NVV)                                                                  \
+  hipLaunchKernelGGL((wide_rows_kernel<VERIFYV, NVV>), dim3((unsigned)rows), dim3(kWideRowThreads), \
+                     0, stream, wa)
+      if (V <= 16 * kWideRowThreads) {
+        if (verify) LAUNCH_ROWS(true, 16);
+        else LAUNCH_ROWS(false, 16);
+      } else {
+        if (verify) LAUNCH_ROWS(true, 0);
+        else LAUNCH_ROWS(false, 0);
+      }
+#undef LAUNCH_ROWS
       NEZHA_HIP_CHECK(hipGetLastError());
     }
     WideSelectArgs sa;

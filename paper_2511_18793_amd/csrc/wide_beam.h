@@ -318,18 +318,156 @@ __device__ __forceinline__ void block_sort_desc(uint32_t* v, int P) {
 }
 
 // ---- per beam: scores as sort keys, per-beam cut and probes -------------------------------------
+template <int NT>
+__device__ __forceinline__ uint32_t block_max_u32(uint32_t v, uint32_t* red) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) {
+    const uint32_t o = (uint32_t)__shfl_xor((int)v, m);
+    v = o > v ? o : v;
+  }
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  uint32_t r = red[0];
+#pragma unroll
+  for (int w = 1; w < NT / 64; ++w) r = red[w] > r ? red[w] : r;
+  return r;
+}
+
+// The same selection as block_radix_select for keys held in registers (NV per thread, 0 = unused
+// slot, at least K + 1 of them nonzero): digits of 8 bits, starting at the highest bit in which
+// the smallest and the largest key differ, so that the first histogram already spreads the keys.
+// hist: 256 words of LDS, bc: 4 words, red: NT/64 words.
+template <int NT, int NV>
+__device__ RadixPick regs_radix_select(const uint32_t (&key)[NV], int K, uint32_t* hist,
+                                       uint32_t* bc, uint32_t* red) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  RadixPick r;
+  r.all = false;
+  uint32_t mx = 0, mn_inv = 0;
+  int n_mine = 0;
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    mx = key[j] > mx ? key[j] : mx;
+    const uint32_t inv = key[j] ? ~key[j] : 0u;
+    mn_inv = inv > mn_inv ? inv : mn_inv;
+    n_mine += key[j] != 0u;
+  }
+  const uint32_t kmax = block_max_u32<NT>(mx, red);
+  const uint32_t kmin = ~block_max_u32<NT>(mn_inv, red);
+  if (kmin == kmax) {                                   // every key the same
+    r.tau = kmax;
+    r.need = K;
+    r.n_eq = (int)block_sum<NT>((float)n_mine, reinterpret_cast<float*>(red));
+    return r;
+  }
+  int remaining = 32 - __clz((int)(kmin ^ kmax));        // low bits that are not common to all keys
+  uint64_t pre = (uint64_t)kmax >> remaining;
+  int need = K, n_eq = 0;
+  while (remaining > 0) {                                // uniform: at most four rounds
+    const int bits = remaining < 8 ? remaining : 8;
+    const int shift = remaining - bits;
+    const int nb = 1 << bits;
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < NV; ++j)
+      if (key[j] != 0u && ((uint64_t)key[j] >> remaining) == pre)
+        atomicAdd(&hist[(key[j] >> shift) & (uint32_t)(nb - 1)], 1u);
+    __syncthreads();
+    if (tid < 64) {
+      // lane l owns the bins nb-1-4l .. nb-1-4l-3 (none when nb is smaller): top first
+      uint32_t h[4], mine = 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int bin = nb - 1 - (4 * lane + i);
+        h[i] = bin >= 0 ? hist[bin] : 0u;
+        mine += h[i];
+      }
+      uint32_t incl = mine;
+#pragma unroll
+      for (int m = 1; m < 64; m <<= 1) {
+        const uint32_t up = (uint32_t)__shfl_up((int)incl, m);
+        if (lane >= m) incl += up;
+      }
+      const uint64_t reach = __ballot(incl >= (uint32_t)need);
+      const int first = __ffsll((unsigned long long)reach) - 1;     // exists: the keys matching
+      if (lane == first) {                                          // `pre` number at least `need`
+        uint32_t above = incl - mine;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          if (above + h[i] >= (uint32_t)need) {
+            bc[0] = (uint32_t)(nb - 1 - (4 * lane + i));
+            bc[1] = above;
+            bc[2] = h[i];
+            break;
+          }
+          above += h[i];
+        }
+      }
+    }
+    __syncthreads();
+    need -= (int)bc[1];
+    n_eq = (int)bc[2];
+    pre = (pre << bits) | bc[0];
+    remaining = shift;
+    __syncthreads();
+  }
+  r.tau = (uint32_t)pre;
+  r.need = need;
+  r.n_eq = n_eq;
+  return r;
+}
+
+// Set membership of two keys with both home buckets in flight at once.
+__device__ __forceinline__ void set_contains_pair(const SetView& s, uint64_t k0, bool live0,
+                                                  uint64_t k1, bool live1, bool& in0, bool& in1) {
+  const uint64_t b0 = live0 ? home_bucket(k0, s.n_buckets) : 0, b1 = live1 ? home_bucket(k1, s.n_buckets) : 0;
+  ulonglong2 q[4], t[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    q[i] = ulonglong2{kEmpty, kEmpty};
+    t[i] = ulonglong2{kEmpty, kEmpty};
+  }
+  if (live0)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) q[i] = load_global_u64x2(s.slots + b0 * kBucketSlots + 2 * i);
+  if (live1)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) t[i] = load_global_u64x2(s.slots + b1 * kBucketSlots + 2 * i);
+  bool hit0 = false, hole0 = false, hit1 = false, hole1 = false;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    hit0 |= (q[i].x == k0) | (q[i].y == k0);
+    hole0 |= (q[i].x == kEmpty) | (q[i].y == kEmpty);
+    hit1 |= (t[i].x == k1) | (t[i].y == k1);
+    hole1 |= (t[i].x == kEmpty) | (t[i].y == kEmpty);
+  }
+  in0 = live0 && hit0;
+  in1 = live1 && hit1;
+  // a full home bucket without the key (rare at the load factors in use): the general scan
+  if (live0 && !hit0 && !hole0) in0 = set_contains(s, k0);
+  if (live1 && !hit1 && !hole1) in1 = set_contains(s, k1);
+}
+
 // One workgroup per beam.  VERIFY: a set is consulted at this level, so the beam is cut to its K
 // most probable codes first (that cut decides which candidates are verified; without a set the
 // request-level selection alone gives the same result) and the survivors are probed.
-template <bool VERIFY>
+// NV > 0: T_l <= NV * 256, the beam's logits and keys stay in registers (one read and one write of
+// the row; the K survivors are gathered in LDS so that every lane has probes in flight);
+// NV == 0: any T_l, the row is read again from L2 for every pass.
+template <bool VERIFY, int NV>
 __global__ __launch_bounds__(kWideRowThreads) void wide_rows_kernel(WideArgs a) {
   constexpr int NT = kWideRowThreads;
+  constexpr bool kRegs = NV > 0;
   __shared__ float red[NT / 64];
-  __shared__ uint32_t hist[VERIFY ? 4096 : 1];
+  __shared__ uint32_t hist[VERIFY ? (kRegs ? 256 : 4096) : 1];
+  __shared__ uint64_t cand[VERIFY && kRegs ? NEZHA_MAX_WIDE_BEAM : 1];    // (key, code) of the survivors
   __shared__ uint32_t bc[4];
   __shared__ int cnt[NT / 64];
+  __shared__ int n_cand;
   const int64_t row = blockIdx.x;
-  const int V = a.V, tid = threadIdx.x;
+  const int V = a.V, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   uint32_t* zk = a.zk + row * V;
   const uint64_t pkey = a.key_in ? a.key_in[row] : 0ull;
   const float sp = a.score_in ? a.score_in[row] : 0.f;
@@ -337,38 +475,117 @@ __global__ __launch_bounds__(kWideRowThreads) void wide_rows_kernel(WideArgs a) 
     for (int v = tid; v < V; v += NT) as_global(zk)[v] = 0u;
     return;
   }
-  float m = -INFINITY;
-  for (int v = tid; v < V; v += NT) m = fmaxf(m, __uint_as_float(as_global(zk)[v]));
-  m = block_max<NT>(m, red);
-  float s = 0.f;
-  for (int v = tid; v < V; v += NT) s += expf(__uint_as_float(as_global(zk)[v]) - m);
-  s = block_sum<NT>(s, red);
-  const float lse = m + logf(s);
-  for (int v = tid; v < V; v += NT) {
-    const float z = __uint_as_float(as_global(zk)[v]);
-    as_global(zk)[v] = ordered_bits(sp + (z - lse));
-  }
-  if constexpr (VERIFY) {
-    __syncthreads();                                     // the keys are read back by other threads
-    uint32_t tau = 0;
-    if (a.K < V) {
-      const RadixPick p = block_radix_select<NT>(zk, V, a.K, hist, bc);
-      if (!p.all) {
-        tau = p.tau;
-        if (p.need < p.n_eq) {
-          // more codes tie with the K-th than fit: the lower codes stay
-          block_take_ties<NT>(zk, V, tau, p.need, cnt, [&](int64_t i, bool taken) {
-            if (!taken) as_global(zk)[i] = 0u;
-          });
-          __syncthreads();
+  if constexpr (kRegs) {
+    float z[NV];
+    float m = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int v = tid + j * NT;
+      z[j] = v < V ? __uint_as_float(as_global(zk)[v]) : -INFINITY;
+      m = fmaxf(m, z[j]);
+    }
+    m = block_max<NT>(m, red);
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) s += expf(z[j] - m);
+    s = block_sum<NT>(s, red);
+    const float lse = m + logf(s);
+    uint32_t key[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) key[j] = tid + j * NT < V ? ordered_bits(sp + (z[j] - lse)) : 0u;
+    if constexpr (!VERIFY) {
+#pragma unroll
+      for (int j = 0; j < NV; ++j)
+        if (tid + j * NT < V) as_global(zk)[tid + j * NT] = key[j];
+    } else {
+      if (a.K >= V) {
+        // no cut: every code is probed, two at a time
+#pragma unroll
+        for (int j = 0; j < NV; j += 2) {
+          const int v0 = tid + j * NT, v1 = v0 + NT;
+          bool in0, in1;
+          set_contains_pair(a.set, pkey + (uint64_t)(uint32_t)v0 * a.mult, v0 < V,
+                            pkey + (uint64_t)(uint32_t)v1 * a.mult, v1 < V, in0, in1);
+          if (v0 < V) as_global(zk)[v0] = in0 ? key[j] : 0u;
+          if (v1 < V) as_global(zk)[v1] = in1 ? key[j + 1] : 0u;
         }
+        return;
+      }
+      if (tid == 0) n_cand = 0;
+      const RadixPick p = regs_radix_select<NT, NV>(key, a.K, hist, bc,
+                                                    reinterpret_cast<uint32_t*>(red));
+      const bool ordered_ties = p.need < p.n_eq;         // more codes tie with the K-th than fit
+      int running = 0;
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        const int v = tid + j * NT;
+        bool take = key[j] > p.tau || (key[j] == p.tau && !ordered_ties);
+        if (ordered_ties) {                              // uniform branch: the lower codes stay
+          const bool tie = key[j] == p.tau;
+          const uint64_t bal = __ballot(tie);
+          __syncthreads();
+          if (lane == 0) cnt[wave] = __popcll(bal);
+          __syncthreads();
+          int before = running, total = 0;
+#pragma unroll
+          for (int w = 0; w < NT / 64; ++w) {
+            if (w < wave) before += cnt[w];
+            total += cnt[w];
+          }
+          running += total;
+          if (tie) take = before + __popcll(bal & ((1ull << lane) - 1ull)) < p.need;
+        }
+        if (take)
+          cand[atomicAdd(&n_cand, 1)] = ((uint64_t)key[j] << 32) | (uint32_t)v;   // K entries in all
+        else if (v < V)
+          as_global(zk)[v] = 0u;
+      }
+      __syncthreads();
+      const int n = n_cand;
+      for (int i = tid; i < n; i += 2 * NT) {
+        const bool live1 = i + NT < n;
+        const uint64_t c0 = cand[i], c1 = live1 ? cand[i + NT] : 0ull;
+        bool in0, in1;
+        set_contains_pair(a.set, pkey + (uint64_t)(uint32_t)c0 * a.mult, true,
+                          pkey + (uint64_t)(uint32_t)c1 * a.mult, live1, in0, in1);
+        as_global(zk)[(uint32_t)c0] = in0 ? (uint32_t)(c0 >> 32) : 0u;
+        if (live1) as_global(zk)[(uint32_t)c1] = in1 ? (uint32_t)(c1 >> 32) : 0u;
       }
     }
+  } else {
+    float m = -INFINITY;
+    for (int v = tid; v < V; v += NT) m = fmaxf(m, __uint_as_float(as_global(zk)[v]));
+    m = block_max<NT>(m, red);
+    float s = 0.f;
+    for (int v = tid; v < V; v += NT) s += expf(__uint_as_float(as_global(zk)[v]) - m);
+    s = block_sum<NT>(s, red);
+    const float lse = m + logf(s);
     for (int v = tid; v < V; v += NT) {
-      const uint32_t k = as_global(zk)[v];
-      if (k == 0u) continue;
-      const bool in = k >= tau && set_contains(a.set, pkey + (uint64_t)(uint32_t)v * a.mult);
-      if (!in) as_global(zk)[v] = 0u;
+      const float z = __uint_as_float(as_global(zk)[v]);
+      as_global(zk)[v] = ordered_bits(sp + (z - lse));
+    }
+    if constexpr (VERIFY) {
+      __syncthreads();                                   // the keys are read back by other threads
+      uint32_t tau = 0;
+      if (a.K < V) {
+        const RadixPick p = block_radix_select<NT>(zk, V, a.K, hist, bc);
+        if (!p.all) {
+          tau = p.tau;
+          if (p.need < p.n_eq) {
+            // more codes tie with the K-th than fit: the lower codes stay
+            block_take_ties<NT>(zk, V, tau, p.need, cnt, [&](int64_t i, bool taken) {
+              if (!taken) as_global(zk)[i] = 0u;
+            });
+            __syncthreads();
+          }
+        }
+      }
+      for (int v = tid; v < V; v += NT) {
+        const uint32_t k = as_global(zk)[v];
+        if (k == 0u) continue;
+        const bool in = k >= tau && set_contains(a.set, pkey + (uint64_t)(uint32_t)v * a.mult);
+        if (!in) as_global(zk)[v] = 0u;
+      }
     }
   }
 }
@@ -419,15 +636,35 @@ __global__ __launch_bounds__(kWideThreads) void wide_select_kernel(WideSelectArg
   const int64_t n = (int64_t)a.K_in * V;                 // a multiple of 16
   const uint32_t* keys = a.zk + (int64_t)b * n;
 
+  // Every thread visits one 16-byte group of each run of 1024 groups, at a position that rotates
+  // from run to run: with T_l = 4096 a fixed position would be the same four codes of every beam,
+  // and the codes the user part favours are the same for all beams of a request, so the best keys
+  // would crowd into few threads and the bound would be weak.
   uint32_t t0 = 0, t1 = 0;
-  for (int64_t q = tid; q < (n >> 2); q += NT) {
-    const uint4 k4 = load_global_u4(keys + 4 * q);
+  const int64_t n4 = n >> 2;
+  auto note = [&](const uint4& k4) {
     const uint32_t kk[4] = {k4.x, k4.y, k4.z, k4.w};
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const uint32_t lo = kk[j] > t0 ? t0 : kk[j];
       t0 = kk[j] > t0 ? kk[j] : t0;
       t1 = lo > t1 ? lo : t1;
+    }
+  };
+  {
+    int64_t q0 = 0;
+    int run = 0;
+    for (; q0 + 4 * NT <= n4; q0 += 4 * NT, run += 4) {   // four loads in flight per thread
+      uint4 k4[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        k4[u] = load_global_u4(keys + 4 * (q0 + u * NT + ((tid + 37 * (run + u)) & (NT - 1))));
+#pragma unroll
+      for (int u = 0; u < 4; ++u) note(k4[u]);
+    }
+    for (; q0 < n4; q0 += NT, ++run) {
+      const int64_t q = q0 + ((tid + 37 * run) & (NT - 1));
+      if (q < n4) note(load_global_u4(keys + 4 * q));
     }
   }
   top[2 * tid] = t0;
@@ -439,13 +676,10 @@ __global__ __launch_bounds__(kWideThreads) void wide_select_kernel(WideSelectArg
   if (tau0 == 0u) tau0 = 1u;                             // fewer than K candidates seen: take all
   __syncthreads();
 
-  for (int64_t q0 = 0; q0 < (n >> 2); q0 += NT) {        // uniform trip count
-    const int64_t q = q0 + tid;
-    uint4 k4 = uint4{0, 0, 0, 0};
-    if (q < (n >> 2)) k4 = load_global_u4(keys + 4 * q);
+  auto collect = [&](const uint4& k4, int64_t q) {          // called by whole waves
     const uint32_t kk[4] = {k4.x, k4.y, k4.z, k4.w};
     const bool any = (kk[0] >= tau0) | (kk[1] >= tau0) | (kk[2] >= tau0) | (kk[3] >= tau0);
-    if (__ballot(any) == 0ull) continue;
+    if (__ballot(any) == 0ull) return;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const bool in = kk[j] >= tau0;
@@ -457,6 +691,22 @@ __global__ __launch_bounds__(kWideThreads) void wide_select_kernel(WideSelectArg
       const int pos = base + __popcll(bal & ((1ull << lane) - 1ull));
       if (in && pos < kWideListCap)
         list[pos] = ((uint64_t)kk[j] << 32) | (uint32_t)~(uint32_t)(4 * q + j);
+    }
+  };
+  {
+    int64_t q0 = 0;
+    for (; q0 + 4 * NT <= n4; q0 += 4 * NT) {
+      uint4 k4[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) k4[u] = load_global_u4(keys + 4 * (q0 + u * NT + tid));
+#pragma unroll
+      for (int u = 0; u < 4; ++u) collect(k4[u], q0 + u * NT + tid);
+    }
+    for (; q0 < n4; q0 += NT) {                            // uniform trip count
+      const int64_t q = q0 + tid;
+      uint4 k4 = uint4{0, 0, 0, 0};
+      if (q < n4) k4 = load_global_u4(keys + 4 * q);
+      collect(k4, q);
     }
   }
   __syncthreads();

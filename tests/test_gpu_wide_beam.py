@@ -30,6 +30,7 @@ def _run(oracle, cfg, seed, N, verify=True, **kw):
     (2, 64, 96, 2048, 130, 2, "bf16"),      # state width that is not a power of two; just above 128
     (2, 24, 12, 320, 200, 3, "f32"),        # float32 path
     (5, 64, 128, 4096, 129, 2, "bf16"),     # large codebook
+    (2, 64, 64, 8192, 140, 2, "bf16"),      # a codebook too large for a beam's logits to stay in registers
 ])
 def test_wide_beam_shapes(oracle, B, d, e, V, K, L, dtype):
     cfg = synth.StepConfig("widebeam", B=B, d=d, e=e, L=L, V=V, K=K, N=min(V ** L // 4, 200_000),
