@@ -2350,6 +2350,14 @@ int check_desc(const nezha_step_desc* dsc, Plan* plan) {
     if (wide) {
       off += align_up(rows * (size_t)V * 4, 256);
       plan->logp_off = plan->list_off = plan->redo_off = plan->redo_req_off = off;
+      // the largest keys of every share of a request (batches too small for one workgroup per
+      // request), the request's list of keys at or above the bound / found in the set, its length
+      const int splits = wide_select_splits(dsc->B);
+      if (splits > 1) off += align_up((size_t)dsc->B * splits * dsc->K * 4, 256);
+      plan->list_off = off;
+      off += align_up((size_t)dsc->B * kWideListCap * 8, 256);
+      plan->redo_off = off;
+      off += align_up((size_t)dsc->B * 4, 256);
       plan->per_request = false;
       plan->total = off;
       plan->cap = 0;
@@ -2701,6 +2709,8 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
     wa.d = d;
     wa.e = e;
     wa.col_splits = 1;
+    wa.glist = reinterpret_cast<uint64_t*>(ws + plan.list_off);
+    wa.gcount = verify ? reinterpret_cast<int32_t*>(ws + plan.redo_off) : nullptr;
     {
       ProfileScope prof(kWideLogits, stream);
       if (bf16) {
@@ -2759,19 +2769,32 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
     sa.V = V;
     sa.e = e;
     sa.transition = desc->transition;
+    sa.splits = wide_select_splits(B);
+    sa.tops = reinterpret_cast<uint32_t*>(ws + plan.logp_off);
+    sa.glist = reinterpret_cast<uint64_t*>(ws + plan.list_off);
+    sa.gcount = reinterpret_cast<int32_t*>(ws + plan.redo_off);
     {
       const size_t lds = wide_select_lds();
       ProfileScope prof(kWideSelect, stream);
-      if (bf16) {
-        rc = allow_lds(wide_select_kernel<true>, lds);
-        if (rc != NEZHA_OK) return rc;
-        hipLaunchKernelGGL((wide_select_kernel<true>), dim3(B), dim3(kWideThreads), lds, stream, sa);
-      } else {
-        rc = allow_lds(wide_select_kernel<false>, lds);
-        if (rc != NEZHA_OK) return rc;
-        hipLaunchKernelGGL((wide_select_kernel<false>), dim3(B), dim3(kWideThreads), lds, stream,
+      if (sa.splits > 1 && !verify) {
+        hipLaunchKernelGGL(wide_bound_kernel, dim3(B * sa.splits), dim3(kWideThreads), 0, stream, sa);
+        hipLaunchKernelGGL(wide_collect_kernel, dim3(B * sa.splits), dim3(kWideThreads), 0, stream,
                            sa);
       }
+#define LAUNCH_SELECT(KERN)                                                             \
+  do {                                                                                  \
+    rc = allow_lds(KERN, lds);                                                          \
+    if (rc != NEZHA_OK) return rc;                                                      \
+    hipLaunchKernelGGL(KERN, dim3(B), dim3(kWideThreads), lds, stream, sa);             \
+  } while (0)
+      if (sa.splits > 1 || verify) {
+        if (bf16) LAUNCH_SELECT(wide_finish_kernel<true>);
+        else LAUNCH_SELECT(wide_finish_kernel<false>);
+      } else {
+        if (bf16) LAUNCH_SELECT(wide_select_kernel<true>);
+        else LAUNCH_SELECT(wide_select_kernel<false>);
+      }
+#undef LAUNCH_SELECT
       NEZHA_HIP_CHECK(hipGetLastError());
     }
     return NEZHA_OK;

@@ -29,6 +29,10 @@ struct WideArgs {
   int64_t rows;
   int K_in, K, V, d, e;
   int col_splits;           // wide_logits_bf16_kernel: waves sharing one group of 32 beams
+  // where a set is consulted: the request's surviving candidates as (key, ~index), at most
+  // kWideListCap per request are stored, and how many there are
+  uint64_t* glist;          // [B, kWideListCap]
+  int32_t* gcount;          // [B], cleared by the logits kernel
 };
 
 // ---- logits --------------------------------------------------------------------------------
@@ -40,6 +44,8 @@ __global__ __launch_bounds__(256) void wide_logits_bf16_kernel(WideArgs a) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int g = lane >> 4, c = lane & 15;
+  if (blockIdx.x == 0 && a.gcount)
+    for (int64_t b = threadIdx.x; b < a.rows / a.K_in; b += 256) a.gcount[b] = 0;
   const int64_t unit = (int64_t)blockIdx.x * 4 + wave;
   const int64_t rg = unit / a.col_splits;
   const int cs = (int)(unit - rg * a.col_splits);
@@ -109,6 +115,8 @@ __global__ __launch_bounds__(256) void wide_logits_bf16_kernel(WideArgs a) {
 __global__ __launch_bounds__(256) void wide_logits_f32_kernel(WideArgs a) {
   extern __shared__ float wide_states[];   // [16][e]
   const int V = a.V, e = a.e;
+  if (blockIdx.x == 0 && a.gcount)
+    for (int64_t b = threadIdx.x; b < a.rows / a.K_in; b += 256) a.gcount[b] = 0;
   const int col_tiles = (V + 255) / 256;
   const int64_t rt = blockIdx.x / col_tiles;
   const int vt = (int)(blockIdx.x - rt * col_tiles);
@@ -465,7 +473,8 @@ __global__ __launch_bounds__(kWideRowThreads) void wide_rows_kernel(WideArgs a) 
   __shared__ uint64_t cand[VERIFY && kRegs ? NEZHA_MAX_WIDE_BEAM : 1];    // (key, code) of the survivors
   __shared__ uint32_t bc[4];
   __shared__ int cnt[NT / 64];
-  __shared__ int n_cand;
+  __shared__ uint64_t kept[VERIFY ? NEZHA_MAX_WIDE_BEAM : 1];            // those found in the set
+  __shared__ int n_cand, n_kept, kept_base;
   const int64_t row = blockIdx.x;
   const int V = a.V, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   uint32_t* zk = a.zk + row * V;
@@ -475,6 +484,13 @@ __global__ __launch_bounds__(kWideRowThreads) void wide_rows_kernel(WideArgs a) 
     for (int v = tid; v < V; v += NT) as_global(zk)[v] = 0u;
     return;
   }
+  const int64_t req = row / a.K_in;
+  const uint32_t idx0 = (uint32_t)(row - req * a.K_in) * (uint32_t)V;   // index of code 0 in the request
+  if (tid == 0) n_kept = 0;                              // (barriers follow before its first use)
+  // a candidate found in the set: its key stays, and it joins the request's list
+  auto keep = [&](int v, uint32_t k) {
+    kept[atomicAdd(&n_kept, 1)] = ((uint64_t)k << 32) | (uint32_t)~(idx0 + (uint32_t)v);
+  };
   if constexpr (kRegs) {
     float z[NV];
     float m = -INFINITY;
@@ -508,48 +524,52 @@ __global__ __launch_bounds__(kWideRowThreads) void wide_rows_kernel(WideArgs a) 
                             pkey + (uint64_t)(uint32_t)v1 * a.mult, v1 < V, in0, in1);
           if (v0 < V) as_global(zk)[v0] = in0 ? key[j] : 0u;
           if (v1 < V) as_global(zk)[v1] = in1 ? key[j + 1] : 0u;
+          if (in0) keep(v0, key[j]);
+          if (in1) keep(v1, key[j + 1]);
         }
-        return;
-      }
-      if (tid == 0) n_cand = 0;
-      const RadixPick p = regs_radix_select<NT, NV>(key, a.K, hist, bc,
-                                                    reinterpret_cast<uint32_t*>(red));
-      const bool ordered_ties = p.need < p.n_eq;         // more codes tie with the K-th than fit
-      int running = 0;
+      } else {
+        if (tid == 0) n_cand = 0;
+        const RadixPick p = regs_radix_select<NT, NV>(key, a.K, hist, bc,
+                                                      reinterpret_cast<uint32_t*>(red));
+        const bool ordered_ties = p.need < p.n_eq;       // more codes tie with the K-th than fit
+        int running = 0;
 #pragma unroll
-      for (int j = 0; j < NV; ++j) {
-        const int v = tid + j * NT;
-        bool take = key[j] > p.tau || (key[j] == p.tau && !ordered_ties);
-        if (ordered_ties) {                              // uniform branch: the lower codes stay
-          const bool tie = key[j] == p.tau;
-          const uint64_t bal = __ballot(tie);
-          __syncthreads();
-          if (lane == 0) cnt[wave] = __popcll(bal);
-          __syncthreads();
-          int before = running, total = 0;
+        for (int j = 0; j < NV; ++j) {
+          const int v = tid + j * NT;
+          bool take = key[j] > p.tau || (key[j] == p.tau && !ordered_ties);
+          if (ordered_ties) {                            // uniform branch: the lower codes stay
+            const bool tie = key[j] == p.tau;
+            const uint64_t bal = __ballot(tie);
+            __syncthreads();
+            if (lane == 0) cnt[wave] = __popcll(bal);
+            __syncthreads();
+            int before = running, total = 0;
 #pragma unroll
-          for (int w = 0; w < NT / 64; ++w) {
-            if (w < wave) before += cnt[w];
-            total += cnt[w];
+            for (int w = 0; w < NT / 64; ++w) {
+              if (w < wave) before += cnt[w];
+              total += cnt[w];
+            }
+            running += total;
+            if (tie) take = before + __popcll(bal & ((1ull << lane) - 1ull)) < p.need;
           }
-          running += total;
-          if (tie) take = before + __popcll(bal & ((1ull << lane) - 1ull)) < p.need;
+          if (take)
+            cand[atomicAdd(&n_cand, 1)] = ((uint64_t)key[j] << 32) | (uint32_t)v;   // K entries in all
+          else if (v < V)
+            as_global(zk)[v] = 0u;
         }
-        if (take)
-          cand[atomicAdd(&n_cand, 1)] = ((uint64_t)key[j] << 32) | (uint32_t)v;   // K entries in all
-        else if (v < V)
-          as_global(zk)[v] = 0u;
-      }
-      __syncthreads();
-      const int n = n_cand;
-      for (int i = tid; i < n; i += 2 * NT) {
-        const bool live1 = i + NT < n;
-        const uint64_t c0 = cand[i], c1 = live1 ? cand[i + NT] : 0ull;
-        bool in0, in1;
-        set_contains_pair(a.set, pkey + (uint64_t)(uint32_t)c0 * a.mult, true,
-                          pkey + (uint64_t)(uint32_t)c1 * a.mult, live1, in0, in1);
-        as_global(zk)[(uint32_t)c0] = in0 ? (uint32_t)(c0 >> 32) : 0u;
-        if (live1) as_global(zk)[(uint32_t)c1] = in1 ? (uint32_t)(c1 >> 32) : 0u;
+        __syncthreads();
+        const int n = n_cand;
+        for (int i = tid; i < n; i += 2 * NT) {
+          const bool live1 = i + NT < n;
+          const uint64_t c0 = cand[i], c1 = live1 ? cand[i + NT] : 0ull;
+          bool in0, in1;
+          set_contains_pair(a.set, pkey + (uint64_t)(uint32_t)c0 * a.mult, true,
+                            pkey + (uint64_t)(uint32_t)c1 * a.mult, live1, in0, in1);
+          as_global(zk)[(uint32_t)c0] = in0 ? (uint32_t)(c0 >> 32) : 0u;
+          if (live1) as_global(zk)[(uint32_t)c1] = in1 ? (uint32_t)(c1 >> 32) : 0u;
+          if (in0) keep((int)(uint32_t)c0, (uint32_t)(c0 >> 32));
+          if (in1) keep((int)(uint32_t)c1, (uint32_t)(c1 >> 32));
+        }
       }
     }
   } else {
@@ -585,8 +605,19 @@ __global__ __launch_bounds__(kWideRowThreads) void wide_rows_kernel(WideArgs a) 
         if (k == 0u) continue;
         const bool in = k >= tau && set_contains(a.set, pkey + (uint64_t)(uint32_t)v * a.mult);
         if (!in) as_global(zk)[v] = 0u;
+        else keep(v, k);
       }
     }
+  }
+  if constexpr (VERIFY) {
+    // the row's survivors join the request's list (one reservation per row)
+    __syncthreads();
+    const int n = n_kept;
+    if (tid == 0) kept_base = atomicAdd(&a.gcount[req], n);
+    __syncthreads();
+    uint64_t* glist = a.glist + req * kWideListCap;
+    for (int i = tid; i < n; i += NT)
+      if (kept_base + i < kWideListCap) glist[kept_base + i] = kept[i];
   }
 }
 
@@ -606,42 +637,54 @@ struct WideSelectArgs {
   void* state_out;
   int32_t* count_out;
   int K_in, K, V, e, transition;
+  // when a request is shared by `splits` > 1 workgroups (small batches):
+  int splits;
+  uint32_t* tops;           // [B, splits, K] each share's K largest keys
+  uint64_t* glist;          // [B, kWideListCap] (key, ~index) at or above the bound
+  int32_t* gcount;          // [B]
 };
 inline size_t wide_select_lds() {
   return (size_t)kWideListCap * 8 + (size_t)2 * kWideThreads * 4 + (size_t)2 * 1024 * 4 + 64;
 }
+// Workgroups per request: a request's keys are walked by one workgroup when the batch fills the
+// chip on its own, by up to 16 when it does not.
+inline int wide_select_splits(int B) {
+  if (B >= 256) return 1;
+  int s = 512 / (B > 0 ? B : 1);
+  return s > 16 ? 16 : s < 1 ? 1 : s;
+}
 
-// One workgroup of 1024 threads per request.  First pass over the request's K_in * T_l keys:
-// every thread keeps the two largest keys of the indices it visits; the K-th largest of those
-// 2048 keys is a lower bound of the K-th largest key (they are K distinct candidates).  Second
-// pass: keys at or above the bound go to an LDS list as (key, ~index); the list is sorted, which
-// orders equal scores by parent and code, and its first K entries are the level's beams.  When
-// the list would overflow (scores crowded into the indices of few threads, massive ties) the
-// selection is done exactly by radix passes instead.
-template <bool BF16>
-__global__ __launch_bounds__(kWideThreads) void wide_select_kernel(WideSelectArgs a) {
+// The LDS of the selection kernels.
+struct WideLds {
+  uint64_t* list;        // [kWideListCap]
+  uint32_t* top;         // [2 * kWideThreads]; later the tie counters
+  int32_t* fin_parent;   // [1024]
+  int32_t* fin_code;     // [1024]
+  uint32_t* bc;          // [4]
+  int* n_list;           // [1]
+  uint32_t* hist;        // 4096 words inside list (exact selection only)
+};
+__device__ __forceinline__ WideLds wide_lds_layout(uint64_t* base) {
+  WideLds l;
+  l.list = base;
+  l.top = reinterpret_cast<uint32_t*>(base + kWideListCap);
+  l.fin_parent = reinterpret_cast<int32_t*>(l.top + 2 * kWideThreads);
+  l.fin_code = l.fin_parent + 1024;
+  l.bc = reinterpret_cast<uint32_t*>(l.fin_code + 1024);
+  l.n_list = reinterpret_cast<int*>(l.bc + 4);
+  l.hist = reinterpret_cast<uint32_t*>(base + 2048);
+  return l;
+}
+
+// First pass: every thread keeps the two largest keys of the 16-byte groups [q_begin, q_end) it
+// visits.  A thread visits one group of each run of 1024 groups, at a position that rotates from
+// run to run: with T_l = 4096 a fixed position would be the same four codes of every beam, and
+// the codes the user part favours are the same for all beams of a request, so the best keys would
+// crowd into few threads and the bound would be weak.
+__device__ __forceinline__ void wide_thread_top2(const uint32_t* keys, int64_t q_begin,
+                                                 int64_t q_end, uint32_t& t0, uint32_t& t1) {
   constexpr int NT = kWideThreads;
-  extern __shared__ __align__(16) uint64_t wide_lds[];
-  uint64_t* list = wide_lds;                                            // [kWideListCap]
-  uint32_t* top = reinterpret_cast<uint32_t*>(list + kWideListCap);     // [2 * NT]
-  int32_t* fin_parent = reinterpret_cast<int32_t*>(top + 2 * NT);       // [1024]
-  int32_t* fin_code = fin_parent + 1024;                                // [1024]
-  uint32_t* bc = reinterpret_cast<uint32_t*>(fin_code + 1024);          // [4]
-  int* n_list = reinterpret_cast<int*>(bc + 4);                         // [1]
-  int* tie_cnt = reinterpret_cast<int*>(top);                           // [NT / 64], after top's use
-  uint32_t* hist = reinterpret_cast<uint32_t*>(list + 2048);            // 4096 words inside list
-
-  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
-  const int K = a.K, V = a.V;
-  const int64_t n = (int64_t)a.K_in * V;                 // a multiple of 16
-  const uint32_t* keys = a.zk + (int64_t)b * n;
-
-  // Every thread visits one 16-byte group of each run of 1024 groups, at a position that rotates
-  // from run to run: with T_l = 4096 a fixed position would be the same four codes of every beam,
-  // and the codes the user part favours are the same for all beams of a request, so the best keys
-  // would crowd into few threads and the bound would be weak.
-  uint32_t t0 = 0, t1 = 0;
-  const int64_t n4 = n >> 2;
+  const int tid = threadIdx.x;
   auto note = [&](const uint4& k4) {
     const uint32_t kk[4] = {k4.x, k4.y, k4.z, k4.w};
 #pragma unroll
@@ -651,31 +694,29 @@ __global__ __launch_bounds__(kWideThreads) void wide_select_kernel(WideSelectArg
       t1 = lo > t1 ? lo : t1;
     }
   };
-  {
-    int64_t q0 = 0;
-    int run = 0;
-    for (; q0 + 4 * NT <= n4; q0 += 4 * NT, run += 4) {   // four loads in flight per thread
-      uint4 k4[4];
+  int64_t q0 = q_begin;
+  int run = 0;
+  for (; q0 + 4 * NT <= q_end; q0 += 4 * NT, run += 4) {   // four loads in flight per thread
+    uint4 k4[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
-        k4[u] = load_global_u4(keys + 4 * (q0 + u * NT + ((tid + 37 * (run + u)) & (NT - 1))));
+    for (int u = 0; u < 4; ++u)
+      k4[u] = load_global_u4(keys + 4 * (q0 + u * NT + ((tid + 37 * (run + u)) & (NT - 1))));
 #pragma unroll
-      for (int u = 0; u < 4; ++u) note(k4[u]);
-    }
-    for (; q0 < n4; q0 += NT, ++run) {
-      const int64_t q = q0 + ((tid + 37 * run) & (NT - 1));
-      if (q < n4) note(load_global_u4(keys + 4 * q));
-    }
+    for (int u = 0; u < 4; ++u) note(k4[u]);
   }
-  top[2 * tid] = t0;
-  top[2 * tid + 1] = t1;
-  if (tid == 0) *n_list = 0;
-  __syncthreads();
-  block_sort_desc<NT>(top, 2 * NT);
-  uint32_t tau0 = top[K - 1];
-  if (tau0 == 0u) tau0 = 1u;                             // fewer than K candidates seen: take all
-  __syncthreads();
+  for (; q0 < q_end; q0 += NT, ++run) {
+    const int64_t q = q0 + ((tid + 37 * run) & (NT - 1));
+    if (q < q_end) note(load_global_u4(keys + 4 * q));
+  }
+}
 
+// Second pass: keys of the groups [q_begin, q_end) at or above tau0 are handed to put(count) ->
+// first position, wave by wave, and stored through store(position, entry) as (key, ~index).
+template <class Reserve, class Store>
+__device__ __forceinline__ void wide_collect(const uint32_t* keys, int64_t q_begin, int64_t q_end,
+                                             uint32_t tau0, Reserve reserve, Store store) {
+  constexpr int NT = kWideThreads;
+  const int tid = threadIdx.x, lane = tid & 63;
   auto collect = [&](const uint4& k4, int64_t q) {          // called by whole waves
     const uint32_t kk[4] = {k4.x, k4.y, k4.z, k4.w};
     const bool any = (kk[0] >= tau0) | (kk[1] >= tau0) | (kk[2] >= tau0) | (kk[3] >= tau0);
@@ -686,36 +727,43 @@ __global__ __launch_bounds__(kWideThreads) void wide_select_kernel(WideSelectArg
       const uint64_t bal = __ballot(in);
       if (bal == 0ull) continue;
       int base = 0;
-      if (lane == 0) base = atomicAdd(n_list, __popcll(bal));
+      if (lane == 0) base = reserve(__popcll(bal));
       base = __shfl(base, 0);
       const int pos = base + __popcll(bal & ((1ull << lane) - 1ull));
       if (in && pos < kWideListCap)
-        list[pos] = ((uint64_t)kk[j] << 32) | (uint32_t)~(uint32_t)(4 * q + j);
+        store(pos, ((uint64_t)kk[j] << 32) | (uint32_t)~(uint32_t)(4 * q + j));
     }
   };
-  {
-    int64_t q0 = 0;
-    for (; q0 + 4 * NT <= n4; q0 += 4 * NT) {
-      uint4 k4[4];
+  int64_t q0 = q_begin;
+  for (; q0 + 4 * NT <= q_end; q0 += 4 * NT) {
+    uint4 k4[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) k4[u] = load_global_u4(keys + 4 * (q0 + u * NT + tid));
+    for (int u = 0; u < 4; ++u) k4[u] = load_global_u4(keys + 4 * (q0 + u * NT + tid));
 #pragma unroll
-      for (int u = 0; u < 4; ++u) collect(k4[u], q0 + u * NT + tid);
-    }
-    for (; q0 < n4; q0 += NT) {                            // uniform trip count
-      const int64_t q = q0 + tid;
-      uint4 k4 = uint4{0, 0, 0, 0};
-      if (q < n4) k4 = load_global_u4(keys + 4 * q);
-      collect(k4, q);
-    }
+    for (int u = 0; u < 4; ++u) collect(k4[u], q0 + u * NT + tid);
   }
-  __syncthreads();
-  int n_in = *n_list;
-  __syncthreads();
+  for (; q0 < q_end; q0 += NT) {                            // uniform trip count
+    const int64_t q = q0 + tid;
+    uint4 k4 = uint4{0, 0, 0, 0};
+    if (q < q_end) k4 = load_global_u4(keys + 4 * q);
+    collect(k4, q);
+  }
+}
+
+// From the n_in entries of the LDS list (or, when the list overflowed, from an exact radix
+// selection over all keys) to the level's outputs: sort by (score, parent, code), write the K
+// best, apply the Transition.
+template <bool BF16>
+__device__ __forceinline__ void wide_finish(const WideSelectArgs& a, int b, const uint32_t* keys,
+                                            int64_t n, const WideLds& l, int n_in) {
+  constexpr int NT = kWideThreads;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int K = a.K, V = a.V;
+  uint64_t* list = l.list;
   if (n_in > kWideListCap) {
     // exact selection; the list is rebuilt from the keys above the K-th and its first ties
-    const RadixPick p = block_radix_select<NT>(keys, n, K, hist, bc);
-    if (tid == 0) *n_list = 0;
+    const RadixPick p = block_radix_select<NT>(keys, n, K, l.hist, l.bc);
+    if (tid == 0) *l.n_list = 0;
     __syncthreads();
     const uint32_t tau = p.all ? 1u : p.tau;
     for (int64_t i0 = 0; i0 < n; i0 += NT) {
@@ -725,18 +773,19 @@ __global__ __launch_bounds__(kWideThreads) void wide_select_kernel(WideSelectArg
       const uint64_t bal = __ballot(in);
       if (bal == 0ull) continue;
       int base = 0;
-      if (lane == 0) base = atomicAdd(n_list, __popcll(bal));
+      if (lane == 0) base = atomicAdd(l.n_list, __popcll(bal));
       base = __shfl(base, 0);
       const int pos = base + __popcll(bal & ((1ull << lane) - 1ull));
       if (in) list[pos] = ((uint64_t)k << 32) | (uint32_t)~(uint32_t)i;   // at most K entries
     }
     if (!p.all) {
-      block_take_ties<NT>(keys, n, tau, p.need, tie_cnt, [&](int64_t i, bool taken) {
-        if (taken) list[atomicAdd(n_list, 1)] = ((uint64_t)tau << 32) | (uint32_t)~(uint32_t)i;
+      block_take_ties<NT>(keys, n, tau, p.need, reinterpret_cast<int*>(l.top),
+                          [&](int64_t i, bool taken) {
+        if (taken) list[atomicAdd(l.n_list, 1)] = ((uint64_t)tau << 32) | (uint32_t)~(uint32_t)i;
       });
     }
     __syncthreads();
-    n_in = *n_list;
+    n_in = *l.n_list;
     __syncthreads();
   }
   int P = 2;
@@ -758,25 +807,116 @@ __global__ __launch_bounds__(kWideThreads) void wide_select_kernel(WideSelectArg
       a.score_out[o] = unordered_bits((uint32_t)(sk >> 32));
       a.parent_out[o] = par;
       a.code_out[o] = code;
-      fin_parent[j] = par;
-      fin_code[j] = code;
+      l.fin_parent[j] = par;
+      l.fin_code[j] = code;
     } else {
       a.key_out[o] = kEmpty;
       a.score_out[o] = -INFINITY;
       a.parent_out[o] = -1;
       a.code_out[o] = -1;
-      fin_parent[j] = -1;
-      fin_code[j] = -1;
+      l.fin_parent[j] = -1;
+      l.fin_code[j] = -1;
     }
   }
   if (tid == 0 && a.count_out) a.count_out[b] = cnt;
   __syncthreads();
   if (a.state_out) {
     if (a.transition == NEZHA_TRANSITION_RNN)
-      update_states_rnn<BF16>(a.state_in, a.E, a.U, a.state_out, b, K, a.K_in, a.e, fin_parent,
-                              fin_code, tid, NT);
+      update_states_rnn<BF16>(a.state_in, a.E, a.U, a.state_out, b, K, a.K_in, a.e, l.fin_parent,
+                              l.fin_code, tid, NT);
     else
-      update_states<BF16>(a.state_in, a.E, a.state_out, b, K, a.K_in, a.e, fin_parent, fin_code,
+      update_states<BF16>(a.state_in, a.E, a.state_out, b, K, a.K_in, a.e, l.fin_parent, l.fin_code,
                           tid, NT);
   }
+}
+
+// One workgroup of 1024 threads per request.  First pass over the request's K_in * T_l keys:
+// every thread keeps the two largest keys of the indices it visits; the K-th largest of those
+// 2048 keys is a lower bound of the K-th largest key (they are K distinct candidates).  Second
+// pass: keys at or above the bound go to an LDS list as (key, ~index); the list is sorted, which
+// orders equal scores by parent and code, and its first K entries are the level's beams.  When
+// the list would overflow (scores crowded into the indices of few threads, massive ties) the
+// selection is done exactly by radix passes instead.
+template <bool BF16>
+__global__ __launch_bounds__(kWideThreads) void wide_select_kernel(WideSelectArgs a) {
+  constexpr int NT = kWideThreads;
+  extern __shared__ __align__(16) uint64_t wide_lds[];
+  const WideLds l = wide_lds_layout(wide_lds);
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int64_t n = (int64_t)a.K_in * a.V;               // a multiple of 16
+  const uint32_t* keys = a.zk + (int64_t)b * n;
+
+  uint32_t t0 = 0, t1 = 0;
+  wide_thread_top2(keys, 0, n >> 2, t0, t1);
+  l.top[2 * tid] = t0;
+  l.top[2 * tid + 1] = t1;
+  if (tid == 0) *l.n_list = 0;
+  __syncthreads();
+  block_sort_desc<NT>(l.top, 2 * NT);
+  uint32_t tau0 = l.top[a.K - 1];
+  if (tau0 == 0u) tau0 = 1u;                             // fewer than K candidates seen: take all
+  __syncthreads();
+  wide_collect(keys, 0, n >> 2, tau0, [&](int c) { return atomicAdd(l.n_list, c); },
+               [&](int pos, uint64_t v) { l.list[pos] = v; });
+  __syncthreads();
+  const int n_in = *l.n_list;
+  __syncthreads();
+  wide_finish<BF16>(a, b, keys, n, l, n_in);
+}
+
+// Where a set was consulted the survivors are few and wide_rows_kernel has listed them already:
+// wide_finish_kernel alone follows.  Otherwise, for batches too small to fill the chip with one
+// workgroup per request, the selection runs in three launches: blockIdx.x = request * splits + share.
+//   wide_bound_kernel    every share's K largest (thread top-2) keys -> tops
+//   wide_collect_kernel  bound = K-th largest of the request's splits * K such keys (every
+//                        workgroup of the request finds it again); the share's keys at or above
+//                        it -> the request's list in global memory
+//   wide_finish_kernel   one workgroup per request: list -> LDS -> outputs
+__global__ __launch_bounds__(kWideThreads) void wide_bound_kernel(WideSelectArgs a) {
+  constexpr int NT = kWideThreads;
+  __shared__ uint32_t top[2 * NT];
+  const int b = blockIdx.x / a.splits, s = blockIdx.x - b * a.splits, tid = threadIdx.x;
+  const int64_t n = (int64_t)a.K_in * a.V, n4 = n >> 2;
+  const uint32_t* keys = a.zk + (int64_t)b * n;
+  uint32_t t0 = 0, t1 = 0;
+  wide_thread_top2(keys, n4 * s / a.splits, n4 * (s + 1) / a.splits, t0, t1);
+  top[2 * tid] = t0;
+  top[2 * tid + 1] = t1;
+  if (s == 0 && tid == 0) a.gcount[b] = 0;
+  __syncthreads();
+  block_sort_desc<NT>(top, 2 * NT);
+  for (int j = tid; j < a.K; j += NT) a.tops[((int64_t)b * a.splits + s) * a.K + j] = top[j];
+}
+
+__global__ __launch_bounds__(kWideThreads) void wide_collect_kernel(WideSelectArgs a) {
+  constexpr int NT = kWideThreads;
+  __shared__ uint32_t hist[4096];
+  __shared__ uint32_t bc[4];
+  const int b = blockIdx.x / a.splits, s = blockIdx.x - b * a.splits;
+  const int64_t n = (int64_t)a.K_in * a.V, n4 = n >> 2;
+  const uint32_t* keys = a.zk + (int64_t)b * n;
+  const RadixPick p = block_radix_select<NT>(a.tops + (int64_t)b * a.splits * a.K,
+                                             (int64_t)a.splits * a.K, a.K, hist, bc);
+  const uint32_t tau0 = p.all ? 1u : p.tau;              // fewer than K candidates seen: take all
+  uint64_t* glist = a.glist + (int64_t)b * kWideListCap;
+  wide_collect(keys, n4 * s / a.splits, n4 * (s + 1) / a.splits, tau0,
+               [&](int c) { return atomicAdd(&a.gcount[b], c); },
+               [&](int pos, uint64_t v) { glist[pos] = v; });
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kWideThreads) void wide_finish_kernel(WideSelectArgs a) {
+  constexpr int NT = kWideThreads;
+  extern __shared__ __align__(16) uint64_t wide_lds[];
+  const WideLds l = wide_lds_layout(wide_lds);
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int64_t n = (int64_t)a.K_in * a.V;
+  const uint32_t* keys = a.zk + (int64_t)b * n;
+  const int n_in = a.gcount[b];
+  if (n_in <= kWideListCap) {
+    const uint64_t* glist = a.glist + (int64_t)b * kWideListCap;
+    for (int i = tid; i < n_in; i += NT) l.list[i] = glist[i];
+  }
+  __syncthreads();
+  wide_finish<BF16>(a, b, keys, n, l, n_in);
 }

@@ -31,6 +31,7 @@ def _run(oracle, cfg, seed, N, verify=True, **kw):
     (2, 24, 12, 320, 200, 3, "f32"),        # float32 path
     (5, 64, 128, 4096, 129, 2, "bf16"),     # large codebook
     (2, 64, 64, 8192, 140, 2, "bf16"),      # a codebook too large for a beam's logits to stay in registers
+    (256, 32, 32, 256, 130, 3, "bf16"),     # a batch large enough for one workgroup per request
 ])
 def test_wide_beam_shapes(oracle, B, d, e, V, K, L, dtype):
     cfg = synth.StepConfig("widebeam", B=B, d=d, e=e, L=L, V=V, K=K, N=min(V ** L // 4, 200_000),
@@ -56,12 +57,12 @@ def test_wide_beam_without_verification_keeps_k_beams(oracle):
     assert (to_np(outs[-1]["count"]) == cfg.K).all()
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
-def test_wide_beam_zero_weights_follow_the_tie_rule(oracle, dtype):
+@pytest.mark.parametrize("dtype,B", [("bf16", 2), ("f32", 2), ("bf16", 256)])
+def test_wide_beam_zero_weights_follow_the_tie_rule(oracle, dtype, B):
     """All logits equal: every selection is decided by the tie rule alone (lower parent, then
     lower code), both in the per-beam cut and in the request's K best; the lists that would hold
     everything at or above the bound overflow, so the exact radix selection runs."""
-    cfg = synth.StepConfig("ties", B=2, d=32, e=32, L=3, V=256, K=200, N=1, dtype=dtype,
+    cfg = synth.StepConfig("ties", B=B, d=32, e=32, L=3, V=256, K=200, N=1, dtype=dtype,
                            catalog="uniform")
     x = synth.draft_inputs(cfg, 3)
     x["W"] = [np.zeros_like(w) for w in x["W"]]
