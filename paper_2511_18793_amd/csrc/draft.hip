@@ -2286,6 +2286,14 @@ struct Plan {
   bool wide;          // beams wider than NEZHA_MAX_BEAM: code_off is where the level's logits go
 };
 inline bool wide_beam(int K, int K_in) { return K > NEZHA_MAX_BEAM || K_in > NEZHA_MAX_BEAM; }
+// wide_fused_bf16_kernel: waves that share the code tiles of one group of 32 beams, so that even
+// a small batch gives the chip a few thousand waves; at most 16 (their parts are merged per beam).
+inline int wide_fused_col_splits(int B, int K_in, int V) {
+  const int64_t groups = (int64_t)B * ((K_in + 31) / 32);
+  int64_t cs = (4096 + groups - 1) / (groups > 0 ? groups : 1);
+  const int64_t most = V / 16 < 16 ? V / 16 : 16;
+  return (int)(cs < 1 ? 1 : cs > most ? most : cs);
+}
 
 // Which kernels take a level is a function of the shape alone, so that the workspace can be sized
 // without the buffers.
@@ -2353,11 +2361,17 @@ int check_desc(const nezha_step_desc* dsc, Plan* plan) {
       // the largest keys of every share of a request (batches too small for one workgroup per
       // request), the request's list of keys at or above the bound / found in the set, its length
       const int splits = wide_select_splits(dsc->B);
-      if (splits > 1) off += align_up((size_t)dsc->B * splits * dsc->K * 4, 256);
+      const int groups = (dsc->K_in + 31) / 32;
+      const int cs = wide_fused_col_splits(dsc->B, dsc->K_in, V);
+      size_t n_tops = (size_t)splits * dsc->K;
+      if ((size_t)groups * cs * 128 > n_tops) n_tops = (size_t)groups * cs * 128;
+      off += align_up((size_t)dsc->B * n_tops * 4, 256);
       plan->list_off = off;
       off += align_up((size_t)dsc->B * kWideListCap * 8, 256);
       plan->redo_off = off;
       off += align_up((size_t)dsc->B * 4, 256);
+      plan->redo_req_off = off;                          // (max, sum) of every beam and column share
+      off += align_up(rows * (size_t)cs * 8, 256);
       plan->per_request = false;
       plan->total = off;
       plan->cap = 0;
@@ -2711,7 +2725,33 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
     wa.col_splits = 1;
     wa.glist = reinterpret_cast<uint64_t*>(ws + plan.list_off);
     wa.gcount = verify ? reinterpret_cast<int32_t*>(ws + plan.redo_off) : nullptr;
-    {
+    const bool fused = bf16 && !verify;                  // logits never stored (wide_beam.h)
+    WideSelectArgs sa;
+    sa.splits = wide_select_splits(B);
+    sa.n_tops = sa.splits * K;
+    if (fused) {
+      WideFusedArgs fa;
+      fa.w = wa;
+      fa.w.gcount = reinterpret_cast<int32_t*>(ws + plan.redo_off);
+      fa.w.col_splits = wide_fused_col_splits(B, K_in, V);
+      fa.part = reinterpret_cast<float2*>(ws + plan.redo_req_off);
+      fa.tops = reinterpret_cast<uint32_t*>(ws + plan.logp_off);
+      fa.groups = (K_in + 31) / 32;
+      sa.n_tops = fa.groups * fa.w.col_splits * 128;
+      const int64_t units = (int64_t)B * fa.groups * fa.w.col_splits;
+      const unsigned blocks = (unsigned)((units + 3) / 4);
+      ProfileScope prof(kWideLogits, stream);
+#define LAUNCH_FUSED(KSTV)                                                                         \
+  do {                                                                                             \
+    hipLaunchKernelGGL((wide_fused_bf16_kernel<KSTV, false>), dim3(blocks), dim3(256), 0, stream, fa); \
+    hipLaunchKernelGGL((wide_fused_bf16_kernel<KSTV, true>), dim3(blocks), dim3(256), 0, stream, fa);  \
+  } while (0)
+      if (e <= 64) LAUNCH_FUSED(2);
+      else if (e <= 128) LAUNCH_FUSED(4);
+      else LAUNCH_FUSED(8);
+#undef LAUNCH_FUSED
+      NEZHA_HIP_CHECK(hipGetLastError());
+    } else {
       ProfileScope prof(kWideLogits, stream);
       if (bf16) {
         const int64_t row_groups = ((int64_t)rows + 31) / 32;
@@ -2735,7 +2775,7 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
       }
       NEZHA_HIP_CHECK(hipGetLastError());
     }
-    {
+    if (!fused) {
       ProfileScope prof(kWideRows, stream);
 #define LAUNCH_ROWS(VERIFYV, NVV)                                                                  \
   hipLaunchKernelGGL((wide_rows_kernel<VERIFYV, NVV>), dim3((unsigned)rows), dim3(kWideRowThreads), \
@@ -2750,7 +2790,6 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
 #undef LAUNCH_ROWS
       NEZHA_HIP_CHECK(hipGetLastError());
     }
-    WideSelectArgs sa;
     sa.zk = wa.zk;
     sa.key_in = key_in;
     sa.score_in = score_in;
@@ -2769,17 +2808,25 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
     sa.V = V;
     sa.e = e;
     sa.transition = desc->transition;
-    sa.splits = wide_select_splits(B);
     sa.tops = reinterpret_cast<uint32_t*>(ws + plan.logp_off);
     sa.glist = reinterpret_cast<uint64_t*>(ws + plan.list_off);
     sa.gcount = reinterpret_cast<int32_t*>(ws + plan.redo_off);
     {
       const size_t lds = wide_select_lds();
       ProfileScope prof(kWideSelect, stream);
-      if (sa.splits > 1 && !verify) {
+      const size_t collect_lds = (size_t)kWideListCap * 8;
+      if (fused || (sa.splits > 1 && !verify)) {
+        rc = allow_lds(wide_collect_kernel, collect_lds);
+        if (rc != NEZHA_OK) return rc;
+      }
+      if (fused) {
+        // the bound comes from the keys the fused kernel kept
+        hipLaunchKernelGGL(wide_collect_kernel, dim3(B * sa.splits), dim3(kWideThreads), collect_lds,
+                           stream, sa);
+      } else if (sa.splits > 1 && !verify) {
         hipLaunchKernelGGL(wide_bound_kernel, dim3(B * sa.splits), dim3(kWideThreads), 0, stream, sa);
-        hipLaunchKernelGGL(wide_collect_kernel, dim3(B * sa.splits), dim3(kWideThreads), 0, stream,
-                           sa);
+        hipLaunchKernelGGL(wide_collect_kernel, dim3(B * sa.splits), dim3(kWideThreads), collect_lds,
+                           stream, sa);
       }
 #define LAUNCH_SELECT(KERN)                                                             \
   do {                                                                                  \
@@ -2787,7 +2834,7 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
     if (rc != NEZHA_OK) return rc;                                                      \
     hipLaunchKernelGGL(KERN, dim3(B), dim3(kWideThreads), lds, stream, sa);             \
   } while (0)
-      if (sa.splits > 1 || verify) {
+      if (sa.splits > 1 || verify || fused) {
         if (bf16) LAUNCH_SELECT(wide_finish_kernel<true>);
         else LAUNCH_SELECT(wide_finish_kernel<false>);
       } else {

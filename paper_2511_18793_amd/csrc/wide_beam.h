@@ -32,7 +32,7 @@ struct WideArgs {
   // where a set is consulted: the request's surviving candidates as (key, ~index), at most
   // kWideListCap per request are stored, and how many there are
   uint64_t* glist;          // [B, kWideListCap]
-  int32_t* gcount;          // [B], cleared by the logits kernel
+  int32_t* gcount;          // [B], cleared by the logits kernel (wide_fused_bf16_kernel: always)
 };
 
 // ---- logits --------------------------------------------------------------------------------
@@ -110,6 +110,150 @@ __global__ __launch_bounds__(256) void wide_logits_bf16_kernel(WideArgs a) {
   }
 }
 
+// bf16, levels where no set is consulted: the logits never reach HBM.  Two launches walk the same
+// MFMA tiles; a wave = up to 32 beams of ONE request x a contiguous share of the code tiles:
+//   wide_lse_bf16_kernel   running (max, sum of exponentials) per beam and share -> part
+//   wide_keys_bf16_kernel  log-sum-exp from the shares' parts; the logits are formed again and
+//                          written as sort keys; every lane keeps the two largest keys it wrote
+//                          (distinct candidates of one request) -> tops, from which the
+//                          selection takes its bound without another pass over the keys
+struct WideFusedArgs {
+  WideArgs w;
+  float2* part;             // [B*K_in, col_splits] (max, sum of exp(z - max))
+  uint32_t* tops;           // [B, groups * col_splits * 128]
+  int groups;               // ceil(K_in / 32)
+};
+__device__ __forceinline__ void softmax_merge(float& m, float& s, float m2, float s2) {
+  const float mn = fmaxf(m, m2);
+  s = (m == mn ? s : s * __expf(m - mn)) + (m2 == mn ? s2 : s2 * __expf(m2 - mn));
+  m = mn;
+}
+template <int KST, bool KEYS>
+__global__ __launch_bounds__(256) void wide_fused_bf16_kernel(WideFusedArgs f) {
+  const WideArgs& a = f.w;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int g = lane >> 4, c = lane & 15;
+  const int CS = a.col_splits;
+  const int64_t unit = (int64_t)blockIdx.x * 4 + wave;
+  const int64_t n_req = a.rows / a.K_in;
+  if (KEYS && blockIdx.x == 0)                           // the selection's list counters start at 0
+    for (int64_t q = threadIdx.x; q < n_req; q += 256) a.gcount[q] = 0;
+  if (unit >= n_req * f.groups * CS) return;
+  const int cs = (int)(unit % CS);
+  const int gr = (int)((unit / CS) % f.groups);
+  const int64_t b = unit / ((int64_t)CS * f.groups);
+  const int V = a.V, e = a.e, KS = e >> 5;
+  const int n_tiles = V >> 4;
+  const int t_begin = (int)((int64_t)n_tiles * cs / CS);
+  const int t_end = (int)((int64_t)n_tiles * (cs + 1) / CS);
+  const uint16_t* S = static_cast<const uint16_t*>(a.state);
+  const uint16_t* Wb = static_cast<const uint16_t*>(a.Wbeam);
+  // The wave's 32 beams are every groups-th beam of the request, starting at gr: beams enter a
+  // level ordered by score, so a run of 32 consecutive beams would put the request's best
+  // candidates into the lanes of one wave, and the two keys a lane keeps would miss most of them.
+  auto beam_of = [&](int j) { return gr + f.groups * j; };    // j = 0..31, may reach past K_in
+
+  uint4 fa[2][KST];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const int r = beam_of(16 * t + c);
+#pragma unroll
+    for (int ks = 0; ks < KST; ++ks) {
+      fa[t][ks] = uint4{0, 0, 0, 0};
+      if (S && r < a.K_in && ks < KS)
+        fa[t][ks] = load_global_u4(S + (b * a.K_in + r) * e + ks * 32 + 8 * g);
+    }
+  }
+  // per accumulator row: KEYS: (parent score - log-sum-exp, live); else running (max, sum)
+  float p0[2][4], p1[2][4];
+  bool live[2][4], in_req[2][4];
+  int64_t zoff[2][4];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r = beam_of(16 * t + 4 * g + i);
+      const int64_t row = b * a.K_in + r;
+      live[t][i] = in_req[t][i] = r < a.K_in;
+      zoff[t][i] = in_req[t][i] ? row * V : 0;
+      if constexpr (KEYS) {
+        float m = -INFINITY, sm = 0.f;
+        if (live[t][i])
+          for (int k = 0; k < CS; ++k) {
+            const float2 q = f.part[row * CS + k];
+            softmax_merge(m, sm, q.x, q.y);
+          }
+        p0[t][i] = m + __logf(sm);                                       // log-sum-exp
+        p1[t][i] = (live[t][i] && a.score_in) ? a.score_in[row] : 0.f;   // parent score
+        if (live[t][i] && a.key_in && a.key_in[row] == kEmpty) live[t][i] = false;   // no children
+      } else {
+        p0[t][i] = -INFINITY;
+        p1[t][i] = 0.f;
+      }
+    }
+  uint32_t top0 = 0, top1 = 0;
+  const float* Arow = a.A + b * V;
+  uint4 w[KST], wn[KST];
+  auto fetch = [&](uint4 (&dst)[KST], int ct) {
+#pragma unroll
+    for (int ks = 0; ks < KST; ++ks) {
+      dst[ks] = uint4{0, 0, 0, 0};
+      if (ks < KS) dst[ks] = load_global_u4(Wb + ((int64_t)(ct * KS + ks) * 64 + lane) * 8);
+    }
+  };
+  if (t_begin < t_end) fetch(w, t_begin);
+  for (int ct = t_begin; ct < t_end; ++ct) {
+    if (ct + 1 < t_end) fetch(wn, ct + 1);
+    const int col = ct * 16 + c;
+    const float a0 = as_global(Arow)[col];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      floatx4 acc = floatx4{a0, a0, a0, a0};
+#pragma unroll
+      for (int ks = 0; ks < KST; ++ks)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8*>(&fa[t][ks]),
+                                                      *reinterpret_cast<const bf16x8*>(&w[ks]), acc,
+                                                      0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if constexpr (KEYS) {
+          const uint32_t k = live[t][i] ? ordered_bits(p1[t][i] + (acc[i] - p0[t][i])) : 0u;
+          if (in_req[t][i]) as_global(a.zk)[zoff[t][i] + col] = k;
+          const uint32_t lo = k > top0 ? top0 : k;
+          top0 = k > top0 ? k : top0;
+          top1 = lo > top1 ? lo : top1;
+        } else {
+          const float mn = fmaxf(p0[t][i], acc[i]);
+          p1[t][i] = p1[t][i] * __expf(p0[t][i] - mn) + __expf(acc[i] - mn);
+          p0[t][i] = mn;
+        }
+      }
+    }
+#pragma unroll
+    for (int ks = 0; ks < KST; ++ks) w[ks] = wn[ks];
+  }
+  if constexpr (KEYS) {
+    uint32_t* tp = f.tops + (b * f.groups * CS + (int64_t)gr * CS + cs) * 128 + 2 * lane;
+    as_global(tp)[0] = top0;
+    as_global(tp)[1] = top1;
+  } else {
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float m = p0[t][i], sm = p1[t][i];
+#pragma unroll
+        for (int x = 1; x < 16; x <<= 1) {               // the 16 lanes that hold this beam's columns
+          const float m2 = __shfl_xor(m, x), s2 = __shfl_xor(sm, x);
+          softmax_merge(m, sm, m2, s2);
+        }
+        if (c == 0 && live[t][i])
+          f.part[(b * a.K_in + beam_of(16 * t + 4 * g + i)) * CS + cs] = float2{m, sm};
+      }
+  }
+}
+
 // float32: a workgroup forms 16 beams x 256 codes; the beams' states sit in LDS, a thread owns
 // one code column and walks the e rows of the beam part of W_l (coalesced across the threads).
 __global__ __launch_bounds__(256) void wide_logits_f32_kernel(WideArgs a) {
@@ -180,10 +324,15 @@ struct RadixPick {
   int need, n_eq;
   bool all;
 };
-// Exact radix selection by a workgroup of NT threads: three passes over the keys (12, 12 and 8
-// bits from the top), each a histogram in LDS of the keys that match the digits found so far.
-// hist: 4096 words of LDS, bc: 4 words of LDS.  Every thread gets the result.
-template <int NT>
+// Exact radix selection by a workgroup of NT threads: a pass for the smallest and largest nonzero
+// key, then passes over the keys for digits of up to 12 bits, starting at the highest bit in which
+// those two differ (keys of one request share their top bits; a histogram of those would be one
+// bin, and LDS atomics on one address run one after the other).  Each pass is a histogram in LDS
+// of the keys that match the digits found so far.
+// hist: 4096 + 256 words of LDS, bc: 4 words of LDS.  Every thread gets the result.
+// BOUND_ONLY: stop after the first digit; tau is then the smallest key that has that digit (the
+// low bits zero), a lower bound of the K-th largest key, and need / n_eq mean nothing.
+template <int NT, bool BOUND_ONLY = false>
 __device__ RadixPick block_radix_select(const uint32_t* keys, int64_t n, int K, uint32_t* hist,
                                         uint32_t* bc) {
   const int tid = threadIdx.x, lane = tid & 63;
@@ -192,69 +341,125 @@ __device__ RadixPick block_radix_select(const uint32_t* keys, int64_t n, int K, 
   r.need = K;
   r.n_eq = 0;
   r.all = false;
-  uint32_t prefix = 0;
+  uint32_t* psum = hist + 4096;
+  uint32_t mx = 0, mn_inv = 0, n_mine = 0;
+  for (int64_t i0 = tid; i0 < n; i0 += 8 * NT) {          // eight loads in flight per thread
+    uint32_t kk[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) kk[u] = i0 + u * NT < n ? as_global(keys)[i0 + u * NT] : 0u;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const uint32_t k = kk[u], inv = k ? ~k : 0u;
+      mx = k > mx ? k : mx;
+      mn_inv = inv > mn_inv ? inv : mn_inv;
+      n_mine += k != 0u;
+    }
+  }
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) {
+    const uint32_t o0 = (uint32_t)__shfl_xor((int)mx, m), o1 = (uint32_t)__shfl_xor((int)mn_inv, m);
+    mx = o0 > mx ? o0 : mx;
+    mn_inv = o1 > mn_inv ? o1 : mn_inv;
+    n_mine += (uint32_t)__shfl_xor((int)n_mine, m);
+  }
+  __syncthreads();                                       // psum may still be read from a call before
+  if (lane == 0) {
+    psum[3 * (tid >> 6)] = mx;
+    psum[3 * (tid >> 6) + 1] = mn_inv;
+    psum[3 * (tid >> 6) + 2] = n_mine;
+  }
+  __syncthreads();
+  uint32_t n_valid = 0;
+  mx = 0;
+  mn_inv = 0;
+  for (int w = 0; w < NT / 64; ++w) {
+    mx = psum[3 * w] > mx ? psum[3 * w] : mx;
+    mn_inv = psum[3 * w + 1] > mn_inv ? psum[3 * w + 1] : mn_inv;
+    n_valid += psum[3 * w + 2];
+  }
+  __syncthreads();
+  if (n_valid < (uint32_t)K) {                           // fewer than K keys: all of them count
+    r.all = true;
+    return r;
+  }
+  const uint32_t kmax = mx, kmin = ~mn_inv;
+  if (kmin == kmax) {                                    // every key the same
+    r.tau = kmax;
+    r.n_eq = (int)n_valid;
+    return r;
+  }
+  int remaining = 32 - __clz((int)(kmin ^ kmax));        // low bits that are not common to all keys
+  uint64_t prefix = (uint64_t)kmax >> remaining;
   int need = K;
 #pragma unroll 1
-  for (int pass = 0; pass < 3; ++pass) {
-    const int shift = pass == 0 ? 20 : pass == 1 ? 8 : 0;
-    const int bits = pass == 2 ? 8 : 12;
-    const int nb = 1 << bits;
+  while (remaining > 0) {                                // uniform: at most three rounds
+    const int bits = remaining < 12 ? remaining : 12;
+    const int shift = remaining - bits;
+    // the histogram always has 4096 or 256 bins (digits narrower than that leave the top ones empty)
+    const int nb = bits > 8 ? 4096 : 256;
     for (int i = tid; i < nb; i += NT) hist[i] = 0;
     __syncthreads();
-    for (int64_t i = tid; i < n; i += NT) {
-      const uint32_t k = as_global(keys)[i];
-      if (k != 0 && (pass == 0 || (k >> (shift + bits)) == prefix))
-        atomicAdd(&hist[(k >> shift) & (uint32_t)(nb - 1)], 1u);
+    for (int64_t i0 = tid; i0 < n; i0 += 8 * NT) {
+      uint32_t kk[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) kk[u] = i0 + u * NT < n ? as_global(keys)[i0 + u * NT] : 0u;
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (kk[u] != 0 && ((uint64_t)kk[u] >> remaining) == prefix)
+          atomicAdd(&hist[(kk[u] >> shift) & (uint32_t)((1 << bits) - 1)], 1u);
+    }
+    __syncthreads();
+    // sums of 16 bins, top first: psum[t] = bins nb-1-16t .. nb-1-16t-15
+    const int np = nb / 16;                               // 256 or 16
+    if (tid < np) {
+      uint32_t sum = 0;
+      for (int i = 0; i < 16; ++i) sum += hist[nb - 1 - (16 * tid + ((i + tid) & 15))];
+      psum[tid] = sum;
     }
     __syncthreads();
     if (tid < 64) {
-      // lane l owns the bins nb-1 - (l*per .. l*per+per-1), i.e. walks down from the top
-      const int per = nb / 64;
+      // lane l owns psum[4l .. 4l+3] (nothing when np is 16 and l >= 4)
       uint32_t mine = 0;
-      for (int i = 0; i < per; ++i) {
-        const int j = (i + lane) % per;                 // skewed: the lanes hit different banks
-        mine += hist[nb - 1 - (lane * per + j)];
-      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) mine += 4 * lane + i < np ? psum[4 * lane + i] : 0u;
       uint32_t incl = mine;
 #pragma unroll
       for (int m = 1; m < 64; m <<= 1) {
         const uint32_t up = __shfl_up(incl, m);
         if (lane >= m) incl += up;
       }
-      const uint32_t total = __shfl(incl, 63);
+      // the keys that match `prefix` number at least `need`, so some lane reaches it
       const uint64_t reach = __ballot(incl >= (uint32_t)need);
-      if (total < (uint32_t)need) {
-        if (lane == 0) bc[0] = 0xFFFFFFFFu;             // fewer than `need` keys (first pass only)
-      } else {
-        const int first = __ffsll((unsigned long long)reach) - 1;
-        if (lane == first) {
-          uint32_t above = incl - mine;                 // keys in bins above this lane's
-          int digit = nb - 1 - lane * per;
-          for (int i = 0; i < per; ++i, --digit) {
-            const uint32_t h = hist[digit];
-            if (above + h >= (uint32_t)need) {
-              bc[0] = (uint32_t)digit;
-              bc[1] = above;
-              bc[2] = h;
-              break;
-            }
-            above += h;
+      const int first = __ffsll((unsigned long long)reach) - 1;
+      if (lane == first) {
+        uint32_t above = incl - mine;                   // keys in the bins above this lane's
+        int pi = 4 * lane;
+        while (above + psum[pi] < (uint32_t)need) above += psum[pi++];   // ends inside the lane's four
+        int digit = nb - 1 - 16 * pi;
+        for (int i = 0; i < 16; ++i, --digit) {
+          const uint32_t h = hist[digit];
+          if (above + h >= (uint32_t)need) {
+            bc[0] = (uint32_t)digit;
+            bc[1] = above;
+            bc[2] = h;
+            break;
           }
+          above += h;
         }
       }
     }
     __syncthreads();
-    const uint32_t digit = bc[0];
-    if (digit == 0xFFFFFFFFu) {
-      r.all = true;
-      return r;
-    }
     need -= (int)bc[1];
     r.n_eq = (int)bc[2];
-    prefix = (prefix << bits) | digit;
+    prefix = (prefix << bits) | bc[0];
+    remaining = shift;
     __syncthreads();                                    // bc and hist are reused by the next pass
+    if constexpr (BOUND_ONLY) {
+      r.tau = (uint32_t)(prefix << remaining);
+      return r;
+    }
   }
-  r.tau = prefix;
+  r.tau = (uint32_t)prefix;
   r.need = need;
   return r;
 }
@@ -469,7 +674,7 @@ __global__ __launch_bounds__(kWideRowThreads) void wide_rows_kernel(WideArgs a) 
   constexpr int NT = kWideRowThreads;
   constexpr bool kRegs = NV > 0;
   __shared__ float red[NT / 64];
-  __shared__ uint32_t hist[VERIFY ? (kRegs ? 256 : 4096) : 1];
+  __shared__ uint32_t hist[VERIFY ? (kRegs ? 256 : 4096 + 256) : 1];
   __shared__ uint64_t cand[VERIFY && kRegs ? NEZHA_MAX_WIDE_BEAM : 1];    // (key, code) of the survivors
   __shared__ uint32_t bc[4];
   __shared__ int cnt[NT / 64];
@@ -639,7 +844,9 @@ struct WideSelectArgs {
   int K_in, K, V, e, transition;
   // when a request is shared by `splits` > 1 workgroups (small batches):
   int splits;
-  uint32_t* tops;           // [B, splits, K] each share's K largest keys
+  int n_tops;               // keys per request in tops
+  uint32_t* tops;           // [B, n_tops] distinct candidates of the request (each share's K largest,
+                            // or what wide_fused_bf16_kernel kept), among them the bound is sought
   uint64_t* glist;          // [B, kWideListCap] (key, ~index) at or above the bound
   int32_t* gcount;          // [B]
 };
@@ -662,7 +869,7 @@ struct WideLds {
   int32_t* fin_code;     // [1024]
   uint32_t* bc;          // [4]
   int* n_list;           // [1]
-  uint32_t* hist;        // 4096 words inside list (exact selection only)
+  uint32_t* hist;        // 4096 + 256 words inside list (exact selection only)
 };
 __device__ __forceinline__ WideLds wide_lds_layout(uint64_t* base) {
   WideLds l;
@@ -890,18 +1097,32 @@ __global__ __launch_bounds__(kWideThreads) void wide_bound_kernel(WideSelectArgs
 
 __global__ __launch_bounds__(kWideThreads) void wide_collect_kernel(WideSelectArgs a) {
   constexpr int NT = kWideThreads;
-  __shared__ uint32_t hist[4096];
+  // the histogram of the bound search, then this workgroup's part of the list (kWideListCap
+  // entries: one reservation in the request's list per workgroup, not one per wave)
+  extern __shared__ __align__(16) uint64_t wide_lds[];
   __shared__ uint32_t bc[4];
-  const int b = blockIdx.x / a.splits, s = blockIdx.x - b * a.splits;
+  __shared__ int n_local, base;
+  uint32_t* hist = reinterpret_cast<uint32_t*>(wide_lds);
+  uint64_t* list = wide_lds;
+  const int b = blockIdx.x / a.splits, s = blockIdx.x - b * a.splits, tid = threadIdx.x;
   const int64_t n = (int64_t)a.K_in * a.V, n4 = n >> 2;
   const uint32_t* keys = a.zk + (int64_t)b * n;
-  const RadixPick p = block_radix_select<NT>(a.tops + (int64_t)b * a.splits * a.K,
-                                             (int64_t)a.splits * a.K, a.K, hist, bc);
+  // any lower bound of the K-th largest of these keys will do: one digit is enough
+  const RadixPick p = block_radix_select<NT, true>(a.tops + (int64_t)b * a.n_tops, a.n_tops, a.K, hist,
+                                                   bc);
   const uint32_t tau0 = p.all ? 1u : p.tau;              // fewer than K candidates seen: take all
-  uint64_t* glist = a.glist + (int64_t)b * kWideListCap;
+  if (tid == 0) n_local = 0;
+  __syncthreads();
   wide_collect(keys, n4 * s / a.splits, n4 * (s + 1) / a.splits, tau0,
-               [&](int c) { return atomicAdd(&a.gcount[b], c); },
-               [&](int pos, uint64_t v) { glist[pos] = v; });
+               [&](int c) { return atomicAdd(&n_local, c); },
+               [&](int pos, uint64_t v) { list[pos] = v; });
+  __syncthreads();
+  const int m = n_local;                                 // may exceed what was stored: then the
+  if (tid == 0) base = atomicAdd(&a.gcount[b], m);       // request's count exceeds the cap as well
+  __syncthreads();
+  uint64_t* glist = a.glist + (int64_t)b * kWideListCap;
+  for (int i = tid; i < m && i < kWideListCap; i += NT)
+    if (base + i < kWideListCap) glist[base + i] = list[i];
 }
 
 template <bool BF16>
