@@ -583,9 +583,12 @@ __device__ RadixPick regs_radix_select(const uint32_t (&key)[NV], int K, uint32_
     const int nb = 1 << bits;
     if (tid < 256) hist[tid] = 0;
     __syncthreads();
+    // (32-bit forms of "the bits above `remaining` equal pre"; remaining == 32: no such bits)
+    const uint32_t hi_mask = remaining >= 32 ? 0u : ~0u << remaining;
+    const uint32_t hi_want = remaining >= 32 ? 0u : (uint32_t)pre << remaining;
 #pragma unroll
     for (int j = 0; j < NV; ++j)
-      if (key[j] != 0u && ((uint64_t)key[j] >> remaining) == pre)
+      if (key[j] != 0u && (key[j] & hi_mask) == hi_want)
         atomicAdd(&hist[(key[j] >> shift) & (uint32_t)(nb - 1)], 1u);
     __syncthreads();
     if (tid < 64) {
@@ -679,6 +682,7 @@ __global__ __launch_bounds__(kWideRowThreads) void wide_rows_kernel(WideArgs a) 
   __shared__ uint32_t bc[4];
   __shared__ int cnt[NT / 64];
   __shared__ uint64_t kept[VERIFY ? NEZHA_MAX_WIDE_BEAM : 1];            // those found in the set
+  __shared__ uint32_t member[VERIFY && kRegs ? NV * NT / 32 : 1];         // the same as a bitmap over the codes
   __shared__ int n_cand, n_kept, kept_base;
   const int64_t row = blockIdx.x;
   const int V = a.V, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -708,7 +712,7 @@ __global__ __launch_bounds__(kWideRowThreads) void wide_rows_kernel(WideArgs a) 
     m = block_max<NT>(m, red);
     float s = 0.f;
 #pragma unroll
-    for (int j = 0; j < NV; ++j) s += expf(z[j] - m);
+    for (int j = 0; j < NV; ++j) s += __expf(z[j] - m);
     s = block_sum<NT>(s, red);
     const float lse = m + logf(s);
     uint32_t key[NV];
@@ -757,11 +761,14 @@ __global__ __launch_bounds__(kWideRowThreads) void wide_rows_kernel(WideArgs a) 
             running += total;
             if (tie) take = before + __popcll(bal & ((1ull << lane) - 1ull)) < p.need;
           }
-          if (take)
-            cand[atomicAdd(&n_cand, 1)] = ((uint64_t)key[j] << 32) | (uint32_t)v;   // K entries in all
-          else if (v < V)
-            as_global(zk)[v] = 0u;
+          // one LDS reservation per wave (atomics on one address run one after the other)
+          const uint64_t tb = __ballot(take);
+          int at = 0;
+          if (lane == 0 && tb) at = atomicAdd(&n_cand, __popcll(tb));
+          at = __shfl(at, 0) + __popcll(tb & ((1ull << lane) - 1ull));
+          if (take) cand[at] = ((uint64_t)key[j] << 32) | (uint32_t)v;    // K entries in all
         }
+        if (tid < NV * NT / 32) member[tid] = 0u;
         __syncthreads();
         const int n = n_cand;
         for (int i = tid; i < n; i += 2 * NT) {
@@ -770,10 +777,22 @@ __global__ __launch_bounds__(kWideRowThreads) void wide_rows_kernel(WideArgs a) 
           bool in0, in1;
           set_contains_pair(a.set, pkey + (uint64_t)(uint32_t)c0 * a.mult, true,
                             pkey + (uint64_t)(uint32_t)c1 * a.mult, live1, in0, in1);
-          as_global(zk)[(uint32_t)c0] = in0 ? (uint32_t)(c0 >> 32) : 0u;
-          if (live1) as_global(zk)[(uint32_t)c1] = in1 ? (uint32_t)(c1 >> 32) : 0u;
-          if (in0) keep((int)(uint32_t)c0, (uint32_t)(c0 >> 32));
-          if (in1) keep((int)(uint32_t)c1, (uint32_t)(c1 >> 32));
+          if (in0) {
+            atomicOr(&member[(uint32_t)c0 >> 5], 1u << ((uint32_t)c0 & 31u));
+            keep((int)(uint32_t)c0, (uint32_t)(c0 >> 32));
+          }
+          if (in1) {
+            atomicOr(&member[(uint32_t)c1 >> 5], 1u << ((uint32_t)c1 & 31u));
+            keep((int)(uint32_t)c1, (uint32_t)(c1 >> 32));
+          }
+        }
+        // the row is written by the threads that hold its keys, in full lines: survivors keep
+        // their key, everything else becomes 0
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+          const int v = tid + j * NT;
+          if (v < V) as_global(zk)[v] = (member[v >> 5] >> (v & 31)) & 1u ? key[j] : 0u;
         }
       }
     }
