@@ -32,6 +32,8 @@ def _run(oracle, cfg, seed, N, verify=True, **kw):
     (5, 64, 128, 4096, 129, 2, "bf16"),     # large codebook
     (2, 64, 64, 8192, 140, 2, "bf16"),      # a codebook too large for a beam's logits to stay in registers
     (256, 32, 32, 256, 130, 3, "bf16"),     # a batch large enough for one workgroup per request
+    (1, 32, 32, 1024, 1024, 2, "bf16"),     # the widest beam there is (= the codebook: no per-beam cut)
+    (1, 32, 64, 2048, 1024, 2, "f32"),      # the widest beam, cut from 2048 codes, float32
 ])
 def test_wide_beam_shapes(oracle, B, d, e, V, K, L, dtype):
     cfg = synth.StepConfig("widebeam", B=B, d=d, e=e, L=L, V=V, K=K, N=min(V ** L // 4, 200_000),
@@ -111,6 +113,31 @@ def test_wide_beam_recurrent_transition_and_prefix_sets(oracle):
     torch.cuda.synchronize()
     soft = check_decode(oracle, nz, cfg, x, outs, oset, tolerance(cfg), U=U, prefix_sets=opre)
     assert soft <= 16
+    assert int(outs[-1]["count"].sum()) > 0
+
+
+def test_wide_beam_with_empty_beam_slots(oracle):
+    """A catalog with few first-level codes and prefix sets: level 1 keeps fewer than K beams, so
+    levels 2 and 3 see empty slots (index 2^64-1, score -inf) among their parents."""
+    cfg = synth.StepConfig("widebeam", B=3, d=64, e=64, L=3, V=512, K=200, N=40_000, dtype="bf16",
+                           catalog="uniform", w_std=0.05)
+    x, cat = planted_workload(oracle, cfg, 31, cfg.N)
+    first = np.unique(cat[:, 0])
+    cat = cat[np.isin(cat[:, 0], first[:150])]
+    oset = oracle.ItemSet(cat, cfg.radices)
+    gset = nz.build_itemset(cat, cfg.radices, cfg.load_factor)
+    opre, gpre = [], []
+    for l in range(1, cfg.L):
+        pre = np.unique(cat[:, :l], axis=0)
+        opre.append(oracle.ItemSet(pre, cfg.radices[:l]))
+        gpre.append(nz.build_itemset(pre, cfg.radices[:l], cfg.load_factor))
+    H, W, E = to_device(x, cfg)
+    outs = nz.decode(H, W, E, cfg.radices, cfg.K, gset, prefix_sets=gpre)
+    torch.cuda.synchronize()
+    soft = check_decode(oracle, nz, cfg, x, outs, oset, tolerance(cfg), prefix_sets=opre)
+    assert soft <= 16
+    c1 = to_np(outs[0]["count"])                        # of a beam's 200 best codes only the valid stay
+    assert c1.max() < cfg.K and c1.min() > 0
     assert int(outs[-1]["count"].sum()) > 0
 
 
