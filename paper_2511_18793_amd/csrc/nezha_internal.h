@@ -102,6 +102,36 @@ __device__ __forceinline__ bool set_contains(const SetView& s, uint64_t key) {
   return false;
 }
 
+// Membership of N keys with all N home buckets in flight at once (the probes of one lane are
+// independent random lines; one at a time leaves the memory system idle).  live[i] == false:
+// key i is not looked up and in[i] is false.
+template <int N>
+__device__ __forceinline__ void set_contains_many(const SetView& s, const uint64_t (&key)[N],
+                                                  const bool (&live)[N], bool (&in)[N]) {
+  ulonglong2 q[N][4];
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    const uint64_t* p = s.slots + (live[i] ? home_bucket(key[i], s.n_buckets) : 0) * kBucketSlots;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      q[i][c] = ulonglong2{kEmpty, kEmpty};
+      if (live[i]) q[i][c] = load_global_u64x2(p + 2 * c);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    bool hit = false, hole = false;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      hit |= (q[i][c].x == key[i]) | (q[i][c].y == key[i]);
+      hole |= (q[i][c].x == kEmpty) | (q[i][c].y == kEmpty);
+    }
+    in[i] = live[i] && hit;
+    // a full home bucket without the key (rare at the load factors in use): the general scan
+    if (live[i] && !hit && !hole) in[i] = set_contains(s, key[i]);
+  }
+}
+
 }  // namespace nezha
 
 struct nezha_itemset {

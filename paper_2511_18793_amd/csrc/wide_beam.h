@@ -638,32 +638,12 @@ __device__ RadixPick regs_radix_select(const uint32_t (&key)[NV], int K, uint32_
 // Set membership of two keys with both home buckets in flight at once.
 __device__ __forceinline__ void set_contains_pair(const SetView& s, uint64_t k0, bool live0,
                                                   uint64_t k1, bool live1, bool& in0, bool& in1) {
-  const uint64_t b0 = live0 ? home_bucket(k0, s.n_buckets) : 0, b1 = live1 ? home_bucket(k1, s.n_buckets) : 0;
-  ulonglong2 q[4], t[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    q[i] = ulonglong2{kEmpty, kEmpty};
-    t[i] = ulonglong2{kEmpty, kEmpty};
-  }
-  if (live0)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) q[i] = load_global_u64x2(s.slots + b0 * kBucketSlots + 2 * i);
-  if (live1)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) t[i] = load_global_u64x2(s.slots + b1 * kBucketSlots + 2 * i);
-  bool hit0 = false, hole0 = false, hit1 = false, hole1 = false;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    hit0 |= (q[i].x == k0) | (q[i].y == k0);
-    hole0 |= (q[i].x == kEmpty) | (q[i].y == kEmpty);
-    hit1 |= (t[i].x == k1) | (t[i].y == k1);
-    hole1 |= (t[i].x == kEmpty) | (t[i].y == kEmpty);
-  }
-  in0 = live0 && hit0;
-  in1 = live1 && hit1;
-  // a full home bucket without the key (rare at the load factors in use): the general scan
-  if (live0 && !hit0 && !hole0) in0 = set_contains(s, k0);
-  if (live1 && !hit1 && !hole1) in1 = set_contains(s, k1);
+  const uint64_t key[2] = {k0, k1};
+  const bool live[2] = {live0, live1};
+  bool in[2];
+  set_contains_many<2>(s, key, live, in);
+  in0 = in[0];
+  in1 = in[1];
 }
 
 // One workgroup per beam.  VERIFY: a set is consulted at this level, so the beam is cut to its K
