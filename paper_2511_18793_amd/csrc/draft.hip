@@ -2501,6 +2501,10 @@ int nezha_user_projection_levels(const nezha_step_desc* desc, int32_t n_levels,
   if (desc->dtype != NEZHA_BF16 || !desc->w_packed)
     return fail(NEZHA_EINVAL, "needs NEZHA_BF16 weights packed by nezha_pack_weights");
   if (!H || !W_packed || !A_out) return fail(NEZHA_EINVAL, "a pointer array is NULL");
+  // small projections are bound by the length of the k loop, not by the tile: 32 x 64 tiles by two
+  // waves give the chip more workgroups than 64 x 64 ones (9.2 against 10.5 us for three 256 x 512
+  // x 256 products)
+  constexpr int kGroupedBM = 32, kGroupedBN = 64;
   GemmGroup grp;
   grp.n = n_levels;
   int tiles = 0;
@@ -2518,9 +2522,9 @@ int nezha_user_projection_levels(const nezha_step_desc* desc, int32_t n_levels,
     grp.Wu[i] = static_cast<const uint16_t*>(W_packed[i]);
     grp.A[i] = A_out[i];
     grp.V[i] = V;
-    grp.tiles_n[i] = (V + 63) / 64;
+    grp.tiles_n[i] = (V + kGroupedBN - 1) / kGroupedBN;
     grp.tile_begin[i] = tiles;
-    tiles += ((B + 63) / 64) * grp.tiles_n[i];
+    tiles += ((B + kGroupedBM - 1) / kGroupedBM) * grp.tiles_n[i];
   }
   grp.tile_begin[n_levels] = tiles;
   for (int i = n_levels; i < NEZHA_MAX_LEVELS; ++i) {
@@ -2546,9 +2550,9 @@ int nezha_user_projection_levels(const nezha_step_desc* desc, int32_t n_levels,
     }
     return NEZHA_OK;
   }
-  const size_t lds = (size_t)kGemmBuffers * (64 * 4) * sizeof(uint4);
+  const size_t lds = (size_t)kGemmBuffers * (kGroupedBM * 4) * sizeof(uint4);
   ProfileScope prof(kUserGemm, stream);
-  hipLaunchKernelGGL((user_gemm_bf16_grouped_kernel<2, 2, 1, 1>), dim3(tiles), dim3(256), lds, stream,
+  hipLaunchKernelGGL((user_gemm_bf16_grouped_kernel<1, 2, 1, 1>), dim3(tiles), dim3(128), lds, stream,
                      grp, desc->h_row_stride, B, d);
   NEZHA_HIP_CHECK(hipGetLastError());
   return NEZHA_OK;
