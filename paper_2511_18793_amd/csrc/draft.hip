@@ -290,7 +290,10 @@ __device__ __forceinline__ void load_block_to_lds(const void* gptr, void* lds_bl
 // barrier per stage.  Workgroup ids are remapped so that the tiles that run on one XCD (ids
 // equal modulo 8) are neighbours and share its L2.
 constexpr int kGemmBuffers = 4;
-template <int NWM, int NWN, int TM, int TN>
+// KSPLIT > 1 (small problems, whose time is the length of the k loop): the workgroup has KSPLIT
+// groups of NWM x NWN waves, group s takes the s-th part of k with its own H buffers, and the
+// groups' partial results are added through LDS at the end (d must be a multiple of 32 * KSPLIT).
+template <int NWM, int NWN, int TM, int TN, int KSPLIT = 1>
 __device__ __forceinline__ void user_gemm_tile(
     const uint16_t* __restrict__ H, int64_t h_stride, const uint16_t* __restrict__ Wu,
     float* __restrict__ A, int B, int d, int V, int tiles_n, int tiles_total, int tile_id) {
@@ -299,8 +302,10 @@ __device__ __forceinline__ void user_gemm_tile(
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
   constexpr int CT = BN / 32;                        // 32-column tiles per workgroup
   constexpr int ASLOTS = BM * 4;                     // 16-byte slots of the H tile (64 B per row)
-  extern __shared__ __align__(16) uint4 smem[];      // [kGemmBuffers][H tile]
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  extern __shared__ __align__(16) uint4 smem_all[];  // [KSPLIT][kGemmBuffers][H tile]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int ksplit = (tid >> 6) / NW, wave = (tid >> 6) % NW;   // wave: index inside its group
+  uint4* const smem = smem_all + ksplit * kGemmBuffers * ASLOTS;
   const int wm = wave / NWN, wn = wave % NWN;
   // Workgroup ids equal modulo 8 run on the same XCD.  When the grid allows it every XCD gets
   // 4 x 8 blocks of tiles (4 H panels and 8 W panels live in its L2 at a time); otherwise a
@@ -322,7 +327,8 @@ __device__ __forceinline__ void user_gemm_tile(
   const int row0 = tile_m * BM, ct0 = tile_n * CT;
   const int n_ct = (V + 31) / 32;
   const int KSu = d / 16;
-  const int stages = d / 32;
+  const int stages = d / 32 / KSPLIT;                // of this group
+  const int stage0 = ksplit * stages;                // its first stage in the whole k range
 
   floatx16 acc[TM][TN];
 #pragma unroll
@@ -363,12 +369,12 @@ __device__ __forceinline__ void user_gemm_tile(
     for (int u = 0; u < APW; ++u) {
       int ins = wave + NW * u;
       ins = ins < AINS ? ins : AINS - 1;
-      load_block_to_lds(a_ptr[u] + stage * 32, sa + ins * 64);
+      load_block_to_lds(a_ptr[u] + (stage0 + stage) * 32, sa + ins * 64);
     }
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-      for (int j = 0; j < TN; ++j) b[ks][j] = b_ptr[j][(stage * 2 + ks) * 64];
+      for (int j = 0; j < TN; ++j) b[ks][j] = b_ptr[j][((stage0 + stage) * 2 + ks) * 64];
   };
   // LDS slot of this lane's A operand for row tile i, step ks: row = (wm*TM+i)*32 + lane%32,
   // chunk = 2*ks + lane/32, slot = row*4 + (chunk ^ (row/4)%4)
@@ -431,6 +437,34 @@ __device__ __forceinline__ void user_gemm_tile(
       }
     }
   }
+  if constexpr (KSPLIT > 1) {
+    // partial results of the groups 1.. -> LDS (over the H buffers, which nobody reads any more),
+    // group 0 adds them to its own
+    __syncthreads();
+    float* red = reinterpret_cast<float*>(smem_all);
+    constexpr int PER_WAVE = TM * TN * 16 * 64;
+    if (ksplit > 0) {
+      float* mine = red + ((ksplit - 1) * NW + wave) * PER_WAVE;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mine[((i * TN + j) * 16 + r) * 64 + lane] = acc[i][j][r];
+    }
+    __syncthreads();
+    if (ksplit > 0) return;
+#pragma unroll
+    for (int g = 1; g < KSPLIT; ++g) {
+      const float* theirs = red + ((g - 1) * NW + wave) * PER_WAVE;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[i][j][r] += theirs[((i * TN + j) * 16 + r) * 64 + lane];
+    }
+  }
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -445,11 +479,12 @@ __device__ __forceinline__ void user_gemm_tile(
     }
 }
 
-template <int NWM, int NWN, int TM, int TN>
-__global__ __launch_bounds__(64 * NWM * NWN, 1) void user_gemm_bf16_kernel(
+template <int NWM, int NWN, int TM, int TN, int KSPLIT = 1>
+__global__ __launch_bounds__(64 * NWM * NWN * KSPLIT, 1) void user_gemm_bf16_kernel(
     const uint16_t* __restrict__ H, int64_t h_stride, const uint16_t* __restrict__ Wu,
     float* __restrict__ A, int B, int d, int V, int tiles_n, int tiles_total) {
-  user_gemm_tile<NWM, NWN, TM, TN>(H, h_stride, Wu, A, B, d, V, tiles_n, tiles_total, blockIdx.x);
+  user_gemm_tile<NWM, NWN, TM, TN, KSPLIT>(H, h_stride, Wu, A, B, d, V, tiles_n, tiles_total,
+                                           blockIdx.x);
 }
 
 // Several levels' projections in one launch: they do not depend on each other (all the hidden
@@ -463,14 +498,14 @@ struct GemmGroup {
   int tile_begin[NEZHA_MAX_LEVELS + 1];
   int n;
 };
-template <int NWM, int NWN, int TM, int TN>
-__global__ __launch_bounds__(64 * NWM * NWN, 1) void user_gemm_bf16_grouped_kernel(
+template <int NWM, int NWN, int TM, int TN, int KSPLIT>
+__global__ __launch_bounds__(64 * NWM * NWN * KSPLIT, 1) void user_gemm_bf16_grouped_kernel(
     GemmGroup grp, int64_t h_stride, int B, int d) {
   int p = 0;
   while (p + 1 < grp.n && (int)blockIdx.x >= grp.tile_begin[p + 1]) ++p;
   // an odd tile count defeats the XCD remapping inside, which is what small problems want
-  user_gemm_tile<NWM, NWN, TM, TN>(grp.H[p], h_stride, grp.Wu[p], grp.A[p], B, d, grp.V[p],
-                                   grp.tiles_n[p], 1, (int)blockIdx.x - grp.tile_begin[p]);
+  user_gemm_tile<NWM, NWN, TM, TN, KSPLIT>(grp.H[p], h_stride, grp.Wu[p], grp.A[p], B, d, grp.V[p],
+                                           grp.tiles_n[p], 1, (int)blockIdx.x - grp.tile_begin[p]);
 }
 
 // ---- user-part projection, fp32 (small correctness-first shapes) -----------------------------
@@ -2407,6 +2442,9 @@ int allow_lds(Kern kern, size_t bytes) {
   return NEZHA_OK;
 }
 
+// Small user-part products run their k loop in four parts side by side (user_gemm_tile, KSPLIT).
+inline bool small_gemm_splits_k(int d) { return (d / 32) % 4 == 0 && d >= 256; }
+
 int launch_pack(const nezha_step_desc* desc, const void* W_l, uint16_t* Wp, hipStream_t stream) {
   const int d = desc->d, e = desc->e, V = desc->radices[desc->level - 1];
   const int64_t total = (int64_t)((V + 31) / 32) * (d / 16) * 64 + (int64_t)(V / 16) * (e / 32) * 64;
@@ -2431,21 +2469,25 @@ int launch_user_part(const nezha_step_desc* desc, const void* H_l, const void* W
     }
     ProfileScope prof(kUserGemm, stream);
     const uint16_t* Hp = static_cast<const uint16_t*>(H_l);
-#define LAUNCH_GEMM(NWM, NWN, TM, TN)                                                          \
+#define LAUNCH_GEMM(NWM, NWN, TM, TN, KSPLIT)                                                  \
   do {                                                                                         \
     constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;                                      \
     const int tiles_m = (B + BM - 1) / BM, tiles_n = (V + BN - 1) / BN;                        \
-    const size_t lds = (size_t)kGemmBuffers * (BM * 4) * sizeof(uint4);                        \
-    rc = allow_lds(user_gemm_bf16_kernel<NWM, NWN, TM, TN>, lds);                              \
+    const size_t lds = (size_t)KSPLIT * kGemmBuffers * (BM * 4) * sizeof(uint4);               \
+    rc = allow_lds(user_gemm_bf16_kernel<NWM, NWN, TM, TN, KSPLIT>, lds);                      \
     if (rc != NEZHA_OK) return rc;                                                             \
-    hipLaunchKernelGGL((user_gemm_bf16_kernel<NWM, NWN, TM, TN>), dim3(tiles_m * tiles_n),     \
-                       dim3(64 * NWM * NWN), lds, stream, Hp, desc->h_row_stride,              \
-                       (const uint16_t*)Wp, A, B, d, V, tiles_n, tiles_m * tiles_n);           \
+    hipLaunchKernelGGL((user_gemm_bf16_kernel<NWM, NWN, TM, TN, KSPLIT>),                      \
+                       dim3(tiles_m * tiles_n), dim3(64 * NWM * NWN * KSPLIT), lds, stream, Hp, \
+                       desc->h_row_stride, (const uint16_t*)Wp, A, B, d, V, tiles_n,           \
+                       tiles_m * tiles_n);                                                     \
   } while (0)
     const int64_t out_elems = (int64_t)B * V;
-    if (out_elems >= (int64_t)256 * 256 * 128) LAUNCH_GEMM(2, 4, 4, 2);       // 256 x 256 tiles
-    else if (out_elems >= (int64_t)128 * 128 * 64) LAUNCH_GEMM(2, 2, 2, 2);   // 128 x 128 tiles
-    else LAUNCH_GEMM(2, 2, 1, 1);                                              // 64 x 64 tiles
+    if (out_elems >= (int64_t)256 * 256 * 128) LAUNCH_GEMM(2, 4, 4, 2, 1);       // 256 x 256 tiles
+    else if (out_elems >= (int64_t)128 * 128 * 64) LAUNCH_GEMM(2, 2, 2, 2, 1);   // 128 x 128 tiles
+    // small products: the same tiles and the same order of summation as the grouped launch of
+    // nezha_user_projection_levels, so that both give the same bits
+    else if (small_gemm_splits_k(d)) LAUNCH_GEMM(1, 2, 1, 1, 4);                  // 32 x 64, k in four parts
+    else LAUNCH_GEMM(1, 2, 1, 1, 1);                                              // 32 x 64 tiles
 #undef LAUNCH_GEMM
     NEZHA_HIP_CHECK(hipGetLastError());
   } else {
@@ -2550,10 +2592,19 @@ int nezha_user_projection_levels(const nezha_step_desc* desc, int32_t n_levels,
     }
     return NEZHA_OK;
   }
-  const size_t lds = (size_t)kGemmBuffers * (kGroupedBM * 4) * sizeof(uint4);
   ProfileScope prof(kUserGemm, stream);
-  hipLaunchKernelGGL((user_gemm_bf16_grouped_kernel<1, 2, 1, 1>), dim3(tiles), dim3(128), lds, stream,
-                     grp, desc->h_row_stride, B, d);
+  if (small_gemm_splits_k(d)) {
+    // the k range in four parts, each by its own pair of waves; LDS: the four groups' H buffers,
+    // later three groups' partial results (2 waves x 16 x 64 floats each)
+    constexpr size_t lds = (size_t)4 * kGemmBuffers * (kGroupedBM * 4) * sizeof(uint4);
+    static_assert(lds >= (size_t)3 * 2 * 16 * 64 * 4, "room for the partial results");
+    hipLaunchKernelGGL((user_gemm_bf16_grouped_kernel<1, 2, 1, 1, 4>), dim3(tiles), dim3(512), lds,
+                       stream, grp, desc->h_row_stride, B, d);
+  } else {
+    const size_t lds = (size_t)kGemmBuffers * (kGroupedBM * 4) * sizeof(uint4);
+    hipLaunchKernelGGL((user_gemm_bf16_grouped_kernel<1, 2, 1, 1, 1>), dim3(tiles), dim3(128), lds,
+                       stream, grp, desc->h_row_stride, B, d);
+  }
   NEZHA_HIP_CHECK(hipGetLastError());
   return NEZHA_OK;
 }
