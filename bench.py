@@ -57,8 +57,12 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="serving")
     ap.add_argument("--seed", type=int, default=42)
-    ap.add_argument("--eager", action="store_true",
-                    help="launch every step through the C ABI instead of replaying a HIP graph")
+    ap.add_argument("--launch", choices=("auto", "direct", "graph"), default="auto",
+                    help="how a step reaches the GPU: 'direct' = one call of the C ABI per step "
+                         "(nezha_decode where it applies), 'graph' = replay of a HIP graph that "
+                         "holds the step; 'auto' = direct where one call per step applies (bf16, "
+                         "weights packed at set-up), else graph")
+    ap.add_argument("--eager", action="store_true", help="same as --launch direct")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pack-per-call", action="store_true",
                     help="rearrange the weights inside every step instead of once at set-up")
@@ -170,12 +174,26 @@ def bench_draft(args, cfg):
     if cfg.dtype == "bf16" and not args.pack_per_call:
         Wrun = [nz.pack_weights(l + 1, cfg.L, cfg.radices, W[l], cfg.d) for l in range(cfg.L)]
 
-    def step():
-        nz.decode(H, Wrun, E, cfg.radices, cfg.K, itemset, buffers=bufs, U=U,
-                  prefix_sets=prefix_sets)
+    plan = None
+    if cfg.dtype == "bf16" and not args.pack_per_call:
+        # everything a decode needs, marshalled once: a step is one call of nezha_decode
+        plan = nz.DecodePlan(H, Wrun, E, cfg.radices, cfg.K, itemset, buffers=bufs, U=U,
+                             prefix_sets=prefix_sets)
 
+    def step():
+        if plan is not None:
+            plan.run()
+        else:
+            nz.decode(H, Wrun, E, cfg.radices, cfg.K, itemset, buffers=bufs, U=U,
+                      prefix_sets=prefix_sets)
+
+    launch = "direct" if args.eager else args.launch
+    if launch == "auto":
+        # one host call per step keeps the GPU busy without a graph (replaying a two-kernel graph
+        # costs about 8 us between replays on this stack); the Python level loop does not
+        launch = "direct" if plan is not None else "graph"
     graph = None
-    if not args.eager:
+    if launch == "graph":
         step()
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
@@ -279,7 +297,9 @@ def bench_draft(args, cfg):
                    "V": cfg.V, "K": cfg.K, "catalog_items": int(catalog.shape[0]),
                    "load_factor": cfg.load_factor, "candidates_per_step": cands,
                    "accepted_per_step": accepted, "hallucinated_topk_frac": round(hallucinated, 3),
-                   "launch": "eager" if args.eager else "hip_graph_replay",
+                   "launch": ("direct: one nezha_decode call per step" if plan is not None
+                              else "direct: one nezha_draft_step call per level")
+                   if launch == "direct" else "hip_graph_replay",
                    "weights": "packed per call" if (args.pack_per_call or cfg.dtype != "bf16")
                    else "packed once at set-up",
                    "transition": args.transition, "prefix_sets": bool(args.prefix_sets),

@@ -199,6 +199,16 @@ int nezha_draft_levels(const nezha_step_desc* desc, const nezha_level_io* io, vo
                        size_t workspace_bytes, void* hip_stream);
 size_t nezha_draft_levels_workspace(const nezha_step_desc* desc); /* 0 if desc is invalid */
 
+/* One decode of a batch in one call: the user parts of all L levels (the beam-independent part
+ * of Eq. 2, as nezha_user_projection_levels forms them) followed by the L levels of the loop of
+ * Alg. 3 (as nezha_draft_levels runs them).  NEZHA_BF16 with desc->w_packed = 1 only.  io as for
+ * nezha_draft_levels, with every io[l-1].H_l given and every io[l-1].user_part pointing to
+ * float32 [B, T_l] device memory that this call WRITES (the level's user part) before the level
+ * reads it.  A serving loop that calls this once per batch pays one host call per decode.
+ * Asynchronous on hip_stream; allocates nothing; workspace as for nezha_draft_levels. */
+int nezha_decode(const nezha_step_desc* desc, const nezha_level_io* io, void* workspace,
+                 size_t workspace_bytes, void* hip_stream);
+
 /* The user parts of levels 1..n_levels in one launch.  They do not depend on the beams, and all
  * hidden states h_1..h_L come out of the same prefill, so they can be formed before the level
  * loop and handed to nezha_draft_step through desc->user_part.  H, W_packed, A_out: host arrays

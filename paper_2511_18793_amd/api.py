@@ -18,7 +18,7 @@ EXPORTS = ["nezha_last_error", "nezha_build_itemset", "nezha_itemset_info", "nez
            "nezha_draft_step_workspace", "nezha_unpack_keys", "nezha_profile_enable",
            "nezha_profile_reset", "nezha_profile_kinds", "nezha_profile_read",
            "nezha_bench_random_gather", "nezha_user_projection", "nezha_pack_weights",
-           "nezha_packed_weights_bytes", "nezha_user_projection_levels", "nezha_draft_levels",
+           "nezha_packed_weights_bytes", "nezha_user_projection_levels", "nezha_draft_levels", "nezha_decode",
            "nezha_draft_levels_workspace"]
 
 
@@ -352,6 +352,50 @@ def draft_levels(H, W, E, radices, K, itemset=None, buffers=None, stream=None, U
     _check(lib.nezha_draft_levels(C.byref(dsc), io, _ptr(buffers.workspace),
                                   buffers.workspace.numel(), _stream(stream)))
     return buffers.outs
+
+
+class DecodePlan:
+    """Everything nezha_decode needs for one fixed set of buffers, marshalled once: run() is a
+    single foreign call (what a serving loop would do per batch).  bf16 with packed weights."""
+
+    def __init__(self, H, W, E, radices, K, itemset=None, buffers=None, stream=None, U=None,
+                 prefix_sets=None):
+        L = len(W)
+        B, _, d = H.shape
+        if not all(isinstance(w, PackedWeights) for w in W):
+            raise ValueError("DecodePlan needs weights from pack_weights")
+        e = W[0].shape[0] - d
+        self.buffers = buffers if buffers is not None else DraftBuffers(B, L, K, d, e, radices,
+                                                                        H.dtype, H.device)
+        self._keep = (H, W, E, U, itemset, prefix_sets)          # the memory the pointers refer to
+        self._dsc = _desc(B, L, 1, K, 1, d, e, radices, H.dtype, H.stride(0), True, None,
+                          U[0] if U is not None else None)
+        esz = H.element_size()
+        self._io = (_LevelIO * L)()
+        for l in range(L):
+            o = self.buffers.outs[l]
+            s = itemset if l == L - 1 else (prefix_sets[l] if prefix_sets else None)
+            self._io[l] = _LevelIO(H.data_ptr() + l * H.stride(1) * esz, W[l].data_ptr(),
+                                   _dp(E[l]) if l < L - 1 else None, s._h if s is not None else None,
+                                   self.buffers.user_parts[l].data_ptr(),
+                                   _dp(U[l]) if (U is not None and l < L - 1) else None,
+                                   o["key"].data_ptr(), o["score"].data_ptr(),
+                                   o["parent"].data_ptr(), o["code"].data_ptr(),
+                                   _dp(o.get("state")), o["count"].data_ptr())
+        lib = load_library()
+        lib.nezha_decode.argtypes = [C.POINTER(_StepDesc), C.POINTER(_LevelIO), C.c_void_p,
+                                     C.c_size_t, C.c_void_p]
+        self._fn = lib.nezha_decode
+        self._dref = C.byref(self._dsc)
+        self._ws = _ptr(self.buffers.workspace)
+        self._ws_bytes = self.buffers.workspace.numel()
+        self._stream = stream
+
+    def run(self):
+        rc = self._fn(self._dref, self._io, self._ws, self._ws_bytes, _stream(self._stream))
+        if rc != 0:
+            _check(rc)
+        return self.buffers.outs
 
 
 def decode(H, W, E, radices, K, itemset=None, buffers=None, stream=None, U=None,

@@ -3102,6 +3102,27 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
   return NEZHA_OK;
 }
 
+int nezha_decode(const nezha_step_desc* desc, const nezha_level_io* io, void* workspace,
+                 size_t workspace_bytes, void* hip_stream) {
+  if (!desc || !io) return fail(NEZHA_EINVAL, "desc or io is NULL");
+  if (desc->L < 1 || desc->L > NEZHA_MAX_LEVELS)
+    return fail(NEZHA_EINVAL, "L = %d outside 1..%d", desc->L, NEZHA_MAX_LEVELS);
+  const void* H[NEZHA_MAX_LEVELS];
+  const void* W[NEZHA_MAX_LEVELS];
+  float* A[NEZHA_MAX_LEVELS];
+  for (int l = 0; l < desc->L; ++l) {
+    if (!io[l].H_l || !io[l].user_part)
+      return fail(NEZHA_EINVAL, "level %d: H_l and user_part (the buffer of the level's user part) are needed",
+                  l + 1);
+    H[l] = io[l].H_l;
+    W[l] = io[l].W_l;
+    A[l] = const_cast<float*>(io[l].user_part);
+  }
+  int rc = nezha_user_projection_levels(desc, desc->L, H, W, A, hip_stream);
+  if (rc != NEZHA_OK) return rc;
+  return nezha_draft_levels(desc, io, workspace, workspace_bytes, hip_stream);
+}
+
 size_t nezha_draft_levels_workspace(const nezha_step_desc* desc) {
   if (!desc || desc->L < 1 || desc->L > NEZHA_MAX_LEVELS) return 0;
   size_t most = 0;

@@ -122,3 +122,14 @@ def test_verify_tuples_rejects_a_non_set():
     lib = nz.load_library()
     rc = lib.nezha_verify_tuples(None, None, 0, None, None, None, None, 0, None)
     assert rc == -1
+
+
+def test_decode_needs_hidden_states_and_user_part_buffers():
+    lib = nz.load_library()
+    dsc = api._desc(4, 3, 1, 4, 1, 64, 64, [256] * 3, torch.bfloat16, 64, True)
+    io = (api._LevelIO * 3)()
+    lib.nezha_decode.argtypes = [C.POINTER(api._StepDesc), C.POINTER(api._LevelIO), C.c_void_p,
+                                 C.c_size_t, C.c_void_p]
+    rc = lib.nezha_decode(C.byref(dsc), io, C.c_void_p(0x10000), 1 << 24, None)
+    assert rc == -1 and "user_part" in lib.nezha_last_error().decode()
+    assert lib.nezha_decode(None, io, None, 0, None) == -1

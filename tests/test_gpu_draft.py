@@ -422,3 +422,40 @@ def test_request_kernel_hands_hard_rows_to_the_general_kernel(oracle):
     # (the bf16 allowance is 2e-2)
     soft = check_decode(oracle, nz, cfg, x, outs, oset, 4e-3)
     assert soft <= 8
+
+
+@pytest.mark.parametrize("name,B,variant", [("serving", 64, "plain"), ("serving", 24, "rnn"),
+                                            ("wide", 5, "prefix"), ("large", 2, "plain")])
+def test_decode_in_one_call_equals_the_level_loop(oracle, name, B, variant):
+    """nezha_decode (projections of all levels + the level loop in one host call, arguments
+    marshalled once) against L calls of nezha_draft_step: the same bits, also on a second run."""
+    cfg = synth.get_config(name).scaled(B=B)
+    x, cat = planted_workload(oracle, cfg, 45, N=50_000)
+    gset = nz.build_itemset(cat, cfg.radices)
+    H, W, E = to_device(x, cfg)
+    U = gpre = None
+    if variant == "rnn":
+        U = [torch.from_numpy(u).to(device()).to(torch_dtype(cfg)) for u in _rnn_inputs(cfg, 45)]
+    if variant == "prefix":
+        gpre = [nz.build_itemset(np.unique(cat[:, :l], axis=0), cfg.radices[:l], cfg.load_factor)
+                for l in range(1, cfg.L)]
+    Wp = [nz.pack_weights(l + 1, cfg.L, cfg.radices, W[l], cfg.d) for l in range(cfg.L)]
+    ref = []
+    state = key = score = None
+    for l in range(1, cfg.L + 1):
+        o = nz.draft_step(l, cfg.L, cfg.radices, cfg.K, H[:, l - 1, :], Wp[l - 1],
+                          E[l - 1] if l < cfg.L else None, state, key, score,
+                          gset if l == cfg.L else (gpre[l - 1] if gpre else None),
+                          h_row_stride=H.stride(0),
+                          U_l=U[l - 1] if (U is not None and l < cfg.L) else None)
+        ref.append({k: v.clone() for k, v in o.items()})
+        state, key, score = o.get("state"), o["key"], o["score"]
+    plan = nz.DecodePlan(H, Wp, E, cfg.radices, cfg.K, gset, U=U, prefix_sets=gpre)
+    for _ in range(2):
+        got = plan.run()
+        torch.cuda.synchronize()
+        for a, b in zip(ref, got):
+            for k in a:
+                assert torch.equal(a[k], b[k]), k
+    with pytest.raises(ValueError):
+        nz.DecodePlan(H, W, E, cfg.radices, cfg.K, gset)       # weights not packed
