@@ -1,13 +1,17 @@
 // One level of the draft head's beam search (Alg. 3, inference loop body; Eq. 2-3) with the
 // last level's hash-set verification (Eq. 4-5) for a batch of requests.
 //
-// Kernels, in launch order:
-//   pack_weights_kernel  W_l (bf16, row major) -> MFMA operand order (bf16 workloads only)
-//   user_gemm_*          A_l = H_l * W_l[0:d]              (the beam-independent part of Eq. 2)
-//   expand_kernel        per beam: z = A_l + c * W_l[d:d+e] by MFMA, online log-sum-exp and
-//                        streaming top-K of the codes; logits never leave the registers
-//   merge_kernel         per request: cumulative scores, Eq. 4 indices, Eq. 5 probes, the K
-//                        best surviving candidates, and the additive Transition of Eq. 3
+// Kernels (which of them take a level follows from its shape alone):
+//   pack_weights_kernel     W_l (bf16, row major) -> MFMA operand order (bf16 workloads only)
+//   user_gemm_*             A_l = H_l * W_l[0:d]           (the beam-independent part of Eq. 2)
+//   expand_*_kernel         per beam: z = A_l + c * W_l[d:d+e] by MFMA, log-sum-exp and the K best
+//                           codes; logits never leave the chip.  expand_request_kernel also does
+//                           the request's selection where no set is consulted
+//   merge_kernel            per request: cumulative scores, Eq. 4 indices, Eq. 5 probes, the K
+//                           best surviving candidates, and the Transition of Eq. 3
+//   level_small_kernel,     all of the above after the projection in one launch per level / per
+//   decode_small_kernel     decode, for small shapes
+//   wide_*_kernel           beams wider than 128 (wide_beam.h)
 #include "nezha_internal.h"
 
 #include <type_traits>
