@@ -2199,76 +2199,125 @@ __device__ __forceinline__ void level_small_body(const LevelArgs& a, uint64_t* l
   }
   __syncthreads();
 
-  {  // phase B: rows 2*wave and 2*wave+1
-    const int r0 = wave * 2;
-    if (r0 < K_in) {
-      two_rows_topk<NVT, CAP>(ztile + r0 * V, ztile + (r0 + 1) * V, true, r0 + 1 < K_in, V, K,
-                              scratch + wave * CAP, [&](int rr, int p, uint64_t kk, float lse) {
-                                lists[(r0 + rr) * kLevelBeam + p] = kk;
-                                if (p == 0) row_lse[r0 + rr] = lse;
-                              });
-    }
-  }
-  __syncthreads();
-
-  // phase C: candidate (parent p, rank r) -> sort key (ordered score, ~(p*K+r)), 0 if rejected
-  const int n_c = K_in * K;                                           // <= 1024 = one per thread
   const bool verify = a.set.slots != nullptr;
-  uint64_t sk = 0;
-  if (tid < n_c) {
-    const int p = tid / K;
-    const uint64_t zk = lists[p * kLevelBeam + (tid - p * K)];
-    const uint32_t code = ~(uint32_t)zk;
-    const float logp = unordered_bits((uint32_t)(zk >> 32)) - row_lse[p];
-    const float score = (a.score_in ? as_global(a.score_in)[b * K_in + p] : 0.f) + logp;
-    const uint64_t pkey = a.key_in ? as_global(a.key_in)[b * K_in + p] : 0ull;
-    bool ok = pkey != kEmpty;                                         // an empty beam slot has no children
-    if (verify && ok) ok = set_contains(a.set, pkey + (uint64_t)code * a.mult);
-    if (ok) sk = ((uint64_t)ordered_bits(score) << 32) | (uint32_t)~(uint32_t)tid;
-    keys2[tid] = sk;
-  }
-  {
-    // K-th largest score of this wave's 64 candidates (scores alone: a bound may ignore ties)
-    uint32_t mk[1][1] = {{(uint32_t)(sk >> 32)}};
-    sort_desc<1, 1, uint32_t>(mk);                                    // K <= 32 <= 64
-    const uint64_t bound = (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)mk[0][0], K - 1) << 32;
-    if (lane == 0) bounds[wave] = bound;
-  }
-  __syncthreads();
-  if (wave == 0) {
-    uint64_t tau = bounds[0];
-#pragma unroll
-    for (int w = 1; w < kLevelWaves; ++w) tau = bounds[w] > tau ? bounds[w] : tau;
-    WaveTopK<CAP> f;
-    f.init(topbuf, K);
-    f.tau = tau ? tau - 1ull : 0ull;                                  // keys >= tau enter
-    for (int base = 0; base < n_c; base += 64) f.push(base + lane < n_c ? keys2[base + lane] : 0ull);
-    f.compact();
-    wave_sync();
-    if (lane < K) {
-      const int64_t o = (int64_t)b * K + lane;
-      if (lane < f.cnt) {
-        const uint64_t s2 = f.buf[lane];
-        const int i = (int)(~(uint32_t)s2);
-        const int par = i / K;
-        const int32_t code = (int32_t)(~(uint32_t)lists[par * kLevelBeam + (i - par * K)]);
-        as_global(a.key_out)[o] =
-            (a.key_in ? as_global(a.key_in)[b * K_in + par] : 0ull) + (uint64_t)(uint32_t)code * a.mult;
-        as_global(a.score_out)[o] = unordered_bits((uint32_t)(s2 >> 32));
-        as_global(a.parent_out)[o] = par;
-        as_global(a.code_out)[o] = code;
-        fin_parent[lane] = par;
-        fin_code[lane] = code;
-      } else {
-        as_global(a.key_out)[o] = kEmpty;
-        as_global(a.score_out)[o] = -INFINITY;
-        as_global(a.parent_out)[o] = -1;
-        as_global(a.code_out)[o] = -1;
-        fin_parent[lane] = -1;
-        fin_code[lane] = -1;
+  if (K_in == 1) {
+    // One entering beam (level 1): its K best codes are the level's beams, so wave 0 does the
+    // beam's top-K, the probes and the ordering by score in one go: no candidate matrix, no
+    // bounds, two barriers fewer.
+    if (wave == 0) {
+      two_rows_topk<NVT, CAP>(ztile, ztile, true, false, V, K, scratch,
+                              [&](int rr, int p, uint64_t kk, float lse) {
+                                lists[p] = kk;
+                                if (p == 0) row_lse[0] = lse;
+                              });
+      wave_sync();
+      uint64_t sk1[1][1] = {{0ull}};
+      if (lane < K) {
+        const uint64_t zk = lists[lane];
+        const uint32_t code = ~(uint32_t)zk;
+        const float logp = unordered_bits((uint32_t)(zk >> 32)) - row_lse[0];
+        const float score = (a.score_in ? as_global(a.score_in)[b] : 0.f) + logp;
+        const uint64_t pkey = a.key_in ? as_global(a.key_in)[b] : 0ull;
+        bool ok = pkey != kEmpty;                                       // an empty beam slot has no children
+        if (verify && ok) ok = set_contains(a.set, pkey + (uint64_t)code * a.mult);
+        if (ok) sk1[0][0] = ((uint64_t)ordered_bits(score) << 32) | (uint32_t)~(uint32_t)lane;
+      }
+      sort_desc<1, 1, uint64_t>(sk1);                                   // (score, place in code order)
+      const int cnt = __popcll(__ballot(sk1[0][0] != 0ull));
+      if (lane < K) {
+        const int64_t o = (int64_t)b * K + lane;
+        if (lane < cnt) {
+          const uint64_t s2 = sk1[0][0];
+          const int32_t code = (int32_t)(~(uint32_t)lists[(int)(~(uint32_t)s2)]);
+          as_global(a.key_out)[o] =
+              (a.key_in ? as_global(a.key_in)[b] : 0ull) + (uint64_t)(uint32_t)code * a.mult;
+          as_global(a.score_out)[o] = unordered_bits((uint32_t)(s2 >> 32));
+          as_global(a.parent_out)[o] = 0;
+          as_global(a.code_out)[o] = code;
+          fin_parent[lane] = 0;
+          fin_code[lane] = code;
+        } else {
+          as_global(a.key_out)[o] = kEmpty;
+          as_global(a.score_out)[o] = -INFINITY;
+          as_global(a.parent_out)[o] = -1;
+          as_global(a.code_out)[o] = -1;
+          fin_parent[lane] = -1;
+          fin_code[lane] = -1;
+        }
+      }
+      if (lane == 0 && a.count_out) as_global(a.count_out)[b] = cnt;
+    }
+  } else {
+    {  // phase B: rows 2*wave and 2*wave+1
+      const int r0 = wave * 2;
+      if (r0 < K_in) {
+        two_rows_topk<NVT, CAP>(ztile + r0 * V, ztile + (r0 + 1) * V, true, r0 + 1 < K_in, V, K,
+                                scratch + wave * CAP, [&](int rr, int p, uint64_t kk, float lse) {
+                                  lists[(r0 + rr) * kLevelBeam + p] = kk;
+                                  if (p == 0) row_lse[r0 + rr] = lse;
+                                });
       }
     }
-    if (lane == 0 && a.count_out) as_global(a.count_out)[b] = f.cnt;
+    __syncthreads();
+
+    // phase C: candidate (parent p, rank r) -> sort key (ordered score, ~(p*K+r)), 0 if rejected
+    const int n_c = K_in * K;                                           // <= 1024 = one per thread
+    uint64_t sk = 0;
+    if (tid < n_c) {
+      const int p = tid / K;
+      const uint64_t zk = lists[p * kLevelBeam + (tid - p * K)];
+      const uint32_t code = ~(uint32_t)zk;
+      const float logp = unordered_bits((uint32_t)(zk >> 32)) - row_lse[p];
+      const float score = (a.score_in ? as_global(a.score_in)[b * K_in + p] : 0.f) + logp;
+      const uint64_t pkey = a.key_in ? as_global(a.key_in)[b * K_in + p] : 0ull;
+      bool ok = pkey != kEmpty;                                         // an empty beam slot has no children
+      if (verify && ok) ok = set_contains(a.set, pkey + (uint64_t)code * a.mult);
+      if (ok) sk = ((uint64_t)ordered_bits(score) << 32) | (uint32_t)~(uint32_t)tid;
+      keys2[tid] = sk;
+    }
+    {
+      // K-th largest score of this wave's 64 candidates (scores alone: a bound may ignore ties)
+      uint32_t mk[1][1] = {{(uint32_t)(sk >> 32)}};
+      sort_desc<1, 1, uint32_t>(mk);                                    // K <= 32 <= 64
+      const uint64_t bound = (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)mk[0][0], K - 1) << 32;
+      if (lane == 0) bounds[wave] = bound;
+    }
+    __syncthreads();
+    if (wave == 0) {
+      uint64_t tau = bounds[0];
+  #pragma unroll
+      for (int w = 1; w < kLevelWaves; ++w) tau = bounds[w] > tau ? bounds[w] : tau;
+      WaveTopK<CAP> f;
+      f.init(topbuf, K);
+      f.tau = tau ? tau - 1ull : 0ull;                                  // keys >= tau enter
+      for (int base = 0; base < n_c; base += 64) f.push(base + lane < n_c ? keys2[base + lane] : 0ull);
+      f.compact();
+      wave_sync();
+      if (lane < K) {
+        const int64_t o = (int64_t)b * K + lane;
+        if (lane < f.cnt) {
+          const uint64_t s2 = f.buf[lane];
+          const int i = (int)(~(uint32_t)s2);
+          const int par = i / K;
+          const int32_t code = (int32_t)(~(uint32_t)lists[par * kLevelBeam + (i - par * K)]);
+          as_global(a.key_out)[o] =
+              (a.key_in ? as_global(a.key_in)[b * K_in + par] : 0ull) + (uint64_t)(uint32_t)code * a.mult;
+          as_global(a.score_out)[o] = unordered_bits((uint32_t)(s2 >> 32));
+          as_global(a.parent_out)[o] = par;
+          as_global(a.code_out)[o] = code;
+          fin_parent[lane] = par;
+          fin_code[lane] = code;
+        } else {
+          as_global(a.key_out)[o] = kEmpty;
+          as_global(a.score_out)[o] = -INFINITY;
+          as_global(a.parent_out)[o] = -1;
+          as_global(a.code_out)[o] = -1;
+          fin_parent[lane] = -1;
+          fin_code[lane] = -1;
+        }
+      }
+      if (lane == 0 && a.count_out) as_global(a.count_out)[b] = f.cnt;
+    }
   }
   __syncthreads();
   if (a.state_out) {
