@@ -2200,16 +2200,21 @@ __device__ __forceinline__ void level_small_body(const LevelArgs& a, uint64_t* l
   __syncthreads();
 
   const bool verify = a.set.slots != nullptr;
+  {  // phase B: rows 2*wave and 2*wave+1
+    const int r0 = wave * 2;
+    if (r0 < K_in) {
+      two_rows_topk<NVT, CAP>(ztile + r0 * V, ztile + (r0 + 1) * V, true, r0 + 1 < K_in, V, K,
+                              scratch + wave * CAP, [&](int rr, int p, uint64_t kk, float lse) {
+                                lists[(r0 + rr) * kLevelBeam + p] = kk;
+                                if (p == 0) row_lse[r0 + rr] = lse;
+                              });
+    }
+  }
   if (K_in == 1) {
-    // One entering beam (level 1): its K best codes are the level's beams, so wave 0 does the
-    // beam's top-K, the probes and the ordering by score in one go: no candidate matrix, no
+    // One entering beam (level 1): its K best codes are the level's beams, so wave 0, which has
+    // just found them, also does the probes and the ordering by score: no candidate matrix, no
     // bounds, two barriers fewer.
     if (wave == 0) {
-      two_rows_topk<NVT, CAP>(ztile, ztile, true, false, V, K, scratch,
-                              [&](int rr, int p, uint64_t kk, float lse) {
-                                lists[p] = kk;
-                                if (p == 0) row_lse[0] = lse;
-                              });
       wave_sync();
       uint64_t sk1[1][1] = {{0ull}};
       if (lane < K) {
@@ -2248,16 +2253,6 @@ __device__ __forceinline__ void level_small_body(const LevelArgs& a, uint64_t* l
       if (lane == 0 && a.count_out) as_global(a.count_out)[b] = cnt;
     }
   } else {
-    {  // phase B: rows 2*wave and 2*wave+1
-      const int r0 = wave * 2;
-      if (r0 < K_in) {
-        two_rows_topk<NVT, CAP>(ztile + r0 * V, ztile + (r0 + 1) * V, true, r0 + 1 < K_in, V, K,
-                                scratch + wave * CAP, [&](int rr, int p, uint64_t kk, float lse) {
-                                  lists[(r0 + rr) * kLevelBeam + p] = kk;
-                                  if (p == 0) row_lse[r0 + rr] = lse;
-                                });
-      }
-    }
     __syncthreads();
 
     // phase C: candidate (parent p, rank r) -> sort key (ordered score, ~(p*K+r)), 0 if rejected
