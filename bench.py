@@ -40,7 +40,7 @@ BUCKET_BYTES = 64
 # are in profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB -> bytes; the factors come from the
 # plain-copy calibration in the same runs).  Only workloads that were profiled have an entry.
 MEASURED_TRAFFIC_BYTES = {
-    ("serving", "decode_small_kernel"): (7826.3 * 2.0 + 2920.0) * 1024,
+    ("serving", "decode_small_kernel"): (7840.1 * 2.0 + 2920.0) * 1024,
     ("stress", "verify_probe_kernel"): (245832.5 * 2.0 + 4064.6) * 1024,
     ("recall", "wide_rows_kernel"): (1344793.2 * 2.0 + 525728.3) * 1024,
     # mean of the two launches of a decode: the whole-level variant (level 2) and the per-beam
