@@ -63,6 +63,9 @@ def parse_args():
                          "holds the step; 'auto' = direct where one call per step applies (bf16, "
                          "weights packed at set-up), else graph")
     ap.add_argument("--eager", action="store_true", help="same as --launch direct")
+    ap.add_argument("--two-streams", action="store_true",
+                    help="also time the same decodes issued alternately on two streams (reported "
+                         "as two_stream_ms_per_step, never as value)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pack-per-call", action="store_true",
                     help="rearrange the weights inside every step instead of once at set-up")
@@ -219,6 +222,27 @@ def bench_draft(args, cfg):
     accepted = int(bufs.outs[-1]["count"].sum().item())
     hallucinated = 1.0 - float(keep.mean())
 
+    # Extra figure (never `value`): the same K decodes issued alternately on two streams, each
+    # with buffers of its own, as a server would overlap consecutive, independent batches: the
+    # projections of one batch run beside the level kernel of the batch before.
+    two_stream_ms = None
+    if plan is not None and args.two_streams:
+        bufs2 = nz.DraftBuffers(cfg.B, cfg.L, cfg.K, cfg.d, cfg.e, cfg.radices, dt, dev)
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        plans = [nz.DecodePlan(H, Wrun, E, cfg.radices, cfg.K, itemset, buffers=b_, U=U,
+                               prefix_sets=prefix_sets, stream=s_)
+                 for b_, s_ in zip((bufs, bufs2), streams)]
+        torch.cuda.synchronize()
+        for i in range(args.warmup):
+            plans[i & 1].run()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for i in range(args.steps):
+            plans[i & 1].run()
+        torch.cuda.synchronize()
+        two_stream_ms = (time.perf_counter() - t2) * 1e3 / args.steps
+        assert torch.equal(bufs.outs[-1]["key"], bufs2.outs[-1]["key"])
+
     # Per-level latency: the same steps eager, events around each level's nezha_draft_step.
     lev_steps = min(args.steps, 50)
     lev_ev = [[[torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)]
@@ -308,6 +332,8 @@ def bench_draft(args, cfg):
         "roofline": roofline,
         "kernels": breakdown,
     }
+    if two_stream_ms is not None:
+        result["two_stream_ms_per_step"] = two_stream_ms
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline_draft(cfg, x, catalog, cands, Unp, args.prefix_sets)
     return result
