@@ -2490,7 +2490,10 @@ int allow_lds(Kern kern, size_t bytes) {
   return NEZHA_OK;
 }
 
-// Small user-part products run their k loop in four parts side by side (user_gemm_tile, KSPLIT).
+// Products with fewer outputs than this are "small": 128 x 128 tiles would leave most of the 256
+// CUs without a workgroup (B = T_l = 1024: 64 tiles), so they get 32 x 64 tiles, and their k
+// loop runs in four parts side by side (user_gemm_tile, KSPLIT).
+constexpr int64_t kSmallGemmElems = (int64_t)128 * 128 * 256;
 inline bool small_gemm_splits_k(int d) { return (d / 32) % 4 == 0 && d >= 256; }
 
 int launch_pack(const nezha_step_desc* desc, const void* W_l, uint16_t* Wp, hipStream_t stream) {
@@ -2531,7 +2534,7 @@ int launch_user_part(const nezha_step_desc* desc, const void* H_l, const void* W
   } while (0)
     const int64_t out_elems = (int64_t)B * V;
     if (out_elems >= (int64_t)256 * 256 * 128) LAUNCH_GEMM(2, 4, 4, 2, 1);       // 256 x 256 tiles
-    else if (out_elems >= (int64_t)128 * 128 * 64) LAUNCH_GEMM(2, 2, 2, 2, 1);   // 128 x 128 tiles
+    else if (out_elems >= kSmallGemmElems) LAUNCH_GEMM(2, 2, 2, 2, 1);             // 128 x 128 tiles
     // small products: the same tiles and the same order of summation as the grouped launch of
     // nezha_user_projection_levels, so that both give the same bits
     else if (small_gemm_splits_k(d)) LAUNCH_GEMM(1, 2, 1, 1, 4);                  // 32 x 64, k in four parts
@@ -2629,7 +2632,7 @@ int nezha_user_projection_levels(const nezha_step_desc* desc, int32_t n_levels,
   hipStream_t stream = (hipStream_t)hip_stream;
   int max_v = 0;
   for (int i = 0; i < n_levels; ++i) max_v = desc->radices[i] > max_v ? desc->radices[i] : max_v;
-  if ((int64_t)B * max_v >= (int64_t)128 * 128 * 64) {
+  if ((int64_t)B * max_v >= kSmallGemmElems) {
     // large projections fill the chip on their own: one launch each, with the large tiles
     for (int i = 0; i < n_levels; ++i) {
       probe.level = i + 1;
