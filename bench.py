@@ -43,6 +43,7 @@ MEASURED_TRAFFIC_BYTES = {
     ("serving", "decode_small_kernel"): (7840.1 * 2.0 + 2920.0) * 1024,
     ("stress", "verify_probe_kernel"): (245832.5 * 2.0 + 4064.6) * 1024,
     ("recall", "wide_rows_kernel"): (1344793.2 * 2.0 + 525728.3) * 1024,
+    ("wide", "expand_kernel"): (12421.0 * 2.0 + 15100.0) * 1024,          # expand_small_kernel
     # mean of the two launches of a decode: the whole-level variant (level 2) and the per-beam
     # variant (level 3, whose candidate lists go through HBM to the merge)
     ("large", "expand_request_kernel"): ((306656.4 * 2.0 + 173510.5) +
