@@ -297,7 +297,11 @@ constexpr int kGemmBuffers = 4;
 // KSPLIT > 1 (small problems, whose time is the length of the k loop): the workgroup has KSPLIT
 // groups of NWM x NWN waves, group s takes the s-th part of k with its own H buffers, and the
 // groups' partial results are added through LDS at the end (d must be a multiple of 32 * KSPLIT).
-template <int NWM, int NWN, int TM, int TN, int KSPLIT = 1>
+// WLDS: the packed W operands go through LDS as well (their 1 KiB blocks are what one fetch
+// instruction brings, and what the 64 lanes of one operand read take): nothing of W is read twice
+// by the waves of a workgroup and no registers hold operands in flight; for tiles whose waves are
+// large enough (128 x 128) that LDS bandwidth still leaves room.
+template <int NWM, int NWN, int TM, int TN, int KSPLIT = 1, bool WLDS = false>
 __device__ __forceinline__ void user_gemm_tile(
     const uint16_t* __restrict__ H, int64_t h_stride, const uint16_t* __restrict__ Wu,
     float* __restrict__ A, int B, int d, int V, int tiles_n, int tiles_total, int tile_id) {
@@ -306,10 +310,13 @@ __device__ __forceinline__ void user_gemm_tile(
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
   constexpr int CT = BN / 32;                        // 32-column tiles per workgroup
   constexpr int ASLOTS = BM * 4;                     // 16-byte slots of the H tile (64 B per row)
-  extern __shared__ __align__(16) uint4 smem_all[];  // [KSPLIT][kGemmBuffers][H tile]
+  constexpr int BINS = 2 * CT;                       // W operand blocks (fetch instructions) per stage
+  constexpr int BSLOTS = WLDS ? BINS * 64 : 0;       // 16-byte slots of the W tile
+  constexpr int SSLOTS = ASLOTS + BSLOTS;            // one stage's buffer
+  extern __shared__ __align__(16) uint4 smem_all[];  // [KSPLIT][kGemmBuffers][H tile | W tile]
   const int tid = threadIdx.x, lane = tid & 63;
   const int ksplit = (tid >> 6) / NW, wave = (tid >> 6) % NW;   // wave: index inside its group
-  uint4* const smem = smem_all + ksplit * kGemmBuffers * ASLOTS;
+  uint4* const smem = smem_all + ksplit * kGemmBuffers * SSLOTS;
   const int wm = wave / NWN, wn = wave % NWN;
   // Workgroup ids equal modulo 8 run on the same XCD.  When the grid allows it every XCD gets
   // 4 x 8 blocks of tiles (4 H panels and 8 W panels live in its L2 at a time); otherwise a
@@ -366,19 +373,47 @@ __device__ __forceinline__ void user_gemm_tile(
     ct = ct < n_ct ? ct : n_ct - 1;                  // tiles beyond V: clamped, never stored
     b_ptr[j] = reinterpret_cast<const uint4*>(Wu) + (int64_t)ct * KSu * 64 + lane;
   }
-  uint4 fb[kGemmBuffers][2][TN];                     // W operands of the stages in flight
+  // WLDS: W block (column tile jb, step ks) of a stage is fetch instruction 2*jb + ks; wave w
+  // issues w, w+NW, ...
+  constexpr int BPW = WLDS ? (BINS + NW - 1) / NW : 0;
+  const uint4* bl_ptr[BPW > 0 ? BPW : 1];
+  if constexpr (WLDS) {
+#pragma unroll
+    for (int u = 0; u < BPW; ++u) {
+      int ins = wave + NW * u;
+      ins = ins < BINS ? ins : BINS - 1;
+      int ct = ct0 + (ins >> 1);
+      ct = ct < n_ct ? ct : n_ct - 1;
+      bl_ptr[u] = reinterpret_cast<const uint4*>(Wu) + ((int64_t)ct * KSu + (ins & 1)) * 64 + lane;
+    }
+  }
+  uint4 fb[WLDS ? 1 : kGemmBuffers][2][TN];          // W operands of the stages in flight (!WLDS)
   auto fetch = [&](int stage, uint4 (&b)[2][TN]) {
-    uint4* sa = smem + (stage % kGemmBuffers) * ASLOTS;
+    uint4* sa = smem + (stage % kGemmBuffers) * SSLOTS;
 #pragma unroll
     for (int u = 0; u < APW; ++u) {
       int ins = wave + NW * u;
       ins = ins < AINS ? ins : AINS - 1;
       load_block_to_lds(a_ptr[u] + (stage0 + stage) * 32, sa + ins * 64);
     }
+    if constexpr (WLDS) {
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
+      for (int u = 0; u < BPW; ++u) {
+        int ins = wave + NW * u;
+        ins = ins < BINS ? ins : BINS - 1;
+        load_block_to_lds(bl_ptr[u] + (int64_t)(stage0 + stage) * 2 * 64, sa + ASLOTS + ins * 64);
+      }
+    } else {
 #pragma unroll
-      for (int j = 0; j < TN; ++j) b[ks][j] = b_ptr[j][((stage0 + stage) * 2 + ks) * 64];
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[ks][j] = b_ptr[j][((stage0 + stage) * 2 + ks) * 64];
+    }
+  };
+  auto read_b = [&](int stage, int ks, uint4 (&b)[TN]) {
+    const uint4* sb = smem + (stage % kGemmBuffers) * SSLOTS + ASLOTS;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) b[j] = sb[(2 * (wn * TN + j) + ks) * 64 + lane];
   };
   // LDS slot of this lane's A operand for row tile i, step ks: row = (wm*TM+i)*32 + lane%32,
   // chunk = 2*ks + lane/32, slot = row*4 + (chunk ^ (row/4)%4)
@@ -386,7 +421,7 @@ __device__ __forceinline__ void user_gemm_tile(
 #pragma unroll
   for (int i = 0; i < TM; ++i) a_slot[i] = ((wm * TM + i) * 32 + (lane & 31)) * 4;
   const int a_sw = (lane >> 2) & 3, a_hi = lane >> 5;
-  constexpr int LOADS = APW + 2 * TN;                // loads per wave and stage
+  constexpr int LOADS = WLDS ? APW + BPW : APW + 2 * TN;   // loads per wave and stage
   // at most `newer` stages' worth of this wave's loads still in flight (they complete in order)
   auto wait_fetches = [&](int newer) {
     constexpr int L1 = LOADS < 15 ? LOADS : 15, L2 = 2 * LOADS < 63 ? 2 * LOADS : 63;
@@ -395,7 +430,7 @@ __device__ __forceinline__ void user_gemm_tile(
     else __builtin_amdgcn_s_waitcnt(0x0F70);
   };
   auto read_a = [&](int stage, int ks, bf16x8 (&fa)[TM]) {
-    const uint4* sa = smem + (stage % kGemmBuffers) * ASLOTS;
+    const uint4* sa = smem + (stage % kGemmBuffers) * SSLOTS;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
       fa[i] = *reinterpret_cast<const bf16x8*>(&sa[a_slot[i] + ((2 * ks + a_hi) ^ a_sw)]);
@@ -414,13 +449,15 @@ __device__ __forceinline__ void user_gemm_tile(
   // step's MFMAs run.
 #pragma unroll
   for (int p = 0; p < kGemmBuffers - 1; ++p)
-    if (p < stages) fetch(p, fb[p]);
+    if (p < stages) fetch(p, fb[WLDS ? 0 : p]);
   bf16x8 fa0[TM], fa1[TM];
+  uint4 fb0[WLDS ? TN : 1], fb1[WLDS ? TN : 1];      // WLDS: W operands of the two steps at hand
   {
     const int ahead = stages - 1;
     wait_fetches(ahead < kGemmBuffers - 2 ? ahead : kGemmBuffers - 2);
     __syncthreads();
     read_a(0, 0, fa0);
+    if constexpr (WLDS) read_b(0, 0, fb0);
   }
   for (int base = 0; base < stages; base += kGemmBuffers) {
 #pragma unroll
@@ -428,16 +465,23 @@ __device__ __forceinline__ void user_gemm_tile(
       const int stage = base + q;
       if (stage < stages) {
         read_a(stage, 1, fa1);
-        multiply(fa0, fb[q][0]);
+        if constexpr (WLDS) {
+          read_b(stage, 1, fb1);
+          multiply(fa0, fb0);
+        } else {
+          multiply(fa0, fb[q][0]);
+        }
         if (stage + 1 < stages) {
           const int ahead = stages - 2 - stage;      // fetched stages after stage+1
           wait_fetches(ahead < kGemmBuffers - 3 ? ahead : kGemmBuffers - 3);
           __syncthreads();  // stage+1 has landed everywhere; the buffer of stage-1 is free everywhere
           if (stage + kGemmBuffers - 1 < stages)
-            fetch(stage + kGemmBuffers - 1, fb[(q + kGemmBuffers - 1) % kGemmBuffers]);
+            fetch(stage + kGemmBuffers - 1, fb[WLDS ? 0 : (q + kGemmBuffers - 1) % kGemmBuffers]);
           read_a(stage + 1, 0, fa0);
+          if constexpr (WLDS) read_b(stage + 1, 0, fb0);
         }
-        multiply(fa1, fb[q][1]);
+        if constexpr (WLDS) multiply(fa1, fb1);
+        else multiply(fa1, fb[q][1]);
       }
     }
   }
@@ -483,12 +527,12 @@ __device__ __forceinline__ void user_gemm_tile(
     }
 }
 
-template <int NWM, int NWN, int TM, int TN, int KSPLIT = 1>
+template <int NWM, int NWN, int TM, int TN, int KSPLIT = 1, bool WLDS = false>
 __global__ __launch_bounds__(64 * NWM * NWN * KSPLIT, 1) void user_gemm_bf16_kernel(
     const uint16_t* __restrict__ H, int64_t h_stride, const uint16_t* __restrict__ Wu,
     float* __restrict__ A, int B, int d, int V, int tiles_n, int tiles_total) {
-  user_gemm_tile<NWM, NWN, TM, TN, KSPLIT>(H, h_stride, Wu, A, B, d, V, tiles_n, tiles_total,
-                                           blockIdx.x);
+  user_gemm_tile<NWM, NWN, TM, TN, KSPLIT, WLDS>(H, h_stride, Wu, A, B, d, V, tiles_n, tiles_total,
+                                                 blockIdx.x);
 }
 
 // Several levels' projections in one launch: they do not depend on each other (all the hidden
@@ -2533,7 +2577,16 @@ int launch_user_part(const nezha_step_desc* desc, const void* H_l, const void* W
                        tiles_m * tiles_n);                                                     \
   } while (0)
     const int64_t out_elems = (int64_t)B * V;
-    if (out_elems >= (int64_t)256 * 256 * 128) LAUNCH_GEMM(2, 4, 4, 2, 1);       // 256 x 256 tiles
+    if (out_elems >= (int64_t)256 * 256 * 128) {                                  // 256 x 256 tiles
+      constexpr int BM = 256, BN = 256;
+      const int tiles_m = (B + BM - 1) / BM, tiles_n = (V + BN - 1) / BN;
+      const size_t lds = (size_t)kGemmBuffers * (BM * 4 + 2 * (BN / 32) * 64) * sizeof(uint4);
+      rc = allow_lds(user_gemm_bf16_kernel<2, 2, 4, 4, 1, true>, lds);
+      if (rc != NEZHA_OK) return rc;
+      hipLaunchKernelGGL((user_gemm_bf16_kernel<2, 2, 4, 4, 1, true>), dim3(tiles_m * tiles_n),
+                         dim3(256), lds, stream, Hp, desc->h_row_stride, (const uint16_t*)Wp, A, B,
+                         d, V, tiles_n, tiles_m * tiles_n);
+    }
     else if (out_elems >= kSmallGemmElems) LAUNCH_GEMM(2, 2, 2, 2, 1);             // 128 x 128 tiles
     // small products: the same tiles and the same order of summation as the grouped launch of
     // nezha_user_projection_levels, so that both give the same bits
