@@ -287,12 +287,13 @@ __device__ __forceinline__ void load_block_to_lds(const void* gptr, void* lds_bl
 }
 
 // Workgroup of NWM x NWN waves, each wave TM x TN tiles of 32x32.  K advances 32 per stage (two
-// MFMA steps of 16).  LDS bandwidth is what bounds this kernel, so only H goes through LDS:
-// its tile is brought by global_load_lds (no staging registers) into one of four buffers, three
-// stages ahead of use.  The packed W operands are loaded straight from global memory / L2 into
-// registers, also three stages ahead (the waves of one column strip read the same lines).  One
-// barrier per stage.  Workgroup ids are remapped so that the tiles that run on one XCD (ids
-// equal modulo 8) are neighbours and share its L2.
+// MFMA steps of 16).  The H tile is brought by global_load_lds (no staging registers) into one of
+// four buffers, three stages ahead of use.  The packed W operands either go the same way (WLDS:
+// the large shapes, four waves of 128 x 128, where a wave's operand reads per MFMA are few enough
+// for the LDS bandwidth) or are loaded straight from global memory / L2 into registers, also three
+// stages ahead (smaller wave tiles, where LDS bandwidth is what binds; the waves of one column
+// strip then read the same lines).  One barrier per stage.  Workgroup ids are remapped so that the
+// tiles that run on one XCD (ids equal modulo 8) are neighbours and share its L2.
 constexpr int kGemmBuffers = 4;
 // KSPLIT > 1 (small problems, whose time is the length of the k loop): the workgroup has KSPLIT
 // groups of NWM x NWN waves, group s takes the s-th part of k with its own H buffers, and the
