@@ -189,6 +189,27 @@ def test_user_projection_is_the_level_one_logits(oracle):
         assert err < min(tol, 1e-4), (name, err)
 
 
+@pytest.mark.parametrize("B,d,V", [
+    (2100, 96, 4112),     # 256 x 256 tiles (both operands through LDS), ragged in rows and columns, a k loop shorter than the pipeline
+    (2304, 1024, 3840),   # the same tiles, a long k loop
+    (700, 256, 2000),     # 32 x 64 tiles with the k loop in four parts, ragged
+    (1500, 160, 4000),    # 128 x 128 tiles
+])
+def test_user_projection_tile_forms(B, d, V):
+    """Every tile form of the bf16 user-part product against the float64 product of the same
+    (bf16-rounded) inputs: float32 accumulation of d products of magnitude <= ~0.1."""
+    rng = np.random.default_rng(B + d + V)
+    Hn = synth.round_to_bf16(rng.standard_normal((B, d)).astype(np.float32))
+    Wn = synth.round_to_bf16((rng.standard_normal((d + 32, V)) * 0.02).astype(np.float32))
+    H = torch.from_numpy(Hn).to(device()).to(torch.bfloat16)
+    W = torch.from_numpy(Wn).to(device()).to(torch.bfloat16)
+    A = nz.user_projection(1, 2, [V, V], H, W)
+    torch.cuda.synchronize()
+    want = (torch.from_numpy(Hn).double() @ torch.from_numpy(Wn[:d]).double()).numpy()
+    err = np.abs(to_np(A) - want).max()
+    assert err < 1e-4, err
+
+
 def test_zero_requests_is_a_no_op():
     dev = device()
     H = torch.zeros((0, 64), dtype=torch.bfloat16, device=dev)
