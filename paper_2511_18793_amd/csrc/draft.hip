@@ -1996,7 +1996,7 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
     if constexpr (WHOLE) {
       const int n = *req_cnt;                 // (the sweep ended with a barrier)
       const bool over = n > kReqListCap;
-      if (threadIdx.x < K_in) redo[(int64_t)b * K_in + threadIdx.x] = over ? 1 : 0;
+      if ((int)threadIdx.x < K_in) redo[(int64_t)b * K_in + threadIdx.x] = over ? 1 : 0;
       if (threadIdx.x == 0) la.redo_req[b] = over ? 1 : 0;
       if (!over) {
         if (wave == 0) {
@@ -2554,7 +2554,7 @@ int launch_pack(const nezha_step_desc* desc, const void* W_l, uint16_t* Wp, hipS
 // a1: packs W_l (bf16, unless it comes packed) and forms A = H_l * W_l[0:d] on `stream`.
 int launch_user_part(const nezha_step_desc* desc, const void* H_l, const void* W_l, uint16_t* Wp,
                      float* A, hipStream_t stream) {
-  const int B = desc->B, d = desc->d, e = desc->e;
+  const int B = desc->B, d = desc->d;
   const int V = desc->radices[desc->level - 1];
   const bool bf16 = desc->dtype == NEZHA_BF16;
   int rc = NEZHA_OK;

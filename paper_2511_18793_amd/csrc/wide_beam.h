@@ -739,7 +739,7 @@ __global__ __launch_bounds__(kWideRowThreads) void wide_rows_kernel(WideArgs a) 
               total += cnt[w];
             }
             running += total;
-            if (tie) take = before + __popcll(bal & ((1ull << lane) - 1ull)) < p.need;
+            if (tie) take = before + (int)__popcll(bal & ((1ull << lane) - 1ull)) < p.need;
           }
           // one LDS reservation per wave (atomics on one address run one after the other)
           const uint64_t tb = __ballot(take);
