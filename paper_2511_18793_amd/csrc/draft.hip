@@ -2752,7 +2752,8 @@ static LevelArgs make_level_args(const nezha_step_desc* desc, const uint16_t* Wp
   la.key_in = key_in;
   la.score_in = score_in;
   la.E = E_l;
-  la.set = SetView{(set && set->L == level) ? set->slots : nullptr, set ? set->n_buckets : 0};
+  la.set = SetView{(set && set->L == level) ? set->slots : nullptr, set ? set->n_buckets : 0,
+                   set ? set->filter : nullptr, set ? set->n_words : 0};
   la.U = desc->U_l;
   la.transition = desc->transition;
   la.mult = mult;
@@ -2874,7 +2875,8 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
     wa.key_in = key_in;
     wa.score_in = score_in;
     const bool verify = set && set->L == level;
-    wa.set = SetView{verify ? set->slots : nullptr, set ? set->n_buckets : 0};
+    wa.set = SetView{verify ? set->slots : nullptr, set ? set->n_buckets : 0,
+                     set ? set->filter : nullptr, set ? set->n_words : 0};
     wa.mult = mult[level - 1];
     wa.rows = rows;
     wa.K_in = K_in;
@@ -3175,7 +3177,8 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
   ma.score_in = score_in;
   ma.state_in = state_in;
   ma.E = E_l;
-  ma.set = SetView{(set && set->L == level) ? set->slots : nullptr, set ? set->n_buckets : 0};
+  ma.set = SetView{(set && set->L == level) ? set->slots : nullptr, set ? set->n_buckets : 0,
+                   set ? set->filter : nullptr, set ? set->n_words : 0};
   ma.U = desc->U_l;
   ma.transition = desc->transition;
   ma.redo_req = redo_req;

@@ -129,6 +129,19 @@ __global__ void insert_kernel(const int32_t* __restrict__ codes, int64_t n, Radi
   }
 }
 
+// The prefilter from the finished table: every stored key sets its 3 bits.
+__global__ void filter_kernel(const uint64_t* __restrict__ slots, uint64_t n_slots,
+                              unsigned long long* filter, uint64_t n_words) {
+  uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  for (; i < n_slots; i += stride) {
+    const uint64_t key = slots[i];
+    if (key == kEmpty) continue;
+    const uint64_t h = hash64(key);
+    atomicOr(&filter[filter_word(h, n_words)], (unsigned long long)filter_mask(h));
+  }
+}
+
 // ---- stand-alone verification ----------------------------------------------------------
 constexpr int kVerifyThreads = 256;
 constexpr int kPerThread = 4;                                 // consecutive tuples per lane
@@ -329,6 +342,8 @@ int nezha_build_itemset(const int32_t* codes, int64_t n, int32_t L, const int32_
   nezha_itemset* s = new (std::nothrow) nezha_itemset;
   if (!s) return fail(NEZHA_ENOMEM, "host allocation failed");
   s->slots = nullptr;
+  s->filter = nullptr;
+  s->n_words = 0;
   s->n_buckets = n_buckets;
   s->n_distinct = 0;
   s->L = L;
@@ -346,6 +361,7 @@ int nezha_build_itemset(const int32_t* codes, int64_t n, int32_t L, const int32_
     if (staged) (void)hipFree(staged);
     if (code != NEZHA_OK) {
       if (s->slots) (void)hipFree(s->slots);
+      if (s->filter) (void)hipFree(s->filter);
       s->magic = 0;
       delete s;
     }
@@ -409,6 +425,27 @@ int nezha_build_itemset(const int32_t* codes, int64_t n, int32_t L, const int32_
     return cleanup(rc);
   }
   s->n_distinct = (int64_t)host_status[2];
+  {
+    // The prefilter: one 64-bit word per 8 keys, 3 bits per key (about N bytes).  Most candidates
+    // of the draft step are not items; a filter word is a small, cache-resident access that turns
+    // most of their table probes (a random HBM line each) away.  It can only say "not in the
+    // set" for keys that are not in it, so results do not change.
+    s->n_words = (uint64_t)(s->n_distinct / 8 + 1);
+    hipError_t fe = hipMalloc((void**)&s->filter, s->n_words * sizeof(uint64_t));
+    if (fe != hipSuccess) {
+      s->filter = nullptr;                               // the set works without its prefilter
+      s->n_words = 0;
+      (void)hipGetLastError();
+    } else {
+      (void)hipMemsetAsync(s->filter, 0, s->n_words * sizeof(uint64_t), stream);
+      uint64_t blocks = (n_slots + 1023) / 1024;
+      if (blocks > 65536) blocks = 65536;
+      hipLaunchKernelGGL(filter_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, s->slots,
+                         (uint64_t)n_slots, reinterpret_cast<unsigned long long*>(s->filter),
+                         s->n_words);
+      (void)hipStreamSynchronize(stream);
+    }
+  }
   *out = s;
   return cleanup(NEZHA_OK);
 }
@@ -428,6 +465,7 @@ int nezha_free_itemset(nezha_itemset* set) {
   if (!set) return NEZHA_OK;
   if (set->magic != kSetMagic) return fail(NEZHA_EINVAL, "not an item set (freed twice?)");
   set->magic = 0;
+  if (set->filter) (void)hipFree(set->filter);
   hipError_t e = set->slots ? hipFree(set->slots) : hipSuccess;
   delete set;
   if (e != hipSuccess) return fail(NEZHA_EHIP, "hipFree failed: %s", hipGetErrorString(e));
@@ -471,7 +509,9 @@ int nezha_verify_tuples(const nezha_itemset* set, const int32_t* codes, int64_t 
     r.T[l] = set->radices[l];
     r.mult[l] = set->mult[l];
   }
-  SetView view{set->slots, set->n_buckets};
+  // (the stand-alone verifier's queries are mostly present keys: the prefilter would only add an
+  // access, so it is left out of the view)
+  SetView view{set->slots, set->n_buckets, nullptr, 0};
   if (n == 0) {
     if (out_count) {
       hipLaunchKernelGGL(verify_scan_kernel, dim3(1), dim3(1024), 0, stream,

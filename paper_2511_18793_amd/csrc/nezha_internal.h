@@ -42,6 +42,10 @@ struct ProfileScope {
 struct SetView {  // what kernels need from an item set
   const uint64_t* slots;
   uint64_t n_buckets;
+  // optional prefilter (NULL: none): one 64-bit word per 8 keys with 3 bits set per key.  A key
+  // whose bits are not all set is not in the set; the others are looked up in the table.
+  const uint64_t* filter;
+  uint64_t n_words;
 };
 
 // ---- device helpers --------------------------------------------------------------------
@@ -57,6 +61,17 @@ __device__ __forceinline__ uint64_t hash64(uint64_t k) {
 }
 __device__ __forceinline__ uint64_t home_bucket(uint64_t key, uint64_t n_buckets) {
   return __umul64hi(hash64(key), n_buckets);  // range reduction without a modulo
+}
+
+// Prefilter word and bit mask of a key (from its hash; independent of the bucket index, which
+// uses the high bits of the same hash through a different product).
+__device__ __forceinline__ uint64_t filter_word(uint64_t h, uint64_t n_words) {
+  uint64_t g = h * 0xD6E8FEB86659FD93ull;
+  g ^= g >> 32;
+  return __umul64hi(g * 0x9E3779B97F4A7C15ull, n_words);
+}
+__device__ __forceinline__ uint64_t filter_mask(uint64_t h) {
+  return (1ull << (h & 63)) | (1ull << ((h >> 6) & 63)) | (1ull << ((h >> 12) & 63));
 }
 
 // A pointer known to address global memory, typed so: loads and stores through it are global
@@ -86,6 +101,11 @@ __device__ __forceinline__ ulonglong2 load_global_u64x2(const void* p) {
 // Membership of one key: scan the home bucket, then following buckets, until the key or an
 // empty slot is seen.  The table is never full, so the scan ends; it is bounded anyway.
 __device__ __forceinline__ bool set_contains(const SetView& s, uint64_t key) {
+  if (s.filter) {
+    const uint64_t h = hash64(key);
+    const uint64_t m = filter_mask(h);
+    if ((*(global_ptr<const uint64_t>)(s.filter + filter_word(h, s.n_words)) & m) != m) return false;
+  }
   uint64_t b = home_bucket(key, s.n_buckets);
   for (uint64_t step = 0; step < s.n_buckets; ++step) {
     const uint64_t* p = s.slots + b * kBucketSlots;
@@ -108,14 +128,29 @@ __device__ __forceinline__ bool set_contains(const SetView& s, uint64_t key) {
 template <int N>
 __device__ __forceinline__ void set_contains_many(const SetView& s, const uint64_t (&key)[N],
                                                   const bool (&live)[N], bool (&in)[N]) {
+  bool go[N];                                          // still to be looked up in the table
+#pragma unroll
+  for (int i = 0; i < N; ++i) go[i] = live[i];
+  if (s.filter) {
+    uint64_t w[N], m[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const uint64_t h = hash64(key[i]);
+      m[i] = filter_mask(h);
+      w[i] = m[i];
+      if (live[i]) w[i] = *(global_ptr<const uint64_t>)(s.filter + filter_word(h, s.n_words));
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) go[i] = live[i] && (w[i] & m[i]) == m[i];
+  }
   ulonglong2 q[N][4];
 #pragma unroll
   for (int i = 0; i < N; ++i) {
-    const uint64_t* p = s.slots + (live[i] ? home_bucket(key[i], s.n_buckets) : 0) * kBucketSlots;
+    const uint64_t* p = s.slots + (go[i] ? home_bucket(key[i], s.n_buckets) : 0) * kBucketSlots;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       q[i][c] = ulonglong2{kEmpty, kEmpty};
-      if (live[i]) q[i][c] = load_global_u64x2(p + 2 * c);
+      if (go[i]) q[i][c] = load_global_u64x2(p + 2 * c);
     }
   }
 #pragma unroll
@@ -126,9 +161,9 @@ __device__ __forceinline__ void set_contains_many(const SetView& s, const uint64
       hit |= (q[i][c].x == key[i]) | (q[i][c].y == key[i]);
       hole |= (q[i][c].x == kEmpty) | (q[i][c].y == kEmpty);
     }
-    in[i] = live[i] && hit;
+    in[i] = go[i] && hit;
     // a full home bucket without the key (rare at the load factors in use): the general scan
-    if (live[i] && !hit && !hole) in[i] = set_contains(s, key[i]);
+    if (go[i] && !hit && !hole) in[i] = set_contains(s, key[i]);
   }
 }
 
@@ -137,6 +172,8 @@ __device__ __forceinline__ void set_contains_many(const SetView& s, const uint64
 struct nezha_itemset {
   uint64_t* slots;      // device, n_buckets * kBucketSlots keys, kEmpty = free
   uint64_t n_buckets;
+  uint64_t* filter;     // device, n_words words (see SetView), or NULL
+  uint64_t n_words;
   int64_t n_distinct;
   int32_t L;
   int32_t radices[NEZHA_MAX_LEVELS];
