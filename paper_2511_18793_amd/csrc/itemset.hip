@@ -174,7 +174,7 @@ __global__ __launch_bounds__(kVerifyThreads) void verify_probe_kernel(
   uint32_t bits = 0;
 #pragma unroll
   for (int j = 0; j < kPerThread; ++j) {
-    bool in = ok[j] && set_contains(set, key[j]);
+    bool in = ok[j] && set_probe(set, key[j]);
     bits |= (in ? 1u : 0u) << (8 * j);
     cnt += in ? 1 : 0;
   }

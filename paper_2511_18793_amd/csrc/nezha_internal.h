@@ -98,14 +98,9 @@ __device__ __forceinline__ ulonglong2 load_global_u64x2(const void* p) {
   return ulonglong2{v.x, v.y};
 }
 
-// Membership of one key: scan the home bucket, then following buckets, until the key or an
-// empty slot is seen.  The table is never full, so the scan ends; it is bounded anyway.
-__device__ __forceinline__ bool set_contains(const SetView& s, uint64_t key) {
-  if (s.filter) {
-    const uint64_t h = hash64(key);
-    const uint64_t m = filter_mask(h);
-    if ((*(global_ptr<const uint64_t>)(s.filter + filter_word(h, s.n_words)) & m) != m) return false;
-  }
+// Membership of one key in the table: scan the home bucket, then following buckets, until the
+// key or an empty slot is seen.  The table is never full, so the scan ends; it is bounded anyway.
+__device__ __forceinline__ bool set_probe(const SetView& s, uint64_t key) {
   uint64_t b = home_bucket(key, s.n_buckets);
   for (uint64_t step = 0; step < s.n_buckets; ++step) {
     const uint64_t* p = s.slots + b * kBucketSlots;
@@ -120,6 +115,16 @@ __device__ __forceinline__ bool set_contains(const SetView& s, uint64_t key) {
     b = (b + 1 == s.n_buckets) ? 0 : b + 1;
   }
   return false;
+}
+
+// The same through the prefilter, where the view has one.
+__device__ __forceinline__ bool set_contains(const SetView& s, uint64_t key) {
+  if (s.filter) {
+    const uint64_t h = hash64(key);
+    const uint64_t m = filter_mask(h);
+    if ((*(global_ptr<const uint64_t>)(s.filter + filter_word(h, s.n_words)) & m) != m) return false;
+  }
+  return set_probe(s, key);
 }
 
 // Membership of N keys with all N home buckets in flight at once (the probes of one lane are
@@ -163,7 +168,7 @@ __device__ __forceinline__ void set_contains_many(const SetView& s, const uint64
     }
     in[i] = go[i] && hit;
     // a full home bucket without the key (rare at the load factors in use): the general scan
-    if (go[i] && !hit && !hole) in[i] = set_contains(s, key[i]);
+    if (go[i] && !hit && !hole) in[i] = set_probe(s, key[i]);
   }
 }
 
