@@ -265,6 +265,7 @@ def bench_draft(args, cfg):
     prof = nz.profile_read()
     nz.profile_enable(False)
     nz.profile_reset()
+    event_overhead_us = nz.profile_event_overhead(200)
 
     models = kernel_models(cfg)
     kernels = {}
@@ -291,7 +292,10 @@ def bench_draft(args, cfg):
                 "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dom)),
                 "avg_launch_us": kd["avg_us"],
                 "timing": "HIP events by the library around each launch, eager pass of %d steps"
-                          % prof_steps}
+                          % prof_steps,
+                # what the same bracket reports for an empty kernel: dispatch latency that
+                # avg_launch_us contains and a profiler's kernel trace does not
+                "event_overhead_us": event_overhead_us}
     if dom in ("expand_kernel", "expand_request_kernel", "level_small_kernel",
                "decode_small_kernel"):
         flops = sum(2.0 * cfg.B * (1 if l == 0 else cfg.K) * cfg.e * cfg.V * (0 if l == 0 else 1)

@@ -251,6 +251,11 @@ int nezha_profile_enable(int on);
 int nezha_profile_reset(void);
 int nezha_profile_kinds(void);
 int nezha_profile_read(int kind, const char** name, int64_t* launches, double* total_ms);
+/* What the same event bracket reports for an EMPTY kernel (mean over `launches` launches on
+ * hip_stream, microseconds): the dispatch latency that every duration from nezha_profile_read
+ * contains on top of the kernel's own run time (a profiler's kernel trace does not count it).
+ * Waits for the stream. */
+int nezha_profile_event_overhead(int launches, void* hip_stream, double* mean_us);
 
 /* Measurement aid for the verifier's roofline: n independent reads of whole, aligned lines of
  * line_bytes (64 or 128) at pseudo-random places of the device buffer buf (bytes long, 128-byte

@@ -19,6 +19,7 @@ EXPORTS = ["nezha_last_error", "nezha_build_itemset", "nezha_itemset_info", "nez
            "nezha_profile_reset", "nezha_profile_kinds", "nezha_profile_read",
            "nezha_bench_random_gather", "nezha_user_projection", "nezha_pack_weights",
            "nezha_packed_weights_bytes", "nezha_user_projection_levels", "nezha_draft_levels", "nezha_decode",
+           "nezha_profile_event_overhead",
            "nezha_draft_levels_workspace"]
 
 
@@ -472,6 +473,15 @@ def profile_read():
         if n.value:
             out[name.value.decode()] = (n.value, ms.value)
     return out
+
+
+def profile_event_overhead(launches=200, stream=None):
+    """Microseconds the library's event bracket reports for an empty kernel."""
+    lib = load_library()
+    lib.nezha_profile_event_overhead.argtypes = [C.c_int, C.c_void_p, C.POINTER(C.c_double)]
+    us = C.c_double()
+    _check(lib.nezha_profile_event_overhead(int(launches), _stream(stream), C.byref(us)))
+    return us.value
 
 
 def unpack_keys(keys, radices):

@@ -609,6 +609,34 @@ int nezha_profile_reset(void) {
 
 int nezha_profile_kinds(void) { return (int)kKernelKinds; }
 
+namespace nezha {
+namespace {
+__global__ void empty_kernel() {}
+}  // namespace
+}  // namespace nezha
+
+int nezha_profile_event_overhead(int launches, void* hip_stream, double* mean_us) {
+  if (launches < 1 || launches > 10000 || !mean_us) return fail(NEZHA_EINVAL, "bad argument");
+  hipStream_t stream = (hipStream_t)hip_stream;
+  std::vector<hipEvent_t> ev(2 * (size_t)launches);
+  for (auto& e : ev) NEZHA_HIP_CHECK(hipEventCreate(&e));
+  for (int i = 0; i < launches; ++i) {
+    NEZHA_HIP_CHECK(hipEventRecord(ev[2 * i], stream));
+    hipLaunchKernelGGL(empty_kernel, dim3(1), dim3(64), 0, stream);
+    NEZHA_HIP_CHECK(hipEventRecord(ev[2 * i + 1], stream));
+  }
+  NEZHA_HIP_CHECK(hipStreamSynchronize(stream));
+  double total = 0.0;
+  for (int i = 0; i < launches; ++i) {
+    float t = 0.f;
+    NEZHA_HIP_CHECK(hipEventElapsedTime(&t, ev[2 * i], ev[2 * i + 1]));
+    total += t;
+  }
+  for (auto& e : ev) (void)hipEventDestroy(e);
+  *mean_us = 1e3 * total / launches;
+  return NEZHA_OK;
+}
+
 int nezha_profile_read(int kind, const char** name, int64_t* launches, double* total_ms) {
   if (kind < 0 || kind >= (int)kKernelKinds) return fail(NEZHA_EINVAL, "kind out of range");
   if (name) *name = kKernelNames[kind];
