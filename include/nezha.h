@@ -64,9 +64,9 @@ const char* nezha_last_error(void); /* thread local, never NULL */
  *               prod T_l <= 2^64 - 1 (the value 2^64-1 is reserved for "empty").
  *   load_factor in (0, 0.9]; the table gets ceil(n / load_factor) key slots,
  *               rounded up to whole 64-byte buckets.
- *               Beside the table the set keeps a prefilter of about one byte per item (3 bits
- *               per key in one 64-bit word per 8 keys) that the draft step consults before the
- *               table: it can only rule keys out that are not in the set.
+ *               Beside the table the set keeps a prefilter of about four bytes per item (bitmaps
+ *               of the last codes present, in 64-byte blocks chosen by the prefix) that the draft
+ *               step consults before the table: it can only rule keys out that are not in the set.
  * Duplicate tuples are stored once.  A code outside [0, T_l) gives NEZHA_ERANGE.
  * The work runs on hip_stream and the call waits for it (building is an offline
  * step in the paper).  On success *out holds the new set. */

@@ -1331,7 +1331,7 @@ __global__ __launch_bounds__(64 * kMergeMaxWaves) void merge_kernel(MergeArgs a)
       const uint64_t pkey = a.key_in ? a.key_in[b * K_in + p] : 0ull;
       bool ok = pkey != kEmpty;                      // an empty beam slot has no children
       if (verify && ok)
-        ok = set_contains(a.set, pkey + (uint64_t)(uint32_t)a.cand_code[o] * a.mult);
+        ok = set_contains(a.set, pkey, (uint32_t)a.cand_code[o]);
       if (ok) sk = ((uint64_t)ordered_bits(score) << 32) | (uint32_t)~(uint32_t)i;
       keys[i] = sk;
     }
@@ -2269,7 +2269,7 @@ __device__ __forceinline__ void level_small_body(const LevelArgs& a, uint64_t* l
         const float score = (a.score_in ? as_global(a.score_in)[b] : 0.f) + logp;
         const uint64_t pkey = a.key_in ? as_global(a.key_in)[b] : 0ull;
         bool ok = pkey != kEmpty;                                       // an empty beam slot has no children
-        if (verify && ok) ok = set_contains(a.set, pkey + (uint64_t)code * a.mult);
+        if (verify && ok) ok = set_contains(a.set, pkey, code);
         if (ok) sk1[0][0] = ((uint64_t)ordered_bits(score) << 32) | (uint32_t)~(uint32_t)lane;
       }
       sort_desc<1, 1, uint64_t>(sk1);                                   // (score, place in code order)
@@ -2311,7 +2311,7 @@ __device__ __forceinline__ void level_small_body(const LevelArgs& a, uint64_t* l
       const float score = (a.score_in ? as_global(a.score_in)[b * K_in + p] : 0.f) + logp;
       const uint64_t pkey = a.key_in ? as_global(a.key_in)[b * K_in + p] : 0ull;
       bool ok = pkey != kEmpty;                                         // an empty beam slot has no children
-      if (verify && ok) ok = set_contains(a.set, pkey + (uint64_t)code * a.mult);
+      if (verify && ok) ok = set_contains(a.set, pkey, code);
       if (ok) sk = ((uint64_t)ordered_bits(score) << 32) | (uint32_t)~(uint32_t)tid;
       keys2[tid] = sk;
     }
@@ -2753,7 +2753,8 @@ static LevelArgs make_level_args(const nezha_step_desc* desc, const uint16_t* Wp
   la.score_in = score_in;
   la.E = E_l;
   la.set = SetView{(set && set->L == level) ? set->slots : nullptr, set ? set->n_buckets : 0,
-                   set ? set->filter : nullptr, set ? set->n_words : 0};
+                   set ? set->filter : nullptr, set ? set->n_blocks : 0,
+                   set ? set->mult[set->L - 1] : 0};
   la.U = desc->U_l;
   la.transition = desc->transition;
   la.mult = mult;
@@ -2876,7 +2877,8 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
     wa.score_in = score_in;
     const bool verify = set && set->L == level;
     wa.set = SetView{verify ? set->slots : nullptr, set ? set->n_buckets : 0,
-                     set ? set->filter : nullptr, set ? set->n_words : 0};
+                     set ? set->filter : nullptr, set ? set->n_blocks : 0,
+                   set ? set->mult[set->L - 1] : 0};
     wa.mult = mult[level - 1];
     wa.rows = rows;
     wa.K_in = K_in;
@@ -3178,7 +3180,8 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
   ma.state_in = state_in;
   ma.E = E_l;
   ma.set = SetView{(set && set->L == level) ? set->slots : nullptr, set ? set->n_buckets : 0,
-                   set ? set->filter : nullptr, set ? set->n_words : 0};
+                   set ? set->filter : nullptr, set ? set->n_blocks : 0,
+                   set ? set->mult[set->L - 1] : 0};
   ma.U = desc->U_l;
   ma.transition = desc->transition;
   ma.redo_req = redo_req;

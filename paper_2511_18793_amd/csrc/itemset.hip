@@ -129,16 +129,16 @@ __global__ void insert_kernel(const int32_t* __restrict__ codes, int64_t n, Radi
   }
 }
 
-// The prefilter from the finished table: every stored key sets its 3 bits.
+// The prefilter from the finished table: every stored key sets its bit.
 __global__ void filter_kernel(const uint64_t* __restrict__ slots, uint64_t n_slots,
-                              unsigned long long* filter, uint64_t n_words) {
+                              unsigned long long* filter, uint64_t n_blocks, uint64_t mult_last) {
   uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
   for (; i < n_slots; i += stride) {
     const uint64_t key = slots[i];
     if (key == kEmpty) continue;
-    const uint64_t h = hash64(key);
-    atomicOr(&filter[filter_word(h, n_words)], (unsigned long long)filter_mask(h));
+    const uint64_t code = key / mult_last, prefix = key - code * mult_last;
+    atomicOr(&filter[filter_word(prefix, (uint32_t)code, n_blocks)], 1ull << (code & 63));
   }
 }
 
@@ -343,7 +343,7 @@ int nezha_build_itemset(const int32_t* codes, int64_t n, int32_t L, const int32_
   if (!s) return fail(NEZHA_ENOMEM, "host allocation failed");
   s->slots = nullptr;
   s->filter = nullptr;
-  s->n_words = 0;
+  s->n_blocks = 0;
   s->n_buckets = n_buckets;
   s->n_distinct = 0;
   s->L = L;
@@ -426,23 +426,23 @@ int nezha_build_itemset(const int32_t* codes, int64_t n, int32_t L, const int32_
   }
   s->n_distinct = (int64_t)host_status[2];
   {
-    // The prefilter: one 64-bit word per 8 keys, 3 bits per key (about N bytes).  Most candidates
-    // of the draft step are not items; a filter word is a small, cache-resident access that turns
-    // most of their table probes (a random HBM line each) away.  It can only say "not in the
-    // set" for keys that are not in it, so results do not change.
-    s->n_words = (uint64_t)(s->n_distinct / 8 + 1);
-    hipError_t fe = hipMalloc((void**)&s->filter, s->n_words * sizeof(uint64_t));
+    // The prefilter: 512-bit blocks, one per 16 keys on average (4 bytes per item).  Most
+    // candidates of the draft step are not items; a filter word is a small, cache-resident access
+    // that turns most of their table probes (a random HBM line each) away.  It can only say "not
+    // in the set" for keys that are not in it, so results do not change.
+    s->n_blocks = (uint64_t)(s->n_distinct / 16 + 1);
+    hipError_t fe = hipMalloc((void**)&s->filter, s->n_blocks * 64);
     if (fe != hipSuccess) {
       s->filter = nullptr;                               // the set works without its prefilter
-      s->n_words = 0;
+      s->n_blocks = 0;
       (void)hipGetLastError();
     } else {
-      (void)hipMemsetAsync(s->filter, 0, s->n_words * sizeof(uint64_t), stream);
+      (void)hipMemsetAsync(s->filter, 0, s->n_blocks * 64, stream);
       uint64_t blocks = (n_slots + 1023) / 1024;
       if (blocks > 65536) blocks = 65536;
       hipLaunchKernelGGL(filter_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, s->slots,
                          (uint64_t)n_slots, reinterpret_cast<unsigned long long*>(s->filter),
-                         s->n_words);
+                         s->n_blocks, s->mult[L - 1]);
       (void)hipStreamSynchronize(stream);
     }
   }
@@ -511,7 +511,7 @@ int nezha_verify_tuples(const nezha_itemset* set, const int32_t* codes, int64_t 
   }
   // (the stand-alone verifier's queries are mostly present keys: the prefilter would only add an
   // access, so it is left out of the view)
-  SetView view{set->slots, set->n_buckets, nullptr, 0};
+  SetView view{set->slots, set->n_buckets, nullptr, 0, 0};
   if (n == 0) {
     if (out_count) {
       hipLaunchKernelGGL(verify_scan_kernel, dim3(1), dim3(1024), 0, stream,

@@ -42,10 +42,14 @@ struct ProfileScope {
 struct SetView {  // what kernels need from an item set
   const uint64_t* slots;
   uint64_t n_buckets;
-  // optional prefilter (NULL: none): one 64-bit word per 8 keys with 3 bits set per key.  A key
-  // whose bits are not all set is not in the set; the others are looked up in the table.
+  // optional prefilter (NULL: none): 64-byte blocks of 512 bits.  The block of a key is chosen by
+  // its prefix (all digits but the last) and the upper bits of its last digit, the bit inside the
+  // block is the last digit modulo 512: a bitmap of the last codes present, shared by the
+  // prefixes that hash to the block.  The candidates of one beam differ in the last digit only,
+  // so their filter reads fall on the same few lines.  A clear bit: the key is not in the set.
   const uint64_t* filter;
-  uint64_t n_words;
+  uint64_t n_blocks;
+  uint64_t mult_last;   // positional multiplier of the set's last digit (Eq. 4)
 };
 
 // ---- device helpers --------------------------------------------------------------------
@@ -63,15 +67,10 @@ __device__ __forceinline__ uint64_t home_bucket(uint64_t key, uint64_t n_buckets
   return __umul64hi(hash64(key), n_buckets);  // range reduction without a modulo
 }
 
-// Prefilter word and bit mask of a key (from its hash; independent of the bucket index, which
-// uses the high bits of the same hash through a different product).
-__device__ __forceinline__ uint64_t filter_word(uint64_t h, uint64_t n_words) {
-  uint64_t g = h * 0xD6E8FEB86659FD93ull;
-  g ^= g >> 32;
-  return __umul64hi(g * 0x9E3779B97F4A7C15ull, n_words);
-}
-__device__ __forceinline__ uint64_t filter_mask(uint64_t h) {
-  return (1ull << (h & 63)) | (1ull << ((h >> 6) & 63)) | (1ull << ((h >> 12) & 63));
+// Prefilter: word index of (prefix, last code); the bit inside the word is code & 63.
+__device__ __forceinline__ uint64_t filter_word(uint64_t prefix, uint32_t code, uint64_t n_blocks) {
+  const uint64_t block = __umul64hi(hash64(prefix * 8 + (code >> 9)), n_blocks);
+  return block * 8 + ((code >> 6) & 7);
 }
 
 // A pointer known to address global memory, typed so: loads and stores through it are global
@@ -117,36 +116,39 @@ __device__ __forceinline__ bool set_probe(const SetView& s, uint64_t key) {
   return false;
 }
 
-// The same through the prefilter, where the view has one.
-__device__ __forceinline__ bool set_contains(const SetView& s, uint64_t key) {
+// The same for the key prefix + code * mult_last, through the prefilter where the view has one.
+__device__ __forceinline__ bool set_contains(const SetView& s, uint64_t prefix, uint32_t code) {
   if (s.filter) {
-    const uint64_t h = hash64(key);
-    const uint64_t m = filter_mask(h);
-    if ((*(global_ptr<const uint64_t>)(s.filter + filter_word(h, s.n_words)) & m) != m) return false;
+    const uint64_t w = *(global_ptr<const uint64_t>)(s.filter + filter_word(prefix, code, s.n_blocks));
+    if (((w >> (code & 63)) & 1ull) == 0ull) return false;
   }
-  return set_probe(s, key);
+  return set_probe(s, prefix + (uint64_t)code * s.mult_last);
 }
 
-// Membership of N keys with all N home buckets in flight at once (the probes of one lane are
-// independent random lines; one at a time leaves the memory system idle).  live[i] == false:
-// key i is not looked up and in[i] is false.
+// Membership of N keys (prefix[i] + code[i] * mult_last) with all N lookups in flight at once
+// (the probes of one lane are independent random lines; one at a time leaves the memory system
+// idle).  live[i] == false: key i is not looked up and in[i] is false.
 template <int N>
-__device__ __forceinline__ void set_contains_many(const SetView& s, const uint64_t (&key)[N],
-                                                  const bool (&live)[N], bool (&in)[N]) {
+__device__ __forceinline__ void set_contains_many(const SetView& s, const uint64_t (&prefix)[N],
+                                                  const uint32_t (&code)[N], const bool (&live)[N],
+                                                  bool (&in)[N]) {
   bool go[N];                                          // still to be looked up in the table
+  uint64_t key[N];
 #pragma unroll
-  for (int i = 0; i < N; ++i) go[i] = live[i];
+  for (int i = 0; i < N; ++i) {
+    go[i] = live[i];
+    key[i] = prefix[i] + (uint64_t)code[i] * s.mult_last;
+  }
   if (s.filter) {
-    uint64_t w[N], m[N];
+    uint64_t w[N];
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      const uint64_t h = hash64(key[i]);
-      m[i] = filter_mask(h);
-      w[i] = m[i];
-      if (live[i]) w[i] = *(global_ptr<const uint64_t>)(s.filter + filter_word(h, s.n_words));
+      w[i] = ~0ull;
+      if (live[i])
+        w[i] = *(global_ptr<const uint64_t>)(s.filter + filter_word(prefix[i], code[i], s.n_blocks));
     }
 #pragma unroll
-    for (int i = 0; i < N; ++i) go[i] = live[i] && (w[i] & m[i]) == m[i];
+    for (int i = 0; i < N; ++i) go[i] = live[i] && ((w[i] >> (code[i] & 63)) & 1ull);
   }
   ulonglong2 q[N][4];
 #pragma unroll
@@ -177,8 +179,8 @@ __device__ __forceinline__ void set_contains_many(const SetView& s, const uint64
 struct nezha_itemset {
   uint64_t* slots;      // device, n_buckets * kBucketSlots keys, kEmpty = free
   uint64_t n_buckets;
-  uint64_t* filter;     // device, n_words words (see SetView), or NULL
-  uint64_t n_words;
+  uint64_t* filter;     // device, n_blocks blocks of 8 words (see SetView), or NULL
+  uint64_t n_blocks;
   int64_t n_distinct;
   int32_t L;
   int32_t radices[NEZHA_MAX_LEVELS];

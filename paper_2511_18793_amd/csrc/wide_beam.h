@@ -635,13 +635,15 @@ __device__ RadixPick regs_radix_select(const uint32_t (&key)[NV], int K, uint32_
   return r;
 }
 
-// Set membership of two keys with both home buckets in flight at once.
-__device__ __forceinline__ void set_contains_pair(const SetView& s, uint64_t k0, bool live0,
-                                                  uint64_t k1, bool live1, bool& in0, bool& in1) {
-  const uint64_t key[2] = {k0, k1};
+// Set membership of two children (codes c0, c1) of one beam with both lookups in flight at once.
+__device__ __forceinline__ void set_contains_pair(const SetView& s, uint64_t pkey, uint32_t c0,
+                                                  bool live0, uint32_t c1, bool live1, bool& in0,
+                                                  bool& in1) {
+  const uint64_t prefix[2] = {pkey, pkey};
+  const uint32_t code[2] = {c0, c1};
   const bool live[2] = {live0, live1};
   bool in[2];
-  set_contains_many<2>(s, key, live, in);
+  set_contains_many<2>(s, prefix, code, live, in);
   in0 = in[0];
   in1 = in[1];
 }
@@ -709,8 +711,7 @@ __global__ __launch_bounds__(kWideRowThreads) void wide_rows_kernel(WideArgs a) 
         for (int j = 0; j < NV; j += 2) {
           const int v0 = tid + j * NT, v1 = v0 + NT;
           bool in0, in1;
-          set_contains_pair(a.set, pkey + (uint64_t)(uint32_t)v0 * a.mult, v0 < V,
-                            pkey + (uint64_t)(uint32_t)v1 * a.mult, v1 < V, in0, in1);
+          set_contains_pair(a.set, pkey, (uint32_t)v0, v0 < V, (uint32_t)v1, v1 < V, in0, in1);
           if (v0 < V) as_global(zk)[v0] = in0 ? key[j] : 0u;
           if (v1 < V) as_global(zk)[v1] = in1 ? key[j + 1] : 0u;
           if (in0) keep(v0, key[j]);
@@ -755,8 +756,7 @@ __global__ __launch_bounds__(kWideRowThreads) void wide_rows_kernel(WideArgs a) 
           const bool live1 = i + NT < n;
           const uint64_t c0 = cand[i], c1 = live1 ? cand[i + NT] : 0ull;
           bool in0, in1;
-          set_contains_pair(a.set, pkey + (uint64_t)(uint32_t)c0 * a.mult, true,
-                            pkey + (uint64_t)(uint32_t)c1 * a.mult, live1, in0, in1);
+          set_contains_pair(a.set, pkey, (uint32_t)c0, true, (uint32_t)c1, live1, in0, in1);
           if (in0) {
             atomicOr(&member[(uint32_t)c0 >> 5], 1u << ((uint32_t)c0 & 31u));
             keep((int)(uint32_t)c0, (uint32_t)(c0 >> 32));
@@ -807,7 +807,7 @@ __global__ __launch_bounds__(kWideRowThreads) void wide_rows_kernel(WideArgs a) 
       for (int v = tid; v < V; v += NT) {
         const uint32_t k = as_global(zk)[v];
         if (k == 0u) continue;
-        const bool in = k >= tau && set_contains(a.set, pkey + (uint64_t)(uint32_t)v * a.mult);
+        const bool in = k >= tau && set_contains(a.set, pkey, (uint32_t)v);
         if (!in) as_global(zk)[v] = 0u;
         else keep(v, k);
       }
