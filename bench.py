@@ -40,14 +40,18 @@ BUCKET_BYTES = 64
 # are in profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB -> bytes; the factors come from the
 # plain-copy calibration in the same runs).  Only workloads that were profiled have an entry.
 MEASURED_TRAFFIC_BYTES = {
-    ("serving", "decode_small_kernel"): (5563.9 * 2.0 + 2920.0) * 1024,
+    ("serving", "decode_small_kernel"): (2852.8 * 2.0 + 2920.0) * 1024,
     ("stress", "verify_probe_kernel"): (245832.5 * 2.0 + 4064.6) * 1024,
-    ("recall", "wide_rows_kernel"): (1217454.8 * 2.0 + 525739.0) * 1024,
-    ("wide", "expand_kernel"): (12417.7 * 2.0 + 15100.0) * 1024,          # expand_small_kernel
+    ("recall", "wide_rows_kernel"): (316710.7 * 2.0 + 525740.9) * 1024,
+    # the library times the logits launches of a level as one: levels 1 and 2 the two fused launches
+    # (counter means over both levels), level 3 the plain logits launch; mean of the three
+    ("recall", "wide_logits_kernel"): (2 * ((7235.8 + 11405.5) * 2.0 + 538.1 + 339455.6) +
+                                       (12774.2 * 2.0 + 694014.5)) / 3 * 1024,
+    ("wide", "expand_kernel"): (12420.3 * 2.0 + 15100.0) * 1024,          # expand_small_kernel
     # mean of the two launches of a decode: the whole-level variant (level 2) and the per-beam
     # variant (level 3, whose candidate lists go through HBM to the merge)
-    ("large", "expand_request_kernel"): ((306393.9 * 2.0 + 173605.6) +
-                                         (553581.4 * 2.0 + 1095151.8)) / 2 * 1024,
+    ("large", "expand_request_kernel"): ((306654.3 * 2.0 + 173439.6) +
+                                         (554139.6 * 2.0 + 1096342.8)) / 2 * 1024,
 }
 
 
