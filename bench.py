@@ -6,8 +6,14 @@ level, hash-set verification and pruning at the last) on synthetic inputs that a
 resident in device memory.  The metric is verified candidate items per second: the B*K*K
 level-L candidates submitted to the verifier per decode, divided by the decode time.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload serving|large|wide|tiny|
-                    paper_yelp|paper_beauty|paper_games|stress] [--eager] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large|serving|wide|recall|tiny|
+                    paper_yelp|paper_beauty|paper_games|stress|user_gemm] [--eager]
+                    [--no-cpu-baseline] [--no-serving-leg]
+
+The default workload is the largest configuration that runs on one GPU (Large: B = 4096, d = 2048,
+T_l = 4096, K = 100, 5 * 10^7 items).  Since the metric also names the p50 latency of a step, the
+same line carries a short second leg under `serving_latency`: the Serving configuration's decode
+latency percentiles (its own set-up, 20 warm-up and 200 timed decodes; never part of `value`).
 
 Prints ONE JSON line.  `roofline` describes the kernel that took the most time, timed with HIP
 events by the library itself; `cpu_baseline` is the CPU oracle timed on the host cores."""
@@ -36,23 +42,56 @@ PEAK_ALU_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # threshold compare (1)
 EXPAND_SLOTS_PER_LOGIT = 8
 BUCKET_BYTES = 64
-# HBM traffic per launch of the dominant kernel, from the rocprofv3 counter runs whose summaries
-# are in profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB -> bytes; the factors come from the
-# plain-copy calibration in the same runs).  Only workloads that were profiled have an entry.
-MEASURED_TRAFFIC_BYTES = {
-    ("serving", "decode_small_kernel"): (2852.8 * 2.0 + 2920.0) * 1024,
-    ("stress", "verify_probe_kernel"): (245832.5 * 2.0 + 4064.6) * 1024,
-    ("recall", "wide_rows_kernel"): (316710.7 * 2.0 + 525740.9) * 1024,
-    # the library times the logits launches of a level as one: levels 1 and 2 the two fused launches
-    # (counter means over both levels), level 3 the plain logits launch; mean of the three
-    ("recall", "wide_logits_kernel"): (2 * ((7235.8 + 11405.5) * 2.0 + 538.1 + 339455.6) +
-                                       (12774.2 * 2.0 + 694014.5)) / 3 * 1024,
-    ("wide", "expand_kernel"): (12420.3 * 2.0 + 15100.0) * 1024,          # expand_small_kernel
-    # mean of the two launches of a decode: the whole-level variant (level 2) and the per-beam
-    # variant (level 3, whose candidate lists go through HBM to the merge)
-    ("large", "expand_request_kernel"): ((306654.3 * 2.0 + 173439.6) +
-                                         (554139.6 * 2.0 + 1096342.8)) / 2 * 1024,
+# Which kernels of a profiler trace belong to a kernel kind of the library's own event timing.
+TRACE_NAMES = {
+    "expand_kernel": ("expand_small_kernel", "expand_chunked_kernel", "expand_kernel"),
+    "expand_request_kernel": ("expand_request_kernel",),
+    "user_gemm_kernel": ("user_gemm_",),
+    "merge_kernel": ("merge_kernel",),
+    "decode_small_kernel": ("decode_small_kernel",),
+    "level_small_kernel": ("level_small_kernel",),
+    "wide_logits_kernel": ("wide_fused_bf16_kernel", "wide_logits_"),
+    "wide_rows_kernel": ("wide_rows_kernel",),
+    "wide_select_kernel": ("wide_collect_kernel", "wide_finish_kernel", "wide_select_kernel",
+                           "wide_bound_kernel"),
+    "verify_probe_kernel": ("verify_probe_kernel",),
 }
+
+
+def traffic_from_profile(workload, kind):
+    """HBM bytes per launch of a kernel kind, read from the counter table of the rocprofv3 summary
+    profiles/<kind's kernel>__<workload>.md (FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each
+    times the scale factor its plain-copy calibration gave; the dispatch-weighted mean over the
+    kernel's template variants).  Nothing is pasted here: the figure is whatever the committed
+    summary holds, and `source` names the file and the commit it was measured at.  (None, reason)
+    when no summary covers the kernel."""
+    import glob
+    import re
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*__%s.md" % workload))):
+        text = open(path).read()
+        m = re.search(r"FETCH_SIZE x ([0-9]+(?:\.[0-9]+)?), WRITE_SIZE x ([0-9]+(?:\.[0-9]+)?)", text)
+        if not m:
+            continue
+        ff, wf = float(m.group(1)), float(m.group(2))
+        total = n = 0.0
+        in_counters = False
+        for line in text.splitlines():
+            if line.startswith("## "):
+                in_counters = "traffic counters" in line
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            if not in_counters or len(cells) != 4 or not cells[0].startswith(TRACE_NAMES.get(kind, (kind,))):
+                continue
+            try:
+                f, w, k = float(cells[1]), float(cells[2]), float(cells[3])
+            except ValueError:
+                continue
+            total += (f * ff + w * wf) * 1024.0 * k
+            n += k
+        if n:
+            c = re.search(r"[Mm]easured at commit[: ]+([0-9a-f]{7,40})", text)
+            return total / n, "%s (measured at commit %s)" % (
+                os.path.relpath(path, ROOT), c.group(1) if c else "not recorded")
+    return None, "no rocprofv3 counter summary for this kernel and workload under profiles/"
 
 
 def parse_args():
@@ -60,7 +99,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="serving")
+    ap.add_argument("--workload", default="large")
     ap.add_argument("--seed", type=int, default=42)
     ap.add_argument("--launch", choices=("auto", "direct", "graph"), default="auto",
                     help="how a step reaches the GPU: 'direct' = one call of the C ABI per step "
@@ -72,6 +111,8 @@ def parse_args():
                     help="also time the same decodes issued alternately on two streams (reported "
                          "as two_stream_ms_per_step, never as value)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-serving-leg", action="store_true",
+                    help="skip the Serving latency leg that the default (Large) run appends")
     ap.add_argument("--pack-per-call", action="store_true",
                     help="rearrange the weights inside every step instead of once at set-up")
     ap.add_argument("--calibrate", action="store_true",
@@ -80,6 +121,11 @@ def parse_args():
     ap.add_argument("--transition", choices=("add", "rnn"), default="add",
                     help="Transition of Eq. 3: additive (the measured path) or the recurrent cell "
                          "c' = tanh(U c + e_l) (variant; U and the embeddings are synthetic)")
+    ap.add_argument("--head", choices=("nezha", "nezha1", "nezha2", "mtp"), default="nezha",
+                    help="comparison heads of the ablation (Sec. 4.3), same kernels with a term "
+                         "removed: nezha1 = no autoregressive state; nezha2 = no placeholder "
+                         "hidden states (one hidden vector for all levels, state kept); mtp = "
+                         "parallel heads on one hidden state, no state")
     ap.add_argument("--prefix-sets", action="store_true",
                     help="variant: also verify each level below L against the set of the "
                          "catalog's prefixes of that length")
@@ -133,11 +179,21 @@ def kernel_models(cfg):
     return per_level
 
 
-def bench_draft(args, cfg):
+class DraftSetup:
+    """Inputs, catalog, item set, packed weights and the step function of one draft workload."""
+
+
+def setup_draft(args, cfg):
+    st = DraftSetup()
     dev = torch.device("cuda:0")
     dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     t0 = time.time()
     x = synth.draft_inputs(cfg, args.seed)
+    if args.head in ("nezha2", "mtp"):
+        # nezha2: the variant without the placeholder hidden states h_l (one hidden vector, the
+        # first, serves every level; the autoregressive state is kept); mtp: parallel heads on
+        # that one hidden vector with no state between the levels
+        x["H"] = np.repeat(x["H"][:, :1], cfg.L, axis=1).copy()
     H = torch.from_numpy(x["H"]).to(dev).to(dt)
     W = [torch.from_numpy(w).to(dev).to(dt) for w in x["W"]]
     E = [torch.from_numpy(w).to(dev).to(dt) for w in x["E"]]
@@ -155,10 +211,11 @@ def bench_draft(args, cfg):
             x["E"] = [(em * 25.0).astype(np.float32) for em in x["E"]]
         E = [torch.from_numpy(w).to(dev).to(dt) for w in x["E"]]
         U = [torch.from_numpy(u).to(dev).to(dt) for u in Unp]
+    use_state = args.head not in ("mtp", "nezha1")
 
     # Catalog: Zipf / uniform background, with about 70 % of the unverified top-K beams planted
     # so that about 30 % of them are hallucinations (this pass runs without a verifier).
-    free = nz.decode(H, W, E, cfg.radices, cfg.K, None, buffers=bufs, U=U)
+    free = nz.decode(H, W, E, cfg.radices, cfg.K, None, buffers=bufs, U=U, use_state=use_state)
     torch.cuda.synchronize()
     beams = nz.unpack_keys(free[-1]["key"].cpu().numpy().ravel(), cfg.radices)
     if cfg.catalog == "uniform":
@@ -174,7 +231,7 @@ def bench_draft(args, cfg):
     if args.prefix_sets:
         prefix_sets = [nz.build_itemset(np.unique(catalog[:, :l], axis=0), cfg.radices[:l],
                                         cfg.load_factor) for l in range(1, cfg.L)]
-    setup_s = time.time() - t0
+    st.setup_s = time.time() - t0
 
     # The head's weights are static in serving: their operand-order form is made once, here,
     # outside the timed region (bf16 only; --pack-per-call keeps the packing inside every step).
@@ -183,7 +240,7 @@ def bench_draft(args, cfg):
         Wrun = [nz.pack_weights(l + 1, cfg.L, cfg.radices, W[l], cfg.d) for l in range(cfg.L)]
 
     plan = None
-    if cfg.dtype == "bf16" and not args.pack_per_call:
+    if cfg.dtype == "bf16" and not args.pack_per_call and use_state:
         # everything a decode needs, marshalled once: a step is one call of nezha_decode
         plan = nz.DecodePlan(H, Wrun, E, cfg.radices, cfg.K, itemset, buffers=bufs, U=U,
                              prefix_sets=prefix_sets)
@@ -193,7 +250,46 @@ def bench_draft(args, cfg):
             plan.run()
         else:
             nz.decode(H, Wrun, E, cfg.radices, cfg.K, itemset, buffers=bufs, U=U,
-                      prefix_sets=prefix_sets)
+                      prefix_sets=prefix_sets, use_state=use_state)
+
+    st.dev, st.dt, st.x, st.H, st.E, st.U, st.Unp, st.Wrun = dev, dt, x, H, E, U, Unp, Wrun
+    st.bufs, st.catalog, st.itemset, st.prefix_sets, st.keep = bufs, catalog, itemset, prefix_sets, keep
+    st.plan, st.step, st.use_state = plan, step, use_state
+    return st
+
+
+def serving_latency_leg(args):
+    """p50 / p90 / p99 latency of one decode of the Serving configuration (the shape a latency
+    figure belongs to): 20 warm-up and 200 timed decodes, one after the other on one stream, one
+    nezha_decode call each.  Reported under `serving_latency`; never part of `value`."""
+    cfg = synth.get_config("serving")
+    st = setup_draft(args, cfg)
+    steps, warmup = 200, 20
+    for _ in range(warmup):
+        st.step()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    ev[0].record()
+    for i in range(steps):
+        st.step()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    per = [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
+    cands = cfg.B * cfg.K * cfg.K
+    ms = ev[0].elapsed_time(ev[-1]) / steps
+    return {"workload": "serving", "B": cfg.B, "d": cfg.d, "e": cfg.e, "L": cfg.L, "V": cfg.V,
+            "K": cfg.K, "catalog_items": int(st.catalog.shape[0]), "steps": steps, "warmup": warmup,
+            "ms_per_step": ms, "p50_step_ms": percentile(per, 50),
+            "p90_step_ms": percentile(per, 90), "p99_step_ms": percentile(per, 99),
+            "items_per_s": cands / (ms * 1e-3),
+            "accepted_per_step": int(st.bufs.outs[-1]["count"].sum().item())}
+
+
+def bench_draft(args, cfg):
+    st = setup_draft(args, cfg)
+    dev, dt, x, H, E, U, Unp, Wrun = st.dev, st.dt, st.x, st.H, st.E, st.U, st.Unp, st.Wrun
+    bufs, catalog, itemset, prefix_sets, keep = st.bufs, st.catalog, st.itemset, st.prefix_sets, st.keep
+    plan, step, setup_s, use_state = st.plan, st.step, st.setup_s, st.use_state
 
     launch = "direct" if args.eager else args.launch
     if launch == "auto":
@@ -254,7 +350,7 @@ def bench_draft(args, cfg):
                for _ in range(cfg.L + 1)] for _ in range(lev_steps)]
     for i in range(lev_steps):
         nz.decode(H, Wrun, E, cfg.radices, cfg.K, itemset, buffers=bufs, U=U,
-                  prefix_sets=prefix_sets, level_events=lev_ev[i])
+                  prefix_sets=prefix_sets, level_events=lev_ev[i], use_state=use_state)
     torch.cuda.synchronize()
     level_ms = [[lev_ev[i][l][0].elapsed_time(lev_ev[i][l][1]) for i in range(lev_steps)]
                 for l in range(cfg.L + 1)]
@@ -293,7 +389,8 @@ def bench_draft(args, cfg):
         achieved = kd["work"] / (kd["total_ms"] * 1e-3) / 1e9
     roofline = {"kernel": dom, "bound": kd["bound"], "achieved": achieved, "peak": peak,
                 "unit": unit, "frac": achieved / peak,
-                "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dom)),
+                "traffic": traffic_from_profile(cfg.name, dom)[0],
+                "traffic_source": traffic_from_profile(cfg.name, dom)[1],
                 "avg_launch_us": kd["avg_us"],
                 "timing": "HIP events by the library around each launch, eager pass of %d steps"
                           % prof_steps,
@@ -336,6 +433,7 @@ def bench_draft(args, cfg):
                    "weights": "packed per call" if (args.pack_per_call or cfg.dtype != "bf16")
                    else "packed once at set-up",
                    "transition": args.transition, "prefix_sets": bool(args.prefix_sets),
+                   "head": args.head,
                    "setup_s": round(setup_s, 1)},
         "accepted_items_per_s": accepted / (ms_per_step * 1e-3),
         "roofline": roofline,
@@ -344,11 +442,12 @@ def bench_draft(args, cfg):
     if two_stream_ms is not None:
         result["two_stream_ms_per_step"] = two_stream_ms
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline_draft(cfg, x, catalog, cands, Unp, args.prefix_sets)
+        result["cpu_baseline"] = cpu_baseline_draft(cfg, x, catalog, cands, Unp, args.prefix_sets,
+                                                    use_state)
     return result
 
 
-def cpu_baseline_draft(cfg, x, catalog, cands, U=None, prefix_sets=False):
+def cpu_baseline_draft(cfg, x, catalog, cands, U=None, prefix_sets=False, use_state=True):
     """The CPU oracle, as it stands, on the host cores: a bounded sample of requests of the same
     workload, scaled to the batch."""
     from oracle import oracle as orc
@@ -369,7 +468,8 @@ def cpu_baseline_draft(cfg, x, catalog, cands, U=None, prefix_sets=False):
     while reps == 0 or (dt < 10.0 and reps < 2000):
         t = time.perf_counter()
         orc.decode(Hs, x["W"], x["E"], cfg.radices, cfg.K, oset,
-                   round_state_bf16=cfg.dtype == "bf16", threads=threads, U=U, prefix_sets=opre)
+                   round_state_bf16=cfg.dtype == "bf16", threads=threads, U=U, prefix_sets=opre,
+                   use_state=use_state)
         dt += time.perf_counter() - t
         reps += 1
     return {"value": cands * (n / cfg.B) * reps / dt, "unit": "items/s", "cores": min(threads, n),
@@ -461,7 +561,8 @@ def bench_stress(args, cfg):
                    "table_bytes": itemset.info()["n_slots"] * 8, "setup_s": round(setup_s, 1)},
         "roofline": {"kernel": "verify_probe_kernel", "bound": "hbm", "achieved": achieved,
                      "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, "verify_probe_kernel")),
+                     "traffic": traffic_from_profile(cfg.name, "verify_probe_kernel")[0],
+                     "traffic_source": traffic_from_profile(cfg.name, "verify_probe_kernel")[1],
                      "avg_launch_us": 1e3 * ms / launches,
                      "bytes_per_probe": bytes_per_probe,
                      "probes_per_s": n * launches / (ms * 1e-3),
@@ -509,6 +610,8 @@ def main():
     if args.catalog and cfg.B:
         cfg = cfg.scaled(N=args.catalog)
     result = bench_stress(args, cfg) if cfg.B == 0 else bench_draft(args, cfg)
+    if cfg.name == "large" and not args.no_serving_leg and not args.batch:
+        result["serving_latency"] = serving_latency_leg(args)
     print(json.dumps(result))
 
 

@@ -69,7 +69,11 @@ const char* nezha_last_error(void); /* thread local, never NULL */
  *               step consults before the table: it can only rule keys out that are not in the set.
  * Duplicate tuples are stored once.  A code outside [0, T_l) gives NEZHA_ERANGE.
  * The work runs on hip_stream and the call waits for it (building is an offline
- * step in the paper).  On success *out holds the new set. */
+ * step in the paper).  On success *out holds the new set.  On any failure *out is NULL and
+ * everything the call had allocated has been released.  (Test aid: with NEZHA_TEST_FAIL_ALLOC=N
+ * in the environment the N-th allocation of a build -- 1 the handle, 2 the table, 3 status words,
+ * then the staging buffer for a host catalog, last the prefilter -- is treated as failed:
+ * NEZHA_ENOMEM, except for the prefilter, without which the set still works.) */
 int nezha_build_itemset(const int32_t* codes, int64_t n, int32_t L, const int32_t* radices,
                         int codes_on_device, double load_factor, void* hip_stream,
                         nezha_itemset** out);
@@ -78,8 +82,20 @@ int nezha_build_itemset(const int32_t* codes, int64_t n, int32_t L, const int32_
 int nezha_itemset_info(const nezha_itemset* set, int64_t* n_distinct, int64_t* n_slots,
                        int32_t* L, int32_t* radices);
 
-/* Frees the set (NULL is accepted).  The caller makes sure no enqueued work still uses it. */
+/* Frees the set (NULL is accepted).  The caller makes sure no enqueued work still uses it.  The
+ * library keeps a registry of the sets it has handed out: a pointer that is not (or no longer) one
+ * of them -- freed before, or never a set -- gives NEZHA_EINVAL here and in every call that takes
+ * a set, and its memory is not read. */
 int nezha_free_itemset(nezha_itemset* set);
+
+/* Self-check of a built set (Sec. 3.3: the set must hold every valid item, or valid drafts would
+ * be dropped): looks every tuple of `codes` up the way the draft step does -- through the
+ * prefilter, then the table -- and returns in *n_missing how many were not found.  Called with
+ * the catalog the set was built from, the answer must be 0.  codes as for nezha_build_itemset
+ * (host or device pointer, int32 [n, L of the set]).  Allocates a few bytes (plus a staging buffer
+ * for host codes) and waits for hip_stream: an offline call, like the build. */
+int nezha_check_itemset(const nezha_itemset* set, const int32_t* codes, int64_t n,
+                        int codes_on_device, void* hip_stream, int64_t* n_missing);
 
 /* ---- stand-alone verification (Eq. 4 + Eq. 5 on a batch of tuples) ---------------------
  *
@@ -139,6 +155,10 @@ typedef struct {
   const void* U_l;        /* NEZHA_TRANSITION_RNN: device [e, e] row major, same dtype as the
                              states, 16-byte aligned: c'[j] = tanh(sum_i U_l[j][i] c[i] + E_l[code][j]).
                              Ignored (may be NULL) otherwise */
+  const void* state_init; /* read by nezha_draft_levels and nezha_decode only: the state the single
+                             beam of level 1 starts from (Eq. 1: the initial context state),
+                             device [B, 1, e], 16-byte aligned; NULL = zeros.  nezha_draft_step
+                             takes it as its state_in argument instead */
 } nezha_step_desc;
 
 /* All data pointers are device pointers.
@@ -175,8 +195,9 @@ size_t nezha_draft_step_workspace(const nezha_step_desc* desc); /* 0 if desc is 
 /* All L levels of the inference loop of Alg. 3 in one call: exactly what L calls of
  * nezha_draft_step do with level = 1..L, K_in = 1 at level 1 and K after it, each level's
  * key_out / score_out / state_out feeding the next level's key_in / score_in / state_in.
- * desc gives B, L, K, d, e, radices, dtype, h_row_stride, w_packed and transition for all
- * levels; its level, K_in, user_part and U_l are not read (they come from io[l-1]).  io: host
+ * desc gives B, L, K, d, e, radices, dtype, h_row_stride, w_packed, transition and state_init
+ * for all levels; its level, K_in, user_part and U_l are not read (they come from io[l-1]).  The
+ * arguments of all L levels are checked before anything is enqueued.  io: host
  * array of L entries; the pointers in it follow the rules of the like-named arguments of
  * nezha_draft_step (device memory; set = items at level L or prefixes of length l below it or
  * NULL; user_part and U_l optional).  When every level is small enough for the single-launch

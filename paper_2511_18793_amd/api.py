@@ -20,7 +20,7 @@ EXPORTS = ["nezha_last_error", "nezha_build_itemset", "nezha_itemset_info", "nez
            "nezha_bench_random_gather", "nezha_user_projection", "nezha_pack_weights",
            "nezha_packed_weights_bytes", "nezha_user_projection_levels", "nezha_draft_levels", "nezha_decode",
            "nezha_profile_event_overhead",
-           "nezha_draft_levels_workspace"]
+           "nezha_draft_levels_workspace", "nezha_check_itemset"]
 
 
 class NezhaError(RuntimeError):
@@ -34,7 +34,8 @@ class _StepDesc(C.Structure):
                 ("K_in", C.c_int32), ("d", C.c_int32), ("e", C.c_int32),
                 ("radices", C.POINTER(C.c_int32)), ("dtype", C.c_int),
                 ("h_row_stride", C.c_int64), ("w_packed", C.c_int32),
-                ("user_part", C.c_void_p), ("transition", C.c_int32), ("U_l", C.c_void_p)]
+                ("user_part", C.c_void_p), ("transition", C.c_int32), ("U_l", C.c_void_p),
+                ("state_init", C.c_void_p)]
 
 
 class _LevelIO(C.Structure):
@@ -73,6 +74,8 @@ def load_library():
     lib.nezha_draft_step.argtypes = [C.POINTER(_StepDesc)] + [C.c_void_p] * 14 + [C.c_size_t,
                                                                                   C.c_void_p]
     lib.nezha_unpack_keys.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.nezha_check_itemset.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p,
+                                        C.POINTER(C.c_int64)]
     _LIB = lib
     return lib
 
@@ -111,6 +114,18 @@ class ItemSet:
         _check(load_library().nezha_itemset_info(self._h, C.byref(n), C.byref(slots), C.byref(L), rad))
         return {"n_distinct": n.value, "n_slots": slots.value, "L": L.value,
                 "radices": list(rad[:L.value])}
+
+    def check(self, codes, stream=None):
+        """nezha_check_itemset: how many of the tuples `codes` (int32 [n, L], numpy / CPU tensor or
+        CUDA tensor) the set does not find; 0 for the catalog it was built from."""
+        if isinstance(codes, np.ndarray):
+            codes = torch.from_numpy(np.ascontiguousarray(codes, dtype=np.int32))
+        codes = codes.contiguous()
+        missing = C.c_int64(-1)
+        _check(load_library().nezha_check_itemset(self._h, _ptr(codes) if codes.numel() else None,
+                                                  codes.shape[0], 1 if codes.is_cuda else 0,
+                                                  _stream(stream), C.byref(missing)))
+        return missing.value
 
     def close(self):
         if self._h is not None:
@@ -169,13 +184,14 @@ def verify_tuples(itemset, codes, out_mask=None, out_index=None, out_count=None,
 
 
 def _desc(B, L, level, K, K_in, d, e, radices, dtype, h_row_stride, w_packed=False,
-          user_part=None, U_l=None):
+          user_part=None, U_l=None, state_init=None):
     rad = _radices(radices)
     dsc = _StepDesc(B, L, level, K, K_in, d, e, C.cast(rad, C.POINTER(C.c_int32)),
                     NEZHA_BF16 if dtype == torch.bfloat16 else NEZHA_F32, h_row_stride,
                     1 if w_packed else 0, None if user_part is None else user_part.data_ptr(),
                     NEZHA_TRANSITION_ADD if U_l is None else NEZHA_TRANSITION_RNN,
-                    None if U_l is None else U_l.data_ptr())
+                    None if U_l is None else U_l.data_ptr(),
+                    None if state_init is None else state_init.data_ptr())
     dsc._keep = rad
     return dsc
 
@@ -323,9 +339,10 @@ def _dp(t):
 
 
 def draft_levels(H, W, E, radices, K, itemset=None, buffers=None, stream=None, U=None,
-                 prefix_sets=None, user_parts=None):
+                 prefix_sets=None, user_parts=None, state_init=None):
     """nezha_draft_levels: all L levels in one C call (one kernel launch when every level is
-    small and `user_parts` are given).  Arguments as for decode()."""
+    small and `user_parts` are given).  Arguments as for decode(); state_init [B, 1, e]: the state
+    level 1 starts from (None = zeros)."""
     L = len(W)
     B, _, d = H.shape
     e = W[0].shape[0] - d
@@ -335,7 +352,7 @@ def draft_levels(H, W, E, radices, K, itemset=None, buffers=None, stream=None, U
     if not packed and any(isinstance(w, PackedWeights) for w in W):
         raise ValueError("either all or none of the W_l may be packed")
     dsc = _desc(B, L, 1, K, 1, d, e, radices, H.dtype, H.stride(0), packed, None,
-                U[0] if U is not None else None)
+                U[0] if U is not None else None, state_init)
     esz = H.element_size()
     io = (_LevelIO * L)()
     for l in range(L):
@@ -360,7 +377,7 @@ class DecodePlan:
     single foreign call (what a serving loop would do per batch).  bf16 with packed weights."""
 
     def __init__(self, H, W, E, radices, K, itemset=None, buffers=None, stream=None, U=None,
-                 prefix_sets=None):
+                 prefix_sets=None, state_init=None):
         L = len(W)
         B, _, d = H.shape
         if not all(isinstance(w, PackedWeights) for w in W):
@@ -368,9 +385,9 @@ class DecodePlan:
         e = W[0].shape[0] - d
         self.buffers = buffers if buffers is not None else DraftBuffers(B, L, K, d, e, radices,
                                                                         H.dtype, H.device)
-        self._keep = (H, W, E, U, itemset, prefix_sets)          # the memory the pointers refer to
+        self._keep = (H, W, E, U, itemset, prefix_sets, state_init)   # the memory the pointers refer to
         self._dsc = _desc(B, L, 1, K, 1, d, e, radices, H.dtype, H.stride(0), True, None,
-                          U[0] if U is not None else None)
+                          U[0] if U is not None else None, state_init)
         esz = H.element_size()
         self._io = (_LevelIO * L)()
         for l in range(L):
@@ -400,13 +417,14 @@ class DecodePlan:
 
 
 def decode(H, W, E, radices, K, itemset=None, buffers=None, stream=None, U=None,
-           prefix_sets=None, use_state=True, level_events=None):
+           prefix_sets=None, use_state=True, level_events=None, state_init=None):
     """All L levels of the inference loop of Alg. 3: L calls of nezha_draft_step on one
     stream, each level's outputs feeding the next.  H [B, L, d]; W, E lists per level; U
     (optional) list of [e, e] per level below L: recurrent Transition; prefix_sets (optional)
     list of L-1 item sets (or None) of the valid prefixes of length 1..L-1; use_state=False
     never hands a state to the next level (the head then sees h_l only: the paper's ablation
     without the autoregressive state, and parallel multi-token heads when all h_l are equal).
+    state_init [B, 1, e]: the state the single beam of level 1 starts from (None = zeros).
     level_events (measurement aid): L+1 pairs of torch.cuda.Event recorded on the current
     stream around the projections made ahead of the loop (pair 0) and around each level's call
     (pairs 1..L)."""
@@ -415,7 +433,7 @@ def decode(H, W, E, radices, K, itemset=None, buffers=None, stream=None, U=None,
     e = W[0].shape[0] - d
     if buffers is None:
         buffers = DraftBuffers(B, L, K, d, e, radices, H.dtype, H.device)
-    state = key = score = None
+    state, key, score = state_init, None, None
     parts = None
     if level_events is not None:
         level_events[0][0].record()
@@ -426,7 +444,8 @@ def decode(H, W, E, radices, K, itemset=None, buffers=None, stream=None, U=None,
         level_events[0][1].record()
     if parts is not None and use_state and level_events is None:
         # the level loop itself in one call (one launch when every level is small)
-        return draft_levels(H, W, E, radices, K, itemset, buffers, stream, U, prefix_sets, parts)
+        return draft_levels(H, W, E, radices, K, itemset, buffers, stream, U, prefix_sets, parts,
+                            state_init)
     for level in range(1, L + 1):
         if level_events is not None:
             level_events[level][0].record()

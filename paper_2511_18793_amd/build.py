@@ -5,7 +5,6 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SOURCES = [os.path.join(HERE, "csrc", f) for f in ("itemset.hip", "draft.hip")]
-HEADERS = [os.path.join(HERE, "csrc", "nezha_internal.h"), os.path.join(ROOT, "include", "nezha.h")]
 OUT = os.path.join(HERE, "libnezha.so")
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -13,13 +12,6 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          # packed fp32 instructions off: hipcc must not form v_pk_*_f32 from float code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument"]
-
-
-def is_stale():
-    if not os.path.exists(OUT):
-        return True
-    t = os.path.getmtime(OUT)
-    return any(os.path.getmtime(f) > t for f in SOURCES + HEADERS)
 
 
 def build(verbose=False):

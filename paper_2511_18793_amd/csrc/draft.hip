@@ -14,6 +14,7 @@
 //   wide_*_kernel           beams wider than 128 (wide_beam.h)
 #include "nezha_internal.h"
 
+#include <atomic>
 #include <type_traits>
 
 namespace nezha {
@@ -2816,7 +2817,7 @@ static int validate_step(const nezha_step_desc* desc, const void* H_l, const voi
        reinterpret_cast<uintptr_t>(state_out)) & 15)
     return fail(NEZHA_EINVAL, "E_l and the states must be 16-byte aligned");
   if (set) {
-    if (set->magic != kSetMagic) return fail(NEZHA_EINVAL, "not an item set");
+    if (!set_is_live(set)) return fail(NEZHA_EINVAL, "not an item set");
     if (set->L != L && set->L != level)
       return fail(NEZHA_EINVAL, "the set's tuples have %d digits; %d (items) or %d (prefixes of this level) expected",
                   set->L, L, level);
@@ -3057,12 +3058,17 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
   const uint8_t* redo_req = nullptr;   // set when a kernel above has already finished most requests
   if (plan.per_request) {
     // one workgroup per request, resident workgroups walk the batch
-    static int n_cu = 0;
+    // compute units of the current device (asked once per device; the cache is per device)
+    constexpr int kMaxDevices = 64;
+    static std::atomic<int> cu_of_device[kMaxDevices];
+    int dev = 0;
+    NEZHA_HIP_CHECK(hipGetDevice(&dev));
+    int n_cu = (dev >= 0 && dev < kMaxDevices) ? cu_of_device[dev].load(std::memory_order_relaxed) : 0;
     if (n_cu == 0) {
-      int dev = 0, v = 0;
-      NEZHA_HIP_CHECK(hipGetDevice(&dev));
+      int v = 0;
       NEZHA_HIP_CHECK(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev));
       n_cu = v > 0 ? v : 1;
+      if (dev >= 0 && dev < kMaxDevices) cu_of_device[dev].store(n_cu, std::memory_order_relaxed);
     }
     const int n_waves = (K_in + 15) / 16;
     int groups = B < 2 * n_cu ? B : 2 * n_cu;
@@ -3213,6 +3219,37 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
   return NEZHA_OK;
 }
 
+// Argument checks of all L levels of nezha_draft_levels / nezha_decode, in the order the levels
+// would run, before anything is enqueued.
+static int validate_levels(const nezha_step_desc* desc, const nezha_level_io* io,
+                           const void* workspace, size_t workspace_bytes) {
+  if (!desc || !io) return fail(NEZHA_EINVAL, "desc or io is NULL");
+  const int L = desc->L;
+  if (L < 1 || L > NEZHA_MAX_LEVELS)
+    return fail(NEZHA_EINVAL, "L = %d outside 1..%d", L, NEZHA_MAX_LEVELS);
+  if (!desc->radices) return fail(NEZHA_EINVAL, "radices is NULL");
+  if (reinterpret_cast<uintptr_t>(desc->state_init) & 15)
+    return fail(NEZHA_EINVAL, "state_init is not 16-byte aligned");
+  nezha_step_desc dl = *desc;
+  const void* state = desc->state_init;
+  for (int l = 1; l <= L; ++l) {
+    const nezha_level_io& x = io[l - 1];
+    dl.level = l;
+    dl.K_in = l == 1 ? 1 : desc->K;
+    dl.user_part = x.user_part;
+    dl.U_l = x.U_l;
+    Plan plan;
+    int rc = validate_step(&dl, x.H_l, x.W_l, x.E_l, state, x.set, x.key_out, x.score_out,
+                           x.parent_out, x.code_out, x.state_out, workspace, workspace_bytes, &plan);
+    if (rc != NEZHA_OK) return rc;
+    state = x.state_out;
+  }
+  return NEZHA_OK;
+}
+
+static int draft_levels_checked(const nezha_step_desc* desc, const nezha_level_io* io,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+
 int nezha_decode(const nezha_step_desc* desc, const nezha_level_io* io, void* workspace,
                  size_t workspace_bytes, void* hip_stream) {
   if (!desc || !io) return fail(NEZHA_EINVAL, "desc or io is NULL");
@@ -3229,9 +3266,14 @@ int nezha_decode(const nezha_step_desc* desc, const nezha_level_io* io, void* wo
     W[l] = io[l].W_l;
     A[l] = const_cast<float*>(io[l].user_part);
   }
-  int rc = nezha_user_projection_levels(desc, desc->L, H, W, A, hip_stream);
+  if (desc->dtype != NEZHA_BF16 || !desc->w_packed)
+    return fail(NEZHA_EINVAL, "needs NEZHA_BF16 weights packed by nezha_pack_weights");
+  // every level's arguments are checked before the projections (which write user_part) are enqueued
+  int rc = validate_levels(desc, io, workspace, workspace_bytes);
   if (rc != NEZHA_OK) return rc;
-  return nezha_draft_levels(desc, io, workspace, workspace_bytes, hip_stream);
+  rc = nezha_user_projection_levels(desc, desc->L, H, W, A, hip_stream);
+  if (rc != NEZHA_OK) return rc;
+  return draft_levels_checked(desc, io, workspace, workspace_bytes, hip_stream);
 }
 
 size_t nezha_draft_levels_workspace(const nezha_step_desc* desc) {
@@ -3250,11 +3292,15 @@ size_t nezha_draft_levels_workspace(const nezha_step_desc* desc) {
 
 int nezha_draft_levels(const nezha_step_desc* desc, const nezha_level_io* io, void* workspace,
                        size_t workspace_bytes, void* hip_stream) {
-  if (!desc || !io) return fail(NEZHA_EINVAL, "desc or io is NULL");
+  int rc = validate_levels(desc, io, workspace, workspace_bytes);
+  if (rc != NEZHA_OK) return rc;
+  return draft_levels_checked(desc, io, workspace, workspace_bytes, hip_stream);
+}
+
+// The level loop; validate_levels has passed.
+static int draft_levels_checked(const nezha_step_desc* desc, const nezha_level_io* io,
+                                void* workspace, size_t workspace_bytes, void* hip_stream) {
   const int L = desc->L;
-  if (L < 1 || L > NEZHA_MAX_LEVELS)
-    return fail(NEZHA_EINVAL, "L = %d outside 1..%d", L, NEZHA_MAX_LEVELS);
-  if (!desc->radices) return fail(NEZHA_EINVAL, "radices is NULL");
   const bool bf16 = desc->dtype == NEZHA_BF16;
   const int K = desc->K;
   // one launch for all levels when every level fits the single-launch kernel and has its user part
@@ -3267,7 +3313,7 @@ int nezha_draft_levels(const nezha_step_desc* desc, const nezha_level_io* io, vo
     max_v = V > max_v ? V : max_v;
   }
   nezha_step_desc dl = *desc;
-  const void* state = nullptr;
+  const void* state = desc->state_init;
   const uint64_t* key = nullptr;
   const float* score = nullptr;
   DecodeArgs da;
@@ -3282,10 +3328,6 @@ int nezha_draft_levels(const nezha_step_desc* desc, const nezha_level_io* io, vo
     dl.user_part = x.user_part;
     dl.U_l = x.U_l;
     if (one_launch) {
-      Plan plan;
-      int rc = validate_step(&dl, x.H_l, x.W_l, x.E_l, state, x.set, x.key_out, x.score_out,
-                             x.parent_out, x.code_out, x.state_out, workspace, workspace_bytes, &plan);
-      if (rc != NEZHA_OK) return rc;
       da.lv[l - 1] = make_level_args(&dl, static_cast<const uint16_t*>(x.W_l), x.user_part, x.E_l,
                                      state, key, score, x.set, x.key_out, x.score_out, x.parent_out,
                                      x.code_out, x.state_out, x.count_out, mult[l - 1]);

@@ -1,8 +1,11 @@
 // The model-free verifier (Sec. 3.3): an open-addressing hash set of the packed 64-bit item
 // indices of Eq. 4 in device memory, its parallel build, and the stand-alone batch
 // verification of Eq. 5 with order-preserving compaction of the accepted tuples.
+#include <stdlib.h>
+
 #include <mutex>
 #include <new>
+#include <unordered_set>
 #include <vector>
 
 #include "nezha_internal.h"
@@ -68,7 +71,44 @@ bool radix_multipliers(int32_t L, const int32_t* radices, uint64_t* mult) {
   return true;
 }
 
+// ---- registry of live sets ------------------------------------------------------------------
+// A handle is valid from the moment nezha_build_itemset returns it until nezha_free_itemset takes
+// it; the registry answers that question without reading the handle's memory, so a handle that
+// was freed (or never was one) is refused instead of dereferenced.
 namespace {
+std::mutex g_sets_mutex;
+std::unordered_set<const nezha_itemset*>& live_sets() {
+  static std::unordered_set<const nezha_itemset*> sets;
+  return sets;
+}
+}  // namespace
+bool set_is_live(const nezha_itemset* set) {
+  if (!set) return false;
+  std::lock_guard<std::mutex> lock(g_sets_mutex);
+  return live_sets().count(set) != 0;
+}
+
+namespace {
+
+// Test hook for the failure path of nezha_build_itemset: with NEZHA_TEST_FAIL_ALLOC=N in the
+// environment the N-th allocation of a build (1 = the host-side handle, 2 = the table, 3 = the
+// status words, then the staging buffer when the catalog is in host memory, last the prefilter)
+// is reported as failed without being attempted.  Unset, empty or 0: no effect.
+struct BuildAllocs {
+  int failing = 0, made = 0;
+  BuildAllocs() {
+    const char* v = getenv("NEZHA_TEST_FAIL_ALLOC");
+    if (v && *v) failing = atoi(v);
+  }
+  bool fails() { return ++made == failing; }
+  hipError_t device(void** p, size_t bytes) {
+    if (fails()) {
+      *p = nullptr;
+      return hipErrorOutOfMemory;
+    }
+    return hipMalloc(p, bytes);
+  }
+};
 
 struct Radix {
   int32_t L;
@@ -276,6 +316,22 @@ __global__ __launch_bounds__(kVerifyThreads) void verify_scatter_kernel(
     if ((bits >> (8 * j)) & 1u) out_index[pos++] = base + j;
 }
 
+// Probes every tuple of `codes` (as the draft step does: through the prefilter, then the table)
+// and counts those that are not found.
+__global__ void check_kernel(const int32_t* __restrict__ codes, int64_t n, Radix r, SetView set,
+                             unsigned long long* missing) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    uint64_t key;
+    bool ok = pack_tuple(codes + i * r.L, r, key);
+    if (ok) {
+      const uint64_t code = key / set.mult_last, prefix = key - code * set.mult_last;
+      ok = set_contains(set, prefix, (uint32_t)code);
+    }
+    if (!ok) atomicAdd(missing, 1ull);
+  }
+}
 // Measurement aid: n independent reads of whole lines (LINE bytes, LINE-aligned) at pseudo-random
 // places of a buffer, four in flight per lane like the verifier's probes.  The loaded words are
 // folded into one value so the reads cannot be dropped.
@@ -339,7 +395,8 @@ int nezha_build_itemset(const int32_t* codes, int64_t n, int32_t L, const int32_
   n_slots = n_buckets * kBucketSlots;
 
   hipStream_t stream = (hipStream_t)hip_stream;
-  nezha_itemset* s = new (std::nothrow) nezha_itemset;
+  BuildAllocs allocs;
+  nezha_itemset* s = allocs.fails() ? nullptr : new (std::nothrow) nezha_itemset;
   if (!s) return fail(NEZHA_ENOMEM, "host allocation failed");
   s->slots = nullptr;
   s->filter = nullptr;
@@ -377,9 +434,10 @@ int nezha_build_itemset(const int32_t* codes, int64_t n, int32_t L, const int32_
     }                                                                                      \
   } while (0)
 
+  s->device = -1;
+  BUILD_CHECK(allocs.device((void**)&s->slots, n_slots * sizeof(uint64_t)));
   BUILD_CHECK(hipGetDevice(&s->device));
-  BUILD_CHECK(hipMalloc((void**)&s->slots, n_slots * sizeof(uint64_t)));
-  BUILD_CHECK(hipMalloc((void**)&status, 4 * sizeof(unsigned long long)));
+  BUILD_CHECK(allocs.device((void**)&status, 4 * sizeof(unsigned long long)));
   BUILD_CHECK(hipMemsetAsync(status, 0, 4 * sizeof(unsigned long long), stream));
   {
     uint64_t blocks = (n_slots + 1023) / 1024;
@@ -391,7 +449,7 @@ int nezha_build_itemset(const int32_t* codes, int64_t n, int32_t L, const int32_
   const int64_t chunk_max = (int64_t)1 << 25;  // tuples staged per copy when codes are on the host
   if (!codes_on_device && n > 0) {
     int64_t cap = n < chunk_max ? n : chunk_max;
-    BUILD_CHECK(hipMalloc((void**)&staged, (size_t)cap * L * sizeof(int32_t)));
+    BUILD_CHECK(allocs.device((void**)&staged, (size_t)cap * L * sizeof(int32_t)));
   }
   for (int64_t start = 0; start < n; start += chunk_max) {
     int64_t m = n - start < chunk_max ? n - start : chunk_max;
@@ -431,20 +489,31 @@ int nezha_build_itemset(const int32_t* codes, int64_t n, int32_t L, const int32_
     // that turns most of their table probes (a random HBM line each) away.  It can only say "not
     // in the set" for keys that are not in it, so results do not change.
     s->n_blocks = (uint64_t)(s->n_distinct / 16 + 1);
-    hipError_t fe = hipMalloc((void**)&s->filter, s->n_blocks * 64);
+    hipError_t fe = allocs.device((void**)&s->filter, s->n_blocks * 64);
+    if (fe == hipSuccess) {
+      fe = hipMemsetAsync(s->filter, 0, s->n_blocks * 64, stream);
+      if (fe == hipSuccess) {
+        uint64_t blocks = (n_slots + 1023) / 1024;
+        if (blocks > 65536) blocks = 65536;
+        hipLaunchKernelGGL(filter_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, s->slots,
+                           (uint64_t)n_slots, reinterpret_cast<unsigned long long*>(s->filter),
+                           s->n_blocks, s->mult[L - 1]);
+        fe = hipGetLastError();
+      }
+      if (fe == hipSuccess) fe = hipStreamSynchronize(stream);
+    }
     if (fe != hipSuccess) {
-      s->filter = nullptr;                               // the set works without its prefilter
+      // A filter that is not known to be complete would turn valid items away (a clear bit means
+      // "not in the set"): the set then works without one.
+      if (s->filter) (void)hipFree(s->filter);
+      s->filter = nullptr;
       s->n_blocks = 0;
       (void)hipGetLastError();
-    } else {
-      (void)hipMemsetAsync(s->filter, 0, s->n_blocks * 64, stream);
-      uint64_t blocks = (n_slots + 1023) / 1024;
-      if (blocks > 65536) blocks = 65536;
-      hipLaunchKernelGGL(filter_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, s->slots,
-                         (uint64_t)n_slots, reinterpret_cast<unsigned long long*>(s->filter),
-                         s->n_blocks, s->mult[L - 1]);
-      (void)hipStreamSynchronize(stream);
     }
+  }
+  {
+    std::lock_guard<std::mutex> lock(g_sets_mutex);
+    live_sets().insert(s);
   }
   *out = s;
   return cleanup(NEZHA_OK);
@@ -452,7 +521,7 @@ int nezha_build_itemset(const int32_t* codes, int64_t n, int32_t L, const int32_
 
 int nezha_itemset_info(const nezha_itemset* set, int64_t* n_distinct, int64_t* n_slots,
                        int32_t* L, int32_t* radices) {
-  if (!set || set->magic != kSetMagic) return fail(NEZHA_EINVAL, "not an item set");
+  if (!set_is_live(set)) return fail(NEZHA_EINVAL, "not an item set");
   if (n_distinct) *n_distinct = set->n_distinct;
   if (n_slots) *n_slots = (int64_t)(set->n_buckets * kBucketSlots);
   if (L) *L = set->L;
@@ -463,7 +532,11 @@ int nezha_itemset_info(const nezha_itemset* set, int64_t* n_distinct, int64_t* n
 
 int nezha_free_itemset(nezha_itemset* set) {
   if (!set) return NEZHA_OK;
-  if (set->magic != kSetMagic) return fail(NEZHA_EINVAL, "not an item set (freed twice?)");
+  {
+    // the registry decides, so a handle that was freed before is refused without being read
+    std::lock_guard<std::mutex> lock(g_sets_mutex);
+    if (live_sets().erase(set) == 0) return fail(NEZHA_EINVAL, "not an item set (freed twice?)");
+  }
   set->magic = 0;
   if (set->filter) (void)hipFree(set->filter);
   hipError_t e = set->slots ? hipFree(set->slots) : hipSuccess;
@@ -480,29 +553,16 @@ size_t nezha_verify_workspace(int64_t n) {
   return counts + blocks * sizeof(int64_t);
 }
 
-int nezha_verify_tuples(const nezha_itemset* set, const int32_t* codes, int64_t n,
-                        uint8_t* out_mask, int64_t* out_index, int64_t* out_count,
-                        void* workspace, size_t workspace_bytes, void* hip_stream) {
-  if (!set || set->magic != kSetMagic) return fail(NEZHA_EINVAL, "not an item set");
-  if (n < 0) return fail(NEZHA_EINVAL, "n = %lld is negative", (long long)n);
-  if (n > 0 && (!codes || !out_mask)) return fail(NEZHA_EINVAL, "codes or out_mask is NULL");
+// The launches of the stand-alone verifier; `workspace` is known to be large enough.
+static int verify_launch(const nezha_itemset* set, const int32_t* codes, int64_t n,
+                         uint8_t* out_mask, int64_t* out_index, int64_t* out_count,
+                         void* workspace, hipStream_t stream) {
   const bool compact = out_index || out_count;
-  if (n > 0 && compact) {
-    if (!workspace) return fail(NEZHA_EINVAL, "workspace is NULL");
-    if (workspace_bytes < nezha_verify_workspace(n))
-      return fail(NEZHA_EINVAL, "workspace has %zu bytes, %zu needed", workspace_bytes,
-                  nezha_verify_workspace(n));
-    if (reinterpret_cast<uintptr_t>(workspace) & 15)
-      return fail(NEZHA_EINVAL, "workspace is not 16-byte aligned");
-  }
-  if (n > (int64_t)kVerifyBlock * 0x7FFFFFFF) return fail(NEZHA_EINVAL, "n too large");
-  hipStream_t stream = (hipStream_t)hip_stream;
-  const int64_t blocks = n == 0 ? 1 : (n + kVerifyBlock - 1) / kVerifyBlock;
+  const int64_t blocks = (n + kVerifyBlock - 1) / kVerifyBlock;
   const size_t counts_bytes = ((size_t)blocks * sizeof(int32_t) + 15) & ~(size_t)15;
-  int32_t* block_count = compact && n > 0 ? static_cast<int32_t*>(workspace) : nullptr;
-  int64_t* block_offset =
-      compact && n > 0 ? reinterpret_cast<int64_t*>(static_cast<char*>(workspace) + counts_bytes)
-                       : nullptr;
+  // (the probe pass writes its block counts whether or not they are wanted afterwards)
+  int32_t* block_count = static_cast<int32_t*>(workspace);
+  int64_t* block_offset = reinterpret_cast<int64_t*>(static_cast<char*>(workspace) + counts_bytes);
   Radix r;
   r.L = set->L;
   for (int l = 0; l < NEZHA_MAX_LEVELS; ++l) {
@@ -512,21 +572,6 @@ int nezha_verify_tuples(const nezha_itemset* set, const int32_t* codes, int64_t 
   // (the stand-alone verifier's queries are mostly present keys: the prefilter would only add an
   // access, so it is left out of the view)
   SetView view{set->slots, set->n_buckets, nullptr, 0, 0};
-  if (n == 0) {
-    if (out_count) {
-      hipLaunchKernelGGL(verify_scan_kernel, dim3(1), dim3(1024), 0, stream,
-                         (const int32_t*)nullptr, (int64_t)0, (int64_t*)nullptr, out_count);
-      NEZHA_HIP_CHECK(hipGetLastError());
-    }
-    return NEZHA_OK;
-  }
-  // The probe pass needs somewhere to put block counts even when they are not wanted.
-  if (!block_count) {
-    if (!workspace || workspace_bytes < nezha_verify_workspace(n))
-      return fail(NEZHA_EINVAL, "workspace has %zu bytes, %zu needed", workspace_bytes,
-                  nezha_verify_workspace(n));
-    block_count = static_cast<int32_t*>(workspace);
-  }
   dim3 grid((unsigned)blocks), block(kVerifyThreads);
   {
   ProfileScope prof(kVerifyProbe, stream);
@@ -567,6 +612,104 @@ int nezha_verify_tuples(const nezha_itemset* set, const int32_t* codes, int64_t 
     NEZHA_HIP_CHECK(hipGetLastError());
   }
   return NEZHA_OK;
+}
+
+// Argument checks shared by the two verifier entry points (everything but the workspace).
+static int verify_check(const nezha_itemset* set, const int32_t* codes, int64_t n,
+                        const uint8_t* out_mask) {
+  if (!set_is_live(set)) return fail(NEZHA_EINVAL, "not an item set");
+  if (n < 0) return fail(NEZHA_EINVAL, "n = %lld is negative", (long long)n);
+  if (n > 0 && (!codes || !out_mask)) return fail(NEZHA_EINVAL, "codes or out_mask is NULL");
+  if (n > (int64_t)kVerifyBlock * 0x7FFFFFFF) return fail(NEZHA_EINVAL, "n too large");
+  return NEZHA_OK;
+}
+
+// n == 0: nothing to probe; the count, if wanted, is written by a one-block launch.
+static int verify_empty(int64_t* out_count, hipStream_t stream) {
+  if (out_count) {
+    hipLaunchKernelGGL(verify_scan_kernel, dim3(1), dim3(1024), 0, stream, (const int32_t*)nullptr,
+                       (int64_t)0, (int64_t*)nullptr, out_count);
+    NEZHA_HIP_CHECK(hipGetLastError());
+  }
+  return NEZHA_OK;
+}
+
+int nezha_verify_tuples(const nezha_itemset* set, const int32_t* codes, int64_t n,
+                        uint8_t* out_mask, int64_t* out_index, int64_t* out_count,
+                        void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = verify_check(set, codes, n, out_mask);
+  if (rc != NEZHA_OK) return rc;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  if (n == 0) return verify_empty(out_count, stream);
+  if (!workspace) return fail(NEZHA_EINVAL, "workspace is NULL");
+  if (workspace_bytes < nezha_verify_workspace(n))
+    return fail(NEZHA_EINVAL, "workspace has %zu bytes, %zu needed", workspace_bytes,
+                nezha_verify_workspace(n));
+  if (reinterpret_cast<uintptr_t>(workspace) & 15)
+    return fail(NEZHA_EINVAL, "workspace is not 16-byte aligned");
+  return verify_launch(set, codes, n, out_mask, out_index, out_count, workspace, stream);
+}
+
+int nezha_check_itemset(const nezha_itemset* set, const int32_t* codes, int64_t n,
+                        int codes_on_device, void* hip_stream, int64_t* n_missing) {
+  if (!set_is_live(set)) return fail(NEZHA_EINVAL, "not an item set");
+  if (n < 0 || (n > 0 && !codes) || !n_missing) return fail(NEZHA_EINVAL, "bad argument");
+  *n_missing = 0;
+  if (n == 0) return NEZHA_OK;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  Radix r;
+  r.L = set->L;
+  for (int l = 0; l < NEZHA_MAX_LEVELS; ++l) {
+    r.T[l] = set->radices[l];
+    r.mult[l] = set->mult[l];
+  }
+  SetView view{set->slots, set->n_buckets, set->filter, set->n_blocks, set->mult[set->L - 1]};
+  unsigned long long* missing = nullptr;
+  int32_t* staged = nullptr;
+  int rc = NEZHA_OK;
+  auto done = [&](int code) {
+    if (missing) (void)hipFree(missing);
+    if (staged) (void)hipFree(staged);
+    return code;
+  };
+#define CHECK_OR_DONE(expr)                                                                \
+  do {                                                                                     \
+    hipError_t _e = (expr);                                                                \
+    if (_e != hipSuccess) {                                                                \
+      rc = fail(_e == hipErrorOutOfMemory ? NEZHA_ENOMEM : NEZHA_EHIP, "%s failed: %s",    \
+                #expr, hipGetErrorString(_e));                                             \
+      return done(rc);                                                                     \
+    }                                                                                      \
+  } while (0)
+  CHECK_OR_DONE(hipMalloc((void**)&missing, sizeof(unsigned long long)));
+  CHECK_OR_DONE(hipMemsetAsync(missing, 0, sizeof(unsigned long long), stream));
+  const int64_t chunk_max = (int64_t)1 << 25;
+  if (!codes_on_device) {
+    const int64_t cap = n < chunk_max ? n : chunk_max;
+    CHECK_OR_DONE(hipMalloc((void**)&staged, (size_t)cap * set->L * sizeof(int32_t)));
+  }
+  for (int64_t start = 0; start < n; start += chunk_max) {
+    const int64_t m = n - start < chunk_max ? n - start : chunk_max;
+    const int32_t* src = codes + start * set->L;
+    if (!codes_on_device) {
+      CHECK_OR_DONE(hipMemcpyAsync(staged, src, (size_t)m * set->L * sizeof(int32_t),
+                                   hipMemcpyHostToDevice, stream));
+      src = staged;
+    }
+    int64_t blocks = (m + 255) / 256;
+    if (blocks > 262144) blocks = 262144;
+    hipLaunchKernelGGL(check_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, m, r, view,
+                       missing);
+    CHECK_OR_DONE(hipGetLastError());
+    if (!codes_on_device) CHECK_OR_DONE(hipStreamSynchronize(stream));
+  }
+  unsigned long long host_missing = 0;
+  CHECK_OR_DONE(hipMemcpyAsync(&host_missing, missing, sizeof(host_missing), hipMemcpyDeviceToHost,
+                               stream));
+  CHECK_OR_DONE(hipStreamSynchronize(stream));
+#undef CHECK_OR_DONE
+  *n_missing = (int64_t)host_missing;
+  return done(NEZHA_OK);
 }
 
 int nezha_bench_random_gather(const void* buf, size_t bytes, int64_t n, int line_bytes,

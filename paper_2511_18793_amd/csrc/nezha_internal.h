@@ -22,6 +22,10 @@ int fail(int code, const char* fmt, ...);
       return ::nezha::fail(NEZHA_EHIP, "%s failed: %s", #expr, hipGetErrorString(_e)); \
   } while (0)
 
+// Whether `set` is a handle nezha_build_itemset returned and nezha_free_itemset has not taken yet
+// (answered from a registry, without reading the handle's memory).
+bool set_is_live(const nezha_itemset* set);
+
 // Positional multipliers of Eq. 4; false if prod T_l > 2^64-1 or a radix < 1.
 bool radix_multipliers(int32_t L, const int32_t* radices, uint64_t* mult);
 

@@ -133,3 +133,69 @@ def test_decode_needs_hidden_states_and_user_part_buffers():
     rc = lib.nezha_decode(C.byref(dsc), io, C.c_void_p(0x10000), 1 << 24, None)
     assert rc == -1 and "user_part" in lib.nezha_last_error().decode()
     assert lib.nezha_decode(None, io, None, 0, None) == -1
+
+
+def test_a_pointer_that_is_not_a_live_set_is_refused_without_being_read():
+    """Freed handles and arbitrary pointers: the registry of live sets answers, the memory behind
+    the pointer is never touched (0x1000 is not mapped: reading it would end the process)."""
+    lib = nz.load_library()
+    bogus = C.c_void_p(0x1000)
+    assert lib.nezha_free_itemset(bogus) == -1
+    assert "item set" in lib.nezha_last_error().decode()
+    assert lib.nezha_itemset_info(bogus, None, None, None, None) == -1
+    assert lib.nezha_verify_tuples(bogus, C.c_void_p(0x2000), 4, C.c_void_p(0x3000), None, None,
+                                   C.c_void_p(0x4000), 1 << 20, None) == -1
+    missing = C.c_int64(0)
+    assert lib.nezha_check_itemset(bogus, C.c_void_p(0x2000), 4, 1, None, C.byref(missing)) == -1
+    rc, text = _call_step_with_set(bogus)
+    assert rc == -1 and "item set" in text
+
+
+def _call_step_with_set(set_ptr):
+    lib = nz.load_library()
+    dsc = api._desc(4, 3, 3, 4, 4, 64, 64, [256] * 3, torch.float32, 64)
+    fake = C.c_void_p(0x1000)
+    ptrs = [fake] * 6 + [set_ptr] + [fake] * 6
+    rc = lib.nezha_draft_step(C.byref(dsc), *ptrs, C.c_void_p(0x10000), 1 << 24, None)
+    return rc, lib.nezha_last_error().decode()
+
+
+@pytest.mark.parametrize("nth", [1, 2])
+def test_build_itemset_allocation_failure_hook(nth, monkeypatch):
+    """NEZHA_TEST_FAIL_ALLOC=N makes the N-th allocation of a build fail: the handle (1) and the
+    table (2) come before any device call, so the error path runs without a GPU.  *out stays
+    NULL, the error is NEZHA_ENOMEM, and the next build is not affected by the hook's counter."""
+    lib = nz.load_library()
+    monkeypatch.setenv("NEZHA_TEST_FAIL_ALLOC", str(nth))
+    codes = np.zeros((4, 3), dtype=np.int32)
+    rad = (C.c_int32 * 3)(4, 4, 4)
+    for _ in range(2):
+        out = C.c_void_p(0x1234)
+        rc = lib.nezha_build_itemset(codes.ctypes.data_as(C.c_void_p), 4, 3, rad, 0, 0.5, None,
+                                     C.byref(out))
+        assert rc == -2, lib.nezha_last_error().decode()
+        assert out.value is None
+
+
+def test_draft_levels_checks_every_level_before_enqueueing():
+    """A bad argument at the LAST level (its key_out is NULL) is reported although levels 1 and 2
+    are fine and would need three launches: nothing has been enqueued by then (no GPU is needed
+    for this call to fail cleanly, and it must not reach a launch with the fake pointers)."""
+    lib = nz.load_library()
+    dsc = api._desc(4, 3, 1, 40, 1, 64, 64, [2048] * 3, torch.bfloat16, 64, True)
+    io = (api._LevelIO * 3)()
+    for l in range(3):
+        fake = 0x100000 * (l + 1)
+        io[l] = api._LevelIO(fake, fake, fake, None, None, None, fake, fake, fake, fake,
+                             fake if l < 2 else None, fake)
+    io[2].key_out = None
+    fn = lib.nezha_draft_levels
+    fn.argtypes = [C.POINTER(api._StepDesc), C.POINTER(api._LevelIO), C.c_void_p, C.c_size_t,
+                   C.c_void_p]
+    rc = fn(C.byref(dsc), io, C.c_void_p(0x10000000), 1 << 40, None)
+    assert rc == -1 and "output pointer" in lib.nezha_last_error().decode()
+    # and a misaligned initial state
+    io[2].key_out = 0x300000
+    dsc.state_init = 0x1008
+    rc = fn(C.byref(dsc), io, C.c_void_p(0x10000000), 1 << 40, None)
+    assert rc == -1 and "state_init" in lib.nezha_last_error().decode()

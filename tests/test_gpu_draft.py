@@ -344,6 +344,76 @@ def test_head_without_state(oracle, name, B, shared_hidden):
     assert lvl2["count"].min() > 0
 
 
+@pytest.mark.parametrize("name,B", [("serving", 48), ("wide", 4), ("large", 2), ("tiny", 16)])
+def test_head_without_placeholder_hidden_states(oracle, name, B):
+    """Ablation "without h_l": one hidden vector (h_1) serves every level, the autoregressive
+    state is kept.  A caller-side combination of the same kernels: every H_l is the same [B, d]
+    view (the row stride of H lets one tensor serve all levels)."""
+    cfg = synth.get_config(name).scaled(B=B)
+    x, cat = planted_workload(oracle, cfg, 83, N=20000, plant=False)
+    x["H"] = np.repeat(x["H"][:, :1], cfg.L, axis=1).copy()
+    free = oracle.decode(x["H"], x["W"], x["E"], cfg.radices, cfg.K,
+                         round_state_bf16=cfg.dtype == "bf16")
+    tuples = oracle.unpack(free[-1]["key"].ravel(), cfg.radices)
+    keep = synth.plant_mask(tuples, cfg.radices, 83)
+    cat = synth.planted_catalog(cfg.radices, cat, tuples[keep], tuples[~keep], 83)
+    oset = oracle.ItemSet(cat, cfg.radices)
+    gset = nz.build_itemset(cat, cfg.radices, cfg.load_factor)
+    H, W, E = to_device(x, cfg)
+    # the device tensor holds h_1 only: [B, 1, d] expanded over the levels without a copy
+    H1 = H[:, :1, :].contiguous().expand(cfg.B, cfg.L, cfg.d)
+    outs = nz.decode(H1, W, E, cfg.radices, cfg.K, gset)
+    torch.cuda.synchronize()
+    soft = check_decode(oracle, nz, cfg, x, outs, oset, tolerance(cfg))
+    assert soft <= 8
+    assert int(outs[-1]["count"].sum()) > 0
+    full = synth.draft_inputs(cfg, 83)
+    Hf = torch.from_numpy(full["H"]).to(device()).to(torch_dtype(cfg))
+    with_h = nz.decode(Hf, W, E, cfg.radices, cfg.K, gset)
+    torch.cuda.synchronize()
+    assert not torch.equal(with_h[-1]["key"], outs[-1]["key"])
+
+
+def test_initial_state_of_level_one(oracle):
+    """Eq. 1: the head may start from a given context state instead of zeros.  nezha_draft_step
+    takes it as state_in at level 1; nezha_draft_levels / nezha_decode through desc.state_init:
+    same bits, and parity with the oracle fed the same state."""
+    for name, B in (("serving", 40), ("large", 2), ("tiny", 8)):
+        cfg = synth.get_config(name).scaled(B=B)
+        x, cat = planted_workload(oracle, cfg, 85, N=20000, plant=False)
+        rng = np.random.default_rng(85)
+        s0 = (rng.standard_normal((cfg.B, 1, cfg.e)) * 0.5).astype(np.float32)
+        if cfg.dtype == "bf16":
+            s0 = synth.round_to_bf16(s0)
+        H, W, E = to_device(x, cfg)
+        S0 = torch.from_numpy(s0).to(device()).to(torch_dtype(cfg))
+        # level by level through nezha_draft_step
+        outs = nz.decode(H, W, E, cfg.radices, cfg.K, None, state_init=S0)
+        torch.cuda.synchronize()
+        g1 = outputs_to_numpy(outs[0])
+        o1 = oracle.draft_level(1, cfg.L, cfg.radices, cfg.K, x["H"][:, 0], x["W"][0], x["E"][0],
+                                s0, None, None, None, round_state_bf16=cfg.dtype == "bf16")
+        zero = oracle.draft_level(1, cfg.L, cfg.radices, cfg.K, x["H"][:, 0], x["W"][0], x["E"][0],
+                                  None, None, None, None, round_state_bf16=cfg.dtype == "bf16")
+        assert (o1["code"] != zero["code"]).any()           # the state changes the answer
+        same = (o1["code"] == g1["code"]).all(axis=1)
+        assert same.mean() > 0.9
+        assert np.abs(o1["score"][same] - g1["score"][same]).max() <= tolerance(cfg)
+        assert (o1["state"][same] == g1["state"][same]).all()
+        if cfg.dtype != "bf16":
+            continue
+        # all levels in one call (one launch at the serving shape): the same bits
+        Wp = [nz.pack_weights(l + 1, cfg.L, cfg.radices, W[l], cfg.d) for l in range(cfg.L)]
+        first = [{k: v.clone() for k, v in o.items()}
+                 for o in nz.decode(H, Wp, E, cfg.radices, cfg.K, None, state_init=S0)]
+        plan = nz.DecodePlan(H, Wp, E, cfg.radices, cfg.K, None, state_init=S0)
+        got = plan.run()
+        torch.cuda.synchronize()
+        for a, b, c in zip(outs, first, got):
+            for k in a:
+                assert torch.equal(a[k], b[k]) and torch.equal(a[k], c[k]), k
+
+
 # ---- all levels in one call ---------------------------------------------------------------------
 @pytest.mark.parametrize("name,B,variant", [("serving", 256, "plain"), ("serving", 40, "rnn"),
                                             ("serving", 40, "prefix"), ("paper_yelp", 64, "plain"),

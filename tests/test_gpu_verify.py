@@ -116,3 +116,75 @@ def test_stress_shape_full_size_by_construction():
     assert (mask.astype(bool) == present).all()
     assert c == int(present.sum()) and (idx == np.nonzero(present)[0]).all()
     gset.close()
+
+
+def test_double_free_is_refused():
+    radices = [16, 16]
+    cat, _ = synth.uniform_catalog(radices, 50, 2)
+    gset = nz.build_itemset(cat, radices)
+    h = gset._h
+    lib = nz.load_library()
+    assert lib.nezha_free_itemset(h) == 0
+    assert lib.nezha_free_itemset(h) == -1              # not read again: the registry answers
+    assert lib.nezha_itemset_info(h, None, None, None, None) == -1
+    gset._h = None
+
+
+def test_self_check_finds_every_item_of_the_catalog():
+    """After a build every tuple of the catalog must be found through prefilter and table
+    (a filter bit that was not set would silently drop a valid item in the draft step)."""
+    cfg = synth.get_config("serving")
+    cat = synth.zipf_catalog(cfg.radices, cfg.N, 42, cfg.zipf_s)
+    gset = nz.build_itemset(cat, cfg.radices)
+    assert gset.check(cat) == 0                                       # host catalog, staged
+    assert gset.check(torch.from_numpy(cat[:70_001]).to(device())) == 0
+    absent = cat[:1000].copy()
+    absent[:, 0] = (absent[:, 0] + 1) % 256
+    own = set(map(tuple, cat.tolist()))
+    want = sum(tuple(t) not in own for t in absent.tolist())
+    assert want > 0 and gset.check(absent) == want
+    bad = cat[:10].copy()
+    bad[3, 1] = 256                                                   # out of range: never found
+    assert gset.check(bad) == 1
+
+
+def test_allocation_failures_during_build_leak_nothing(monkeypatch):
+    """Each allocation of a build is made to fail in turn (host catalog: handle, table, status
+    words, staging buffer, prefilter).  Failures 1-4 give NEZHA_ENOMEM and return the device
+    memory they held; without its prefilter (5) the set is still exact."""
+    radices = [256, 256, 256]
+    N = 3_000_000                                     # a 48 MB table: a leak would show
+    cat, pi = synth.uniform_catalog(radices, N, 8)
+    torch.cuda.synchronize()
+    nz.build_itemset(cat[:10], radices).close()       # anything lazy in the runtime is paid now
+    free0 = torch.cuda.mem_get_info()[0]
+    for nth in (1, 2, 3, 4):
+        monkeypatch.setenv("NEZHA_TEST_FAIL_ALLOC", str(nth))
+        with pytest.raises(nz.NezhaError) as ei:
+            nz.build_itemset(cat, radices)
+        assert ei.value.code == -2
+        assert abs(torch.cuda.mem_get_info()[0] - free0) < (4 << 20), nth
+    monkeypatch.setenv("NEZHA_TEST_FAIL_ALLOC", "5")
+    gset = nz.build_itemset(cat, radices)
+    monkeypatch.delenv("NEZHA_TEST_FAIL_ALLOC")
+    assert gset.info()["n_distinct"] == N and gset.check(cat) == 0
+    q, present = synth.stress_queries(radices, N, pi, 8, 100_000)
+    mask, idx, c = run_verify(gset, q)
+    assert (mask.astype(bool) == present).all() and c == int(present.sum())
+    # the draft step consults the set without a prefilter: same answer as with one
+    cfg = synth.StepConfig("nofilter", B=8, d=64, e=32, L=3, V=256, K=8, N=N, dtype="bf16",
+                           catalog="uniform")
+    x = synth.draft_inputs(cfg, 8)
+    H = torch.from_numpy(x["H"]).to(device()).to(torch.bfloat16)
+    W = [torch.from_numpy(w).to(device()).to(torch.bfloat16) for w in x["W"]]
+    E = [torch.from_numpy(w).to(device()).to(torch.bfloat16) for w in x["E"]]
+    full = nz.build_itemset(cat, radices)
+    a = nz.decode(H, W, E, cfg.radices, cfg.K, gset)
+    a = [{k: v.clone() for k, v in o.items()} for o in a]
+    b = nz.decode(H, W, E, cfg.radices, cfg.K, full)
+    torch.cuda.synchronize()
+    for k in a[-1]:
+        assert torch.equal(a[-1][k], b[-1][k]), k
+    gset.close()
+    full.close()
+    assert abs(torch.cuda.mem_get_info()[0] - free0) < (4 << 20)

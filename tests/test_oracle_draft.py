@@ -329,6 +329,34 @@ def test_without_state_the_score_factorizes(oracle):
     assert np.abs(with_state[-1]["score"] - last["score"]).max() > 1e-4
 
 
+def test_head_without_placeholder_hidden_states(oracle):
+    """Ablation "without h_l" (Sec. 4.3): the head sees one hidden vector at every level (the
+    caller passes h_1 as every H_l) and keeps its autoregressive state.  With an exhaustive beam
+    the scores must be the chain scores written from the definition with that single vector, for
+    all tuples, and they must differ from the full model's."""
+    cfg, x = _small(27, B=2, d=6, e=3, V=4, L=3)
+    K = 4 ** 3
+    H2 = np.repeat(x["H"][:, :1], 3, axis=1).copy()
+    last = oracle.decode(H2, x["W"], x["E"], cfg.radices, K)[-1]
+    full = oracle.decode(x["H"], x["W"], x["E"], cfg.radices, K)[-1]
+    for b in range(2):
+        one_vector = np.tile(x["H"][b, 0], (3, 1))
+        truth = chain_scores_by_definition(one_vector, x["W"], x["E"])
+        assert abs(sum(np.exp(v) for v in truth.values()) - 1) < 1e-12
+        assert last["count"][b] == K
+        got = oracle.unpack(last["key"][b], cfg.radices)
+        assert len(set(map(tuple, got.tolist()))) == K
+        for t, sc in zip(got.tolist(), last["score"][b]):
+            assert abs(truth[tuple(t)] - sc) < 2e-6
+        # the state still matters (unlike the head without state, scores do not factorize) ...
+        lp = [log_softmax(one_vector[l].astype(np.float64) @ x["W"][l][:6].astype(np.float64))
+              for l in range(3)]
+        fact = lp[0][got[:, 0]] + lp[1][got[:, 1]] + lp[2][got[:, 2]]
+        assert np.abs(fact - last["score"][b]).max() > 1e-4
+    # ... and the placeholder hidden states matter too
+    assert np.abs(np.sort(full["score"], axis=1) - np.sort(last["score"], axis=1)).max() > 1e-4
+
+
 def test_wide_beam_against_the_grid_of_all_tuples(oracle):
     """A beam wider than 128 (the recall setting of the paper: beam 512 to 1000), checked against
     beam search restated on the array of all V^3 chain scores: level 1 keeps the K most probable
