@@ -113,6 +113,20 @@ int nezha_verify_tuples(const nezha_itemset* set, const int32_t* codes, int64_t 
                         void* workspace, size_t workspace_bytes, void* hip_stream);
 size_t nezha_verify_workspace(int64_t n);
 
+/* nezha_verify_tuples for callers that cannot allocate device memory and have no workspace to
+ * hand over (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * allocation): the same kernels, with the block counts and offsets in a fixed array of
+ * NEZHA_VERIFY_STATIC_MAX / 1024 * 12 bytes (384 KiB) that is part of the library's device code
+ * (one copy per GPU, held until the process ends).  Arguments, results and error behaviour as for
+ * nezha_verify_tuples, without workspace; n above NEZHA_VERIFY_STATIC_MAX gives NEZHA_EINVAL.
+ * The call allocates nothing (the first call on a device asks the runtime for the array's address,
+ * which is kept).  All calls on one GPU share that array: calls whose work overlaps on one GPU
+ * (two streams, two threads) race; issue them on one stream or wait between them. */
+#define NEZHA_VERIFY_STATIC_MAX (32 * 1024 * 1024)
+int nezha_verify_tuples_static(const nezha_itemset* set, const int32_t* codes, int64_t n,
+                               uint8_t* out_mask, int64_t* out_index, int64_t* out_count,
+                               void* hip_stream);
+
 /* ---- one level of the draft head's beam search (Alg. 3, inference loop body) -----------
  *
  * For each of B requests and each of its K_in live beams (rank order) the call

@@ -20,7 +20,7 @@ EXPORTS = ["nezha_last_error", "nezha_build_itemset", "nezha_itemset_info", "nez
            "nezha_bench_random_gather", "nezha_user_projection", "nezha_pack_weights",
            "nezha_packed_weights_bytes", "nezha_user_projection_levels", "nezha_draft_levels", "nezha_decode",
            "nezha_profile_event_overhead",
-           "nezha_draft_levels_workspace", "nezha_check_itemset"]
+           "nezha_draft_levels_workspace", "nezha_check_itemset", "nezha_verify_tuples_static"]
 
 
 class NezhaError(RuntimeError):
@@ -74,6 +74,8 @@ def load_library():
     lib.nezha_draft_step.argtypes = [C.POINTER(_StepDesc)] + [C.c_void_p] * 14 + [C.c_size_t,
                                                                                   C.c_void_p]
     lib.nezha_unpack_keys.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.nezha_verify_tuples_static.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
+                                               C.c_void_p, C.c_void_p, C.c_void_p]
     lib.nezha_check_itemset.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p,
                                         C.POINTER(C.c_int64)]
     _LIB = lib
@@ -180,6 +182,18 @@ def verify_tuples(itemset, codes, out_mask=None, out_index=None, out_count=None,
     _check(load_library().nezha_verify_tuples(itemset._h, _ptr(codes), n, _ptr(out_mask),
                                               _ptr(out_index), _ptr(out_count), _ptr(workspace),
                                               workspace.numel(), _stream(stream)))
+    return out_mask, out_index, out_count
+
+
+VERIFY_STATIC_MAX = 32 * 1024 * 1024
+
+
+def verify_tuples_static(itemset, codes, out_mask, out_index=None, out_count=None, stream=None):
+    """nezha_verify_tuples_static: the verifier with its scratch in a fixed device array of the
+    library; the caller passes every output (nothing is allocated here or in the library)."""
+    _check(load_library().nezha_verify_tuples_static(itemset._h, _ptr(codes), codes.shape[0],
+                                                     _ptr(out_mask), _ptr(out_index),
+                                                     _ptr(out_count), _stream(stream)))
     return out_mask, out_index, out_count
 
 

@@ -650,6 +650,64 @@ int nezha_verify_tuples(const nezha_itemset* set, const int32_t* codes, int64_t 
   return verify_launch(set, codes, n, out_mask, out_index, out_count, workspace, stream);
 }
 
+}  // extern "C"
+
+// ---- the verifier for callers that cannot allocate -------------------------------------------
+// The block counts and offsets of nezha_verify_tuples live in a fixed array in device memory that
+// belongs to the library's code object (one copy per GPU, held until the process ends).
+namespace nezha {
+namespace {
+constexpr int64_t kStaticVerifyBlocks = NEZHA_VERIFY_STATIC_MAX / kVerifyBlock;
+constexpr size_t kStaticVerifyBytes =
+    (size_t)kStaticVerifyBlocks * sizeof(int32_t) + (size_t)kStaticVerifyBlocks * sizeof(int64_t);
+static_assert(NEZHA_VERIFY_STATIC_MAX % kVerifyBlock == 0, "whole blocks");
+static_assert(((size_t)kStaticVerifyBlocks * sizeof(int32_t)) % 16 == 0, "offsets stay aligned");
+static __device__ __align__(256) unsigned char scratch[kStaticVerifyBytes];
+
+// The array's address on each device, asked for once per device with that device current.  (In
+// host code the array's name is only a handle for this query, never an address.)
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void** out) {
+  int dev = -1;
+  NEZHA_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(NEZHA_EINVAL, "device %d out of range", dev);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    NEZHA_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(NEZHA_EHIP, "hipGetSymbolAddress gave no address");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return NEZHA_OK;
+}
+}  // namespace
+}  // namespace nezha
+
+extern "C" {
+
+int nezha_verify_tuples_static(const nezha_itemset* set, const int32_t* codes, int64_t n,
+                               uint8_t* out_mask, int64_t* out_index, int64_t* out_count,
+                               void* hip_stream) {
+  int rc = verify_check(set, codes, n, out_mask);
+  if (rc != NEZHA_OK) return rc;
+  if (n > NEZHA_VERIFY_STATIC_MAX)
+    return fail(NEZHA_EINVAL, "n = %lld exceeds NEZHA_VERIFY_STATIC_MAX = %lld; use "
+                "nezha_verify_tuples with a workspace", (long long)n,
+                (long long)NEZHA_VERIFY_STATIC_MAX);
+  hipStream_t stream = (hipStream_t)hip_stream;
+  if (n == 0) return verify_empty(out_count, stream);
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc != NEZHA_OK) return rc;
+  // Nothing in the array has to start at zero: the probe pass writes the count of every block of
+  // this call before any other pass reads it, and the scan writes every offset that is read.
+  return verify_launch(set, codes, n, out_mask, out_index, out_count, ws, stream);
+}
+
 int nezha_check_itemset(const nezha_itemset* set, const int32_t* codes, int64_t n,
                         int codes_on_device, void* hip_stream, int64_t* n_missing) {
   if (!set_is_live(set)) return fail(NEZHA_EINVAL, "not an item set");
