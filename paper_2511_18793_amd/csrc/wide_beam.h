@@ -112,11 +112,13 @@ __global__ __launch_bounds__(256) void wide_logits_bf16_kernel(WideArgs a) {
 
 // bf16, levels where no set is consulted: the logits never reach HBM.  Two launches walk the same
 // MFMA tiles; a wave = up to 32 beams of ONE request x a contiguous share of the code tiles:
-//   wide_lse_bf16_kernel   running (max, sum of exponentials) per beam and share -> part
-//   wide_keys_bf16_kernel  log-sum-exp from the shares' parts; the logits are formed again and
-//                          written as sort keys; every lane keeps the two largest keys it wrote
-//                          (distinct candidates of one request) -> tops, from which the
-//                          selection takes its bound without another pass over the keys
+//   wide_fused_bf16_kernel<KST, false>  running (max, sum of exponentials) per beam and share
+//                                       -> part
+//   wide_fused_bf16_kernel<KST, true>   log-sum-exp from the shares' parts; the logits are formed
+//                                       again and written as sort keys; every lane keeps the two
+//                                       largest keys it wrote (distinct candidates of one request)
+//                                       -> tops, from which the selection takes its bound without
+//                                       another pass over the keys
 struct WideFusedArgs {
   WideArgs w;
   float2* part;             // [B*K_in, col_splits] (max, sum of exp(z - max))
