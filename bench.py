@@ -129,6 +129,8 @@ def parse_args():
     ap.add_argument("--prefix-sets", action="store_true",
                     help="variant: also verify each level below L against the set of the "
                          "catalog's prefixes of that length")
+    ap.add_argument("--gemm-shape", default="4096x2048x4096",
+                    help="--workload user_gemm: B x d x T_l of the projection")
     ap.add_argument("--batch", type=int, default=0, help="override B (debugging)")
     ap.add_argument("--catalog", type=int, default=0, help="override N (debugging)")
     return ap.parse_args()
@@ -588,6 +590,88 @@ def bench_stress(args, cfg):
     return result
 
 
+def bench_user_gemm(args):
+    """Row a1 on its own: A = H W_l[0:d] (bf16 in, float32 accumulation and output) through
+    nezha_user_projection with packed weights, at the Large workload's shape (B x d x T_l = 4096 x
+    2048 x 4096) or the shape given by --gemm-shape.  A step is one projection; the roofline is
+    the bf16 MFMA peak on 2 B d T_l flops."""
+    dev = torch.device("cuda:0")
+    B, d, V = (int(v) for v in args.gemm_shape.lower().split("x"))
+    e = 32
+    rng = np.random.default_rng(args.seed)
+    H = torch.from_numpy(synth.round_to_bf16(rng.standard_normal((B, d)).astype(np.float32))).to(dev).to(torch.bfloat16)
+    W = torch.from_numpy(synth.round_to_bf16((rng.standard_normal((d + e, V)) * 0.02).astype(np.float32))).to(dev).to(torch.bfloat16)
+    Wp = nz.pack_weights(1, 1, [V], W, d)
+    A = torch.empty((B, V), dtype=torch.float32, device=dev)
+    ws = torch.empty(256, dtype=torch.uint8, device=dev)
+
+    def step():
+        nz.user_projection(1, 1, [V], H, Wp, out=A, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    ev[0].record()
+    for i in range(args.steps):
+        step()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    total_ms = ev[0].elapsed_time(ev[-1])
+    per_step = [ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]
+    # check of a sample of the outputs against a float64 product of the same bf16 values
+    rows = rng.integers(0, B, 64)
+    cols = rng.integers(0, V, 64)
+    want = (H[rows].double().cpu().numpy() @ W[:d].double().cpu().numpy()[:, cols])
+    err = float(np.abs(A[rows][:, cols].cpu().numpy() - want).max())
+    nz.profile_reset()
+    nz.profile_enable(True)
+    prof_steps = min(args.steps, 50)
+    for _ in range(prof_steps):
+        step()
+    torch.cuda.synchronize()
+    launches, ms = nz.profile_read()["user_gemm_kernel"]
+    nz.profile_enable(False)
+    nz.profile_reset()
+    overhead = nz.profile_event_overhead(200)
+    # what the matrix units sustain on these operand values with nothing else to do (the chip
+    # lowers its clock under matrix load, by an amount that depends on the values)
+    sus_h, clk_h = nz.bench_mfma_rate(H)
+    sus_w, clk_w = nz.bench_mfma_rate(W)
+    sus_0, clk_0 = nz.bench_mfma_rate(torch.zeros(4096, dtype=torch.bfloat16, device=dev))
+    flops = 2.0 * B * d * V
+    ms_per_step = total_ms / args.steps
+    achieved = flops * launches / (ms * 1e-3) / 1e12
+    return {
+        "metric": "user-part projection of the draft head (Eq. 2, beam-independent part), "
+                  "request rows per second, 1 MI355X",
+        "value": B / (ms_per_step * 1e-3), "unit": "rows/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "p50_step_ms": percentile(per_step, 50), "p99_step_ms": percentile(per_step, 99),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "user_gemm", "B": B, "d": d, "V": V, "output": "float32",
+                   "max_abs_error_vs_float64_on_a_sample": err},
+        "roofline": {"kernel": "user_gemm_kernel", "bound": "mfma", "achieved": achieved,
+                     "peak": PEAK_MFMA_TFLOPS["bf16"], "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_MFMA_TFLOPS["bf16"],
+                     "traffic": traffic_from_profile("user_gemm", "user_gemm_kernel")[0],
+                     "traffic_source": traffic_from_profile("user_gemm", "user_gemm_kernel")[1],
+                     "avg_launch_us": 1e3 * ms / launches, "event_overhead_us": overhead,
+                     "frac_from_back_to_back_steps": flops / (ms_per_step * 1e-3) / 1e12
+                                                     / PEAK_MFMA_TFLOPS["bf16"],
+                     "algorithmic_bytes": 2.0 * B * d + 2.0 * d * V + 4.0 * B * V,
+                     "sustained_mfma": {
+                         "what": "loop of independent 32x32x16 bf16 MFMAs alone, one wave per SIMD "
+                                 "on all CUs, operand values from the workload; clock from the "
+                                 "core-clock and 100 MHz counters read inside the kernel",
+                         "hidden_state_values": {"TFLOP/s": sus_h, "clock_MHz": clk_h},
+                         "weight_values": {"TFLOP/s": sus_w, "clock_MHz": clk_w},
+                         "zero_values": {"TFLOP/s": sus_0, "clock_MHz": clk_0}},
+                     "frac_of_sustained_mfma": achieved / min(sus_h, sus_w)},
+    }
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -604,6 +688,9 @@ def main():
             torch.mul(src, 1.0, out=dst)
         torch.cuda.synchronize()
         del src, dst
+    if args.workload == "user_gemm":
+        print(json.dumps(bench_user_gemm(args)))
+        return
     cfg = synth.get_config(args.workload)
     if args.batch:
         cfg = cfg.scaled(B=args.batch)

@@ -300,6 +300,17 @@ int nezha_profile_event_overhead(int launches, void* hip_stream, double* mean_us
 int nezha_bench_random_gather(const void* buf, size_t bytes, int64_t n, int line_bytes,
                               uint64_t seed, void* sink, void* hip_stream);
 
+/* Measurement aid for the projections' roofline: `workgroups` workgroups of four waves (one wave
+ * per SIMD, as in the large projection kernel) each run `iters` iterations of 32 independent
+ * 32x32x16 bf16 matrix instructions on operand values taken from `operands` (device, `bytes`
+ * long, 16-byte aligned; pass the hidden states or weights of the workload: the clock the chip
+ * sustains under matrix load depends on the values) and record, per workgroup, the core-clock
+ * cycles and the ticks of the constant 100 MHz counter the loop took: ticks[2*w], ticks[2*w+1]
+ * (device uint64 [2 * workgroups]).  flops = workgroups * 4 * iters * 32 * 32768; clock = 100 MHz
+ * * cycles / ticks.  sink: device float [1], scratch.  Asynchronous on hip_stream. */
+int nezha_bench_mfma_rate(const void* operands, size_t bytes, int iters, int workgroups,
+                          uint64_t* ticks, float* sink, void* hip_stream);
+
 /* Inverse of Eq. 4 on the host: keys[n] -> codes int32 [n, L] (level 1 first).  Host pointers. */
 int nezha_unpack_keys(const uint64_t* keys, int64_t n, int32_t L, const int32_t* radices,
                       int32_t* codes);

@@ -20,7 +20,8 @@ EXPORTS = ["nezha_last_error", "nezha_build_itemset", "nezha_itemset_info", "nez
            "nezha_bench_random_gather", "nezha_user_projection", "nezha_pack_weights",
            "nezha_packed_weights_bytes", "nezha_user_projection_levels", "nezha_draft_levels", "nezha_decode",
            "nezha_profile_event_overhead",
-           "nezha_draft_levels_workspace", "nezha_check_itemset", "nezha_verify_tuples_static"]
+           "nezha_draft_levels_workspace", "nezha_check_itemset", "nezha_verify_tuples_static",
+           "nezha_bench_mfma_rate"]
 
 
 class NezhaError(RuntimeError):
@@ -486,6 +487,25 @@ def bench_random_gather(buf, n, line_bytes=64, seed=1, stream=None):
     _check(lib.nezha_bench_random_gather(_ptr(buf), buf.numel() * buf.element_size(), int(n),
                                          int(line_bytes), int(seed), _ptr(sink), _stream(stream)))
     return sink
+
+
+def bench_mfma_rate(operands, iters=2000, workgroups=256, stream=None):
+    """nezha_bench_mfma_rate on the values of the CUDA tensor `operands`.  Returns (TFLOP/s summed
+    over the workgroups' own loop times, core clock in MHz during the loop)."""
+    dev = operands.device
+    ticks = torch.zeros(2 * workgroups, dtype=torch.int64, device=dev)
+    sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    lib = load_library()
+    lib.nezha_bench_mfma_rate.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_void_p,
+                                          C.c_void_p, C.c_void_p]
+    _check(lib.nezha_bench_mfma_rate(_ptr(operands), operands.numel() * operands.element_size(),
+                                     int(iters), int(workgroups), _ptr(ticks), _ptr(sink),
+                                     _stream(stream)))
+    torch.cuda.synchronize()
+    t = ticks.cpu().numpy().reshape(workgroups, 2).astype(np.float64)
+    seconds = t[:, 1] / 100e6
+    flops_per_wg = 4.0 * iters * 32 * 32768
+    return float((flops_per_wg / seconds).sum() / 1e12), float((t[:, 0] / t[:, 1]).mean() * 100.0)
 
 
 def profile_enable(on):

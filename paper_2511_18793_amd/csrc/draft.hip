@@ -289,21 +289,16 @@ __device__ __forceinline__ void load_block_to_lds(const void* gptr, void* lds_bl
 
 // Workgroup of NWM x NWN waves, each wave TM x TN tiles of 32x32.  K advances 32 per stage (two
 // MFMA steps of 16).  The H tile is brought by global_load_lds (no staging registers) into one of
-// four buffers, three stages ahead of use.  The packed W operands either go the same way (WLDS:
-// the large shapes, four waves of 128 x 128, where a wave's operand reads per MFMA are few enough
-// for the LDS bandwidth) or are loaded straight from global memory / L2 into registers, also three
-// stages ahead (smaller wave tiles, where LDS bandwidth is what binds; the waves of one column
-// strip then read the same lines).  One barrier per stage.  Workgroup ids are remapped so that the
-// tiles that run on one XCD (ids equal modulo 8) are neighbours and share its L2.
+// four buffers, three stages ahead of use.  The packed W operands are loaded straight from global
+// memory / L2 into registers, also three stages ahead (at these wave tiles LDS bandwidth is what
+// binds; the waves of one column strip read the same lines).  One barrier per stage.  Workgroup
+// ids are remapped so that the tiles that run on one XCD (ids equal modulo 8) are neighbours and
+// share its L2.  (The largest products take user_gemm_big_tile below instead.)
 constexpr int kGemmBuffers = 4;
 // KSPLIT > 1 (small problems, whose time is the length of the k loop): the workgroup has KSPLIT
 // groups of NWM x NWN waves, group s takes the s-th part of k with its own H buffers, and the
 // groups' partial results are added through LDS at the end (d must be a multiple of 32 * KSPLIT).
-// WLDS: the packed W operands go through LDS as well (their 1 KiB blocks are what one fetch
-// instruction brings, and what the 64 lanes of one operand read take): nothing of W is read twice
-// by the waves of a workgroup and no registers hold operands in flight; for tiles whose waves are
-// large enough (128 x 128) that LDS bandwidth still leaves room.
-template <int NWM, int NWN, int TM, int TN, int KSPLIT = 1, bool WLDS = false>
+template <int NWM, int NWN, int TM, int TN, int KSPLIT = 1>
 __device__ __forceinline__ void user_gemm_tile(
     const uint16_t* __restrict__ H, int64_t h_stride, const uint16_t* __restrict__ Wu,
     float* __restrict__ A, int B, int d, int V, int tiles_n, int tiles_total, int tile_id) {
@@ -312,10 +307,8 @@ __device__ __forceinline__ void user_gemm_tile(
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
   constexpr int CT = BN / 32;                        // 32-column tiles per workgroup
   constexpr int ASLOTS = BM * 4;                     // 16-byte slots of the H tile (64 B per row)
-  constexpr int BINS = 2 * CT;                       // W operand blocks (fetch instructions) per stage
-  constexpr int BSLOTS = WLDS ? BINS * 64 : 0;       // 16-byte slots of the W tile
-  constexpr int SSLOTS = ASLOTS + BSLOTS;            // one stage's buffer
-  extern __shared__ __align__(16) uint4 smem_all[];  // [KSPLIT][kGemmBuffers][H tile | W tile]
+  constexpr int SSLOTS = ASLOTS;                     // one stage's buffer
+  extern __shared__ __align__(16) uint4 smem_all[];  // [KSPLIT][kGemmBuffers][H tile]
   const int tid = threadIdx.x, lane = tid & 63;
   const int ksplit = (tid >> 6) / NW, wave = (tid >> 6) % NW;   // wave: index inside its group
   uint4* const smem = smem_all + ksplit * kGemmBuffers * SSLOTS;
@@ -375,21 +368,7 @@ __device__ __forceinline__ void user_gemm_tile(
     ct = ct < n_ct ? ct : n_ct - 1;                  // tiles beyond V: clamped, never stored
     b_ptr[j] = reinterpret_cast<const uint4*>(Wu) + (int64_t)ct * KSu * 64 + lane;
   }
-  // WLDS: W block (column tile jb, step ks) of a stage is fetch instruction 2*jb + ks; wave w
-  // issues w, w+NW, ...
-  constexpr int BPW = WLDS ? (BINS + NW - 1) / NW : 0;
-  const uint4* bl_ptr[BPW > 0 ? BPW : 1];
-  if constexpr (WLDS) {
-#pragma unroll
-    for (int u = 0; u < BPW; ++u) {
-      int ins = wave + NW * u;
-      ins = ins < BINS ? ins : BINS - 1;
-      int ct = ct0 + (ins >> 1);
-      ct = ct < n_ct ? ct : n_ct - 1;
-      bl_ptr[u] = reinterpret_cast<const uint4*>(Wu) + ((int64_t)ct * KSu + (ins & 1)) * 64 + lane;
-    }
-  }
-  uint4 fb[WLDS ? 1 : kGemmBuffers][2][TN];          // W operands of the stages in flight (!WLDS)
+  uint4 fb[kGemmBuffers][2][TN];                     // W operands of the stages in flight
   auto fetch = [&](int stage, uint4 (&b)[2][TN]) {
     uint4* sa = smem + (stage % kGemmBuffers) * SSLOTS;
 #pragma unroll
@@ -398,24 +377,10 @@ __device__ __forceinline__ void user_gemm_tile(
       ins = ins < AINS ? ins : AINS - 1;
       load_block_to_lds(a_ptr[u] + (stage0 + stage) * 32, sa + ins * 64);
     }
-    if constexpr (WLDS) {
 #pragma unroll
-      for (int u = 0; u < BPW; ++u) {
-        int ins = wave + NW * u;
-        ins = ins < BINS ? ins : BINS - 1;
-        load_block_to_lds(bl_ptr[u] + (int64_t)(stage0 + stage) * 2 * 64, sa + ASLOTS + ins * 64);
-      }
-    } else {
+    for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) b[ks][j] = b_ptr[j][((stage0 + stage) * 2 + ks) * 64];
-    }
-  };
-  auto read_b = [&](int stage, int ks, uint4 (&b)[TN]) {
-    const uint4* sb = smem + (stage % kGemmBuffers) * SSLOTS + ASLOTS;
-#pragma unroll
-    for (int j = 0; j < TN; ++j) b[j] = sb[(2 * (wn * TN + j) + ks) * 64 + lane];
+      for (int j = 0; j < TN; ++j) b[ks][j] = b_ptr[j][((stage0 + stage) * 2 + ks) * 64];
   };
   // LDS slot of this lane's A operand for row tile i, step ks: row = (wm*TM+i)*32 + lane%32,
   // chunk = 2*ks + lane/32, slot = row*4 + (chunk ^ (row/4)%4)
@@ -423,7 +388,7 @@ __device__ __forceinline__ void user_gemm_tile(
 #pragma unroll
   for (int i = 0; i < TM; ++i) a_slot[i] = ((wm * TM + i) * 32 + (lane & 31)) * 4;
   const int a_sw = (lane >> 2) & 3, a_hi = lane >> 5;
-  constexpr int LOADS = WLDS ? APW + BPW : APW + 2 * TN;   // loads per wave and stage
+  constexpr int LOADS = APW + 2 * TN;                // loads per wave and stage
   // at most `newer` stages' worth of this wave's loads still in flight (they complete in order)
   auto wait_fetches = [&](int newer) {
     constexpr int L1 = LOADS < 15 ? LOADS : 15, L2 = 2 * LOADS < 63 ? 2 * LOADS : 63;
@@ -451,15 +416,13 @@ __device__ __forceinline__ void user_gemm_tile(
   // step's MFMAs run.
 #pragma unroll
   for (int p = 0; p < kGemmBuffers - 1; ++p)
-    if (p < stages) fetch(p, fb[WLDS ? 0 : p]);
+    if (p < stages) fetch(p, fb[p]);
   bf16x8 fa0[TM], fa1[TM];
-  uint4 fb0[WLDS ? TN : 1], fb1[WLDS ? TN : 1];      // WLDS: W operands of the two steps at hand
   {
     const int ahead = stages - 1;
     wait_fetches(ahead < kGemmBuffers - 2 ? ahead : kGemmBuffers - 2);
     __syncthreads();
     read_a(0, 0, fa0);
-    if constexpr (WLDS) read_b(0, 0, fb0);
   }
   for (int base = 0; base < stages; base += kGemmBuffers) {
 #pragma unroll
@@ -467,23 +430,16 @@ __device__ __forceinline__ void user_gemm_tile(
       const int stage = base + q;
       if (stage < stages) {
         read_a(stage, 1, fa1);
-        if constexpr (WLDS) {
-          read_b(stage, 1, fb1);
-          multiply(fa0, fb0);
-        } else {
-          multiply(fa0, fb[q][0]);
-        }
+        multiply(fa0, fb[q][0]);
         if (stage + 1 < stages) {
           const int ahead = stages - 2 - stage;      // fetched stages after stage+1
           wait_fetches(ahead < kGemmBuffers - 3 ? ahead : kGemmBuffers - 3);
           __syncthreads();  // stage+1 has landed everywhere; the buffer of stage-1 is free everywhere
           if (stage + kGemmBuffers - 1 < stages)
-            fetch(stage + kGemmBuffers - 1, fb[WLDS ? 0 : (q + kGemmBuffers - 1) % kGemmBuffers]);
+            fetch(stage + kGemmBuffers - 1, fb[(q + kGemmBuffers - 1) % kGemmBuffers]);
           read_a(stage + 1, 0, fa0);
-          if constexpr (WLDS) read_b(stage + 1, 0, fb0);
         }
-        if constexpr (WLDS) multiply(fa1, fb1);
-        else multiply(fa1, fb[q][1]);
+        multiply(fa1, fb[q][1]);
       }
     }
   }
@@ -529,12 +485,12 @@ __device__ __forceinline__ void user_gemm_tile(
     }
 }
 
-template <int NWM, int NWN, int TM, int TN, int KSPLIT = 1, bool WLDS = false>
+template <int NWM, int NWN, int TM, int TN, int KSPLIT = 1>
 __global__ __launch_bounds__(64 * NWM * NWN * KSPLIT, 1) void user_gemm_bf16_kernel(
     const uint16_t* __restrict__ H, int64_t h_stride, const uint16_t* __restrict__ Wu,
     float* __restrict__ A, int B, int d, int V, int tiles_n, int tiles_total) {
-  user_gemm_tile<NWM, NWN, TM, TN, KSPLIT, WLDS>(H, h_stride, Wu, A, B, d, V, tiles_n, tiles_total,
-                                                 blockIdx.x);
+  user_gemm_tile<NWM, NWN, TM, TN, KSPLIT>(H, h_stride, Wu, A, B, d, V, tiles_n, tiles_total,
+                                           blockIdx.x);
 }
 
 // Several levels' projections in one launch: they do not depend on each other (all the hidden
@@ -556,6 +512,263 @@ __global__ __launch_bounds__(64 * NWM * NWN * KSPLIT, 1) void user_gemm_bf16_gro
   // an odd tile count defeats the XCD remapping inside, which is what small problems want
   user_gemm_tile<NWM, NWN, TM, TN, KSPLIT>(grp.H[p], h_stride, grp.Wu[p], grp.A[p], B, d, grp.V[p],
                                            grp.tiles_n[p], 1, (int)blockIdx.x - grp.tile_begin[p]);
+}
+
+// ---- the largest products: 256 x 256 tiles, both operands through LDS ------------------------------
+// Four waves (2 x 2), each 128 x 128 = 4 x 4 accumulator tiles of 32 x 32 (256 accumulator
+// registers, one wave per SIMD: the tile shape that moves the fewest LDS and L2 bytes per flop).
+// A stage is 32 k: the H tile (256 rows x 64 B, XOR-swizzled as above) and the packed W tile (16
+// operand blocks of 1 KiB) are brought by global_load_lds into one of four 32 KiB buffers, and
+// stage s+4 is requested as soon as the barrier of iteration s has shown that every wave is done
+// with buffer s: three stages are in flight while a wave waits for the next one.  The instruction
+// order inside an iteration is pinned (scheduling groups): the LDS operand reads of the next MFMA
+// step go out under the first MFMAs of the current one, the barrier sits behind eight MFMAs, and
+// the eight fetch instructions are spread one per MFMA, so that the matrix pipe is not left idle
+// while the wave issues memory instructions (in-kernel clock reads: 39 cycles per MFMA against 33.6
+// for a loop of MFMAs alone).
+// The product is accumulated TRANSPOSED (W fragment as the first MFMA operand): a lane then holds
+// four consecutive output columns of one row per accumulator quad and writes them as one 16-byte
+// store (64 store instructions per wave instead of 256).
+constexpr int kBigSlotsA = 1024, kBigSlotsStage = 2048;   // 16-byte slots: H tile, H + W tiles
+__host__ __device__ constexpr size_t big_gemm_lds() {
+  return (size_t)kGemmBuffers * kBigSlotsStage * sizeof(uint4);
+}
+__device__ __forceinline__ void user_gemm_big_tile(
+    const uint16_t* __restrict__ H, int64_t h_stride, const uint16_t* __restrict__ Wu,
+    float* __restrict__ A, int B, int d, int V, int tiles_n, int tiles_total, int tile_id) {
+  typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+  typedef float float4v __attribute__((ext_vector_type(4)));
+  extern __shared__ __align__(16) uint4 smem_all[];
+  uint4* const smem = smem_all;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  int tile_m, tile_n;
+  {
+    // (the same XCD-aware order as user_gemm_tile)
+    const int t = tile_id, xcd = t & 7, local = t >> 3;
+    if (tiles_total % 256 == 0 && tiles_n % 8 == 0 && (tiles_total / tiles_n) % 4 == 0) {
+      const int group = xcd + 8 * (local >> 5), groups_n = tiles_n >> 3;
+      tile_m = (group / groups_n) * 4 + ((local & 31) >> 3);
+      tile_n = (group % groups_n) * 8 + (local & 7);
+    } else {
+      const int per_xcd = tiles_total / 8;
+      const int lin = (per_xcd * 8 == tiles_total) ? xcd * per_xcd + local : t;
+      tile_m = lin / tiles_n;
+      tile_n = lin - tile_m * tiles_n;
+    }
+  }
+  const int row0 = tile_m * 256, ct0 = tile_n * 8;
+  const int n_ct = (V + 31) / 32;
+  const int KSu = d / 16;
+  const int stages = d / 32;
+
+  floatx16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // Wave w issues H fetch instructions w, w+4, w+8, w+12 (16 rows x 64 B each) and W operand
+  // blocks w, w+4, w+8, w+12 of the stage's 16 (block 2*jb + ks: column tile jb, MFMA step ks).
+  // Rows beyond B and column tiles beyond T_l are clamped (their results are never stored).
+  const uint16_t* a_ptr[4];
+  const uint4* b_ptr[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int ins = wave + 4 * u;
+    int row = row0 + ins * 16 + (lane >> 2);
+    row = row < B ? row : B - 1;
+    a_ptr[u] = H + (int64_t)row * h_stride + 8 * ((lane & 3) ^ ((lane >> 4) & 3));
+    int ct = ct0 + (ins >> 1);
+    ct = ct < n_ct ? ct : n_ct - 1;
+    b_ptr[u] = reinterpret_cast<const uint4*>(Wu) + ((int64_t)ct * KSu + (ins & 1)) * 64 + lane;
+  }
+  auto fetch = [&](int stage) {
+    uint4* sa = smem + (stage & (kGemmBuffers - 1)) * kBigSlotsStage;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) load_block_to_lds(a_ptr[u] + stage * 32, sa + (wave + 4 * u) * 64);
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      load_block_to_lds(b_ptr[u] + (int64_t)stage * 128, sa + kBigSlotsA + (wave + 4 * u) * 64);
+  };
+  int a_slot[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) a_slot[i] = ((wm * 4 + i) * 32 + (lane & 31)) * 4;
+  const int a_sw = (lane >> 2) & 3, a_hi = lane >> 5;
+  auto read_a = [&](int stage, int ks, bf16x8 (&fa)[4]) {
+    const uint4* sa = smem + (stage & (kGemmBuffers - 1)) * kBigSlotsStage;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      fa[i] = *reinterpret_cast<const bf16x8*>(&sa[a_slot[i] + ((2 * ks + a_hi) ^ a_sw)]);
+  };
+  auto read_b = [&](int stage, int ks, bf16x8 (&fb)[4]) {
+    const uint4* sb = smem + (stage & (kGemmBuffers - 1)) * kBigSlotsStage + kBigSlotsA;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      fb[j] = *reinterpret_cast<const bf16x8*>(&sb[(2 * (wn * 4 + j) + ks) * 64 + lane]);
+  };
+  auto mm = [&](bf16x8 (&fa)[4], bf16x8 (&fb)[4], int i0, int i1) {
+#pragma unroll
+    for (int i = i0; i < i1; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+  };
+  constexpr int kMfma = 0x008, kVmemRead = 0x020, kDsRead = 0x100;   // scheduling group masks
+
+  fetch(0);
+  if (stages > 1) fetch(1);
+  if (stages > 2) fetch(2);
+  if (stages > 3) fetch(3);
+  bf16x8 fa0[4], fb0[4], fa1[4], fb1[4];
+  // stage 0 has landed: at most the 24 loads of stages 1..3 are still in flight
+  if (stages > 3) __builtin_amdgcn_s_waitcnt(0x0F70 | (24 & 15) | ((24 >> 4) << 14));
+  else __builtin_amdgcn_s_waitcnt(0x0F70);
+  __syncthreads();
+  read_a(0, 0, fa0);
+  read_b(0, 0, fb0);
+  auto iteration = [&](int s, auto fetch_c, auto drain_c) {
+    constexpr bool FETCH = decltype(fetch_c)::value;     // s + 4 < stages: stage s+4 is requested
+    constexpr bool DRAIN = decltype(drain_c)::value;     // s + 3 >= stages: nothing newer in flight
+    // first half of MFMA step (s, 0); the operands of step (s, 1) go out under its first MFMAs
+    read_a(s, 1, fa1);
+    read_b(s, 1, fb1);
+    mm(fa0, fb0, 0, 2);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(kDsRead, 2, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(kMfma, 4, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    // this wave's part of stage s+1 has landed (its loads complete in order: 16 newer ones may
+    // be in flight) and its reads of buffer s are complete; then everybody's
+    if (DRAIN) __builtin_amdgcn_s_waitcnt(0x0070);
+    else __builtin_amdgcn_s_waitcnt(0x0070 | (16 & 15) | ((16 >> 4) << 14));
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    if (FETCH) fetch(s + 4);                             // buffer s is free now
+    mm(fa0, fb0, 2, 4);
+    read_a(s + 1, 0, fa0);
+    read_b(s + 1, 0, fb0);
+    mm(fa1, fb1, 0, 4);
+    if (FETCH) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(kVmemRead, 1, 0);
+      }
+    } else {
+      __builtin_amdgcn_sched_group_barrier(kMfma, 8, 0);
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(kDsRead, 2, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(kMfma, 12, 0);
+  };
+  int s = 0;
+  for (; s + 4 < stages; ++s) iteration(s, std::true_type{}, std::false_type{});
+  for (; s + 3 < stages; ++s) iteration(s, std::false_type{}, std::false_type{});
+  for (; s + 1 < stages; ++s) iteration(s, std::false_type{}, std::true_type{});
+  read_a(s, 1, fa1);                                     // the last stage
+  read_b(s, 1, fb1);
+  mm(fa0, fb0, 0, 4);
+  mm(fa1, fb1, 0, 4);
+  // register 4q + t of lane l: row l%32 of row tile i, column 8q + 4*(l/32) + t of column tile j
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = row0 + (wm * 4 + i) * 32 + (lane & 31);
+    if (row >= B) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int colb = (ct0 + wn * 4 + j) * 32 + 4 * (lane >> 5);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int col = colb + 8 * q;                    // T_l is a multiple of 16: all four or none
+        if (col < V)
+          *reinterpret_cast<float4v*>(A + (int64_t)row * V + col) = float4v{
+              acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(256, 1) void user_gemm_big_kernel(
+    const uint16_t* __restrict__ H, int64_t h_stride, const uint16_t* __restrict__ Wu,
+    float* __restrict__ A, int B, int d, int V, int tiles_n, int tiles_total) {
+  user_gemm_big_tile(H, h_stride, Wu, A, B, d, V, tiles_n, tiles_total, blockIdx.x);
+}
+// All levels' tiles in one launch: a CU takes its next tile as soon as the waves of the one before
+// have issued their result stores, so the 4 * B * T_l bytes of one level drain to memory under the
+// next level's k loop instead of at the end of a launch of their own.
+__global__ __launch_bounds__(256, 1) void user_gemm_big_grouped_kernel(GemmGroup grp,
+                                                                       int64_t h_stride, int B,
+                                                                       int d) {
+  int p = 0;
+  while (p + 1 < grp.n && (int)blockIdx.x >= grp.tile_begin[p + 1]) ++p;
+  user_gemm_big_tile(grp.H[p], h_stride, grp.Wu[p], grp.A[p], B, d, grp.V[p], grp.tiles_n[p],
+                     grp.tile_begin[p + 1] - grp.tile_begin[p], (int)blockIdx.x - grp.tile_begin[p]);
+}
+
+// Measurement aid for the projection's roofline: the loop of user_gemm_big_tile with everything but
+// its MFMAs taken out (one wave per SIMD, 32 independent 32x32x16 bf16 MFMAs per iteration on
+// operand values read from the caller's buffer), timed from inside with the core-clock counter and
+// the constant 100 MHz counter.  The chip lowers its clock under matrix load by an amount that
+// depends on the operand values (all-zero operands run faster than random ones), so the product
+// of unit count and nominal clock is not what a projection on real values can reach; this gives
+// the rate that is sustained with the values at hand, and the clock it runs at.
+__global__ __launch_bounds__(256, 1) void mfma_rate_kernel(const uint4* __restrict__ operands,
+                                                           int n_vec, int iters,
+                                                           unsigned long long* __restrict__ ticks,
+                                                           float* __restrict__ sink) {
+  typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+  const int tid = threadIdx.x;
+  bf16x8 fa[2][4], fb[2][4];
+#pragma unroll
+  for (int h = 0; h < 2; ++h)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint4 x = operands[(int)(((unsigned)blockIdx.x * 2048u + (h * 8 + i) * 256 + tid) % (unsigned)n_vec)];
+      const uint4 y = operands[(int)(((unsigned)blockIdx.x * 2048u + (h * 8 + 4 + i) * 256 + tid) % (unsigned)n_vec)];
+      fa[h][i] = *reinterpret_cast<const bf16x8*>(&x);
+      fb[h][i] = *reinterpret_cast<const bf16x8*>(&y);
+    }
+  floatx16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  __syncthreads();
+  const unsigned long long c0 = __builtin_amdgcn_s_memtime(), r0 = __builtin_amdgcn_s_memrealtime();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[h][j], fa[h][i], acc[i][j], 0, 0, 0);
+  }
+  const unsigned long long c1 = __builtin_amdgcn_s_memtime(), r1 = __builtin_amdgcn_s_memrealtime();
+  float t = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) t += acc[i][j][r];
+  if (t == 123.456f) sink[0] = t;                        // keeps every accumulator alive
+  if (tid == 0) {
+    ticks[2 * blockIdx.x] = c1 - c0;
+    ticks[2 * blockIdx.x + 1] = r1 - r0;
+  }
 }
 
 // ---- user-part projection, fp32 (small correctness-first shapes) -----------------------------
@@ -2540,6 +2753,7 @@ int allow_lds(Kern kern, size_t bytes) {
 // CUs without a workgroup (B = T_l = 1024: 64 tiles), so they get 32 x 64 tiles, and their k
 // loop runs in four parts side by side (user_gemm_tile, KSPLIT).
 constexpr int64_t kSmallGemmElems = (int64_t)128 * 128 * 256;
+constexpr int64_t kBigGemmElems = (int64_t)256 * 256 * 128;   // from here on: 256 x 256 tiles
 inline bool small_gemm_splits_k(int d) { return (d / 32) % 4 == 0 && d >= 256; }
 
 int launch_pack(const nezha_step_desc* desc, const void* W_l, uint16_t* Wp, hipStream_t stream) {
@@ -2579,15 +2793,13 @@ int launch_user_part(const nezha_step_desc* desc, const void* H_l, const void* W
                        tiles_m * tiles_n);                                                     \
   } while (0)
     const int64_t out_elems = (int64_t)B * V;
-    if (out_elems >= (int64_t)256 * 256 * 128) {                                  // 256 x 256 tiles
-      constexpr int BM = 256, BN = 256;
-      const int tiles_m = (B + BM - 1) / BM, tiles_n = (V + BN - 1) / BN;
-      const size_t lds = (size_t)kGemmBuffers * (BM * 4 + 2 * (BN / 32) * 64) * sizeof(uint4);
-      rc = allow_lds(user_gemm_bf16_kernel<2, 2, 4, 4, 1, true>, lds);
+    if (out_elems >= kBigGemmElems) {                                             // 256 x 256 tiles
+      const int tiles_m = (B + 255) / 256, tiles_n = (V + 255) / 256;
+      rc = allow_lds(user_gemm_big_kernel, big_gemm_lds());
       if (rc != NEZHA_OK) return rc;
-      hipLaunchKernelGGL((user_gemm_bf16_kernel<2, 2, 4, 4, 1, true>), dim3(tiles_m * tiles_n),
-                         dim3(256), lds, stream, Hp, desc->h_row_stride, (const uint16_t*)Wp, A, B,
-                         d, V, tiles_n, tiles_m * tiles_n);
+      hipLaunchKernelGGL(user_gemm_big_kernel, dim3(tiles_m * tiles_n), dim3(256), big_gemm_lds(),
+                         stream, Hp, desc->h_row_stride, (const uint16_t*)Wp, A, B, d, V, tiles_n,
+                         tiles_m * tiles_n);
     }
     else if (out_elems >= kSmallGemmElems) LAUNCH_GEMM(2, 2, 2, 2, 1);             // 128 x 128 tiles
     // small products: the same tiles and the same order of summation as the grouped launch of
@@ -2687,6 +2899,27 @@ int nezha_user_projection_levels(const nezha_step_desc* desc, int32_t n_levels,
   hipStream_t stream = (hipStream_t)hip_stream;
   int max_v = 0;
   for (int i = 0; i < n_levels; ++i) max_v = desc->radices[i] > max_v ? desc->radices[i] : max_v;
+  int min_v = max_v;
+  for (int i = 0; i < n_levels; ++i) min_v = desc->radices[i] < min_v ? desc->radices[i] : min_v;
+  if ((int64_t)B * min_v >= kBigGemmElems) {
+    // the largest projections: the 256 x 256 tiles of all levels in one launch
+    GemmGroup big = grp;
+    int big_tiles = 0;
+    const int tiles_m = (B + 255) / 256;
+    for (int i = 0; i < n_levels; ++i) {
+      big.tiles_n[i] = (desc->radices[i] + 255) / 256;
+      big.tile_begin[i] = big_tiles;
+      big_tiles += tiles_m * big.tiles_n[i];
+    }
+    for (int i = n_levels; i <= NEZHA_MAX_LEVELS; ++i) big.tile_begin[i] = big_tiles;
+    int rc = allow_lds(user_gemm_big_grouped_kernel, big_gemm_lds());
+    if (rc != NEZHA_OK) return rc;
+    ProfileScope prof(kUserGemm, stream);
+    hipLaunchKernelGGL(user_gemm_big_grouped_kernel, dim3(big_tiles), dim3(256), big_gemm_lds(),
+                       stream, big, desc->h_row_stride, B, d);
+    NEZHA_HIP_CHECK(hipGetLastError());
+    return NEZHA_OK;
+  }
   if ((int64_t)B * max_v >= kSmallGemmElems) {
     // large projections fill the chip on their own: one launch each, with the large tiles
     for (int i = 0; i < n_levels; ++i) {
@@ -2730,6 +2963,20 @@ int nezha_pack_weights(const nezha_step_desc* desc, const void* W_l, void* W_pac
   if ((reinterpret_cast<uintptr_t>(W_l) | reinterpret_cast<uintptr_t>(W_packed)) & 15)
     return fail(NEZHA_EINVAL, "W_l and W_packed must be 16-byte aligned");
   return launch_pack(desc, W_l, static_cast<uint16_t*>(W_packed), (hipStream_t)hip_stream);
+}
+
+int nezha_bench_mfma_rate(const void* operands, size_t bytes, int iters, int workgroups,
+                          uint64_t* ticks, float* sink, void* hip_stream) {
+  if (!operands || !ticks || !sink || bytes < 16 || bytes > ((size_t)1 << 34) || iters < 1 ||
+      iters > (1 << 20) || workgroups < 1 || workgroups > 65536 ||
+      (reinterpret_cast<uintptr_t>(operands) & 15))
+    return fail(NEZHA_EINVAL, "bad argument");
+  hipStream_t stream = (hipStream_t)hip_stream;
+  hipLaunchKernelGGL(mfma_rate_kernel, dim3(workgroups), dim3(256), 0, stream,
+                     static_cast<const uint4*>(operands), (int)(bytes / 16), iters,
+                     reinterpret_cast<unsigned long long*>(ticks), sink);
+  NEZHA_HIP_CHECK(hipGetLastError());
+  return NEZHA_OK;
 }
 
 size_t nezha_draft_step_workspace(const nezha_step_desc* desc) {
