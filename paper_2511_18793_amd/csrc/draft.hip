@@ -34,6 +34,41 @@ __device__ __forceinline__ uint16_t float_to_bf16(float f) {  // round to neares
   u += 0x7FFFu + ((u >> 16) & 1u);
   return (uint16_t)(u >> 16);
 }
+// max(a, b) for operands that are never NaN, as the single instruction it is (the generic maximum
+// first rewrites both operands into canonical form, two more instructions per call).
+__device__ __forceinline__ float max_of_numbers(float a, float b) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+// Two running maxima in one register: (a, b) rounded towards zero to half precision, packed, and
+// the element-wise maximum of two such pairs.  A maximum kept this way is off by less than one
+// half-precision unit in the last place (2^-10 relative; below 2^-14 in magnitude: 2^-24
+// absolute); half_floor / half_ceil turn it back into a float32 bound on the true maximum from
+// below / above.  Values beyond the half range (|x| > 65504) are clamped by the conversion and
+// must be detected by the caller (half_out_of_range).
+__device__ __forceinline__ uint32_t pack_halves_rtz(float a, float b) {
+  auto p = __builtin_amdgcn_cvt_pkrtz(a, b);
+  uint32_t r;
+  __builtin_memcpy(&r, &p, 4);
+  return r;
+}
+__device__ __forceinline__ uint32_t max_of_half_pairs(uint32_t a, uint32_t b) {
+  uint32_t r;
+  asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+__device__ __forceinline__ float half_bits_to_float(uint32_t h) {
+  const uint16_t x = (uint16_t)h;
+  _Float16 f;
+  __builtin_memcpy(&f, &x, 2);
+  return (float)f;
+}
+__device__ __forceinline__ float half_floor(float m) { return m - fabsf(m) * 0.0009765625f - 1e-7f; }
+__device__ __forceinline__ float half_ceil(float m) { return m + fabsf(m) * 0.0009765625f + 1e-7f; }
+__device__ __forceinline__ bool half_out_of_range(float m) {
+  return fabsf(m) >= 60000.f && fabsf(m) < INFINITY;
+}
 // Order-preserving map float -> uint32 (larger float <=> larger integer) and back.
 __device__ __forceinline__ uint32_t ordered_bits(float f) {
   uint32_t u = __float_as_uint(f);
@@ -1972,13 +2007,15 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
     // (as few values as possible live through the first sweep: it is the one short of registers)
     // What the second sweep needs (bounds, parent scores, log-sum-exps, threshold) is handed over
     // through LDS and read at its start, so that nothing but this lives through the first sweep.
-    float gmax[4][kReqTiles], nml[4], ssum[4];
+    // group maxima of beams (4g, 4g+1) and (4g+2, 4g+3) as packed half pairs: half the registers
+    uint32_t gmaxp[2][kReqTiles];
+    float nml[4], ssum[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       nml[i] = 0.f;
       ssum[i] = 0.f;
 #pragma unroll
-      for (int j = 0; j < kReqTiles; ++j) gmax[i][j] = -INFINITY;
+      for (int j = 0; j < kReqTiles; ++j) gmaxp[i >> 1][j] = 0xFC00FC00u;   // (-inf, -inf)
     }
     if constexpr (WHOLE) {
       const int g = lane >> 4, c = lane & 15;
@@ -2047,30 +2084,34 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
         const int tiles = n_ct - ch * kReqTiles;            // >= kReqTiles except in the last chunk
         auto chunk_body = [&](auto ragged_c) {
           constexpr bool ragged = decltype(ragged_c)::value;
-          // Operands of tile ct+1 are requested right after the MFMAs of tile ct have been
-          // issued, into the same registers, and arrive under tile ct's vector work.  The
-          // scheduling fences keep the compiler from hoisting a whole chunk's LDS reads at once,
-          // which costs more registers than there are.
-#pragma unroll
-          for (int ct = 0; ct < kReqTiles; ++ct) {
-            // (operands are read tile by tile, not a tile ahead: the other waves of the SIMD
-            // cover the LDS latency, and the registers a second operand set would take are the
-            // ones this loop is short of)
-            uint4 w[KST];
+          // One operand set, two accumulators: the operands of tile ct+1 are requested right
+          // after the MFMAs of tile ct have been issued (into the same registers: the matrix pipe
+          // has taken its operands long before LDS answers) and arrive under the vector work of
+          // tile ct-1, which in turn covers the latency of tile ct's MFMAs.  The scheduling fences
+          // keep one tile's work per step (hoisting a whole chunk's LDS reads at once costs more
+          // registers than there are).
+          uint4 w[KST];
+          float a0;
+          floatx4 acc[2];
+          auto reads = [&](int ct) {
 #pragma unroll
             for (int ks = 0; ks < KST; ++ks)
               w[ks] = *reinterpret_cast<const uint4*>(wb + ((ct * KS + ks) * 64 + ln) * 16);
-            const float a0 = ab[ct * 16 + c];
-            floatx4 acc = floatx4{a0, a0, a0, a0};
+            a0 = ab[ct * 16 + c];
+          };
+          auto mfmas = [&](int buf) {
+            floatx4 t = floatx4{a0, a0, a0, a0};
 #pragma unroll
             for (int ks = 0; ks < KST; ++ks)
-              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                  fa16[ks], *reinterpret_cast<const bf16x8*>(&w[ks]), acc, 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+              t = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                  fa16[ks], *reinterpret_cast<const bf16x8*>(&w[ks]), t, 0, 0, 0);
+            acc[buf] = t;
+          };
+          auto vector_work = [&](int ct, int buf) {
             const bool live = !ragged || ct < tiles;
             float z[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) z[i] = live ? acc[i] : -INFINITY;
+            for (int i = 0; i < 4; ++i) z[i] = live ? acc[buf][i] : -INFINITY;
             if constexpr (sweep == 0) {
               // Sum of exp(z - m) about a fixed reference m = (the lane's first logit of the
               // beam) + 20, held as nml = -m * log2(e): no rescaling while streaming.  A beam with
@@ -2079,11 +2120,11 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
 #pragma unroll
                 for (int i = 0; i < 4; ++i) nml[i] = -(z[i] + 20.f) * kLog2e;
               }
+              gmaxp[0][ct] = max_of_half_pairs(gmaxp[0][ct], pack_halves_rtz(z[0], z[1]));
+              gmaxp[1][ct] = max_of_half_pairs(gmaxp[1][ct], pack_halves_rtz(z[2], z[3]));
 #pragma unroll
-              for (int i = 0; i < 4; ++i) {
-                gmax[i][ct] = __builtin_amdgcn_fmed3f(gmax[i][ct], z[i], INFINITY);   // max
+              for (int i = 0; i < 4; ++i)
                 ssum[i] += __builtin_amdgcn_exp2f(fmaf(z[i], kLog2e, nml[i]));
-              }
             } else if constexpr (WHOLE) {
               const uint32_t code = (uint32_t)((ch * kReqTiles + ct) * 16 + c);
 #pragma unroll
@@ -2111,8 +2152,18 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
                   my_lists[(4 * g + i) * kReqCap + pos[i]] =
                       ((uint64_t)__float_as_uint(z[i]) << 32) | code;
             }
+          };
+          reads(0);
+#pragma unroll
+          for (int ct = 0; ct < kReqTiles; ++ct) {
+            mfmas(ct & 1);
+            __builtin_amdgcn_sched_barrier(0);
+            if (ct + 1 < kReqTiles) reads(ct + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            if (ct > 0) vector_work(ct - 1, (ct - 1) & 1);
             __builtin_amdgcn_sched_barrier(0);
           }
+          vector_work(kReqTiles - 1, (kReqTiles - 1) & 1);
         };
         if (tiles >= kReqTiles) chunk_body(std::false_type{});
         else chunk_body(std::true_type{});
@@ -2139,12 +2190,17 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
           merge_with(__uint_as_float(lane_xor<8>(__float_as_uint(mm), lane)),
                      __uint_as_float(lane_xor<8>(__float_as_uint(ss), lane)));
           if (c == 0) my_info[16 + 4 * g + i] = mm + __builtin_amdgcn_logf(ss) * kLn2;
-          float top = gmax[i][0];
+          float top = -INFINITY;
+          bool clamped = false;
 #pragma unroll
-          for (int j = 1; j < kReqTiles; ++j) top = fmaxf(top, gmax[i][j]);
-          // this lane's sum may have overflowed: push the beam's (the request's) count past
-          // the list size
-          if (top > m_ref + 64.f) {
+          for (int j = 0; j < kReqTiles; ++j) {
+            const float m = half_bits_to_float(gmaxp[i >> 1][j] >> (16 * (i & 1)));
+            top = fmaxf(top, m);
+            clamped |= half_out_of_range(m);
+          }
+          // this lane's sum may have overflowed, or a maximum left the half range: push the
+          // beam's (the request's) count past the list size
+          if (half_ceil(top) > m_ref + 64.f || clamped) {
             if constexpr (WHOLE) atomicAdd(req_cnt, kReqListCap + 1);
             else atomicAdd(&my_cnt[4 * g + i], kReqCap + 1);
           }
@@ -2155,8 +2211,11 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
         for (int i = 0; i < 4; ++i)
 #pragma unroll
           for (int h = 0; h < 2; ++h)
-            *reinterpret_cast<float4*>(gm + (4 * g + i) * 128 + c * 8 + h * 4) =
-                float4{gmax[i][4 * h], gmax[i][4 * h + 1], gmax[i][4 * h + 2], gmax[i][4 * h + 3]};
+            *reinterpret_cast<float4*>(gm + (4 * g + i) * 128 + c * 8 + h * 4) = float4{
+                half_floor(half_bits_to_float(gmaxp[i >> 1][4 * h] >> (16 * (i & 1)))),
+                half_floor(half_bits_to_float(gmaxp[i >> 1][4 * h + 1] >> (16 * (i & 1)))),
+                half_floor(half_bits_to_float(gmaxp[i >> 1][4 * h + 2] >> (16 * (i & 1)))),
+                half_floor(half_bits_to_float(gmaxp[i >> 1][4 * h + 3] >> (16 * (i & 1))))};
         wave_sync();
 #pragma unroll 1
         for (int q = 0; q < 4; ++q) {
