@@ -2171,6 +2171,7 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
       __builtin_amdgcn_s_waitcnt(0x0F70);     // list stores are done before anyone reads them
       __syncthreads();                        // every wave is done with the chunk buffers
       if constexpr (sweep == 0) {
+        uint32_t lane_key[4] = {0, 0, 0, 0};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {         // (reference, sum) over the beam's 16 lanes
           const float m_ref = -nml[i] * kLn2;                // the reference the sum was taken about
@@ -2189,7 +2190,8 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
                      __uint_as_float(lane_xor<4>(__float_as_uint(ss), lane)));
           merge_with(__uint_as_float(lane_xor<8>(__float_as_uint(mm), lane)),
                      __uint_as_float(lane_xor<8>(__float_as_uint(ss), lane)));
-          if (c == 0) my_info[16 + 4 * g + i] = mm + __builtin_amdgcn_logf(ss) * kLn2;
+          const float lse_i = mm + __builtin_amdgcn_logf(ss) * kLn2;   // the same in the beam's 16 lanes
+          if (c == 0) my_info[16 + 4 * g + i] = lse_i;
           float top = -INFINITY;
           bool clamped = false;
 #pragma unroll
@@ -2204,41 +2206,47 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
             if constexpr (WHOLE) atomicAdd(req_cnt, kReqListCap + 1);
             else atomicAdd(&my_cnt[4 * g + i], kReqCap + 1);
           }
-        }
-        // the beams' 128 group maxima each, through this wave's part of the chunk buffers
-        float* gm = reinterpret_cast<float*>(req_lds) + wave * (16 * 128);
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int h = 0; h < 2; ++h)
-            *reinterpret_cast<float4*>(gm + (4 * g + i) * 128 + c * 8 + h * 4) = float4{
-                half_floor(half_bits_to_float(gmaxp[i >> 1][4 * h] >> (16 * (i & 1)))),
-                half_floor(half_bits_to_float(gmaxp[i >> 1][4 * h + 1] >> (16 * (i & 1)))),
-                half_floor(half_bits_to_float(gmaxp[i >> 1][4 * h + 2] >> (16 * (i & 1)))),
-                half_floor(half_bits_to_float(gmaxp[i >> 1][4 * h + 3] >> (16 * (i & 1))))};
-        wave_sync();
-#pragma unroll 1
-        for (int q = 0; q < 4; ++q) {
-          uint32_t mk[4][2];
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) mk[r][j] = ordered_bits(gm[(4 * q + r) * 128 + j * 64 + ln]);
-          sort_desc<2, 4, uint32_t>(mk);                                // position 2*lane + j
           if constexpr (WHOLE) {
-            // the 16 largest group maxima of each of the 4 beams as scores: 64 keys, parked in
-            // the (already read) first row of this quad's maxima
-            wave_sync();
+            // the lane's largest logit of this beam, as a score no larger than the true one
+            // (formed as the final scores are: parent score + (logit - log-sum-exp); the margin
+            // covers the last-place differences between the 16 lanes' copies of the log-sum-exp)
+            const float sp_i = my_info[32 + 4 * g + i];
+            const float low = sp_i + (half_floor(top) - lse_i);
+            lane_key[i] = ordered_bits(low - 4e-6f * (fabsf(lse_i) + fabsf(sp_i) + 1.f));
+          }
+        }
+        if constexpr (WHOLE) {
+          // Threshold of the request: each lane holds, per beam, the largest of its 256 logits: 16
+          // distinct candidates per beam, 256 per wave, whose scores bound the K-th best score of
+          // the request from below by their K-th largest (K <= 128); the best of the waves'
+          // bounds is taken.
+          uint32_t uk[1][4] = {{lane_key[0], lane_key[1], lane_key[2], lane_key[3]}};
+          sort_desc<4, 1, uint32_t>(uk);                                  // position 4*lane + j
+          const uint32_t tw = (uint32_t)__builtin_amdgcn_readlane(
+              (int)pick_element<4>(uk[0], (K - 1) & 3), (K - 1) >> 2);
+          if (lane == 0) tau_s[wave] = tw;
+          __syncthreads();                    // all bounds are in
+        } else {
+          // the beams' 128 group maxima each, through this wave's part of the chunk buffers
+          float* gm = reinterpret_cast<float*>(req_lds) + wave * (16 * 128);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              const float p_sc = my_info[32 + 4 * q + r], p_lse = my_info[16 + 4 * q + r];
+          for (int i = 0; i < 4; ++i)
 #pragma unroll
-              for (int j = 0; j < 2; ++j) {
-                const uint32_t key = ordered_bits(p_sc + (unordered_bits(mk[r][j]) - p_lse));
-                if (ln < 8) reinterpret_cast<uint32_t*>(gm)[(4 * q) * 128 + r * 16 + 2 * ln + j] = key;
-              }
-            }
-          } else {
+            for (int h = 0; h < 2; ++h)
+              *reinterpret_cast<float4*>(gm + (4 * g + i) * 128 + c * 8 + h * 4) = float4{
+                  half_floor(half_bits_to_float(gmaxp[i >> 1][4 * h] >> (16 * (i & 1)))),
+                  half_floor(half_bits_to_float(gmaxp[i >> 1][4 * h + 1] >> (16 * (i & 1)))),
+                  half_floor(half_bits_to_float(gmaxp[i >> 1][4 * h + 2] >> (16 * (i & 1)))),
+                  half_floor(half_bits_to_float(gmaxp[i >> 1][4 * h + 3] >> (16 * (i & 1))))};
+          wave_sync();
+#pragma unroll 1
+          for (int q = 0; q < 4; ++q) {
+            uint32_t mk[4][2];
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+              for (int j = 0; j < 2; ++j) mk[r][j] = ordered_bits(gm[(4 * q + r) * 128 + j * 64 + ln]);
+            sort_desc<2, 4, uint32_t>(mk);                                // position 2*lane + j
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
               const uint32_t pick = pick_element<2>(mk[r], (K - 1) & 1);
@@ -2247,18 +2255,7 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
               if (lane == 0) my_info[4 * q + r] = bnd;
             }
           }
-        }
-        wave_sync();
-        if constexpr (WHOLE) {
-          uint32_t uk[1][4];
-#pragma unroll
-          for (int t = 0; t < 4; ++t) uk[0][t] = reinterpret_cast<const uint32_t*>(gm)[(4 * t) * 128 + ln];
-          sort_desc<4, 1, uint32_t>(uk);                                // position 4*lane + j
-          const uint32_t tw = (uint32_t)__builtin_amdgcn_readlane(
-              (int)pick_element<4>(uk[0], (K - 1) & 3), (K - 1) >> 2);
-          if (lane == 0) tau_s[wave] = tw;
-          __syncthreads();                    // all bounds are in; maxima have been read
-        } else {
+          wave_sync();
           __syncthreads();                    // maxima read before the next chunk lands on them
         }
       }
