@@ -299,6 +299,14 @@ int nezha_profile_event_overhead(int launches, void* hip_stream, double* mean_us
  * for that buffer size.  sink: device uint64 [1], scratch.  Asynchronous on hip_stream. */
 int nezha_bench_random_gather(const void* buf, size_t bytes, int64_t n, int line_bytes,
                               uint64_t seed, void* sink, void* hip_stream);
+/* The same with the number of lines in flight chosen: depth = 1, 2, 4, 8 or 16 (16: 64-byte
+ * lines only) per lane, or, with lanes_per_line = 8 (64-byte lines), per group of eight lanes that
+ * read each line together, eight bytes apiece.  The best of these forms is what "achievable
+ * random-access rate" means in the verifier's roofline: a denominator that does not copy the
+ * verifier's own launch shape. */
+int nezha_bench_random_gather_depth(const void* buf, size_t bytes, int64_t n, int line_bytes,
+                                    int depth, int lanes_per_line, uint64_t seed, void* sink,
+                                    void* hip_stream);
 
 /* Measurement aid for the projections' roofline: `workgroups` workgroups of four waves (one wave
  * per SIMD, as in the large projection kernel) each run `iters` iterations of 32 independent

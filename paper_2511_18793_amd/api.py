@@ -21,7 +21,7 @@ EXPORTS = ["nezha_last_error", "nezha_build_itemset", "nezha_itemset_info", "nez
            "nezha_packed_weights_bytes", "nezha_user_projection_levels", "nezha_draft_levels", "nezha_decode",
            "nezha_profile_event_overhead",
            "nezha_draft_levels_workspace", "nezha_check_itemset", "nezha_verify_tuples_static",
-           "nezha_bench_mfma_rate"]
+           "nezha_bench_mfma_rate", "nezha_bench_random_gather_depth"]
 
 
 class NezhaError(RuntimeError):
@@ -478,14 +478,18 @@ def decode(H, W, E, radices, K, itemset=None, buffers=None, stream=None, U=None,
     return buffers.outs
 
 
-def bench_random_gather(buf, n, line_bytes=64, seed=1, stream=None):
-    """nezha_bench_random_gather over the CUDA tensor `buf` (any dtype, 128-byte aligned)."""
-    sink = torch.zeros(1, dtype=torch.int64, device=buf.device)
+def bench_random_gather(buf, n, line_bytes=64, seed=1, stream=None, depth=4, lanes_per_line=1,
+                        sink=None):
+    """nezha_bench_random_gather_depth over the CUDA tensor `buf` (any dtype, 128-byte aligned)."""
+    if sink is None:
+        sink = torch.zeros(1, dtype=torch.int64, device=buf.device)
     lib = load_library()
-    lib.nezha_bench_random_gather.argtypes = [C.c_void_p, C.c_size_t, C.c_int64, C.c_int,
-                                              C.c_uint64, C.c_void_p, C.c_void_p]
-    _check(lib.nezha_bench_random_gather(_ptr(buf), buf.numel() * buf.element_size(), int(n),
-                                         int(line_bytes), int(seed), _ptr(sink), _stream(stream)))
+    lib.nezha_bench_random_gather_depth.argtypes = [C.c_void_p, C.c_size_t, C.c_int64, C.c_int,
+                                                    C.c_int, C.c_int, C.c_uint64, C.c_void_p,
+                                                    C.c_void_p]
+    _check(lib.nezha_bench_random_gather_depth(_ptr(buf), buf.numel() * buf.element_size(), int(n),
+                                               int(line_bytes), int(depth), int(lanes_per_line),
+                                               int(seed), _ptr(sink), _stream(stream)))
     return sink
 
 

@@ -23,9 +23,10 @@ def _both(gset, qd, outs):
     i2[:n].fill_(-1)
     c2.fill_(-1)
     torch.cuda.synchronize()
-    before = torch.cuda.memory_allocated()
-    nz.verify_tuples_static(gset, qd, m2[:n], i2[:n], c2)
-    assert torch.cuda.memory_allocated() == before
+    mv, iv = m2[:n], i2[:n]
+    before = torch.cuda.memory_stats()["allocation.all.allocated"]      # allocation events so far
+    nz.verify_tuples_static(gset, qd, mv, iv, c2)
+    assert torch.cuda.memory_stats()["allocation.all.allocated"] == before
     torch.cuda.synchronize()
     c = int(cnt.item())
     return ((mask.cpu().numpy(), idx.cpu().numpy()[:c], c),
