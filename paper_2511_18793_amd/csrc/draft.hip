@@ -1667,26 +1667,20 @@ __global__ __launch_bounds__(64 * kMergeMaxWaves) void merge_kernel(MergeArgs a)
 // overflow (more than 256 logits tie with the bound) is redone in a third sweep with the
 // general streaming top-K.  K <= 128.
 constexpr int kChunk = 256;
+// The 16 beams R0 .. R0+15 (one workgroup; redo_flag is a word of static LDS).
 template <int KST>
-__global__ __launch_bounds__(512, 4) void expand_chunked_kernel(ExpandArgs a) {
+__device__ __forceinline__ void expand_chunked_group(const ExpandArgs& a, const int R0,
+                                                     uint64_t* lds, int& redo_flag) {
   constexpr int CAP = 256;
-  extern __shared__ __align__(16) uint64_t lds[];
   uint64_t* lists = lds;                                              // [16 rows][CAP]
   float* ztile = reinterpret_cast<float*>(lds + 16 * CAP);            // [2][16][kChunk]
-  __shared__ int redo_flag;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = lane >> 4, c = lane & 15;
-  const int R0 = blockIdx.x * 16;
   const int V = a.V, K = a.K, e = a.e;
   const bool has_beam = a.state != nullptr;
   const int KS = e / 32;
   const int n_ct = V / 16;
   const int n_chunks = (V + kChunk - 1) / kChunk;
-  if (a.redo) {                      // a pass over the rows another kernel left: most groups leave
-    bool any = false;
-    for (int i = 0; i < 16; ++i) any = any || (R0 + i < a.rows && a.redo[R0 + i] != 0);
-    if (!any) return;
-  }
 
   bf16x8 fa16[KST];
   if (has_beam) {
@@ -1887,6 +1881,52 @@ __global__ __launch_bounds__(512, 4) void expand_chunked_kernel(ExpandArgs a) {
     }
   }
 }
+// Without a.redo: workgroup i takes beams 16 i .. 16 i + 15.  With a.redo (a pass over the beams
+// another kernel left, usually a handful among tens of thousands): every workgroup of a small grid
+// looks through its share of the groups of 16 beams, one group per thread and one 16-byte load
+// per group, and then takes the flagged ones of its share in turn.  (A workgroup per
+// group that leaves at once costs more in dispatch than the pass does in work.)  The flags are
+// padded to a multiple of 256 bytes and 16-byte aligned.
+constexpr int kRedoScanGroups = 256;   // workgroups of a redo pass
+template <int KST>
+__global__ __launch_bounds__(512, 4) void expand_chunked_kernel(ExpandArgs a) {
+  extern __shared__ __align__(16) uint64_t lds[];
+  __shared__ int redo_flag;
+  if (!a.redo) {
+    expand_chunked_group<KST>(a, blockIdx.x * 16, lds, redo_flag);
+    return;
+  }
+  __shared__ int n_found;
+  __shared__ int found[512];
+  const int n_groups = (a.rows + 15) / 16;
+  // thread t of workgroup w looks at groups w + (t + 512 k) * (number of workgroups): the groups of
+  // one flagged request (neighbours) go to different workgroups
+  const int G = (int)gridDim.x;
+  for (int base = 0; base * G + (int)blockIdx.x < n_groups; base += 512) {
+    if (threadIdx.x == 0) n_found = 0;
+    __syncthreads();
+    const int gi = (base + (int)threadIdx.x) * G + (int)blockIdx.x;
+    if (gi < n_groups) {
+      const uint4 f = load_global_u4(a.redo + (int64_t)gi * 16);
+      const int live = a.rows - gi * 16;                   // rows of the group inside the batch
+      const uint32_t word[4] = {f.x, f.y, f.z, f.w};
+      bool any = false;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int n = live - 4 * i;                         // bytes of this word that are flags
+        const uint32_t mask = n >= 4 ? 0xFFFFFFFFu : (n <= 0 ? 0u : (1u << (8 * n)) - 1u);
+        any = any || (word[i] & mask) != 0;
+      }
+      if (any) found[atomicAdd(&n_found, 1)] = gi;
+    }
+    __syncthreads();
+    const int n = n_found;
+    for (int k = 0; k < n; ++k) {
+      expand_chunked_group<KST>(a, found[k] * 16, lds, redo_flag);
+      __syncthreads();                                      // the lists and tiles are reused
+    }
+  }
+}
 
 // ---- the same step with one workgroup per request (bf16, K_in >= 16) ---------------------------
 // The beams of a request share its user-part row and all beams share W_l: wave w owns the
@@ -1901,6 +1941,8 @@ __global__ __launch_bounds__(512, 4) void expand_chunked_kernel(ExpandArgs a) {
 //   sweep 2: logits at or above the bound are appended to the beam's list of 256 (logit, code)
 //            pairs in global scratch, the place taken from a counter in LDS.  The scratch belongs
 //            to the workgroup and is reused for each of its requests, so it lives in L2 / MALL.
+//            (A list per (beam, lane) pair with its counter in a register needs no atomic, but
+//            its stores fall on 64 different lines per instruction: measured, 23 % slower.)
 //   Then, per beam, a sort of the listed logits alone (32-bit keys) gives the K-th largest; the
 //   entries above it and the lowest codes among those equal to it are written out, in list order.
 //   (The merge step orders equal scores by parent and code, so the order inside a beam's
@@ -2029,7 +2071,10 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
         }
         if (c == 0) my_info[32 + 4 * g + i] = v;   // read back after the first sweep
       }
-      if (threadIdx.x == 0) *req_cnt = 0;
+      if (threadIdx.x == 0) {
+        *req_cnt = 0;
+        tau_s[0] = 0;
+      }
     } else {
       if (lane < 16) my_cnt[lane] = 0;
     }
@@ -2052,9 +2097,7 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
       }
       if constexpr (sweep == 1) {
         if constexpr (WHOLE) {
-          tau = tau_s[0];
-          for (int w2 = 1; w2 < NW; ++w2) tau = tau_s[w2] > tau ? tau_s[w2] : tau;
-          tau = (uint32_t)__builtin_amdgcn_readfirstlane((int)tau);
+          tau = (uint32_t)__builtin_amdgcn_readfirstlane((int)tau_s[0]);
           // a logit bound per beam that no candidate with score >= tau can fall below: the
           // threshold moved back through the (rounded) score formula, minus a margin far above
           // the rounding of two float32 additions
@@ -2084,86 +2127,78 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
         const int tiles = n_ct - ch * kReqTiles;            // >= kReqTiles except in the last chunk
         auto chunk_body = [&](auto ragged_c) {
           constexpr bool ragged = decltype(ragged_c)::value;
-          // One operand set, two accumulators: the operands of tile ct+1 are requested right
-          // after the MFMAs of tile ct have been issued (into the same registers: the matrix pipe
-          // has taken its operands long before LDS answers) and arrive under the vector work of
-          // tile ct-1, which in turn covers the latency of tile ct's MFMAs.  The scheduling fences
-          // keep one tile's work per step (hoisting a whole chunk's LDS reads at once costs more
-          // registers than there are).
+          // One operand set, two accumulators.  The matrix instructions of a tile form a dependent
+          // chain (each adds to the result of the one before), so a wave that issued them back to
+          // back would sit out each one's latency; instead the vector work on the previous tile's
+          // logits is cut into four pieces (one per beam of the lane) that are issued between the
+          // chain's links, and each operand register is requested again (for the next tile) right
+          // after the instruction that consumed it.  The scheduling fences pin that order.
+          // (Worth 2 % here: with four waves on a SIMD the other waves already fill most of such
+          // gaps, and matrix and vector instructions of one SIMD overlap only in part: a loop of
+          // both takes the vector time plus about half the matrix time, however they are ordered.)
           uint4 w[KST];
           float a0;
           floatx4 acc[2];
-          auto reads = [&](int ct) {
-#pragma unroll
-            for (int ks = 0; ks < KST; ++ks)
-              w[ks] = *reinterpret_cast<const uint4*>(wb + ((ct * KS + ks) * 64 + ln) * 16);
-            a0 = ab[ct * 16 + c];
+          auto read_operand = [&](int ct, int ks) {
+            w[ks] = *reinterpret_cast<const uint4*>(wb + ((ct * KS + ks) * 64 + ln) * 16);
+            if (ks == 0) a0 = ab[ct * 16 + c];
           };
-          auto mfmas = [&](int buf) {
-            floatx4 t = floatx4{a0, a0, a0, a0};
-#pragma unroll
-            for (int ks = 0; ks < KST; ++ks)
-              t = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                  fa16[ks], *reinterpret_cast<const bf16x8*>(&w[ks]), t, 0, 0, 0);
-            acc[buf] = t;
-          };
-          auto vector_work = [&](int ct, int buf) {
+          // piece i of the vector work on tile ct (the lane's logit of beam 4g+i)
+          auto piece = [&](int ct, int buf, int i) {
             const bool live = !ragged || ct < tiles;
-            float z[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) z[i] = live ? acc[buf][i] : -INFINITY;
+            auto zv = [&](int j) { return live ? acc[buf][j] : -INFINITY; };
+            const float z = zv(i);
             if constexpr (sweep == 0) {
               // Sum of exp(z - m) about a fixed reference m = (the lane's first logit of the
               // beam) + 20, held as nml = -m * log2(e): no rescaling while streaming.  A beam with
               // a logit more than 64 above a lane's reference is redone by the general kernel.
-              if (ct == 0 && ch == 0) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) nml[i] = -(z[i] + 20.f) * kLog2e;
-              }
-              gmaxp[0][ct] = max_of_half_pairs(gmaxp[0][ct], pack_halves_rtz(z[0], z[1]));
-              gmaxp[1][ct] = max_of_half_pairs(gmaxp[1][ct], pack_halves_rtz(z[2], z[3]));
-#pragma unroll
-              for (int i = 0; i < 4; ++i)
-                ssum[i] += __builtin_amdgcn_exp2f(fmaf(z[i], kLog2e, nml[i]));
+              if (ct == 0 && ch == 0) nml[i] = -(z + 20.f) * kLog2e;
+              if ((i & 1) == 0)
+                gmaxp[i >> 1][ct] =
+                    max_of_half_pairs(gmaxp[i >> 1][ct], pack_halves_rtz(z, zv(i + 1)));
+              ssum[i] += __builtin_amdgcn_exp2f(fmaf(z, kLog2e, nml[i]));
             } else if constexpr (WHOLE) {
-              const uint32_t code = (uint32_t)((ch * kReqTiles + ct) * 16 + c);
-#pragma unroll
-              for (int i = 0; i < 4; ++i) {
-                if (live && z[i] >= bound[i]) {             // bound: a logit that cannot be missed
-                  const uint32_t key = ordered_bits(sp[i] + (z[i] - lse_r[i]));   // the final score
-                  if (key >= tau) {
-                    const int pos = atomicAdd(req_cnt, 1);
-                    const uint32_t who = ((uint32_t)(wave * 16 + 4 * g + i) << 24) | code;
-                    if (pos < kReqListCap) req_list[pos] = ((uint64_t)key << 32) | (uint32_t)~who;
-                  }
+              if (live && z >= bound[i]) {                  // bound: a logit that cannot be missed
+                const uint32_t key = ordered_bits(sp[i] + (z - lse_r[i]));        // the final score
+                if (key >= tau) {
+                  const uint32_t code = (uint32_t)((ch * kReqTiles + ct) * 16 + c);
+                  const int pos = atomicAdd(req_cnt, 1);
+                  const uint32_t who = ((uint32_t)(wave * 16 + 4 * g + i) << 24) | code;
+                  if (pos < kReqListCap) req_list[pos] = ((uint64_t)key << 32) | (uint32_t)~who;
                 }
               }
             } else {
-              const uint32_t code = (uint32_t)((ch * kReqTiles + ct) * 16 + c);
-              int pos[4];
-#pragma unroll
-              for (int i = 0; i < 4; ++i) {
-                pos[i] = kReqCap;
-                if (live && z[i] >= bound[i]) pos[i] = atomicAdd(&my_cnt[4 * g + i], 1);
+              if (live && z >= bound[i]) {
+                const uint32_t code = (uint32_t)((ch * kReqTiles + ct) * 16 + c);
+                const int pos = atomicAdd(&my_cnt[4 * g + i], 1);
+                if (pos < kReqCap)
+                  my_lists[(4 * g + i) * kReqCap + pos] = ((uint64_t)__float_as_uint(z) << 32) | code;
               }
-#pragma unroll
-              for (int i = 0; i < 4; ++i)
-                if (pos[i] < kReqCap)
-                  my_lists[(4 * g + i) * kReqCap + pos[i]] =
-                      ((uint64_t)__float_as_uint(z[i]) << 32) | code;
             }
           };
-          reads(0);
 #pragma unroll
-          for (int ct = 0; ct < kReqTiles; ++ct) {
-            mfmas(ct & 1);
-            __builtin_amdgcn_sched_barrier(0);
-            if (ct + 1 < kReqTiles) reads(ct + 1);
-            __builtin_amdgcn_sched_barrier(0);
-            if (ct > 0) vector_work(ct - 1, (ct - 1) & 1);
-            __builtin_amdgcn_sched_barrier(0);
+          for (int ks = 0; ks < KST; ++ks) read_operand(0, ks);
+#pragma unroll
+          for (int ct = 0; ct <= kReqTiles; ++ct) {
+            floatx4 t = floatx4{a0, a0, a0, a0};
+#pragma unroll
+            for (int ks = 0; ks < KST; ++ks) {
+              if (ct < kReqTiles) {
+                t = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                    fa16[ks], *reinterpret_cast<const bf16x8*>(&w[ks]), t, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (ct + 1 < kReqTiles) read_operand(ct + 1, ks);
+                __builtin_amdgcn_sched_barrier(0);
+              }
+              if (ct > 0) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                  if ((i * KST) / 4 == ks) piece(ct - 1, (ct - 1) & 1, i);
+                __builtin_amdgcn_sched_barrier(0);
+              }
+            }
+            if (ct < kReqTiles) acc[ct & 1] = t;
           }
-          vector_work(kReqTiles - 1, (kReqTiles - 1) & 1);
         };
         if (tiles >= kReqTiles) chunk_body(std::false_type{});
         else chunk_body(std::true_type{});
@@ -2217,15 +2252,43 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
         }
         if constexpr (WHOLE) {
           // Threshold of the request: each lane holds, per beam, the largest of its 256 logits: 16
-          // distinct candidates per beam, 256 per wave, whose scores bound the K-th best score of
-          // the request from below by their K-th largest (K <= 128); the best of the waves'
-          // bounds is taken.
+          // distinct candidates per beam, 256 per wave, 256 NW in the workgroup, whose scores
+          // bound the K-th best score of the request from below by their K-th largest.  Every
+          // wave sorts its 256 and leaves its 128 best (K <= 128) in the chunk buffers; then each
+          // lane ranks two of its wave's entries among all waves' lists (a binary search per
+          // list): the largest entry with at least K entries at or above it is that K-th largest.
           uint32_t uk[1][4] = {{lane_key[0], lane_key[1], lane_key[2], lane_key[3]}};
           sort_desc<4, 1, uint32_t>(uk);                                  // position 4*lane + j
-          const uint32_t tw = (uint32_t)__builtin_amdgcn_readlane(
-              (int)pick_element<4>(uk[0], (K - 1) & 3), (K - 1) >> 2);
-          if (lane == 0) tau_s[wave] = tw;
-          __syncthreads();                    // all bounds are in
+          uint32_t* const best = reinterpret_cast<uint32_t*>(req_lds);    // [NW][128], descending
+          if (lane < 32)
+            *reinterpret_cast<uint4*>(best + wave * 128 + 4 * lane) =
+                uint4{uk[0][0], uk[0][1], uk[0][2], uk[0][3]};
+          __syncthreads();                    // all lists are in
+          uint32_t mine[2], at_least[2] = {0u, 0u};
+#pragma unroll
+          for (int t = 0; t < 2; ++t) mine[t] = best[wave * 128 + lane + 64 * t];
+          for (int v = 0; v < NW; ++v) {
+            const uint32_t* list = best + v * 128;
+            uint32_t lo[2] = {0u, 0u}, hi[2] = {128u, 128u};   // entries [0, lo) are >= mine, [hi, 128) are not
+#pragma unroll
+            for (int step = 0; step < 8; ++step)           // 129 possible answers
+#pragma unroll
+              for (int t = 0; t < 2; ++t) {
+                const bool open = lo[t] < hi[t];
+                const uint32_t mid = (lo[t] + hi[t]) >> 1;   // < 128 while the interval is open
+                const bool ge = open && list[open ? mid : 0u] >= mine[t];
+                lo[t] = ge ? mid + 1 : lo[t];
+                hi[t] = (open && !ge) ? mid : hi[t];
+              }
+#pragma unroll
+            for (int t = 0; t < 2; ++t) at_least[t] += lo[t];
+          }
+          uint32_t cand = 0;
+#pragma unroll
+          for (int t = 0; t < 2; ++t)
+            if (at_least[t] >= (uint32_t)K && mine[t] > cand) cand = mine[t];
+          if (cand != 0) atomicMax(&tau_s[0], cand);
+          __syncthreads();                    // the threshold is in; the lists may be overwritten
         } else {
           // the beams' 128 group maxima each, through this wave's part of the chunk buffers
           float* gm = reinterpret_cast<float*>(req_lds) + wave * (16 * 128);
@@ -2323,7 +2386,7 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
       constexpr int NPL = decltype(npl_c)::value;
       int ln = lane;
       asm volatile("" : "+v"(ln));
-      uint32_t zk[2][NPL], code[2][NPL], sk[2][NPL];
+      uint32_t zk[2][NPL], code[2][NPL];
 #pragma unroll
       for (int r = 0; r < 2; ++r)
 #pragma unroll
@@ -2333,14 +2396,55 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
           if (idx < n[r]) ent = my_lists[(2 * q + r) * kReqCap + idx];
           zk[r][j] = idx < n[r] ? ordered_bits(__uint_as_float((uint32_t)(ent >> 32))) : 0u;
           code[r][j] = (uint32_t)ent;
-          sk[r][j] = zk[r][j];
         }
-      sort_desc<NPL, 2, uint32_t>(sk);                                  // position NPL*lane + j
+      // A threshold T per beam with exactly K listed keys >= T, or, where keys tie there, the
+      // K-th largest key itself: bit by bit from the top, T takes a bit while at least K keys stay
+      // at or above it (a compare per register and scalar counting per step; the whole kernel is
+      // bound by the number of instructions issued, and a sort of the keys takes three times as
+      // many).  The bits that the listed keys share (they lie between the beam's bound and its
+      // largest logit: sign, exponent and a little more) are set at the start, and the walk ends
+      // as soon as both beams hold exactly K keys, some ten steps later as a rule.
+      uint32_t kth[2] = {0u, 0u};
+      int held[2], top_bit = -1;
+#pragma unroll
+      for (int r = 0; r < 2; ++r) {
+        held[r] = n[r] ? n[r] : K;                          // keys >= kth[r] (no beam: nothing to find)
+        if (n[r] == 0) continue;
+        uint32_t hi = zk[r][0];
+#pragma unroll
+        for (int j = 1; j < NPL; ++j) hi = hi > zk[r][j] ? hi : zk[r][j];
+        auto wider = [&](uint32_t o) { hi = hi > o ? hi : o; };
+        wider(lane_xor<1>(hi, ln));
+        wider(lane_xor<2>(hi, ln));
+        wider(lane_xor<4>(hi, ln));
+        wider(lane_xor<8>(hi, ln));
+        wider(lane_xor<16>(hi, ln));
+        wider(lane_xor<32>(hi, ln));
+        hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)hi);
+        const uint32_t lo = ordered_bits(my_info[2 * q + r]);   // every listed logit is >= the bound
+        const uint32_t differ = lo ^ hi;
+        const int top = differ ? 31 - __builtin_clz(differ) : -1;
+        kth[r] = top < 0 ? hi : (hi & ~((2u << top) - 1u));
+        top_bit = top > top_bit ? top : top_bit;
+      }
+#pragma unroll 1
+      for (int bit = top_bit; bit >= 0 && (held[0] != K || held[1] != K); --bit) {
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+          const uint32_t cand = kth[r] | (1u << bit);
+          int at_least = 0;
+#pragma unroll
+          for (int j = 0; j < NPL; ++j) at_least += __popcll(__ballot(zk[r][j] >= cand));
+          if (at_least >= K) {
+            kth[r] = cand;
+            held[r] = at_least;
+          }
+        }
+      }
 #pragma unroll
       for (int r = 0; r < 2; ++r) {
         if (n[r] == 0) continue;
-        const uint32_t tau = (uint32_t)__builtin_amdgcn_readlane(
-            (int)pick_element<NPL>(sk[r], (K - 1) % NPL), (K - 1) / NPL);
+        const uint32_t tau = kth[r];
         int n_gt = 0, n_eq = 0;
 #pragma unroll
         for (int j = 0; j < NPL; ++j) {
@@ -3460,7 +3564,7 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
       if (bf16) {
         // large codebook (or K > 64): two sweeps in chunks of 256 codes, 8 waves per 16 beams
         const size_t lds2 = (size_t)16 * 256 * 8 + (size_t)2 * 16 * kChunk * 4;
-        dim3 grid2(groups), block2(512);
+        dim3 grid2(ea.redo && groups > kRedoScanGroups ? kRedoScanGroups : groups), block2(512);
 #define LAUNCH_CHUNKED(KSTV)                                                              \
   do {                                                                                    \
     rc = allow_lds(expand_chunked_kernel<KSTV>, lds2);                                    \
