@@ -404,6 +404,28 @@ def bench_draft(args, cfg):
         flops = sum(2.0 * cfg.B * (1 if l == 0 else cfg.K) * cfg.e * cfg.V * (0 if l == 0 else 1)
                     for l in range(cfg.L)) * prof_steps
         roofline["mfma_tflops"] = flops / (kd["total_ms"] * 1e-3) / 1e12
+    if dom == "expand_request_kernel" and cfg.e == 128:
+        # The kernel's two sweeps issue one "tile step" (16 beams x 16 codes: four MFMAs and the
+        # vector work on four logits per lane) per wave, tile and sweep.  Matrix and vector
+        # instructions of a SIMD overlap only in part, so the peak of neither unit bounds that
+        # loop; the library's microbenchmark times the same instruction mix without any memory
+        # access at the kernel's occupancy (four waves per SIMD), and the kernel's own rate of
+        # tile steps per SIMD is set against it.
+        props = torch.cuda.get_device_properties(0)
+        simds = 4 * props.multi_processor_count
+        waves = (cfg.K + 15) // 16
+        steps_per_launch = 2.0 * (cfg.V // 16) * waves * cfg.B      # levels 2 .. L: one launch each
+        kernel_rate = steps_per_launch / simds / (kd["avg_us"] * 1e-6)
+        both, clk = nz.bench_tile_step(2)
+        mat, _ = nz.bench_tile_step(0)
+        vec, _ = nz.bench_tile_step(1)
+        roofline["tile_steps"] = {
+            "unit": "tile steps/s per SIMD", "kernel": kernel_rate,
+            "instruction_mix_bound": both, "frac_of_bound": kernel_rate / both,
+            "matrix_only": mat, "vector_only": vec, "clock_mhz": clk,
+            "note": "bound: nezha_bench_tile_step mode 2 (sweep 1's instructions, no memory "
+                    "access, 4 waves per SIMD); the kernel's figure includes both sweeps' LDS "
+                    "traffic, list appends, per-beam selection and output"}
     breakdown = {k: {"avg_us": round(v["avg_us"], 3), "launches": v["launches"]}
                  for k, v in kernels.items()}
 

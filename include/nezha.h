@@ -319,6 +319,19 @@ int nezha_bench_random_gather_depth(const void* buf, size_t bytes, int64_t n, in
 int nezha_bench_mfma_rate(const void* operands, size_t bytes, int iters, int workgroups,
                           uint64_t* ticks, float* sink, void* hip_stream);
 
+/* Measurement aid for the per-request expansion's roofline (Alg. 3's expansion at K_in >= 16):
+ * `workgroups` workgroups of four waves each run `iters` tile steps of that kernel's first sweep
+ * without its LDS traffic: mode 0 the four dependent 16x16x32 bf16 matrix instructions of one
+ * 16 x 16 logit tile at e = 128 alone, mode 1 the vector work on one tile alone (per lane four
+ * fused multiply-adds, exponentials and additions, two conversions to packed halves, two packed
+ * maxima), mode 2 both, interleaved as the kernel issues them.  With workgroups = (compute units)
+ * * w every SIMD holds w waves.  values: device float [256] that the operands are formed from.
+ * ticks (device uint64 [2 * workgroups]): core-clock cycles and ticks of the constant 100 MHz
+ * counter per workgroup.  Tile steps = workgroups * 4 * iters.  sink: device float [1], scratch.
+ * Asynchronous on hip_stream. */
+int nezha_bench_tile_step(int mode, int iters, int workgroups, const float* values,
+                          uint64_t* ticks, float* sink, void* hip_stream);
+
 /* Inverse of Eq. 4 on the host: keys[n] -> codes int32 [n, L] (level 1 first).  Host pointers. */
 int nezha_unpack_keys(const uint64_t* keys, int64_t n, int32_t L, const int32_t* radices,
                       int32_t* codes);

@@ -21,7 +21,7 @@ EXPORTS = ["nezha_last_error", "nezha_build_itemset", "nezha_itemset_info", "nez
            "nezha_packed_weights_bytes", "nezha_user_projection_levels", "nezha_draft_levels", "nezha_decode",
            "nezha_profile_event_overhead",
            "nezha_draft_levels_workspace", "nezha_check_itemset", "nezha_verify_tuples_static",
-           "nezha_bench_mfma_rate", "nezha_bench_random_gather_depth"]
+           "nezha_bench_mfma_rate", "nezha_bench_random_gather_depth", "nezha_bench_tile_step"]
 
 
 class NezhaError(RuntimeError):
@@ -510,6 +510,34 @@ def bench_mfma_rate(operands, iters=2000, workgroups=256, stream=None):
     seconds = t[:, 1] / 100e6
     flops_per_wg = 4.0 * iters * 32 * 32768
     return float((flops_per_wg / seconds).sum() / 1e12), float((t[:, 0] / t[:, 1]).mean() * 100.0)
+
+
+def bench_tile_step(mode, waves_per_simd=4, iters=20000, stream=None):
+    """nezha_bench_tile_step with `waves_per_simd` waves on every SIMD of the device.  Returns
+    (tile steps per second and SIMD, core clock in MHz during the loop)."""
+    dev = torch.device("cuda", torch.cuda.current_device())
+    n_cu = torch.cuda.get_device_properties(dev).multi_processor_count
+    workgroups = n_cu * int(waves_per_simd)
+    g = torch.Generator().manual_seed(1)
+    values = (torch.rand(256, generator=g) - 0.5).to(dev)
+    ticks = torch.zeros(2 * workgroups, dtype=torch.int64, device=dev)
+    sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    lib = load_library()
+    lib.nezha_bench_tile_step.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                          C.c_void_p, C.c_void_p]
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    s = stream if stream is not None else torch.cuda.current_stream()
+    for timed in (False, True):
+        if timed:
+            start.record(s)
+        _check(lib.nezha_bench_tile_step(int(mode), int(iters), workgroups, _ptr(values),
+                                         _ptr(ticks), _ptr(sink), _stream(stream)))
+    stop.record(s)
+    torch.cuda.synchronize()
+    seconds = start.elapsed_time(stop) * 1e-3
+    t = ticks.cpu().numpy().reshape(workgroups, 2).astype(np.float64)
+    steps_per_simd = float(waves_per_simd) * iters      # a SIMD holds that many waves, each does iters
+    return steps_per_simd / seconds, float((t[:, 0] / t[:, 1]).mean() * 100.0)
 
 
 def profile_enable(on):

@@ -806,6 +806,64 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(const uint4* __restri
   }
 }
 
+// Measurement aid for the per-request expansion's roofline: one "tile step" of its first sweep as
+// a wave issues it, without the LDS traffic: four dependent 16x16x32 bf16 MFMAs (one logit tile at
+// e = 128) and the vector work on the tile before (per lane four logits: fused multiply-add,
+// exponential, addition; two conversions to packed halves, two packed maxima; three moves for the
+// accumulator's start value), the pieces issued between the MFMAs as the kernel does.  MODE 0:
+// the MFMAs alone, 1: the vector work alone, 2: both.  Matrix and vector instructions of a SIMD
+// overlap only in part on this chip, so neither unit's peak bounds such a loop; the rate of mode 2
+// at the kernel's occupancy is the bound that the kernel's tile rate is compared with.
+template <int MODE>
+__global__ __launch_bounds__(256) void tile_step_kernel(const float* __restrict__ values, int iters,
+                                                        unsigned long long* __restrict__ ticks,
+                                                        float* __restrict__ sink) {
+  const int lane = threadIdx.x & 63;
+  bf16x8 fa[4], fb[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      fa[ks][j] = (__bf16)values[(lane * 7 + ks * 8 + j) & 255];
+      fb[ks][j] = (__bf16)values[(lane * 3 + ks * 8 + j + 64) & 255];
+    }
+  }
+  float a0 = values[lane], nml[4], ssum[4] = {0.f, 0.f, 0.f, 0.f};
+  uint32_t gmax[2] = {0xFC00FC00u, 0xFC00FC00u};
+  floatx4 prev = floatx4{values[lane + 1], values[lane + 2], values[lane + 3], values[lane + 4]};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) nml[i] = -(prev[i] + 20.f) * kLog2e;
+  __syncthreads();
+  const unsigned long long c0 = __builtin_amdgcn_s_memtime(), r0 = __builtin_amdgcn_s_memrealtime();
+  for (int it = 0; it < iters; ++it) {
+    floatx4 t = floatx4{a0, a0, a0, a0};
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      if constexpr (MODE != 1) {
+        t = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[ks], fb[ks], t, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if constexpr (MODE != 0) {
+        const float z = prev[ks];
+        if ((ks & 1) == 0)
+          gmax[ks >> 1] = max_of_half_pairs(gmax[ks >> 1], pack_halves_rtz(z, prev[ks + 1]));
+        ssum[ks] += __builtin_amdgcn_exp2f(fmaf(z, kLog2e, nml[ks]));
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    if constexpr (MODE != 1) prev = t;
+    else asm volatile("" : "+v"(prev));       // the vector work stays in the loop
+  }
+  const unsigned long long c1 = __builtin_amdgcn_s_memtime(), r1 = __builtin_amdgcn_s_memrealtime();
+  const float r = prev[0] + prev[1] + prev[2] + prev[3] + ssum[0] + ssum[1] + ssum[2] + ssum[3] +
+                  __uint_as_float(gmax[0] ^ gmax[1]);
+  if (r == 12345.678f) *sink = r;
+  if (threadIdx.x == 0) {
+    ticks[2 * blockIdx.x] = c1 - c0;
+    ticks[2 * blockIdx.x + 1] = r1 - r0;
+  }
+}
+
 // ---- user-part projection, fp32 (small correctness-first shapes) -----------------------------
 __global__ __launch_bounds__(256) void user_gemm_f32_kernel(const float* __restrict__ H,
                                                             int64_t h_stride,
@@ -3135,6 +3193,23 @@ int nezha_bench_mfma_rate(const void* operands, size_t bytes, int iters, int wor
   hipLaunchKernelGGL(mfma_rate_kernel, dim3(workgroups), dim3(256), 0, stream,
                      static_cast<const uint4*>(operands), (int)(bytes / 16), iters,
                      reinterpret_cast<unsigned long long*>(ticks), sink);
+  NEZHA_HIP_CHECK(hipGetLastError());
+  return NEZHA_OK;
+}
+
+int nezha_bench_tile_step(int mode, int iters, int workgroups, const float* values,
+                          uint64_t* ticks, float* sink, void* hip_stream) {
+  if (!values || !ticks || !sink || mode < 0 || mode > 2 || iters < 1 || iters > (1 << 24) ||
+      workgroups < 1 || workgroups > 65536)
+    return fail(NEZHA_EINVAL, "bad argument");
+  hipStream_t stream = (hipStream_t)hip_stream;
+  unsigned long long* tk = reinterpret_cast<unsigned long long*>(ticks);
+  if (mode == 0)
+    hipLaunchKernelGGL(tile_step_kernel<0>, dim3(workgroups), dim3(256), 0, stream, values, iters, tk, sink);
+  else if (mode == 1)
+    hipLaunchKernelGGL(tile_step_kernel<1>, dim3(workgroups), dim3(256), 0, stream, values, iters, tk, sink);
+  else
+    hipLaunchKernelGGL(tile_step_kernel<2>, dim3(workgroups), dim3(256), 0, stream, values, iters, tk, sink);
   NEZHA_HIP_CHECK(hipGetLastError());
   return NEZHA_OK;
 }

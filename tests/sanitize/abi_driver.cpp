@@ -195,6 +195,9 @@ int main() {
   REQUIRE(nezha_bench_mfma_rate(nullptr, 4096, 10, 4, (uint64_t*)fake(0x1000), (float*)fake(0x2000), nullptr) == NEZHA_EINVAL);
   REQUIRE(nezha_bench_mfma_rate(fake(0x1008), 4096, 10, 4, (uint64_t*)fake(0x1000), (float*)fake(0x2000), nullptr) == NEZHA_EINVAL);
   REQUIRE(nezha_bench_mfma_rate(fake(0x1000), 4096, 0, 4, (uint64_t*)fake(0x1000), (float*)fake(0x2000), nullptr) == NEZHA_EINVAL);
+  REQUIRE(nezha_bench_tile_step(3, 10, 4, (const float*)fake(0x1000), (uint64_t*)fake(0x1000), (float*)fake(0x2000), nullptr) == NEZHA_EINVAL);
+  REQUIRE(nezha_bench_tile_step(2, 0, 4, (const float*)fake(0x1000), (uint64_t*)fake(0x1000), (float*)fake(0x2000), nullptr) == NEZHA_EINVAL);
+  REQUIRE(nezha_bench_tile_step(2, 10, 4, nullptr, (uint64_t*)fake(0x1000), (float*)fake(0x2000), nullptr) == NEZHA_EINVAL);
   {
     const uint64_t keys[2] = {852723ull, 104ull};
     const int32_t r512[3] = {512, 512, 512}, r357[3] = {3, 5, 7};
