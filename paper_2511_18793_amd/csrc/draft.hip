@@ -1171,15 +1171,19 @@ __global__ __launch_bounds__(64 * NW) void expand_kernel(ExpandArgs a) {
 // Element j (wave uniform, 0 <= j < N) of a small register array, without indexing it.
 template <int N>
 __device__ __forceinline__ uint32_t pick_element(const uint32_t (&v)[N], int j) {
-  static_assert(N == 1 || N == 2 || N == 4, "1, 2 or 4 elements");
+  static_assert(N == 1 || N == 2 || N == 4 || N == 8, "1, 2, 4 or 8 elements");
   if constexpr (N == 1) {
     return v[0];
   } else if constexpr (N == 2) {
     return v[0] ^ ((v[0] ^ v[1]) & (0u - (uint32_t)(j & 1)));
-  } else {
+  } else if constexpr (N == 4) {
     const uint32_t m1 = 0u - (uint32_t)(j & 1), m2 = 0u - (uint32_t)((j >> 1) & 1);
     const uint32_t lo = v[0] ^ ((v[0] ^ v[1]) & m1), hi = v[2] ^ ((v[2] ^ v[3]) & m1);
     return lo ^ ((lo ^ hi) & m2);
+  } else {
+    const uint32_t a[4] = {v[0], v[1], v[2], v[3]}, b[4] = {v[4], v[5], v[6], v[7]};
+    const uint32_t lo = pick_element<4>(a, j & 3), hi = pick_element<4>(b, j & 3);
+    return lo ^ ((lo ^ hi) & (0u - (uint32_t)((j >> 2) & 1)));
   }
 }
 // Two rows of float32 logits in LDS (T_l = V values each, V/64 per lane): log-sum-exp and the K
@@ -1996,7 +2000,7 @@ __global__ __launch_bounds__(512, 4) void expand_chunked_kernel(ExpandArgs a) {
 //            maxima of 8 code groups (column tile modulo 8).  A beam's 16 lanes x 8 groups give
 //            128 group maxima; the K-th largest of them is a lower bound of the beam's K-th
 //            largest logit.
-//   sweep 2: logits at or above the bound are appended to the beam's list of 256 (logit, code)
+//   sweep 2: logits at or above the bound are appended to the beam's list of 384 (logit, code)
 //            pairs in global scratch, the place taken from a counter in LDS.  The scratch belongs
 //            to the workgroup and is reused for each of its requests, so it lives in L2 / MALL.
 //            (A list per (beam, lane) pair with its counter in a register needs no atomic, but
@@ -2007,7 +2011,7 @@ __global__ __launch_bounds__(512, 4) void expand_chunked_kernel(ExpandArgs a) {
 //   candidates carries no meaning.)
 // A beam whose list would overflow (ties, or large logits crowded into few groups) is flagged in
 // redo[] and left to a pass of expand_chunked_kernel.
-constexpr int kReqCap = 256;         // list entries per beam
+constexpr int kReqCap = 384;         // list entries per beam (about 190 are used at K = 100, T_l = 4096)
 constexpr int kReqTiles = 8;         // column tiles per chunk = code groups per lane and beam
 constexpr int kReqMaxGroups = 1024;  // workgroups that own list scratch
 __host__ __device__ inline size_t request_w_region(int e, int n_waves) {
@@ -2041,6 +2045,7 @@ struct RequestLevelArgs {
   int transition;
 };
 constexpr int kReqListCap = 768;     // WHOLE: candidates per request kept for the final sort
+constexpr int kReqForced = 1 << 30;  // WHOLE: bit of the request's counter that hands it to the general kernels
 __host__ __device__ inline size_t request_whole_lds() {
   // request list, wave 0's sorting buffer, per-wave bounds + counter, survivors' parents / codes
   return (size_t)kReqListCap * 8 + 256 * 8 + 16 * 4 + 2 * NEZHA_MAX_BEAM * 4;
@@ -2296,7 +2301,7 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
           // this lane's sum may have overflowed, or a maximum left the half range: push the
           // beam's (the request's) count past the list size
           if (half_ceil(top) > m_ref + 64.f || clamped) {
-            if constexpr (WHOLE) atomicAdd(req_cnt, kReqListCap + 1);
+            if constexpr (WHOLE) atomicOr(req_cnt, kReqForced);
             else atomicAdd(&my_cnt[4 * g + i], kReqCap + 1);
           }
           if constexpr (WHOLE) {
@@ -2382,7 +2387,31 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
       }
     };
     run_sweep(std::integral_constant<int, 0>{});
-    run_sweep(std::integral_constant<int, 1>{});
+    for (int attempt = 0;; ++attempt) {
+      run_sweep(std::integral_constant<int, 1>{});
+      if constexpr (!WHOLE) {
+        break;
+      } else {
+        // More candidates at or above the threshold than the list holds (one beam far ahead of
+        // the others gives few of the candidates the threshold was taken from): the K-th best of
+        // the listed ones, all of them real candidates, is a tighter threshold; sweep again.
+        const int n0 = *req_cnt;              // (the sweep ended with a barrier)
+        if (n0 <= kReqListCap || n0 >= kReqForced || attempt == 2) break;
+        __syncthreads();                      // everyone has read the counter
+        if (wave == 0) {
+          WaveTopK<256> f;
+          f.init(topbuf, K);
+          for (int base = 0; base < kReqListCap; base += 64) f.push(req_list[base + lane]);
+          f.compact();
+          wave_sync();
+          if (lane == 0) {
+            tau_s[0] = (uint32_t)(f.buf[K - 1] >> 32);
+            *req_cnt = 0;
+          }
+        }
+        __syncthreads();
+      }
+    }
 
     if constexpr (WHOLE) {
       const int n = *req_cnt;                 // (the sweep ended with a barrier)
@@ -2512,12 +2541,13 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
         const int need = K - n_gt;                                      // >= 1 of the n_eq ties
         uint32_t cthr = 0;                                              // ~code must reach this
         if (n_eq > need) {
-          uint32_t ck[1][NPL];
+          constexpr int NP2 = NPL <= 1 ? 1 : NPL <= 2 ? 2 : NPL <= 4 ? 4 : 8;   // the sort's size
+          uint32_t ck[1][NP2];
 #pragma unroll
-          for (int j = 0; j < NPL; ++j) ck[0][j] = zk[r][j] == tau ? ~code[r][j] : 0u;
-          sort_desc<NPL, 1, uint32_t>(ck);
+          for (int j = 0; j < NP2; ++j) ck[0][j] = (j < NPL && zk[r][j < NPL ? j : 0] == tau) ? ~code[r][j < NPL ? j : 0] : 0u;
+          sort_desc<NP2, 1, uint32_t>(ck);
           cthr = (uint32_t)__builtin_amdgcn_readlane(
-              (int)pick_element<NPL>(ck[0], (need - 1) % NPL), (need - 1) / NPL);
+              (int)pick_element<NP2>(ck[0], (need - 1) % NP2), (need - 1) / NP2);
         }
         const int64_t row = (int64_t)b * K_in + wave * 16 + 2 * q + r;
         const float lse = my_info[16 + 2 * q + r];
@@ -2553,7 +2583,8 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
       if (most == 0) continue;
       if (most <= 64) emit(std::integral_constant<int, 1>{}, q, n);
       else if (most <= 128) emit(std::integral_constant<int, 2>{}, q, n);
-      else emit(std::integral_constant<int, 4>{}, q, n);
+      else if (most <= 256) emit(std::integral_constant<int, 4>{}, q, n);
+      else emit(std::integral_constant<int, 6>{}, q, n);
     }
     wave_sync();                              // counters and info are rewritten for the next request
   }

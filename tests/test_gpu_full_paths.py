@@ -91,6 +91,32 @@ def test_flagged_requests_inside_a_walked_batch(oracle):
     assert soft <= cfg.B // 50 + 8
 
 
+def test_one_beam_far_ahead_of_the_others(oracle):
+    """Requests whose first-level distribution is sharply peaked: the best beam's children take
+    all K places of level 2, while the request's threshold is taken from 16 candidates per beam,
+    most of them from the other beams.  The list of candidates at or above it overflows, and the
+    kernel tightens the threshold from the listed candidates and sweeps again (also at level 3,
+    where the same beams arrive with the same gaps).  Lists of more than 256 entries per beam at
+    the verified level are covered by the crowded requests of the test above."""
+    cfg = _per_request_config(300, 64, 24, V=2048)
+    x, cat = planted_workload(oracle, cfg, 31, plant=False)
+    peaked = np.array([0, 5, 17, 150, 299])
+    x["H"][peaked, 0] = synth.round_to_bf16(x["H"][peaked, 0] * 400.0)
+    free = oracle.decode(x["H"], x["W"], x["E"], cfg.radices, cfg.K, round_state_bf16=True)
+    gap = free[0]["score"][peaked, 0] - free[0]["score"][peaked, 1]
+    assert (gap > 6.0).all()                            # the best first-level code is far ahead
+    tuples = oracle.unpack(free[-1]["key"].ravel(), cfg.radices)
+    keep = synth.plant_mask(tuples, cfg.radices, 31)
+    cat = synth.planted_catalog(cfg.radices, cat, tuples[keep], tuples[~keep], 31)
+    oset = oracle.ItemSet(cat, cfg.radices)
+    gset = nz.build_itemset(cat, cfg.radices, cfg.load_factor)
+    H, W, E = to_device(x, cfg)
+    outs = nz.decode(H, W, E, cfg.radices, cfg.K, gset)
+    torch.cuda.synchronize()
+    soft = check_decode(oracle, nz, cfg, x, outs, oset, 4e-3)
+    assert soft <= cfg.B // 50 + 8
+
+
 def test_verifier_scan_over_more_than_16384_blocks():
     """17.3 million queries: the accepted positions of a block are offset by a scan over the block
     counts (above 16384 blocks of 1024 queries a kernel of its own).  Membership and therefore the
