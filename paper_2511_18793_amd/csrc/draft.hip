@@ -1631,25 +1631,62 @@ __global__ __launch_bounds__(64 * kMergeMaxWaves) void merge_kernel(MergeArgs a)
   uint64_t* keys = dyn;
   uint64_t* topbuf = dyn + ((n_c + 1) & ~1);
 
+  // Sort keys (score, ~candidate number) of the candidates that exist and, where a set is
+  // consulted, are in it, packed at keys[0 .. n_valid): with verification a few per cent of the
+  // candidates survive, and the selection below then reads those instead of all K_in * K.  Four
+  // candidates per lane are looked up together (the filter words of all four, then the table
+  // lines of those that remain): one after the other, a workgroup's ten rounds of three dependent
+  // memory accesses each are most of this kernel's time.
+  __shared__ int n_valid;
+  if (tid == 0) n_valid = 0;
+  __syncthreads();
+  constexpr int NB = 4;
   uint32_t top0 = 0, top1 = 0;                       // this lane's two largest scores (ordered bits)
-  for (int base = wave * 64; base < n_c; base += n_threads) {   // wave uniform trip count
-    const int i = base + lane;
-    uint64_t sk = 0;
-    if (i < n_c) {
-      const int p = i / K;
-      const int64_t o = (int64_t)(b * K_in + p) * K + (i - p * K);
-      const float score = (a.score_in ? a.score_in[b * K_in + p] : 0.f) + a.cand_logp[o];
-      const uint64_t pkey = a.key_in ? a.key_in[b * K_in + p] : 0ull;
-      bool ok = pkey != kEmpty;                      // an empty beam slot has no children
-      if (verify && ok)
-        ok = set_contains(a.set, pkey, (uint32_t)a.cand_code[o]);
-      if (ok) sk = ((uint64_t)ordered_bits(score) << 32) | (uint32_t)~(uint32_t)i;
-      keys[i] = sk;
+  for (int base = wave * 64; base < n_c; base += n_threads * NB) {   // wave uniform trip count
+    uint64_t prefix[NB], sk[NB];
+    uint32_t code[NB];
+    float score[NB];
+    bool live[NB], in[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      const int i = base + j * n_threads + lane;
+      prefix[j] = 0ull;
+      code[j] = 0u;
+      score[j] = 0.f;
+      live[j] = false;
+      if (i < n_c) {
+        const int p = i / K;
+        const int64_t o = (int64_t)(b * K_in + p) * K + (i - p * K);
+        score[j] = (a.score_in ? a.score_in[b * K_in + p] : 0.f) + a.cand_logp[o];
+        prefix[j] = a.key_in ? a.key_in[b * K_in + p] : 0ull;
+        live[j] = prefix[j] != kEmpty;               // an empty beam slot has no children
+        if (verify) code[j] = (uint32_t)a.cand_code[o];
+      }
     }
-    const uint32_t s32 = (uint32_t)(sk >> 32);
-    const uint32_t lo = s32 > top0 ? top0 : s32;     // the smaller of (score, top0)
-    top0 = s32 > top0 ? s32 : top0;
-    top1 = lo > top1 ? lo : top1;
+    if (verify) {
+      set_contains_many<NB>(a.set, prefix, code, live, in);
+    } else {
+#pragma unroll
+      for (int j = 0; j < NB; ++j) in[j] = live[j];
+    }
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      const int i = base + j * n_threads + lane;
+      sk[j] = in[j] ? (((uint64_t)ordered_bits(score[j]) << 32) | (uint32_t)~(uint32_t)i) : 0ull;
+      const uint64_t bal = __ballot(in[j]);
+      if (bal) {
+        int at = 0;
+        if (lane == 0) at = atomicAdd(&n_valid, __popcll(bal));
+        at = __builtin_amdgcn_readfirstlane(at);
+        if (in[j])
+          keys[at + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32),
+                                              __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0))] = sk[j];
+      }
+      const uint32_t s32 = (uint32_t)(sk[j] >> 32);
+      const uint32_t lo = s32 > top0 ? top0 : s32;   // the smaller of (score, top0)
+      top0 = s32 > top0 ? s32 : top0;
+      top1 = lo > top1 ? lo : top1;
+    }
   }
   {
     // scores alone: a lower bound of the K-th largest key may ignore how ties are ordered
@@ -1673,7 +1710,8 @@ __global__ __launch_bounds__(64 * kMergeMaxWaves) void merge_kernel(MergeArgs a)
     WaveTopK<CAP> f;
     f.init(topbuf, K);
     f.tau = tau ? tau - 1ull : 0ull;                 // keys >= tau enter
-    for (int base = 0; base < n_c; base += 64) f.push(base + lane < n_c ? keys[base + lane] : 0ull);
+    const int n_in = n_valid;                        // (written before the barrier above)
+    for (int base = 0; base < n_in; base += 64) f.push(base + lane < n_in ? keys[base + lane] : 0ull);
     f.compact();
     wave_sync();
     constexpr int NPL = (NEZHA_MAX_BEAM + 63) / 64;
