@@ -1633,20 +1633,51 @@ __global__ __launch_bounds__(64 * kMergeMaxWaves) void merge_kernel(MergeArgs a)
 
   // Sort keys (score, ~candidate number) of the candidates that exist and, where a set is
   // consulted, are in it, packed at keys[0 .. n_valid): with verification a few per cent of the
-  // candidates survive, and the selection below then reads those instead of all K_in * K.  Four
-  // candidates per lane are looked up together (the filter words of all four, then the table
-  // lines of those that remain): one after the other, a workgroup's ten rounds of three dependent
-  // memory accesses each are most of this kernel's time.
+  // candidates survive, and the selection below then reads those instead of all K_in * K.
+  // A lane takes NB candidates at a time: their inputs, then the filter words of all of them, are
+  // in flight together.  The few that pass the filter are gathered per wave (64 at a time, in
+  // LDS) and looked up in the table one per lane, so a round of table accesses has full waves
+  // instead of a lane or two per instruction.  (One candidate after the other, a workgroup's ten
+  // rounds of three dependent memory accesses each were most of this kernel's time.)
   __shared__ int n_valid;
+  __shared__ uint64_t staged_key[kMergeMaxWaves][64], staged_sk[kMergeMaxWaves][64];
   if (tid == 0) n_valid = 0;
   __syncthreads();
-  constexpr int NB = 4;
+  constexpr int NB = 8;
   uint32_t top0 = 0, top1 = 0;                       // this lane's two largest scores (ordered bits)
+  auto keep = [&](bool ok, uint64_t sk) {            // all lanes of the wave together
+    const uint64_t bal = __ballot(ok);
+    if (bal) {
+      int at = 0;
+      if (lane == 0) at = atomicAdd(&n_valid, __popcll(bal));
+      at = __builtin_amdgcn_readfirstlane(at);
+      if (ok)
+        keys[at + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32),
+                                            __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0))] = sk;
+      const uint32_t s32 = ok ? (uint32_t)(sk >> 32) : 0u;
+      const uint32_t lo = s32 > top0 ? top0 : s32;   // the smaller of (score, top0)
+      top0 = s32 > top0 ? s32 : top0;
+      top1 = lo > top1 ? lo : top1;
+    }
+  };
+  int staged = 0;                                    // wave uniform
+  auto look_up_staged = [&]() {
+    wave_sync();
+    bool ok = false;
+    uint64_t sk = 0;
+    if (lane < staged) {
+      ok = set_probe(a.set, staged_key[wave][lane]);
+      sk = staged_sk[wave][lane];
+    }
+    keep(ok, sk);
+    wave_sync();
+    staged = 0;
+  };
   for (int base = wave * 64; base < n_c; base += n_threads * NB) {   // wave uniform trip count
-    uint64_t prefix[NB], sk[NB];
+    uint64_t prefix[NB];
     uint32_t code[NB];
     float score[NB];
-    bool live[NB], in[NB];
+    bool live[NB];
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
       const int i = base + j * n_threads + lane;
@@ -1663,31 +1694,37 @@ __global__ __launch_bounds__(64 * kMergeMaxWaves) void merge_kernel(MergeArgs a)
         if (verify) code[j] = (uint32_t)a.cand_code[o];
       }
     }
-    if (verify) {
-      set_contains_many<NB>(a.set, prefix, code, live, in);
-    } else {
+    uint64_t word[NB];
 #pragma unroll
-      for (int j = 0; j < NB; ++j) in[j] = live[j];
+    for (int j = 0; j < NB; ++j) {
+      word[j] = ~0ull;
+      if (verify && a.set.filter && live[j])
+        word[j] = *(global_ptr<const uint64_t>)(a.set.filter +
+                                                filter_word(prefix[j], code[j], a.set.n_blocks));
     }
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
       const int i = base + j * n_threads + lane;
-      sk[j] = in[j] ? (((uint64_t)ordered_bits(score[j]) << 32) | (uint32_t)~(uint32_t)i) : 0ull;
-      const uint64_t bal = __ballot(in[j]);
-      if (bal) {
-        int at = 0;
-        if (lane == 0) at = atomicAdd(&n_valid, __popcll(bal));
-        at = __builtin_amdgcn_readfirstlane(at);
-        if (in[j])
-          keys[at + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32),
-                                              __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0))] = sk[j];
+      const bool go = live[j] && ((word[j] >> (code[j] & 63)) & 1ull);
+      const uint64_t sk = ((uint64_t)ordered_bits(score[j]) << 32) | (uint32_t)~(uint32_t)i;
+      if (!verify) {
+        keep(go, sk);
+        continue;
       }
-      const uint32_t s32 = (uint32_t)(sk[j] >> 32);
-      const uint32_t lo = s32 > top0 ? top0 : s32;   // the smaller of (score, top0)
-      top0 = s32 > top0 ? s32 : top0;
-      top1 = lo > top1 ? lo : top1;
+      const uint64_t bal = __ballot(go);
+      const int n = __popcll(bal);
+      if (n == 0) continue;
+      if (staged + n > 64) look_up_staged();
+      if (go) {
+        const int at = staged + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32),
+                                                          __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0));
+        staged_key[wave][at] = prefix[j] + (uint64_t)code[j] * a.set.mult_last;
+        staged_sk[wave][at] = sk;
+      }
+      staged += n;
     }
   }
+  if (staged) look_up_staged();
   {
     // scores alone: a lower bound of the K-th largest key may ignore how ties are ordered
     uint32_t b32;
