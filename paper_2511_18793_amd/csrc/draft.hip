@@ -2245,9 +2245,16 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
             sp[i] = my_info[32 + 4 * g + i];
             lse_r[i] = my_info[16 + 4 * g + i];
             const float margin = 1e-5f * (fabsf(tf) + fabsf(sp[i]) + fabsf(lse_r[i]) + 1.f);
-            float bz = (tf - sp[i]) + lse_r[i] - margin;
-            if (!(tf > -INFINITY)) bz = -INFINITY;
+            const float bz = (tf - sp[i]) + lse_r[i] - margin;
             bound[i] = (sp[i] == -INFINITY) ? INFINITY : bz;
+          }
+          // No threshold (fewer than K candidates with a finite score, i.e. nearly all entering
+          // beams are empty slots): everything would be listed; the general kernels take the
+          // request.
+          if (!(tf > -INFINITY)) {
+            if (threadIdx.x == 0) atomicOr(req_cnt, kReqForced);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) bound[i] = INFINITY;
           }
         } else {
 #pragma unroll
@@ -2296,13 +2303,26 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
                     max_of_half_pairs(gmaxp[i >> 1][ct], pack_halves_rtz(z, zv(i + 1)));
               ssum[i] += __builtin_amdgcn_exp2f(fmaf(z, kLog2e, nml[i]));
             } else if constexpr (WHOLE) {
-              if (live && z >= bound[i]) {                  // bound: a logit that cannot be missed
-                const uint32_t key = ordered_bits(sp[i] + (z - lse_r[i]));        // the final score
-                if (key >= tau) {
-                  const uint32_t code = (uint32_t)((ch * kReqTiles + ct) * 16 + c);
-                  const int pos = atomicAdd(req_cnt, 1);
-                  const uint32_t who = ((uint32_t)(wave * 16 + 4 * g + i) << 24) | code;
-                  if (pos < kReqListCap) req_list[pos] = ((uint64_t)key << 32) | (uint32_t)~who;
+              // The accumulators started at (user part - bound of the beam), so the lane's four
+              // values are logit - bound and one test serves all four; candidates are so rare
+              // after the request-wide threshold that the branch is almost never taken.
+              if (i == 3) {
+                const float most = fmaxf(fmaxf(zv(0), zv(1)), fmaxf(zv(2), zv(3)));
+                if (most >= 0.f) {
+#pragma unroll
+                  for (int k = 0; k < 4; ++k) {
+                    const float over = zv(k);
+                    if (over >= 0.f) {                       // the logit cannot be missed
+                      const float zl = over + bound[k];
+                      const uint32_t key = ordered_bits(sp[k] + (zl - lse_r[k]));   // the final score
+                      if (key >= tau) {
+                        const uint32_t code = (uint32_t)((ch * kReqTiles + ct) * 16 + c);
+                        const int pos = atomicAdd(req_cnt, 1);
+                        const uint32_t who = ((uint32_t)(wave * 16 + 4 * g + k) << 24) | code;
+                        if (pos < kReqListCap) req_list[pos] = ((uint64_t)key << 32) | (uint32_t)~who;
+                      }
+                    }
+                  }
                 }
               }
             } else {
@@ -2319,6 +2339,8 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
 #pragma unroll
           for (int ct = 0; ct <= kReqTiles; ++ct) {
             floatx4 t = floatx4{a0, a0, a0, a0};
+            if constexpr (WHOLE && sweep == 1)
+              t = floatx4{a0 - bound[0], a0 - bound[1], a0 - bound[2], a0 - bound[3]};
 #pragma unroll
             for (int ks = 0; ks < KST; ++ks) {
               if (ct < kReqTiles) {
