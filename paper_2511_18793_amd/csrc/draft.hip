@@ -2298,9 +2298,10 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
               // beam) + 20, held as nml = -m * log2(e): no rescaling while streaming.  A beam with
               // a logit more than 64 above a lane's reference is redone by the general kernel.
               if (ct == 0 && ch == 0) nml[i] = -(z + 20.f) * kLog2e;
+              // (the whole-level form only uses the lane's largest logit per beam: one group)
               if ((i & 1) == 0)
-                gmaxp[i >> 1][ct] =
-                    max_of_half_pairs(gmaxp[i >> 1][ct], pack_halves_rtz(z, zv(i + 1)));
+                gmaxp[i >> 1][WHOLE ? 0 : ct] =
+                    max_of_half_pairs(gmaxp[i >> 1][WHOLE ? 0 : ct], pack_halves_rtz(z, zv(i + 1)));
               ssum[i] += __builtin_amdgcn_exp2f(fmaf(z, kLog2e, nml[i]));
             } else if constexpr (WHOLE) {
               // The accumulators started at (user part - bound of the beam), so the lane's four
@@ -2390,7 +2391,7 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
           float top = -INFINITY;
           bool clamped = false;
 #pragma unroll
-          for (int j = 0; j < kReqTiles; ++j) {
+          for (int j = 0; j < (WHOLE ? 1 : kReqTiles); ++j) {
             const float m = half_bits_to_float(gmaxp[i >> 1][j] >> (16 * (i & 1)));
             top = fmaxf(top, m);
             clamped |= half_out_of_range(m);
