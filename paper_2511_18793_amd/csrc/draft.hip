@@ -12,6 +12,9 @@
 //   level_small_kernel,     all of the above after the projection in one launch per level / per
 //   decode_small_kernel     decode, for small shapes
 //   wide_*_kernel           beams wider than 128 (wide_beam.h)
+//   mfma_rate_kernel,       measurement aids: what the chip sustains on the bare instruction mixes
+//   tile_step_kernel        of the projection and of the per-request expansion (the rooflines'
+//                           measured denominators)
 #include "nezha_internal.h"
 
 #include <atomic>
