@@ -2146,7 +2146,9 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
   float* const abuf = reinterpret_cast<float*>(req_lds + request_w_region(e, NW));   // [2][128]
   // per wave: bound[16], lse[16], count[16] (WHOLE: the parents' scores instead of the counts)
   float* const my_info = abuf + 2 * kReqTiles * 16 + wave * 48;
-  int* const my_cnt = reinterpret_cast<int*>(my_info + 32);
+  // list form: entries listed per beam, four 16-bit counts to a word (word g: beams 4g .. 4g+3), so
+  // that a lane reserves places for its four beams with one LDS atomic
+  unsigned long long* const my_cnt4 = reinterpret_cast<unsigned long long*>(my_info + 32);
   uint64_t* const my_lists = lists_all + ((int64_t)blockIdx.x * 128 + wave * 16) * kReqCap;
   // WHOLE only (after the NW waves' info):
   uint64_t* const req_list = reinterpret_cast<uint64_t*>(abuf + 2 * kReqTiles * 16 + NW * 48);
@@ -2217,7 +2219,7 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
         tau_s[0] = 0;
       }
     } else {
-      if (lane < 16) my_cnt[lane] = 0;
+      if (lane < 4) my_cnt4[lane] = 0ull;
     }
 
     auto run_sweep = [&](auto sweep_c) {
@@ -2330,11 +2332,27 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
                 }
               }
             } else {
-              if (live && z >= bound[i]) {
-                const uint32_t code = (uint32_t)((ch * kReqTiles + ct) * 16 + c);
-                const int pos = atomicAdd(&my_cnt[4 * g + i], 1);
-                if (pos < kReqCap)
-                  my_lists[(4 * g + i) * kReqCap + pos] = ((uint64_t)__float_as_uint(z) << 32) | code;
+              // all four beams of the lane after the chain's last link: one atomic on the lane's
+              // word of counts reserves a place in each list the lane appends to
+              if (i == 3) {
+                bool pass[4];
+                unsigned long long add = 0ull;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                  pass[k] = live && zv(k) >= bound[k];
+                  add |= pass[k] ? (1ull << (16 * k)) : 0ull;
+                }
+                if (add != 0ull) {
+                  const unsigned long long before = atomicAdd(&my_cnt4[g], add);
+                  const uint32_t code = (uint32_t)((ch * kReqTiles + ct) * 16 + c);
+#pragma unroll
+                  for (int k = 0; k < 4; ++k) {
+                    const int pos = (int)((before >> (16 * k)) & 0xFFFFull);
+                    if (pass[k] && pos < kReqCap)
+                      my_lists[(4 * g + k) * kReqCap + pos] =
+                          ((uint64_t)__float_as_uint(zv(k)) << 32) | code;
+                  }
+                }
               }
             }
           };
@@ -2403,7 +2421,7 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
           // beam's (the request's) count past the list size
           if (half_ceil(top) > m_ref + 64.f || clamped) {
             if constexpr (WHOLE) atomicOr(req_cnt, kReqForced);
-            else atomicAdd(&my_cnt[4 * g + i], kReqCap + 1);
+            else atomicAdd(&my_cnt4[g], (unsigned long long)(kReqCap + 1) << (16 * i));
           }
           if constexpr (WHOLE) {
             // the lane's largest logit of this beam, as a score no larger than the true one
@@ -2672,8 +2690,11 @@ __global__ __launch_bounds__(512, KST <= 4 ? 4 : 2) void expand_request_kernel(
       const int ra = wave * 16 + 2 * q;
       if (ra >= K_in) break;
       int n[2];
-      n[0] = __builtin_amdgcn_readfirstlane(my_cnt[2 * q]);
-      n[1] = ra + 1 < K_in ? __builtin_amdgcn_readfirstlane(my_cnt[2 * q + 1]) : 0;
+      // (a count that was pushed past the list's size by up to 16 lanes still fits its 16 bits)
+      const unsigned long long word = my_cnt4[q >> 1];
+      const uint32_t pair = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(word >> (32 * (q & 1))));
+      n[0] = (int)(pair & 0xFFFFu);
+      n[1] = ra + 1 < K_in ? (int)(pair >> 16) : 0;
 #pragma unroll
       for (int r = 0; r < 2; ++r) {
         const bool over = n[r] > kReqCap;
@@ -2995,7 +3016,8 @@ inline bool level_fits_one_launch(bool bf16, int K, int K_in, int V, int e) {
 }
 inline bool codebook_fits_lds(bool bf16, int K, int V) { return bf16 && V <= 1024 && K <= 64; }
 inline bool expand_per_request(bool bf16, int K, int K_in, int V, int e) {
-  return bf16 && K_in >= 16 && V <= (1 << 24) && (e == 32 || e == 64 || e == 128 || e == 256) &&
+  // (T_l <= 32768: the kernel counts a beam's list entries, at most T_l plus 16 flags of 385, in 16 bits)
+  return bf16 && K_in >= 16 && V <= (1 << 15) && (e == 32 || e == 64 || e == 128 || e == 256) &&
          !level_fits_one_launch(bf16, K, K_in, V, e) && !codebook_fits_lds(bf16, K, V);
 }
 

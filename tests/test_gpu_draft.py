@@ -477,6 +477,8 @@ def test_draft_levels_equals_the_level_loop(oracle, name, B, variant):
     (2, 64, 256, 1536, 100, 2),    # widest state
     (2, 128, 128, 4096, 128, 2),   # the largest beam, eight full waves
     (5, 64, 128, 80, 70, 2),       # fewer codes than one chunk: most code groups are empty
+    (1, 32, 32, 32768, 16, 2),     # the largest codebook this kernel takes (16-bit list counts)
+    (1, 32, 32, 32784, 16, 2),     # one tile more: the general kernel takes the level
 ])
 def test_request_kernel_shapes(oracle, B, d, e, V, K, L):
     cfg = synth.StepConfig("req", B=B, d=d, e=e, L=L, V=V, K=K, N=min(V ** L // 4, 50_000),
