@@ -7,6 +7,8 @@
 //   expand_*_kernel         per beam: z = A_l + c * W_l[d:d+e] by MFMA, log-sum-exp and the K best
 //                           codes; logits never leave the chip.  expand_request_kernel also does
 //                           the request's selection where no set is consulted
+//   first_level_kernel      a level with one entering beam and no state (level 1): the logits are
+//                           the user part; selection, outputs and Transition in one launch
 //   merge_kernel            per request: cumulative scores, Eq. 4 indices, Eq. 5 probes, the K
 //                           best surviving candidates, and the Transition of Eq. 3
 //   level_small_kernel,     all of the above after the projection in one launch per level / per
@@ -1792,6 +1794,165 @@ __global__ __launch_bounds__(64 * kMergeMaxWaves) void merge_kernel(MergeArgs a)
     else
       update_states<BF16>(a.state_in, a.E, a.state_out, b, K, K_in, a.e, fin_parent, fin_code, tid,
                           n_threads);
+  }
+}
+
+// ---- a level with one entering beam whose state is zero (level 1 of a decode) -------------------
+// The logits are the user part itself (Eq. 2 with c = 0), so there is nothing to multiply: one
+// workgroup of four waves per request holds the row in registers (16 per thread, T_l <= 4096),
+// forms the log-sum-exp, and selects the K best codes: every lane's two largest keys give each
+// wave a lower bound of its K-th largest (one small sort), the largest of the waves' bounds is a
+// lower bound of the row's K-th largest, the keys at or above it are gathered in LDS and wave 0
+// sorts them (score first, lower code first among equal scores).  Outputs and the Transition as
+// merge_kernel writes them; no candidate arrays, no second launch.
+struct FirstLevelArgs {
+  const float* A;           // [B, V] user part
+  const void* E;            // [V, e] (used when state_out != NULL)
+  const void* U;            // recurrent Transition, else unused
+  uint64_t mult;            // prod_{j<level} T_j
+  uint64_t* key_out;
+  float* score_out;
+  int32_t* parent_out;
+  int32_t* code_out;
+  void* state_out;          // or NULL
+  int32_t* count_out;       // or NULL
+  int K, V, e, transition;
+};
+constexpr int kFirstThreads = 256, kFirstPerThread = 16, kFirstListCap = 1024;
+template <bool BF16>
+__global__ __launch_bounds__(kFirstThreads) void first_level_kernel(FirstLevelArgs a) {
+  __shared__ uint64_t list[kFirstListCap + 256];        // gathered keys, then wave 0's sort buffer
+  __shared__ float red[8];
+  __shared__ uint32_t bounds[4];
+  __shared__ int n_listed;
+  __shared__ int32_t fin_parent[NEZHA_MAX_BEAM], fin_code[NEZHA_MAX_BEAM];
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int V = a.V, K = a.K;
+  float z[kFirstPerThread];
+  float m = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < kFirstPerThread; ++j) {
+    const int v = tid + j * kFirstThreads;
+    z[j] = v < V ? a.A[(int64_t)b * V + v] : -INFINITY;
+    m = fmaxf(m, z[j]);
+  }
+  auto wave_max = [&](float x) {
+    x = fmaxf(x, __uint_as_float(lane_xor<1>(__float_as_uint(x), lane)));
+    x = fmaxf(x, __uint_as_float(lane_xor<2>(__float_as_uint(x), lane)));
+    x = fmaxf(x, __uint_as_float(lane_xor<4>(__float_as_uint(x), lane)));
+    x = fmaxf(x, __uint_as_float(lane_xor<8>(__float_as_uint(x), lane)));
+    x = fmaxf(x, __uint_as_float(lane_xor<16>(__float_as_uint(x), lane)));
+    x = fmaxf(x, __uint_as_float(lane_xor<32>(__float_as_uint(x), lane)));
+    return x;
+  };
+  auto wave_sum = [&](float x) {
+    x += __uint_as_float(lane_xor<1>(__float_as_uint(x), lane));
+    x += __uint_as_float(lane_xor<2>(__float_as_uint(x), lane));
+    x += __uint_as_float(lane_xor<4>(__float_as_uint(x), lane));
+    x += __uint_as_float(lane_xor<8>(__float_as_uint(x), lane));
+    x += __uint_as_float(lane_xor<16>(__float_as_uint(x), lane));
+    x += __uint_as_float(lane_xor<32>(__float_as_uint(x), lane));
+    return x;
+  };
+  m = wave_max(m);
+  if (lane == 0) red[wave] = m;
+  if (tid == 0) n_listed = 0;
+  __syncthreads();
+  m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  float ssum = 0.f;
+  uint32_t top0 = 0, top1 = 0;                       // the lane's two largest keys
+#pragma unroll
+  for (int j = 0; j < kFirstPerThread; ++j) {
+    const int v = tid + j * kFirstThreads;
+    if (v < V) ssum += __builtin_amdgcn_exp2f((z[j] - m) * kLog2e);
+    const uint32_t k = v < V ? ordered_bits(z[j]) : 0u;
+    const uint32_t lo = k > top0 ? top0 : k;
+    top0 = k > top0 ? k : top0;
+    top1 = lo > top1 ? lo : top1;
+  }
+  ssum = wave_sum(ssum);
+  if (lane == 0) red[4 + wave] = ssum;
+  {
+    uint32_t mk[1][2] = {{top0, top1}};
+    sort_desc<2, 1, uint32_t>(mk);                   // position 2*lane + j; K <= 128
+    const uint32_t bw = (uint32_t)__builtin_amdgcn_readlane((int)pick_element<2>(mk[0], (K - 1) & 1),
+                                                            (K - 1) >> 1);
+    if (lane == 0) bounds[wave] = bw;
+  }
+  __syncthreads();
+  const float lse = m + __builtin_amdgcn_logf((red[4] + red[5]) + (red[6] + red[7])) * kLn2;
+  uint32_t tau = bounds[0];
+#pragma unroll
+  for (int w = 1; w < 4; ++w) tau = bounds[w] > tau ? bounds[w] : tau;
+  bool over = false;
+#pragma unroll
+  for (int j = 0; j < kFirstPerThread; ++j) {
+    const int v = tid + j * kFirstThreads;
+    const uint32_t k = v < V ? ordered_bits(z[j]) : 0u;
+    const bool take = v < V && k >= tau;
+    const uint64_t bal = __ballot(take);
+    if (bal) {
+      int at = 0;
+      if (lane == 0) at = atomicAdd(&n_listed, __popcll(bal));
+      at = __builtin_amdgcn_readfirstlane(at) +
+           __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0));
+      if (take && at < kFirstListCap) list[at] = ((uint64_t)k << 32) | (uint32_t)~(uint32_t)v;
+    }
+  }
+  __syncthreads();
+  int n = n_listed;
+  over = n > kFirstListCap;
+  if (wave == 0) {
+    WaveTopK<256> f;
+    f.init(list + kFirstListCap, K);
+    if (!over) {
+      for (int base = 0; base < n; base += 64) f.push(base + lane < n ? list[base + lane] : 0ull);
+    } else {
+      // more keys tie with the bound than the list holds: stream the whole row
+      for (int v0 = 0; v0 < V; v0 += 64) {
+        const int v = v0 + lane;
+        f.push(v < V ? (((uint64_t)ordered_bits(a.A[(int64_t)b * V + v]) << 32) | (uint32_t)~(uint32_t)v)
+                     : 0ull);
+      }
+    }
+    f.compact();
+    wave_sync();
+    constexpr int NPLK = (NEZHA_MAX_BEAM + 63) / 64;
+#pragma unroll
+    for (int j = 0; j < NPLK; ++j) {
+      const int p = lane + 64 * j;
+      if (p < K) {
+        const int64_t o = (int64_t)b * K + p;
+        if (p < f.cnt) {
+          const uint64_t sk = f.buf[p];
+          const int32_t code = (int32_t)(~(uint32_t)sk);
+          a.key_out[o] = (uint64_t)(uint32_t)code * a.mult;
+          a.score_out[o] = unordered_bits((uint32_t)(sk >> 32)) - lse;
+          a.parent_out[o] = 0;
+          a.code_out[o] = code;
+          fin_parent[p] = 0;
+          fin_code[p] = code;
+        } else {
+          a.key_out[o] = kEmpty;
+          a.score_out[o] = -INFINITY;
+          a.parent_out[o] = -1;
+          a.code_out[o] = -1;
+          fin_parent[p] = -1;
+          fin_code[p] = -1;
+        }
+      }
+    }
+    if (lane == 0 && a.count_out) a.count_out[b] = f.cnt;
+  }
+  __syncthreads();
+  if (a.state_out) {
+    if (a.transition == NEZHA_TRANSITION_RNN)
+      update_states_rnn<BF16>(nullptr, a.E, a.U, a.state_out, b, K, 1, a.e, fin_parent, fin_code, tid,
+                              kFirstThreads);
+    else
+      update_states<BF16>(nullptr, a.E, a.state_out, b, K, 1, a.e, fin_parent, fin_code, tid,
+                          kFirstThreads);
   }
 }
 
@@ -3674,6 +3835,34 @@ int nezha_draft_step(const nezha_step_desc* desc, const void* H_l, const void* W
       else LAUNCH_LEVEL(8, 8);
     }
 #undef LAUNCH_LEVEL
+    NEZHA_HIP_CHECK(hipGetLastError());
+    return NEZHA_OK;
+  }
+
+  if (K_in == 1 && !state_in && !key_in && !score_in && !(set && set->L == level) &&
+      V <= kFirstThreads * kFirstPerThread &&
+      K <= NEZHA_MAX_BEAM) {
+    // level 1 of a decode: the logits are the user part; one launch
+    FirstLevelArgs fa;
+    fa.A = A;
+    fa.E = E_l;
+    fa.U = desc->U_l;
+    fa.mult = mult[level - 1];
+    fa.key_out = key_out;
+    fa.score_out = score_out;
+    fa.parent_out = parent_out;
+    fa.code_out = code_out;
+    fa.state_out = state_out;
+    fa.count_out = count_out;
+    fa.K = K;
+    fa.V = V;
+    fa.e = e;
+    fa.transition = desc->transition;
+    ProfileScope prof(kExpand, stream);
+    if (bf16)
+      hipLaunchKernelGGL(first_level_kernel<true>, dim3(B), dim3(kFirstThreads), 0, stream, fa);
+    else
+      hipLaunchKernelGGL(first_level_kernel<false>, dim3(B), dim3(kFirstThreads), 0, stream, fa);
     NEZHA_HIP_CHECK(hipGetLastError());
     return NEZHA_OK;
   }
